@@ -1,0 +1,102 @@
+"""fprop / dgrad / wgrad on split-quantized operands (Sec. 3.2) -- oracle side.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Layout (PyTorch convention): X[L,K] activations, W[N,K] weight (out x in, the
+transpose of the paper's W), Y = X W^T [L,N], G = dL/dY [L,N].
+A split operand holds Q(U), S (unquantized, Sec. 3.2: singular values are kept
+in high precision), Q(V) and Q(R).  The quantized operand is
+    Abar = deq(Q(U)) diag(S) deq(Q(V))^T + deq(Q(R))
+and the three products are plain fp64 matmuls of those (the paper's own
+emulation is dequantize-then-multiply, App. C.1):
+    fwd   Y  = Xbar Wbar^T      (Eq. 2)
+    dgrad dX = Gbar Wbar        (Eq. 3)
+    wgrad dW = Gbar^T Xbar      (the dL/dW_R line after Eq. 3, transposed)
+
+Blocks of 16 lie along the contraction axis of the consuming GEMM (a reading:
+the paper does not say).  A residual used by two GEMMs is therefore quantized
+twice from the same unquantized residual, once along each axis; `R` below is
+quantized along the columns of A, `Rt` is the transpose quantized along the
+rows of A.  Factors are quantized along their long axis (each singular vector
+contiguous).
+"""
+import numpy as np
+from . import quant
+
+
+class SplitQ:
+    """Quantized split of one matrix A[M,N]; every member is plain numpy.
+
+    Ut: (codes, scales, g) of U^T [k,M];  Vt: of V^T [k,N];
+    R : of R [M,N] (blocks along N);      Rt: of R^T [N,M] (blocks along M);
+    S : fp64 [k].  k == 0 means "not split": R holds Q(A)."""
+
+    def __init__(self, Ut, S, Vt, R, Rt):
+        self.Ut, self.S, self.Vt, self.R, self.Rt = Ut, S, Vt, R, Rt
+
+
+def split_quantize(A, U, S, V, g_u, g_v, g_r, want_t=True):
+    """Q_b applied separately to U, V and R, not to S (Sec. 3.2 before Eq. 2)."""
+    from .decompose import residual
+    A = np.asarray(A, dtype=np.float64)
+    if U is None or U.shape[1] == 0:
+        R = A
+        Ut = Vt = None
+        S = np.zeros(0)
+    else:
+        R = residual(A, U, S, V)
+        Ut = quant.quantize(U.T, g_u) + (g_u,)
+        Vt = quant.quantize(V.T, g_v) + (g_v,)
+    Rq = quant.quantize(R, g_r) + (g_r,)
+    Rtq = quant.quantize(R.T, g_r) + (g_r,) if want_t else None
+    return SplitQ(Ut, np.asarray(S, dtype=np.float64), Vt, Rq, Rtq)
+
+
+def assemble(sq, transposed_residual=False):
+    """Abar [M,N] from a SplitQ, using R (blocks along N) or Rt (blocks along M)."""
+    if transposed_residual:
+        Rb = quant.dequantize(*sq.Rt).T
+    else:
+        Rb = quant.dequantize(*sq.R)
+    if sq.Ut is None:
+        return Rb
+    Ub = quant.dequantize(*sq.Ut).T
+    Vb = quant.dequantize(*sq.Vt).T
+    return (Ub * sq.S) @ Vb.T + Rb
+
+
+def linear_fwd(xq, wq):
+    """Y = Xbar Wbar^T; contraction over K: X_R and W_R blocked along K."""
+    return assemble(xq) @ assemble(wq).T
+
+
+def linear_dgrad(gq, wq):
+    """dX = Gbar Wbar; contraction over N: G_R blocked along N (its columns),
+    W_R blocked along N (its rows -> Rt)."""
+    return assemble(gq) @ assemble(wq, transposed_residual=True)
+
+
+def linear_wgrad(gq, xq):
+    """dW = Gbar^T Xbar; contraction over L: both residuals blocked along rows."""
+    return assemble(gq, transposed_residual=True).T @ assemble(xq, transposed_residual=True)
+
+
+def linear_fwd_expanded(xq, wq):
+    """Eq. 2 written out term by term (used only to pin linear_fwd)."""
+    XR = quant.dequantize(*xq.R)
+    WR = quant.dequantize(*wq.R)
+    Y = XR @ WR.T
+    have_x, have_w = xq.Ut is not None, wq.Ut is not None
+    if have_x:
+        Ax = quant.dequantize(*xq.Ut).T
+        Bx = quant.dequantize(*xq.Vt).T
+    if have_w:
+        Uw = quant.dequantize(*wq.Ut).T      # [N,k]: left factor of W[N,K]
+        Vw = quant.dequantize(*wq.Vt).T      # [K,k]
+    if have_w:
+        Y = Y + ((XR @ Vw) * wq.S) @ Uw.T
+    if have_x:
+        Y = Y + (Ax * xq.S) @ (Bx.T @ WR.T)
+    if have_x and have_w:
+        Y = Y + ((Ax * xq.S) @ (Bx.T @ Vw) * wq.S) @ Uw.T
+    return Y

@@ -1,0 +1,91 @@
+"""NVFP4 block quantizer Q_4^NV (Sec. 2.3; value set in App. C.1) -- oracle side.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+A row-major matrix is cut into blocks of 16 consecutive elements along its
+last axis.  Per block one scale s in FP8-E4M3 is chosen from the block's
+largest magnitude, rounded UP so that the largest element is covered
+(6*s*g >= amax, 6 being the largest E2M1 magnitude); every element becomes
+round(e / (s*g)) * (s*g) on the grid +-{0, .5, 1, 1.5, 2, 3, 4, 6}.
+
+Readings of this build where the paper is silent:
+  * g is a per-tensor power-of-two scale (g = 1 is the paper's text verbatim);
+  * round() is round-to-nearest, ties to the even E2M1 code;
+  * a block whose amax exceeds 6*448*g saturates (scale 448, elements clamp to 6);
+  * an all-zero block gets scale byte 0 and codes that keep only the sign bit.
+
+Storage: codes[rows, cols/2] uint8, low nibble = even column, nibble =
+sign<<3 | magnitude code; scales[rows, cols/16] uint8 = E4M3 bit pattern.
+"""
+import numpy as np
+
+BLOCK = 16
+E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+# decision boundaries between neighbouring grid values
+E2M1_MID = (E2M1_GRID[:-1] + E2M1_GRID[1:]) / 2.0
+
+
+def e4m3_value(byte):
+    """Value of a non-negative FP8-E4M3 (4 exponent bits, bias 7, 3 mantissa
+    bits, no infinities, largest finite 448) bit pattern 0x00..0x7E."""
+    byte = np.asarray(byte, dtype=np.int64)
+    e = byte >> 3
+    m = byte & 7
+    sub = m * 2.0 ** -9
+    nor = (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64))
+    return np.where(e == 0, sub, nor)
+
+
+E4M3_POS = e4m3_value(np.arange(0, 127))      # 0, 2^-9, ..., 448 ascending
+
+
+def quantize(x, g=1.0):
+    """Quantize x[rows, cols] (cols % 16 == 0).  Returns (codes, scales)."""
+    x = np.asarray(x, dtype=np.float64)
+    rows, cols = x.shape
+    assert cols % BLOCK == 0
+    xb = x.reshape(rows, cols // BLOCK, BLOCK)
+    amax = np.abs(xb).max(axis=2)
+    # smallest E4M3 value s with 6*s*g >= amax  ("rounded up ... to ensure coverage")
+    cover = 6.0 * E4M3_POS * g
+    sidx = np.searchsorted(cover, amax, side="left")
+    sidx = np.minimum(sidx, 126)                    # saturate at 448
+    s = E4M3_POS[sidx] * g                          # effective step per block
+    a = np.abs(xb)
+    step = s[:, :, None]
+    mag = np.zeros(xb.shape, dtype=np.int64)
+    for j, mid in enumerate(E2M1_MID):
+        bound = mid * step
+        # a tie goes to the even code: boundary j separates codes j and j+1
+        if (j + 1) % 2 == 0:
+            mag += (a >= bound)
+        else:
+            mag += (a > bound)
+    mag = np.where(step == 0, 0, mag)
+    sign = np.signbit(xb).astype(np.int64)
+    nib = (sign << 3) | mag
+    nib = nib.reshape(rows, cols)
+    codes = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    return codes, sidx.astype(np.uint8)
+
+
+def dequantize(codes, scales, g=1.0):
+    """Inverse map: fp64 matrix [rows, cols] of grid * s * g."""
+    codes = np.asarray(codes, dtype=np.int64)
+    rows, half = codes.shape
+    nib = np.empty((rows, half * 2), dtype=np.int64)
+    nib[:, 0::2] = codes & 15
+    nib[:, 1::2] = codes >> 4
+    val = E2M1_GRID[nib & 7] * np.where(nib & 8, -1.0, 1.0)
+    s = e4m3_value(scales) * g
+    return val * np.repeat(s, BLOCK, axis=1)
+
+
+def tensor_scale_for(amax, headroom=1.0):
+    """Smallest power of two g with 6*448*g >= amax*headroom (g <= 1 kept as is
+    when amax is 0).  Power of two keeps every quantizer comparison exact."""
+    amax = float(amax) * headroom
+    if amax <= 0.0:
+        return 1.0
+    m, e = np.frexp(amax / (6.0 * 448.0))       # amax/2688 = m * 2^e, 0.5 <= m < 1
+    return float(np.ldexp(1.0, e - 1 if m == 0.5 else e))

@@ -1,0 +1,120 @@
+"""Pins for oracle/linear.py: Eq. 2 written out term by term, scalar triple
+loops on tiny shapes, the k = 0 reduction, and losslessly-representable inputs
+for which all three products must equal the plain products."""
+import numpy as np
+
+from oracle import decompose as dec
+from oracle import linear as lin
+from oracle import quant
+
+
+def _split(rs, M, N, k, g=(2.0 ** -11, 2.0 ** -11, 2.0 ** -6)):
+    A = rs.standard_normal((M, N)) + np.outer(rs.standard_normal(M), rs.standard_normal(N)) * 3
+    U, S, V = dec.decompose(A, k, 4, 1.0, seed=M + N)
+    return A, lin.split_quantize(A, U, S, V, *g)
+
+
+def test_eq2_expansion_equals_assembled_product():
+    rs = np.random.default_rng(0)
+    _, xq = _split(rs, 48, 64, 4)
+    _, wq = _split(rs, 32, 64, 4)
+    Y = lin.linear_fwd(xq, wq)
+    assert np.allclose(Y, lin.linear_fwd_expanded(xq, wq), rtol=1e-12, atol=1e-12)
+
+
+def test_triple_loop_tiny():
+    rs = np.random.default_rng(1)
+    _, xq = _split(rs, 16, 32, 2)
+    _, wq = _split(rs, 16, 32, 2)
+    _, gq = _split(rs, 16, 16, 2)
+    Xb, Wb = lin.assemble(xq), lin.assemble(wq)
+    Y = lin.linear_fwd(xq, wq)
+    ref = np.zeros((16, 16))
+    for l in range(16):
+        for n in range(16):
+            for kk in range(32):
+                ref[l, n] += Xb[l, kk] * Wb[n, kk]
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-12)
+    # dgrad: dX[l,k] = sum_n Gbar[l,n] Wbar_t[n,k], with W's residual blocked along N
+    Gb, Wt = lin.assemble(gq), lin.assemble(wq, transposed_residual=True)
+    dX = lin.linear_dgrad(gq, wq)
+    ref = np.zeros((16, 32))
+    for l in range(16):
+        for kk in range(32):
+            for n in range(16):
+                ref[l, kk] += Gb[l, n] * Wt[n, kk]
+    assert np.allclose(dX, ref, rtol=1e-12, atol=1e-12)
+    Gt, Xt = lin.assemble(gq, True), lin.assemble(xq, True)
+    dW = lin.linear_wgrad(gq, xq)
+    ref = np.zeros((16, 32))
+    for n in range(16):
+        for kk in range(32):
+            for l in range(16):
+                ref[n, kk] += Gt[l, n] * Xt[l, kk]
+    assert np.allclose(dW, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_assemble_element_by_element():
+    rs = np.random.default_rng(2)
+    A, sq = _split(rs, 32, 48, 3)
+    Ab = lin.assemble(sq)
+    Ud = quant.dequantize(*sq.Ut)       # [k, M]
+    Vd = quant.dequantize(*sq.Vt)       # [k, N]
+    Rd = quant.dequantize(*sq.R)
+    for (i, j) in [(0, 0), (5, 17), (31, 47)]:
+        v = sum(Ud[c, i] * sq.S[c] * Vd[c, j] for c in range(3)) + Rd[i, j]
+        assert np.isclose(Ab[i, j], v, rtol=1e-13)
+    # S is not quantized: it is carried verbatim
+    U, S, V = dec.decompose(A, 3, 4, 1.0, seed=32 + 48)
+    assert np.array_equal(sq.S, S)
+    # the quantized operand approximates A
+    assert np.linalg.norm(Ab - A) / np.linalg.norm(A) < 0.15
+
+
+def test_k0_is_plain_quantized_gemm():
+    rs = np.random.default_rng(3)
+    X, W = rs.standard_normal((16, 32)), rs.standard_normal((32, 32))
+    xq = lin.split_quantize(X, None, None, None, 1, 1, 2.0 ** -6)
+    wq = lin.split_quantize(W, None, None, None, 1, 1, 2.0 ** -6)
+    ref = quant.dequantize(*quant.quantize(X, 2.0 ** -6), 2.0 ** -6) @ \
+        quant.dequantize(*quant.quantize(W, 2.0 ** -6), 2.0 ** -6).T
+    assert np.array_equal(lin.linear_fwd(xq, wq), ref)
+    assert np.array_equal(lin.linear_fwd_expanded(xq, wq), ref)
+
+
+def test_lossless_inputs_give_plain_products():
+    # entries on the E2M1 grid with a common power-of-two scale quantize without
+    # error along either axis, so all three products equal the plain ones
+    rs = np.random.default_rng(4)
+    grid = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+
+    def lossless(m, n):
+        a = grid[rs.integers(0, 8, (m, n))] * rs.choice([-1, 1], (m, n))
+        a[:, ::16] = 6.0
+        a[::16, :] = 6.0
+        return a * 0.25
+    X, W, G = lossless(32, 48), lossless(16, 48), lossless(32, 16)
+    q = lambda a: lin.split_quantize(a, None, None, None, 1, 1, 1.0)
+    xq, wq, gq = q(X), q(W), q(G)
+    assert np.array_equal(lin.assemble(xq), X) and np.array_equal(lin.assemble(xq, True), X)
+    assert np.array_equal(lin.linear_fwd(xq, wq), X @ W.T)
+    assert np.array_equal(lin.linear_dgrad(gq, wq), G @ W)
+    assert np.array_equal(lin.linear_wgrad(gq, xq), G.T @ X)
+
+
+def test_residual_is_narrower_and_quantizes_with_less_error():
+    # the paper's premise (Sec. 2.2, 2.3): removing the dominant components narrows the
+    # distribution (residual one to two orders of magnitude narrower), so the long-tail
+    # part is quantized with far smaller absolute error than under direct quantization
+    rs = np.random.default_rng(5)
+    q_, _ = np.linalg.qr(rs.standard_normal((128, 64)))
+    p_, _ = np.linalg.qr(rs.standard_normal((256, 64)))
+    s = 100.0 * np.arange(1, 65) ** -2.0
+    A = (q_ * s) @ p_.T
+    U, S, V = dec.decompose(A, 8, 8, 1.0, seed=1)
+    R = dec.residual(A, U, S, V)
+    assert np.abs(R).max() < 0.1 * np.abs(A).max()
+    g = quant.tensor_scale_for(np.abs(A).max())
+    err_r = np.linalg.norm(quant.dequantize(*quant.quantize(R, g), g) - R)
+    err_a = np.linalg.norm(quant.dequantize(*quant.quantize(A, g), g) - A)
+    assert err_r < 0.2 * err_a

@@ -1,0 +1,176 @@
+"""Pins for oracle/quant.py: the paper's value table, a library decode of E4M3,
+an exact rational-arithmetic restatement of round(e/s)*s, ties, scale coverage."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+from oracle import quant
+
+
+def test_grid_matches_paper_table(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "e2m1_grid.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert [float(v) for _, v in rows] == list(quant.E2M1_GRID)
+    # E2M1 bit semantics: code = e(2 bits) m(1 bit), bias 1, subnormal at e = 0
+    for c in range(8):
+        e, m = c >> 1, c & 1
+        v = m * 0.5 if e == 0 else (1 + m / 2) * 2.0 ** (e - 1)
+        assert v == quant.E2M1_GRID[c]
+
+
+def test_e4m3_table_matches_library_decode():
+    ref = torch.arange(0, 127, dtype=torch.uint8).view(torch.float8_e4m3fn).double().numpy()
+    assert np.array_equal(ref, quant.E4M3_POS)
+    assert quant.E4M3_POS[126] == 448.0 and quant.E4M3_POS[1] == 2.0 ** -9
+    assert np.all(np.diff(quant.E4M3_POS) > 0)
+    assert np.count_nonzero(quant.E4M3_POS) == 126
+
+
+def _exact_quantize_block(block, g):
+    """round(e/s)*s with exact rationals: scale = smallest E4M3 covering amax/6,
+    nearest grid value, ties to the even code."""
+    fr = [Fraction(float(v)) for v in block]
+    amax = max(abs(v) for v in fr)
+    gq = Fraction(float(g))
+    sidx = 126
+    for i in range(127):
+        if 6 * Fraction(float(quant.E4M3_POS[i])) * gq >= amax:
+            sidx = i
+            break
+    step = Fraction(float(quant.E4M3_POS[sidx])) * gq
+    grid = [Fraction(float(v)) for v in quant.E2M1_GRID]
+    codes = []
+    for v in fr:
+        if step == 0:
+            codes.append(0)
+            continue
+        t = abs(v) / step
+        best = min(range(8), key=lambda c: (abs(t - grid[c]), c % 2))
+        codes.append(best)
+    return sidx, codes
+
+
+def _nibbles(codes):
+    n = np.empty((codes.shape[0], codes.shape[1] * 2), dtype=np.int64)
+    n[:, 0::2] = codes & 15
+    n[:, 1::2] = codes >> 4
+    return n
+
+
+def test_against_exact_rational_rounding_random():
+    rs = np.random.default_rng(1)
+    for g in (1.0, 2.0 ** -11, 2.0 ** 3):
+        x = rs.standard_normal((40, 32)) * np.exp(rs.uniform(-8, 8, (40, 1))) * g
+        x = x.astype(np.float32).astype(np.float64)
+        codes, scales = quant.quantize(x, g)
+        nib = _nibbles(codes)
+        for i in range(x.shape[0]):
+            for b in range(2):
+                sidx, mags = _exact_quantize_block(x[i, 16 * b:16 * b + 16], g)
+                assert scales[i, b] == sidx
+                assert list(nib[i, 16 * b:16 * b + 16] & 7) == mags
+        assert np.array_equal(nib >> 3, np.signbit(x).astype(np.int64))
+
+
+def test_against_exact_rational_all_scales_bf16_inputs():
+    # every E4M3 scale is exercised; inputs are bf16 values (what the path feeds)
+    rs = np.random.default_rng(2)
+    for sidx in range(1, 127):
+        s = quant.E4M3_POS[sidx]
+        blk = rs.uniform(-6.2, 6.2, 16) * s
+        blk[0] = 5.9 * s * rs.choice([-1, 1])       # pins the scale to >= this index region
+        blk = torch.from_numpy(blk).to(torch.bfloat16).double().numpy()
+        codes, scales = quant.quantize(blk[None, :])
+        ref_s, ref_c = _exact_quantize_block(blk, 1.0)
+        assert scales[0, 0] == ref_s
+        assert list(_nibbles(codes)[0] & 7) == ref_c
+
+
+def test_ties_go_to_even_code():
+    # with scale 1.0 (byte 0x38) and the block max at 6, midpoints map as RNE demands
+    blk = np.zeros(16)
+    blk[0] = 6.0
+    mids = [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]
+    blk[1:8] = mids
+    blk[8:15] = [-m for m in mids]
+    codes, scales = quant.quantize(blk[None, :])
+    assert scales[0, 0] == 0x38 and quant.E4M3_POS[0x38] == 1.0
+    d = quant.dequantize(codes, scales)[0]
+    assert list(d[1:8]) == [0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
+    assert list(d[8:15]) == [-0.0, -1.0, -1.0, -2.0, -2.0, -4.0, -4.0]
+    assert d[0] == 6.0
+    # just above / below a midpoint
+    blk[1:3] = [np.nextafter(0.25, 1), np.nextafter(0.75, 0)]
+    d = quant.dequantize(*quant.quantize(blk[None, :]))[0]
+    assert list(d[1:3]) == [0.5, 0.5]
+
+
+def test_scale_covers_block_max_and_is_minimal():
+    rs = np.random.default_rng(3)
+    x = (rs.standard_normal((64, 64)) * np.exp(rs.uniform(-6, 4, (64, 4)).repeat(16, axis=1)))
+    for g in (1.0, 0.25):
+        codes, scales = quant.quantize(x, g)
+        amax = np.abs(x.reshape(64, 4, 16)).max(axis=2)
+        s = quant.E4M3_POS[scales] * g
+        assert np.all(6 * s >= amax)
+        below = quant.E4M3_POS[np.maximum(scales.astype(int) - 1, 0)] * g
+        assert np.all((6 * below < amax) | (scales == 0))
+        # for normal-range scales the block max lands on +-6
+        d = quant.dequantize(codes, scales, g).reshape(64, 4, 16)
+        normal = scales >= 8
+        assert np.all(np.abs(d).max(axis=2)[normal] == 6 * s[normal])
+
+
+def test_error_bound_and_idempotence():
+    rs = np.random.default_rng(4)
+    x = rs.standard_normal((32, 128))
+    codes, scales = quant.quantize(x)
+    d = quant.dequantize(codes, scales)
+    s = np.repeat(quant.E4M3_POS[scales], 16, axis=1)
+    # widest grid gap is 2 (between 4 and 6): error <= 1 step everywhere, <= 0.25 step below 2
+    assert np.all(np.abs(x - d) <= 1.0 * s + 1e-15)
+    small = np.abs(x) <= 2 * s
+    assert np.all(np.abs(x - d)[small] <= 0.25 * s[small] + 1e-15)
+    c2, s2 = quant.quantize(d)
+    assert np.array_equal(c2, codes) and np.array_equal(s2, scales)
+
+
+def test_zero_block_saturation_and_signs():
+    blk = np.zeros((1, 32))
+    blk[0, 3] = -0.0
+    blk[0, 16:] = 1e9
+    blk[0, 17] = -1e9
+    codes, scales = quant.quantize(blk)
+    assert scales[0, 0] == 0 and scales[0, 1] == 126
+    nib = _nibbles(codes)[0]
+    assert nib[3] == 8 and np.all(np.delete(nib[:16], 3) == 0)
+    assert nib[16] == 7 and nib[17] == 15
+    d = quant.dequantize(codes, scales)
+    assert np.all(d[0, :16] == 0) and d[0, 16] == 6 * 448 and d[0, 17] == -6 * 448
+
+
+def test_tiny_values_flush_without_tensor_scale():
+    # paper-literal g = 1: a block below 6*2^-9 cannot be covered finer than 2^-9 steps
+    blk = np.full((1, 16), 2.0 ** -13)
+    d1 = quant.dequantize(*quant.quantize(blk, 1.0), 1.0)
+    assert np.all(d1 == 0)
+    g = 2.0 ** -11
+    d2 = quant.dequantize(*quant.quantize(blk, g), g)
+    # the scale is rounded up, so the block max maps to 6*s*g >= amax (within one E4M3 step)
+    assert np.all(d2 >= blk) and np.all(d2 <= blk * 1.125)
+
+
+def test_tensor_scale_for():
+    assert quant.tensor_scale_for(6 * 448.0) == 1.0
+    assert quant.tensor_scale_for(6 * 448.0 + 1) == 2.0
+    assert quant.tensor_scale_for(1.0) == 2.0 ** -11
+    assert quant.tensor_scale_for(0.0) == 1.0
+
+
+def test_packing_layout():
+    blk = np.zeros((1, 16))
+    blk[0, 0], blk[0, 1] = 6.0, -3.0       # codes 7 and 8|5
+    codes, _ = quant.quantize(blk)
+    assert codes[0, 0] == (7 | (13 << 4))
