@@ -1,0 +1,165 @@
+/*
+ * metis.h -- C ABI of the MI355X-native Metis hot path (spectral split + NVFP4
+ * quantization + FP4 GEMMs of one linear layer; Metis, arXiv 2509.00404).
+ *
+ * Conventions that hold for every entry point
+ *   - Every matrix pointer is DEVICE memory owned by the caller, row-major.
+ *     Scalars and the structs themselves are HOST memory, read before return.
+ *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it and
+ *     the call returns without synchronising.  Nothing is allocated or freed.
+ *   - Return value: METIS_OK (0) or a negative metis_status.  Argument and shape
+ *     errors are detected on the host before anything is enqueued.
+ *   - Layout of one linear layer (PyTorch convention): X[L,K] activations,
+ *     W[N,K] weight, Y = X W^T [L,N], G = dL/dY [L,N].  The paper's W (Sec. 3.2)
+ *     is the transpose of this W.
+ */
+#ifndef METIS_H
+#define METIS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    METIS_OK = 0,
+    METIS_INVALID_ARG = -1,      /* null pointer, k < 1, rho outside (0,1], unknown dtype */
+    METIS_BAD_SHAPE = -2,        /* quantized axis not a multiple of 16, k+p too large, mismatched operands */
+    METIS_WORKSPACE_TOO_SMALL = -3,
+    METIS_HIP_ERROR = -4,        /* a launch failed; hipGetLastError() has the reason */
+    METIS_UNSUPPORTED = -5       /* size outside what the kernels are built for (e.g. k+p > 128) */
+} metis_status;
+
+enum { METIS_BF16 = 0, METIS_F32 = 1 };
+
+/* Dense device matrix, row-major, leading dimension `ld` in elements. */
+typedef struct {
+    void*   ptr;
+    int64_t rows, cols, ld;
+    int     dtype;               /* METIS_BF16 or METIS_F32 */
+} metis_mat;
+
+/*
+ * NVFP4-quantized device matrix (Sec. 2.3; value set in App. C.1).
+ *   codes  [rows, cols/2]  two E2M1 codes per byte, low nibble = even column,
+ *                          nibble = sign<<3 | magnitude code (0..7 -> 0,.5,1,1.5,2,3,4,6)
+ *   scales [rows, cols/16] one FP8-E4M3 bit pattern (0x00..0x7E) per block of 16
+ *                          consecutive columns
+ *   tscale                 per-tensor power-of-two scale g; element value =
+ *                          grid[code] * e4m3(scale) * g.  g = 1 is the paper's text verbatim.
+ * Blocks always run along `cols` (the contiguous axis).  A matrix that must be
+ * blocked along its rows is stored transposed.
+ */
+typedef struct {
+    uint8_t* codes;
+    uint8_t* scales;
+    float    tscale;
+    int64_t  rows, cols;
+} metis_fp4;
+
+/*
+ * Split-quantized operand A[M,N] ~ U diag(S) V^T + R  (Sec. 3.2: Q_b is applied to
+ * U, V and R separately, S stays in high precision).
+ *   Ut  Q(U^T) [k,M]   each left singular vector contiguous, blocks along M
+ *   Vt  Q(V^T) [k,N]
+ *   R   Q(R)   [M,N]   blocks along N (for a GEMM contracting over A's columns)
+ *   Rt  Q(R^T) [N,M]   blocks along M (for a GEMM contracting over A's rows); may be
+ *                      all-null if the caller does not need that orientation
+ *   S   fp32 [k]
+ * k = 0: not split; R (and Rt) hold Q(A), Ut/Vt/S are ignored.
+ */
+typedef struct {
+    metis_fp4 Ut, Vt, R, Rt;
+    float*    S;
+    int       k;
+} metis_split;
+
+const char* metis_status_string(int status);
+int metis_version(void);
+
+/* ---- random draws of the decomposition (Sec. 3.1) ------------------------------------- */
+
+/* Number of sampled rows l_k = min(M, max(k+p, ceil(rho*M))). Host-only helper. */
+int64_t metis_sample_count(int64_t M, int k, int p, double rho);
+
+/*
+ * Row sample (Sec. 3.1, sparse random sampling): idx[Ms] (device, uint32), ascending,
+ * distinct, one row per stratum [floor(j*M/Ms), floor((j+1)*M/Ms)), offset = word j of
+ * Philox4x32-10 stream 1 under `seed`, modulo the stratum length.
+ */
+int metis_sample_rows(void* stream, uint64_t seed, int64_t M, int64_t Ms, uint32_t* idx);
+
+/*
+ * Gaussian test matrix (Sec. 3.1, random projection): omega[N,r] (device, bf16 bits as
+ * uint16, row-major).  Entry e = n*r+c: Box-Muller on words 2e, 2e+1 of Philox stream 2,
+ * u1 = ((w0>>9)+0.5)*2^-23, u2 = (w1>>8)*2^-24, z = sqrt(-2 ln u1) cos(2 pi u2), rounded
+ * to bf16 (nearest even).
+ */
+int metis_gaussian_omega(void* stream, uint64_t seed, int64_t N, int r, uint16_t* omega);
+
+/* ---- decomposition (Sec. 3.1 + the split of Sec. 3.2) ---------------------------------- */
+
+/* Bytes of device workspace metis_decompose needs for an M x N input. */
+size_t metis_decompose_workspace_bytes(int64_t M, int64_t N, int k, int p, double rho);
+
+/*
+ * A[M,N] (bf16) -> U[M,k], S[k], V[N,k] (all fp32, row-major, device) such that
+ * U diag(S) V^T = A V V^T, U^T U = V^T V = I, S descending; span(V) is the top-k right
+ * singular subspace of the sampled, sketched matrix:
+ *   sample l_k rows -> Z = A_s Omega -> thin QR (CholeskyQR2) Z = H R -> B = H^T A_s ->
+ *   top-k right singular vectors V0 of B -> broadcast C = A V0 over ALL rows ->
+ *   SVD of C = U S W^T, V = V0 W.
+ * No power iteration.  `amax_out` (device fp32[1], optional) receives max|A|.
+ * `idx` / `omega` (optional, device): explicit draws replacing the seeded ones (n_idx rows;
+ * omega is [N, k+p] bf16); pass NULL/0 to draw from `seed`.
+ * `info` (device int32[1], optional): set non-zero if a Cholesky pivot was not positive
+ * (rank-deficient sketch); the outputs are then unspecified.
+ * Errors: INVALID_ARG, BAD_SHAPE (k+p > min(l_k, N)), UNSUPPORTED (k+p > 128, dtype not
+ * bf16), WORKSPACE_TOO_SMALL.
+ */
+int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
+                    uint64_t seed, float* U, float* S, float* V, float* amax_out,
+                    void* workspace, size_t workspace_bytes,
+                    const uint32_t* idx, int64_t n_idx, const uint16_t* omega, int32_t* info);
+
+/* ---- quantization (Sec. 2.3) and split (Sec. 3.2) -------------------------------------- */
+
+/*
+ * Plain NVFP4 quantization of A[M,N] (bf16 or fp32): per block of 16 along the columns,
+ * scale = smallest E4M3 s with 6*s*g >= block amax (saturating at 448), codes = nearest
+ * E2M1 value of e/(s*g), ties to the even code.  `out` (blocks along N, may be NULL) and
+ * `out_t` (A^T [N,M], blocks along M, may be NULL) are filled from the same input; their
+ * tscale members are read as g.
+ */
+int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t);
+
+/*
+ * Split + quantize: R = A - U diag(S) V^T in fp32 (unquantized factors, Sec. 3.2), then
+ * Q(R) into out->R (and Q(R^T) into out->Rt when its codes pointer is non-null), Q(U^T)
+ * into out->Ut, Q(V^T) into out->Vt, S copied to out->S.  out->k must equal k.
+ * `R_debug` (device fp32 [M,N], optional) receives the exact quantizer input.
+ */
+int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S,
+                         const float* V, int k, metis_split* out, float* R_debug);
+
+/* ---- FP4 GEMMs on split operands (Eq. 2, Eq. 3, and the W_R gradient after Eq. 3) ------ */
+
+/* Bytes of device workspace the three GEMM calls need (max over them). */
+size_t metis_linear_workspace_bytes(int64_t L, int64_t N, int64_t K, int k);
+
+/* Y[L,N]  = Xbar Wbar^T   uses X.R [L,K], W.R [N,K]                       (Eq. 2) */
+int metis_fp4_linear_fwd(void* stream, const metis_split* X, const metis_split* W, metis_mat* Y,
+                         void* workspace, size_t workspace_bytes);
+/* dX[L,K] = Gbar Wbar     uses G.R [L,N], W.Rt [K,N]                      (Eq. 3) */
+int metis_fp4_linear_dgrad(void* stream, const metis_split* G, const metis_split* W, metis_mat* dX,
+                           void* workspace, size_t workspace_bytes);
+/* dW[N,K] = Gbar^T Xbar   uses G.Rt [N,L], X.Rt [K,L]   (dL/dW_R of Sec. 3.2, transposed) */
+int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const metis_split* X, metis_mat* dW,
+                           void* workspace, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* METIS_H */

@@ -1,0 +1,60 @@
+// Shared device/host helpers of the HIP path (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/metis.h"
+
+#define METIS_WAVE 64
+
+#define METIS_LAUNCH_CHECK()                                   \
+    do {                                                       \
+        if (hipGetLastError() != hipSuccess) return METIS_HIP_ERROR; \
+    } while (0)
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// low / high half of a dword holding two bf16
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fp32 -> bf16, round to nearest even (finite inputs)
+__device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), written from the published round function ----
+struct u32x4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        u32x4 n;
+        n.x = hi1 ^ c.y ^ k0;
+        n.y = lo1;
+        n.z = hi0 ^ c.w ^ k1;
+        n.w = lo0;
+        c = n;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c;
+}
+
+// word `w` of stream `t` under `seed`: lane w%4 of block w/4, counter (blk lo, blk hi, t, 0)
+__device__ __forceinline__ u32x4 philox_block(uint64_t seed, uint32_t stream, uint64_t blk) {
+    u32x4 c = {(uint32_t)blk, (uint32_t)(blk >> 32), stream, 0u};
+    return philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// ---- FP8 E4M3 (bias 7, no inf, max 448) for non-negative block scales ----
+__device__ __forceinline__ float e4m3_decode(uint32_t b) {
+    return b >= 8u ? __uint_as_float((b + (120u << 3)) << 20) : (float)b * 0.001953125f;
+}

@@ -1,0 +1,119 @@
+// Plain NVFP4 quantization of a dense matrix (Sec. 2.3), row orientation and/or transposed.
+#include "quant_dev.h"
+
+// ---- row orientation, bf16 input: one lane per block of 16, 32 contiguous bytes per lane ----
+__global__ void __launch_bounds__(256)
+k_quantize_rows_bf16(const bf16_t* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* N/16 */,
+                     QuantParams qp, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= M * nblk) return;
+    int64_t row = t / nblk, bc = t - row * nblk;
+    const uint4* src = reinterpret_cast<const uint4*>(A + row * ld + bc * 16);
+    uint4 a = src[0], b = src[1];
+    uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[2 * i] = bf16lo_to_f32(w[i]);
+        v[2 * i + 1] = bf16hi_to_f32(w[i]);
+    }
+    uint2 c;
+    uint32_t sc = quantize_block16(v, qp, c);
+    *reinterpret_cast<uint2*>(codes + t * 8) = c;     // codes are [M, N/2] contiguous: block t at byte 8t
+    scales[t] = (uint8_t)sc;
+}
+
+// ---- generic tile kernel: 64x64 tile through LDS, either orientation, bf16 or fp32 ----
+template <typename T> __device__ __forceinline__ float load_as_f32(const T* p);
+template <> __device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, QuantParams qp, QuantParams qpt,
+                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t) {
+    __shared__ float tile[64][65];
+    const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < 64 * 64; i += 256) {
+        int r = i >> 6, c = i & 63;
+        float v = 0.0f;
+        if (m0 + r < M && n0 + c < N) v = load_as_f32<T>(A + (m0 + r) * ld + n0 + c);
+        tile[r][c] = v;
+    }
+    __syncthreads();
+    const int line = tid >> 2, blk = tid & 3;      // 64 lines x 4 blocks of 16
+    if (codes) {
+        int64_t m = m0 + line, n = n0 + blk * 16;
+        if (m < M && n < N) {
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = tile[line][blk * 16 + i];
+            uint2 c;
+            uint32_t sc = quantize_block16(v, qp, c);
+            *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
+            scales[m * (N / 16) + n / 16] = (uint8_t)sc;
+        }
+    }
+    if (codes_t) {
+        int64_t n = n0 + line, m = m0 + blk * 16;
+        if (n < N && m < M) {
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = tile[blk * 16 + i][line];
+            uint2 c;
+            uint32_t sc = quantize_block16(v, qpt, c);
+            *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
+            scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
+        }
+    }
+}
+
+static bool pow2(float g) {
+    if (!(g > 0.0f)) return false;
+    uint32_t u;
+    __builtin_memcpy(&u, &g, 4);
+    return (u & 0x7FFFFFu) == 0 && (u >> 23) != 0 && (u >> 23) != 255;
+}
+
+extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t) {
+    if (!A || !A->ptr || (!out && !out_t)) return METIS_INVALID_ARG;
+    if (A->dtype != METIS_BF16 && A->dtype != METIS_F32) return METIS_INVALID_ARG;
+    const int64_t M = A->rows, N = A->cols;
+    if (M < 1 || N < 1 || A->ld < N) return METIS_BAD_SHAPE;
+    if (out) {
+        if (!out->codes || !out->scales || !pow2(out->tscale)) return METIS_INVALID_ARG;
+        if (out->rows != M || out->cols != N || N % 16) return METIS_BAD_SHAPE;
+    }
+    if (out_t) {
+        if (!out_t->codes || !out_t->scales || !pow2(out_t->tscale)) return METIS_INVALID_ARG;
+        if (out_t->rows != N || out_t->cols != M || M % 16) return METIS_BAD_SHAPE;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const bool vec_ok = A->dtype == METIS_BF16 && !out_t && (A->ld % 8 == 0) &&
+                        (reinterpret_cast<uintptr_t>(A->ptr) % 16 == 0);
+    if (vec_ok) {
+        int64_t nb = M * (N / 16);
+        hipLaunchKernelGGL(k_quantize_rows_bf16, dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
+                           (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale),
+                           out->codes, out->scales);
+        METIS_LAUNCH_CHECK();
+        return METIS_OK;
+    }
+    dim3 grid((unsigned)ceil_div64(N, 64), (unsigned)ceil_div64(M, 64));
+    QuantParams qp = make_quant_params(out ? out->tscale : 1.0f);
+    QuantParams qpt = make_quant_params(out_t ? out_t->tscale : 1.0f);
+    uint8_t* c = out ? out->codes : nullptr;
+    uint8_t* sc = out ? out->scales : nullptr;
+    uint8_t* ct = out_t ? out_t->codes : nullptr;
+    uint8_t* sct = out_t ? out_t->scales : nullptr;
+    if (A->dtype == METIS_BF16)
+        hipLaunchKernelGGL(k_quantize_tile<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)A->ptr, A->ld, M, N,
+                           qp, qpt, c, sc, ct, sct);
+    else
+        hipLaunchKernelGGL(k_quantize_tile<float>, grid, dim3(256), 0, s, (const float*)A->ptr, A->ld, M, N,
+                           qp, qpt, c, sc, ct, sct);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}

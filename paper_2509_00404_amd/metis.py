@@ -1,0 +1,205 @@
+"""ctypes binding of libmetis_hip.so (declared in include/metis.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the path runs in the library's kernels.  There is no CPU
+fallback: a missing library or a non-zero status raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmetis_hip.so")
+
+BF16, F32 = 0, 1
+
+
+class Mat(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("dtype", C.c_int)]
+
+
+class Fp4(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scales", C.c_void_p), ("tscale", C.c_float),
+                ("rows", C.c_int64), ("cols", C.c_int64)]
+
+
+class Split(C.Structure):
+    _fields_ = [("Ut", Fp4), ("Vt", Fp4), ("R", Fp4), ("Rt", Fp4), ("S", C.c_void_p), ("k", C.c_int)]
+
+
+class MetisError(RuntimeError):
+    pass
+
+
+_lib = None
+
+_SIGNATURES = {
+    "metis_status_string": (C.c_char_p, [C.c_int]),
+    "metis_version": (C.c_int, []),
+    "metis_sample_count": (C.c_int64, [C.c_int64, C.c_int, C.c_int, C.c_double]),
+    "metis_sample_rows": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int64, C.c_void_p]),
+    "metis_gaussian_omega": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int, C.c_void_p]),
+    "metis_decompose_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double]),
+    "metis_decompose": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_int, C.c_int, C.c_double, C.c_uint64,
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                  C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
+    "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_int, C.POINTER(Split), C.c_void_p]),
+    "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
+    "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
+                                       C.c_void_p, C.c_size_t]),
+    "metis_fp4_linear_dgrad": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
+                                         C.c_void_p, C.c_size_t]),
+    "metis_fp4_linear_wgrad": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
+                                         C.c_void_p, C.c_size_t]),
+}
+
+
+def exported_symbols():
+    """Names include/metis.h declares (the library must export every one)."""
+    return sorted(_SIGNATURES)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MetisError(f"{LIB_PATH} is not built; run: python -c 'import __graft_entry__ as g; g.build()'")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)          # AttributeError if the symbol is missing: fail loudly
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise MetisError(f"metis status {status}: {lib().metis_status_string(status).decode()}")
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _mat(t):
+    assert t.is_cuda and t.dim() == 2 and t.stride(1) == 1
+    dt = {torch.bfloat16: BF16, torch.float32: F32}[t.dtype]
+    return Mat(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dt)
+
+
+class Fp4Tensor:
+    """Device NVFP4 matrix: codes [rows, cols/2] u8, scales [rows, cols/16] u8, tscale."""
+
+    def __init__(self, rows, cols, tscale, device="cuda"):
+        self.rows, self.cols, self.tscale = rows, cols, float(tscale)
+        self.codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=device)
+        self.scales = torch.empty((rows, cols // 16), dtype=torch.uint8, device=device)
+
+    def c(self):
+        return Fp4(self.codes.data_ptr(), self.scales.data_ptr(), self.tscale, self.rows, self.cols)
+
+
+def _null_fp4():
+    return Fp4(None, None, 1.0, 0, 0)
+
+
+class SplitTensor:
+    """Device split-quantized operand of A[M,N] (see metis_split in include/metis.h)."""
+
+    def __init__(self, M, N, k, g_u, g_v, g_r, want_t=True, device="cuda"):
+        self.M, self.N, self.k = M, N, k
+        self.Ut = Fp4Tensor(k, M, g_u, device) if k else None
+        self.Vt = Fp4Tensor(k, N, g_v, device) if k else None
+        self.R = Fp4Tensor(M, N, g_r, device)
+        self.Rt = Fp4Tensor(N, M, g_r, device) if want_t else None
+        self.S = torch.empty((max(k, 1),), dtype=torch.float32, device=device)
+
+    def c(self):
+        return Split(self.Ut.c() if self.Ut else _null_fp4(), self.Vt.c() if self.Vt else _null_fp4(),
+                     self.R.c(), self.Rt.c() if self.Rt else _null_fp4(), self.S.data_ptr(), self.k)
+
+
+def sample_count(M, k, p, rho):
+    return int(lib().metis_sample_count(M, k, p, rho))
+
+
+def sample_rows(seed, M, Ms, device="cuda"):
+    idx = torch.empty((Ms,), dtype=torch.int32, device=device)      # uint32 bits
+    _check(lib().metis_sample_rows(_stream(), seed, M, Ms, idx.data_ptr()))
+    return idx
+
+
+def gaussian_omega(seed, N, r, device="cuda"):
+    om = torch.empty((N, r), dtype=torch.bfloat16, device=device)
+    _check(lib().metis_gaussian_omega(_stream(), seed, N, r, om.data_ptr()))
+    return om
+
+
+def decompose_workspace_bytes(M, N, k, p, rho):
+    return int(lib().metis_decompose_workspace_bytes(M, N, k, p, rho))
+
+
+def decompose(A, k, oversample, sample_rate, seed, idx=None, omega=None, workspace=None,
+              out=None, want_amax=False, info=None):
+    """A[M,N] bf16 cuda -> (U[M,k], S[k], V[N,k]) fp32 (+ amax tensor when asked)."""
+    M, N = A.shape
+    if out is None:
+        U = torch.empty((M, k), dtype=torch.float32, device=A.device)
+        S = torch.empty((k,), dtype=torch.float32, device=A.device)
+        V = torch.empty((N, k), dtype=torch.float32, device=A.device)
+    else:
+        U, S, V = out
+    if workspace is None:
+        nbytes = decompose_workspace_bytes(M, N, k, oversample, sample_rate)
+        workspace = torch.empty((nbytes,), dtype=torch.uint8, device=A.device)
+    amax = torch.empty((1,), dtype=torch.float32, device=A.device) if want_amax else None
+    a = _mat(A)
+    _check(lib().metis_decompose(
+        _stream(), C.byref(a), k, oversample, sample_rate, seed, U.data_ptr(), S.data_ptr(), V.data_ptr(),
+        amax.data_ptr() if want_amax else None, workspace.data_ptr(), workspace.numel(),
+        idx.data_ptr() if idx is not None else None, idx.numel() if idx is not None else 0,
+        omega.data_ptr() if omega is not None else None, info.data_ptr() if info is not None else None))
+    return (U, S, V, amax) if want_amax else (U, S, V)
+
+
+def quantize(A, out=None, out_t=None):
+    """Plain NVFP4 quantization into out (blocks along cols) and/or out_t (A^T)."""
+    a = _mat(A)
+    o = out.c() if out is not None else None
+    ot = out_t.c() if out_t is not None else None
+    _check(lib().metis_quantize(_stream(), C.byref(a), C.byref(o) if o else None, C.byref(ot) if ot else None))
+
+
+def split_quantize(A, U, S, V, out, R_debug=None):
+    a = _mat(A)
+    s = out.c()
+    _check(lib().metis_split_quantize(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
+                                      out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None))
+
+
+def linear_workspace_bytes(L, N, K, k):
+    return int(lib().metis_linear_workspace_bytes(L, N, K, k))
+
+
+def _linear(fn, a, b, out, workspace):
+    sa, sb, o = a.c(), b.c(), _mat(out)
+    _check(fn(_stream(), C.byref(sa), C.byref(sb), C.byref(o),
+              workspace.data_ptr() if workspace is not None else None,
+              workspace.numel() if workspace is not None else 0))
+    return out
+
+
+def fp4_linear_fwd(X, W, Y, workspace):
+    return _linear(lib().metis_fp4_linear_fwd, X, W, Y, workspace)
+
+
+def fp4_linear_dgrad(G, W, dX, workspace):
+    return _linear(lib().metis_fp4_linear_dgrad, G, W, dX, workspace)
+
+
+def fp4_linear_wgrad(G, X, dW, workspace):
+    return _linear(lib().metis_fp4_linear_wgrad, G, X, dW, workspace)
