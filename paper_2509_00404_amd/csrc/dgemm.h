@@ -1,0 +1,126 @@
+// Small fp64 GEMM on the f64 matrix cores (v_mfma_f64_16x16x4_f64), used for the
+// sample-stage contractions of the decomposition (Sec. 3.1), whose conditioning needs
+// fp64 accumulation.  C[m,n] (+)= sum_k A(m,k) B(n,k) with freely strided / gathered
+// operands of type bf16, fp32 or fp64; several epilogues.
+#pragma once
+#include "common.h"
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+struct DOperand {
+    const void* p;
+    int64_t s_outer;             // element stride between consecutive m (resp. n)
+    int64_t s_k;                 // element stride between consecutive k
+    const uint32_t* map_outer;   // optional gather on the outer index
+    const uint32_t* map_k;       // optional gather on the contraction index
+};
+
+enum { EPI_STORE_F64 = 0, EPI_ATOMIC_F64 = 1, EPI_STORE_F32 = 2, EPI_STORE_SPLIT_T = 3 };
+
+struct DEpilogue {
+    void* c;                     // F64 / F32 output, element (m,n) at c[m*ldc + n]
+    int64_t ldc;
+    bf16_t* hi_t;                // SPLIT_T: bf16 hi/lo parts stored transposed, (m,n) at [n*ld_t + m]
+    bf16_t* lo_t;
+    int64_t ld_t;
+};
+
+template <typename T> __device__ __forceinline__ double dload(const void* p, int64_t off);
+template <> __device__ __forceinline__ double dload<bf16_t>(const void* p, int64_t off) {
+    return (double)bf16_to_f32(((const bf16_t*)p)[off]);
+}
+template <> __device__ __forceinline__ double dload<float>(const void* p, int64_t off) {
+    return (double)((const float*)p)[off];
+}
+template <> __device__ __forceinline__ double dload<double>(const void* p, int64_t off) {
+    return ((const double*)p)[off];
+}
+
+#define DG_BM 32
+#define DG_BN 32
+#define DG_BK 32
+#define DG_PAD 2
+
+// grid: (ceil(N/32), ceil(M/32), ksplit); block 256 (4 waves, each a 16x16 sub-tile)
+template <typename TA, typename TB, int EPI>
+__global__ void __launch_bounds__(256)
+k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
+    __shared__ double As[DG_BK][DG_BM + DG_PAD];
+    __shared__ double Bs[DG_BK][DG_BN + DG_PAD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t m0 = (int64_t)blockIdx.y * DG_BM, n0 = (int64_t)blockIdx.x * DG_BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
+    const int64_t kend = kbeg + kchunk < K ? kbeg + kchunk : K;
+    const int wm = (wave >> 1) * 16, wn = (wave & 1) * 16;
+    double4_t acc = {0.0, 0.0, 0.0, 0.0};
+    const bool a_kfast = A.s_k == 1 && !A.map_k, b_kfast = B.s_k == 1 && !B.map_k;
+
+    for (int64_t kt = kbeg; kt < kend; kt += DG_BK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int e = tid + 256 * i;
+            {
+                int mm = a_kfast ? e >> 5 : e & 31, kk = a_kfast ? e & 31 : e >> 5;
+                int64_t m = m0 + mm, k = kt + kk;
+                double v = 0.0;
+                if (m < M && k < kend) {
+                    int64_t mo = A.map_outer ? (int64_t)A.map_outer[m] : m;
+                    int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
+                    v = dload<TA>(A.p, mo * A.s_outer + ko * A.s_k);
+                }
+                As[kk][mm] = v;
+            }
+            {
+                int nn = b_kfast ? e >> 5 : e & 31, kk = b_kfast ? e & 31 : e >> 5;
+                int64_t n = n0 + nn, k = kt + kk;
+                double v = 0.0;
+                if (n < N && k < kend) {
+                    int64_t no = B.map_outer ? (int64_t)B.map_outer[n] : n;
+                    int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
+                    v = dload<TB>(B.p, no * B.s_outer + ko * B.s_k);
+                }
+                Bs[kk][nn] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < DG_BK / 4; ++s) {
+            double a = As[4 * s + (lane >> 4)][wm + (lane & 15)];
+            double b = Bs[4 * s + (lane >> 4)][wn + (lane & 15)];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // D layout of the 16x16x4 f64 instruction: lane l, element v -> row 4*v + l/16, column l%16
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        int64_t m = m0 + wm + 4 * v + (lane >> 4), n = n0 + wn + (lane & 15);
+        if (m >= M || n >= N) continue;
+        double x = acc[v];
+        if (EPI == EPI_STORE_F64) {
+            ((double*)ep.c)[m * ep.ldc + n] = x;
+        } else if (EPI == EPI_ATOMIC_F64) {
+            unsafeAtomicAdd(&((double*)ep.c)[m * ep.ldc + n], x);
+        } else if (EPI == EPI_STORE_F32) {
+            ((float*)ep.c)[m * ep.ldc + n] = (float)x;
+        } else {
+            float f = (float)x;
+            bf16_t hi = f32_to_bf16_rne(f);
+            float rem = f - bf16_to_f32(hi);
+            bf16_t lo = f32_to_bf16_rne(rem);
+            ep.hi_t[n * ep.ld_t + m] = hi;
+            ep.lo_t[n * ep.ld_t + m] = lo;
+            ((float*)ep.c)[m * ep.ldc + n] = bf16_to_f32(hi) + bf16_to_f32(lo);
+        }
+    }
+}
+
+template <typename TA, typename TB, int EPI>
+static inline void launch_dgemm(hipStream_t s, DOperand A, DOperand B, int64_t M, int64_t N, int64_t K,
+                                int ksplit, DEpilogue ep) {
+    if (ksplit < 1) ksplit = 1;
+    int64_t kchunk = ceil_div64(ceil_div64(K, ksplit), DG_BK) * DG_BK;
+    ksplit = (int)ceil_div64(K, kchunk);
+    dim3 grid((unsigned)ceil_div64(N, DG_BN), (unsigned)ceil_div64(M, DG_BM), (unsigned)ksplit);
+    hipLaunchKernelGGL((k_dgemm<TA, TB, EPI>), grid, dim3(256), 0, s, A, B, M, N, K, kchunk, ep);
+}

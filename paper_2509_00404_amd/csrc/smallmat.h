@@ -1,0 +1,8 @@
+// One-workgroup fp64 factorizations (see smallmat.hip).
+#pragma once
+#include "common.h"
+#define SM_MAX_N 128          // Jacobi: largest matrix order
+#define SM_MAX_CHOL 96        // Cholesky + inverse: two n x (n+1) fp64 arrays must fit in 160 KB of LDS
+int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info);
+int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
+                      float* sval);

@@ -1,8 +1,5 @@
 // Entry points not implemented yet: they refuse loudly instead of computing anything.
 #include "common.h"
-extern "C" size_t metis_decompose_workspace_bytes(int64_t, int64_t, int, int, double) { return 0; }
-extern "C" int metis_decompose(void*, const metis_mat*, int, int, double, uint64_t, float*, float*, float*, float*,
-                               void*, size_t, const uint32_t*, int64_t, const uint16_t*, int32_t*) { return METIS_UNSUPPORTED; }
 extern "C" int metis_split_quantize(void*, const metis_mat*, const float*, const float*, const float*, int,
                                     metis_split*, float*) { return METIS_UNSUPPORTED; }
 extern "C" size_t metis_linear_workspace_bytes(int64_t, int64_t, int64_t, int) { return 0; }

@@ -1,0 +1,140 @@
+"""GPU parity: metis_decompose against the fp64 oracle on identical seeded inputs.
+
+Tolerances (from the benchmark spec): top-k singular values within 1e-3 relative,
+largest principal angle of span(V) (and span(U)) below 1e-2 rad."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decompose as odec
+from oracle import rng as orng
+
+pytestmark = pytest.mark.gpu
+
+SIGMA_RTOL = 1e-3
+ANGLE_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def metis():
+    from paper_2509_00404_amd import metis as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _planted_bf16(M, N, s, seed):
+    from paper_2509_00404_amd import workloads
+    return workloads.planted(M, N, s, seed)
+
+
+def _run(metis, A, k, p, rho, seed, explicit=False):
+    Ad = A.cuda()
+    M, N = A.shape
+    kw = {}
+    if explicit:
+        Ms = orng.sample_count(M, k, p, rho)
+        idx = orng.sample_rows(seed, M, Ms)
+        om = orng.gaussian_omega(seed, N, k + p)
+        kw["idx"] = torch.from_numpy(idx.astype(np.int32)).cuda()
+        kw["omega"] = torch.from_numpy(om).to(torch.bfloat16).cuda()
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    U, S, V, amax = metis.decompose(Ad, k, p, rho, seed, want_amax=True, info=info, **kw)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    return (U.double().cpu().numpy(), S.double().cpu().numpy(), V.double().cpu().numpy(), float(amax.item()))
+
+
+def _compare(A, got, ref, k, check_u=True):
+    U, S, V, amax = got
+    Ur, Sr, Vr = ref
+    An = A.double().numpy()
+    assert amax == float(A.abs().max())
+    # invariants of the split (Sec. 3.2) at fp32 accuracy
+    I = np.eye(k)
+    assert np.abs(U.T @ U - I).max() < 1e-4
+    assert np.abs(V.T @ V - I).max() < 1e-4
+    assert np.all(np.diff(S) <= 1e-6 * S[0])
+    assert np.allclose(np.linalg.norm(An @ V, axis=0), S, rtol=1e-4)
+    # parity with the oracle
+    assert np.max(np.abs(S - Sr) / Sr) < SIGMA_RTOL
+    assert odec.principal_angle(V, Vr) < ANGLE_TOL
+    if check_u:
+        assert odec.principal_angle(U, Ur) < ANGLE_TOL
+    # projector: U S V^T = A V V^T on both sides
+    P = (U * S) @ V.T
+    Pr = (Ur * Sr) @ Vr.T
+    assert np.linalg.norm(P - Pr) / np.linalg.norm(An) < 1e-3
+
+
+@pytest.mark.parametrize("explicit", [False, True])
+def test_config1_tiny_planted(metis, explicit):
+    from paper_2509_00404_amd import workloads
+    A = workloads.tiny_planted(workloads.seed_for(1, 0))
+    seed = workloads.seed_for(1, 0) + 7
+    got = _run(metis, A, 8, 8, 0.25, seed, explicit)
+    ref = odec.decompose(A.double().numpy(), 8, 8, 0.25, seed)
+    _compare(A, got, ref, 8)
+
+
+@pytest.mark.parametrize("M,N,k,p,rho", [(200, 96, 12, 4, 0.5), (333, 264, 5, 3, 0.1), (1000, 520, 33, 7, 0.25),
+                                         (96, 1024, 16, 16, 1.0)])
+def test_ragged_shapes(metis, M, N, k, p, rho):
+    q = min(M, N)
+    s = 50.0 * np.arange(1, q + 1) ** -1.3 + 0.02
+    A = _planted_bf16(M, N, s, seed=M + N)
+    got = _run(metis, A, k, p, rho, seed=99)
+    ref = odec.decompose(A.double().numpy(), k, p, rho, seed=99)
+    _compare(A, got, ref, k)
+
+
+def test_medium_llama_like(metis):
+    from paper_2509_00404_amd import workloads
+    A = workloads.planted(2048, 1024, workloads.power_law(512, 1.2), 5, rms=1.0, outlier_cols=1)
+    got = _run(metis, A, 64, 16, 1 / 8, seed=1234)
+    ref = odec.decompose(A.double().numpy(), 64, 16, 1 / 8, seed=1234)
+    _compare(A, got, ref, 64)
+
+
+def test_steep_gradient_like_spectrum(metis):
+    from paper_2509_00404_amd import workloads
+    A = workloads.planted(2048, 1024, workloads.power_law(512, 2.0, head=4, head_gain=100.0), 6, rms=1e-3)
+    got = _run(metis, A, 64, 16, 1 / 8, seed=4321)
+    ref = odec.decompose(A.double().numpy(), 64, 16, 1 / 8, seed=4321)
+    U, S, V, _ = got
+    Ur, Sr, Vr = ref
+    assert np.max(np.abs(S - Sr) / Sr) < SIGMA_RTOL
+    assert odec.principal_angle(V, Vr) < ANGLE_TOL
+
+
+def test_exact_low_rank_is_recovered(metis):
+    s = np.array([40.0, 10.0, 5.0, 2.0, 1.0, 0.5])
+    A = _planted_bf16(512, 256, s, seed=3)          # bf16 rounding adds a ~2^-9 relative floor
+    U, S, V, _ = _run(metis, A, 8, 8, 0.25, seed=5)
+    sv = np.linalg.svd(A.double().numpy(), compute_uv=False)
+    assert np.allclose(S[:6], sv[:6], rtol=1e-3)
+    R = A.double().numpy() - (U * S) @ V.T
+    assert np.linalg.norm(R) <= 1.05 * np.sqrt((sv[8:] ** 2).sum()) + 1e-3 * sv[6]
+
+
+def test_argument_errors(metis):
+    A = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(metis.MetisError):
+        metis.decompose(A, 0, 4, 1.0, 1)
+    with pytest.raises(metis.MetisError):
+        metis.decompose(A, 8, 4, 1.5, 1)
+    with pytest.raises(metis.MetisError):
+        metis.decompose(A, 60, 16, 1.0, 1)                        # k+p > min(l_k, N)
+    with pytest.raises(metis.MetisError):
+        metis.decompose(A, 8, 4, 1.0, 1, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(metis.MetisError):
+        metis.decompose(A.float(), 8, 4, 1.0, 1) if False else metis.decompose(
+            torch.zeros((64, 60), dtype=torch.bfloat16, device="cuda"), 8, 4, 1.0, 1)   # N % 8 != 0
+
+
+def test_rank_deficient_sketch_sets_info(metis):
+    A = torch.zeros((128, 64), dtype=torch.bfloat16, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    metis.decompose(A, 4, 4, 1.0, 1, info=info)
+    torch.cuda.synchronize()
+    assert int(info.item()) != 0
