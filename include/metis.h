@@ -140,9 +140,14 @@ int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* 
  * Q(R) into out->R (and Q(R^T) into out->Rt when its codes pointer is non-null), Q(U^T)
  * into out->Ut, Q(V^T) into out->Vt, S copied to out->S.  out->k must equal k.
  * `R_debug` (device fp32 [M,N], optional) receives the exact quantizer input.
+ * `workspace`: metis_split_workspace_bytes(M, N, k) bytes of device scratch.
+ * Errors: INVALID_ARG, BAD_SHAPE (N % 16, or M % 16 when Rt is requested, mismatched out),
+ * UNSUPPORTED (A not bf16, k > 128), WORKSPACE_TOO_SMALL.
  */
+size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k);
 int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S,
-                         const float* V, int k, metis_split* out, float* R_debug);
+                         const float* V, int k, metis_split* out, float* R_debug,
+                         void* workspace, size_t workspace_bytes);
 
 /* ---- FP4 GEMMs on split operands (Eq. 2, Eq. 3, and the W_R gradient after Eq. 3) ------ */
 

@@ -1,0 +1,383 @@
+// FP4 GEMMs on split operands (Sec. 3.2: Eq. 2 fprop, Eq. 3 dgrad, dL/dW_R wgrad).
+//
+// One NT kernel serves all three: C[M,N] = alpha * deq(A)[M,K] deq(B)[N,K]^T + Aext Bext^T.
+// NVFP4 (block 16, E4M3 scale) is not an MX format, so the scaled-MFMA path cannot apply
+// the block scales; codes are expanded in registers to fp16 (grid * e4m3 has at most 6
+// significant bits: exact) and multiplied on the fp16 matrix cores with fp32 accumulation.
+// The low-rank terms of the split enter as extra contraction columns (bf16, same
+// accumulators):  Abar Bbar^T = Ra Rb^T + [(Ra Vb + Ua Sa Va^T Vb) Sb] Ub^T + (Ua Sa)(Rb Va)^T.
+#include "common.h"
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+namespace {
+
+#define G_KI 128                    // contraction elements per LDS stage
+#define G_CROW (G_KI / 2 + 4)       // padded code row in LDS (bytes): dword stride 17
+#define G_SROW 16                   // 8 fp16 block scales per row and stage
+
+struct Fp4Operand {
+    const uint8_t* codes;           // [rows, K/2]
+    const uint8_t* scales;          // [rows, K/16]
+    int64_t rows;
+};
+
+__device__ __forceinline__ uint16_t e4m3_to_f16_bits(uint32_t b) {
+    // normal: exponent rebias 7 -> 15, mantissa left-aligned; subnormal b*2^-9 is a normal fp16
+    if (b >= 8u) return (uint16_t)((b << 7) + 0x2000u);
+    _Float16 h = (_Float16)((float)b * 0.001953125f);
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// Stage `rows` rows of codes/scales for contraction range [k0, k0+128) into LDS.
+template <int ROWS, bool VEC>
+__device__ __forceinline__ void stage_operand(const Fp4Operand& op, int64_t r0, int64_t K, int64_t k0,
+                                              uint8_t* __restrict__ lc, uint16_t* __restrict__ ls, int tid) {
+    const int64_t cstride = K / 2, sstride = K / 16;
+    for (int e = tid; e < ROWS * 4; e += 256) {
+        int row = e >> 2, seg = e & 3;
+        int64_t gr = r0 + row;
+        if (gr >= op.rows) gr = op.rows - 1;
+        const uint8_t* src = op.codes + gr * cstride + k0 / 2 + 16 * seg;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (VEC) {
+            v = *reinterpret_cast<const uint4*>(src);
+        } else {
+            uint32_t w[4] = {0, 0, 0, 0};
+            for (int b = 0; b < 16; ++b) {
+                int64_t kb = k0 / 2 + 16 * seg + b;
+                if (kb < cstride) w[b >> 2] |= (uint32_t)src[b] << (8 * (b & 3));
+            }
+            v = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    for (int e = tid; e < ROWS; e += 256) {
+        int64_t gr = r0 + e;
+        if (gr >= op.rows) gr = op.rows - 1;
+        const uint8_t* src = op.scales + gr * sstride + k0 / 16;
+        uint32_t b[8];
+        if (VEC) {
+            uint2 v = *reinterpret_cast<const uint2*>(src);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { b[i] = (v.x >> (8 * i)) & 0xFFu; b[4 + i] = (v.y >> (8 * i)) & 0xFFu; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) b[i] = (k0 / 16 + i < sstride) ? src[i] : 0u;
+        }
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)e4m3_to_f16_bits(b[2 * i]) | ((uint32_t)e4m3_to_f16_bits(b[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(ls + e * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// 8 codes (one dword) times one fp16 block scale -> 8 fp16
+__device__ __forceinline__ half8_t dequant8(uint32_t cw, uint16_t sbits) {
+    _Float16 s = __builtin_bit_cast(_Float16, sbits);
+    half2_t s2 = {s, s};
+    half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0) * s2;
+    half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1) * s2;
+    half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2) * s2;
+    half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 3) * s2;
+    half8_t r = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+    return r;
+}
+
+union BFrag {
+    uint4 u;
+    bf16x8_t v;
+};
+
+template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
+template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16_rne(v); }
+
+// grid: (ceil(N / (64*TN)), ceil(M / (64*TM))); block 256 = 2x2 waves, each wave TM x TN tiles of 32x32.
+template <int TM, int TN, bool VEC, typename OUT>
+__global__ void __launch_bounds__(256)
+k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
+              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    __shared__ __attribute__((aligned(16))) uint8_t lcA[2][BM * G_CROW];
+    __shared__ __attribute__((aligned(16))) uint8_t lcB[2][BN * G_CROW];
+    __shared__ __attribute__((aligned(16))) uint16_t lsA[2][BM * 8];
+    __shared__ __attribute__((aligned(16))) uint16_t lsB[2][BN * 8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    const int li = lane & 31, half = lane >> 5;
+
+    float16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int64_t niter = (K + G_KI - 1) / G_KI;
+    stage_operand<BM, VEC>(A, m0, K, 0, lcA[0], lsA[0], tid);
+    stage_operand<BN, VEC>(B, n0, K, 0, lcB[0], lsB[0], tid);
+    __syncthreads();
+    for (int64_t it = 0; it < niter; ++it) {
+        const int cur = (int)(it & 1);
+        if (it + 1 < niter) {
+            stage_operand<BM, VEC>(A, m0, K, (it + 1) * G_KI, lcA[cur ^ 1], lsA[cur ^ 1], tid);
+            stage_operand<BN, VEC>(B, n0, K, (it + 1) * G_KI, lcB[cur ^ 1], lsB[cur ^ 1], tid);
+        }
+        uint4 sa[TM], sb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint4*>(&lsA[cur][(wm + 32 * i + li) * 8]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint4*>(&lsB[cur][(wn + 32 * j + li) * 8]);
+#pragma unroll
+        for (int s = 0; s < G_KI / 16; ++s) {
+            half8_t fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                uint32_t cw = *reinterpret_cast<const uint32_t*>(&lcA[cur][(wm + 32 * i + li) * G_CROW + 8 * s + 4 * half]);
+                uint32_t sw = (&sa[i].x)[s >> 1];
+                fa[i] = dequant8(cw, (uint16_t)((s & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                uint32_t cw = *reinterpret_cast<const uint32_t*>(&lcB[cur][(wn + 32 * j + li) * G_CROW + 8 * s + 4 * half]);
+                uint32_t sw = (&sb[j].x)[s >> 1];
+                fb[j] = dequant8(cw, (uint16_t)((s & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // low-rank terms: extra contraction columns in bf16, read straight from global memory
+    if (Ke > 0) {
+        for (int ks = 0; ks < Ke; ks += 16) {
+            BFrag fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                int64_t r = m0 + wm + 32 * i + li;
+                if (r >= A.rows) r = A.rows - 1;
+                fa[i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + ks + 8 * half);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int64_t r = n0 + wn + 32 * j + li;
+                if (r >= B.rows) r = B.rows - 1;
+                fb[j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + ks + 8 * half);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+        }
+    }
+    // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int64_t c = n0 + wn + 32 * j + li;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int64_t r = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+            }
+        }
+}
+
+template <typename OUT>
+int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf16_t* Aext, const bf16_t* Bext, int Ke,
+                float alpha, OUT* C, int64_t ldc) {
+    const int64_t M = A.rows, N = B.rows, K = A.cols;
+    Fp4Operand a = {A.codes, A.scales, M}, b = {B.codes, B.scales, N};
+    const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
+                     reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
+    if (N > 64 && M > 64) {
+        dim3 grid((unsigned)ceil_div64(N, 128), (unsigned)ceil_div64(M, 128));
+        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<2, 2, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+        else hipLaunchKernelGGL((k_fp4_gemm_nt<2, 2, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+    } else if (N <= 64) {
+        dim3 grid((unsigned)ceil_div64(N, 64), (unsigned)ceil_div64(M, 128));
+        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<2, 1, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+        else hipLaunchKernelGGL((k_fp4_gemm_nt<2, 1, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+    } else {
+        dim3 grid((unsigned)ceil_div64(N, 128), (unsigned)ceil_div64(M, 64));
+        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<1, 2, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+        else hipLaunchKernelGGL((k_fp4_gemm_nt<1, 2, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+    }
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+// value of one FP4 element without the tensor scale: grid[code] * e4m3(scale)
+__device__ __forceinline__ float fp4_elem_nog(const uint8_t* codes, const uint8_t* scales, int64_t cols, int64_t r,
+                                              int64_t c) {
+    uint32_t byte = codes[r * (cols / 2) + c / 2];
+    uint32_t nib = (c & 1) ? (byte >> 4) : (byte & 15u);
+    const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    float v = grid[nib & 7u] * e4m3_decode(scales[r * (cols / 16) + c / 16]);
+    return (nib & 8u) ? -v : v;
+}
+
+// Extra contraction columns for Abar Bbar^T (see file header).  Column layout, Kep = padded kb+ka:
+//   Aext[m, 0:kb]     = (T1[m,:] + sum_j Ua[m,j] Sa_j Mk[j,:]) * Sb * gUb / (gRa gRb)
+//   Aext[m, kb:kb+ka] = Ua[m,:] without its tensor scale (exact in bf16)
+//   Bext[n, 0:kb]     = Ub[n,:] without its tensor scale (exact in bf16)
+//   Bext[n, kb:kb+ka] = E2[n,:] * Sa * gUa / (gRa gRb)
+__global__ void k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1,
+                               const float* __restrict__ Mk, const float* __restrict__ E2,
+                               const uint8_t* __restrict__ ua_codes, const uint8_t* __restrict__ ua_scales, float g_ua,
+                               const float* __restrict__ Sa, const uint8_t* __restrict__ ub_codes,
+                               const uint8_t* __restrict__ ub_scales, float g_ub, const float* __restrict__ Sb,
+                               float inv_grr, bf16_t* __restrict__ Aext, bf16_t* __restrict__ Bext) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (Ma + Nb) * Kep) return;
+    int64_t row = t / Kep;
+    int c = (int)(t - row * Kep);
+    float v = 0.0f;
+    if (row < Ma) {
+        if (c < kb) {
+            float acc = T1[row * kb + c];
+            for (int j = 0; j < ka; ++j)
+                acc += fp4_elem_nog(ua_codes, ua_scales, Ma, j, row) * g_ua * Sa[j] * Mk[(int64_t)j * kb + c];
+            v = acc * Sb[c] * g_ub * inv_grr;
+        } else if (c < kb + ka) {
+            v = fp4_elem_nog(ua_codes, ua_scales, Ma, c - kb, row);
+        }
+        Aext[row * Kep + c] = f32_to_bf16_rne(v);
+    } else {
+        row -= Ma;
+        if (c < kb) {
+            v = fp4_elem_nog(ub_codes, ub_scales, Nb, c, row);
+        } else if (c < kb + ka) {
+            int j = c - kb;
+            v = E2[row * ka + j] * Sa[j] * g_ua * inv_grr;
+        }
+        Bext[row * Kep + c] = f32_to_bf16_rne(v);
+    }
+}
+
+struct NtOperand {            // one side of Abar Bbar^T: Abar = U diag(S) V^T + R, R [rows, Kc]
+    metis_fp4 R, Ut, Vt;      // Ut [k, rows], Vt [k, Kc]
+    const float* S;
+    int k;
+};
+
+struct LinWs {
+    size_t off_t1, off_mk, off_e2, off_aext, off_bext, total;
+    int Kep;
+};
+
+LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb) {
+    LinWs w;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    w.Kep = (ka + kb + 15) / 16 * 16;
+    w.off_t1 = take((size_t)Ma * (kb > 0 ? kb : 1) * 4);
+    w.off_mk = take((size_t)(ka > 0 ? ka : 1) * (kb > 0 ? kb : 1) * 4);
+    w.off_e2 = take((size_t)Nb * (ka > 0 ? ka : 1) * 4);
+    w.off_aext = take((size_t)Ma * (w.Kep > 0 ? w.Kep : 16) * 2);
+    w.off_bext = take((size_t)Nb * (w.Kep > 0 ? w.Kep : 16) * 2);
+    w.total = o;
+    return w;
+}
+
+bool fp4_valid(const metis_fp4& f) { return f.codes && f.scales && f.rows > 0 && f.cols > 0 && f.cols % 16 == 0; }
+
+int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* out, void* workspace,
+              size_t workspace_bytes) {
+    if (!out || !out->ptr) return METIS_INVALID_ARG;
+    if (!fp4_valid(a.R) || !fp4_valid(b.R) || a.R.cols != b.R.cols) return METIS_BAD_SHAPE;
+    const int64_t Ma = a.R.rows, Nb = b.R.rows, Kc = a.R.cols;
+    if (out->rows != Ma || out->cols != Nb || out->ld < Nb) return METIS_BAD_SHAPE;
+    if (out->dtype != METIS_BF16 && out->dtype != METIS_F32) return METIS_INVALID_ARG;
+    const int ka = a.k, kb = b.k;
+    if (ka < 0 || kb < 0 || ka > 128 || kb > 128) return METIS_UNSUPPORTED;
+    if (ka > 0 && (!a.S || !fp4_valid(a.Ut) || !fp4_valid(a.Vt) || a.Ut.rows != ka || a.Ut.cols != Ma ||
+                   a.Vt.rows != ka || a.Vt.cols != Kc)) return METIS_BAD_SHAPE;
+    if (kb > 0 && (!b.S || !fp4_valid(b.Ut) || !fp4_valid(b.Vt) || b.Ut.rows != kb || b.Ut.cols != Nb ||
+                   b.Vt.rows != kb || b.Vt.cols != Kc)) return METIS_BAD_SHAPE;
+    const float grr = a.R.tscale * b.R.tscale;
+    int Ke = 0;
+    const bf16_t *Aext = nullptr, *Bext = nullptr;
+    int st;
+    if (ka > 0 || kb > 0) {
+        const LinWs w = lin_layout(Ma, Nb, ka, kb);
+        if (!workspace || workspace_bytes < w.total) return METIS_WORKSPACE_TOO_SMALL;
+        if (reinterpret_cast<uintptr_t>(workspace) % 16) return METIS_INVALID_ARG;
+        char* ws = (char*)workspace;
+        float* T1 = (float*)(ws + w.off_t1);
+        float* Mk = (float*)(ws + w.off_mk);
+        float* E2 = (float*)(ws + w.off_e2);
+        bf16_t* ae = (bf16_t*)(ws + w.off_aext);
+        bf16_t* be = (bf16_t*)(ws + w.off_bext);
+        if (kb > 0 && (st = launch_gemm<float>(s, a.R, b.Vt, nullptr, nullptr, 0, a.R.tscale * b.Vt.tscale, T1, kb)))
+            return st;
+        if (ka > 0 && (st = launch_gemm<float>(s, b.R, a.Vt, nullptr, nullptr, 0, b.R.tscale * a.Vt.tscale, E2, ka)))
+            return st;
+        if (ka > 0 && kb > 0 &&
+            (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb)))
+            return st;
+        int64_t tot = (Ma + Nb) * w.Kep;
+        hipLaunchKernelGGL(k_assemble_ext, dim3((unsigned)ceil_div64(tot, 256)), dim3(256), 0, s, Ma, Nb, ka, kb, w.Kep,
+                           T1, Mk, E2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
+                           b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);
+        METIS_LAUNCH_CHECK();
+        Ke = w.Kep;
+        Aext = ae;
+        Bext = be;
+    }
+    if (out->dtype == METIS_BF16)
+        return launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld);
+    return launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld);
+}
+
+NtOperand nt(const metis_fp4& R, const metis_fp4& Ut, const metis_fp4& Vt, const float* S, int k) {
+    NtOperand o;
+    o.R = R; o.Ut = Ut; o.Vt = Vt; o.S = S; o.k = k;
+    return o;
+}
+
+}  // namespace
+
+extern "C" size_t metis_linear_workspace_bytes(int64_t L, int64_t N, int64_t K, int k) {
+    if (L < 1 || N < 1 || K < 1 || k < 0) return 0;
+    size_t a = lin_layout(L, N, k, k).total, b = lin_layout(L, K, k, k).total, c = lin_layout(N, K, k, k).total;
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
+}
+
+// Y[L,N] = Xbar Wbar^T: contraction over K
+extern "C" int metis_fp4_linear_fwd(void* stream, const metis_split* X, const metis_split* W, metis_mat* Y,
+                                    void* workspace, size_t workspace_bytes) {
+    if (!X || !W) return METIS_INVALID_ARG;
+    return linear_nt((hipStream_t)stream, nt(X->R, X->Ut, X->Vt, X->S, X->k), nt(W->R, W->Ut, W->Vt, W->S, W->k), Y,
+                     workspace, workspace_bytes);
+}
+
+// dX[L,K] = Gbar Wbar: contraction over N; Wbar^T [K,N] = Vw Sw Uw^T + Rw^T
+extern "C" int metis_fp4_linear_dgrad(void* stream, const metis_split* G, const metis_split* W, metis_mat* dX,
+                                      void* workspace, size_t workspace_bytes) {
+    if (!G || !W) return METIS_INVALID_ARG;
+    return linear_nt((hipStream_t)stream, nt(G->R, G->Ut, G->Vt, G->S, G->k), nt(W->Rt, W->Vt, W->Ut, W->S, W->k), dX,
+                     workspace, workspace_bytes);
+}
+
+// dW[N,K] = Gbar^T Xbar: contraction over L; Gbar^T [N,L] = Vg Sg Ug^T + Rg^T, Xbar^T [K,L] likewise
+extern "C" int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const metis_split* X, metis_mat* dW,
+                                      void* workspace, size_t workspace_bytes) {
+    if (!G || !X) return METIS_INVALID_ARG;
+    return linear_nt((hipStream_t)stream, nt(G->Rt, G->Vt, G->Ut, G->S, G->k), nt(X->Rt, X->Vt, X->Ut, X->S, X->k), dW,
+                     workspace, workspace_bytes);
+}

@@ -46,8 +46,9 @@ _SIGNATURES = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
     "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
+    "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
-                                       C.c_int, C.POINTER(Split), C.c_void_p]),
+                                       C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                        C.c_void_p, C.c_size_t]),
@@ -174,11 +175,19 @@ def quantize(A, out=None, out_t=None):
     _check(lib().metis_quantize(_stream(), C.byref(a), C.byref(o) if o else None, C.byref(ot) if ot else None))
 
 
-def split_quantize(A, U, S, V, out, R_debug=None):
+def split_workspace_bytes(M, N, k):
+    return int(lib().metis_split_workspace_bytes(M, N, k))
+
+
+def split_quantize(A, U, S, V, out, R_debug=None, workspace=None):
     a = _mat(A)
     s = out.c()
+    if workspace is None:
+        workspace = torch.empty((split_workspace_bytes(A.shape[0], A.shape[1], out.k),), dtype=torch.uint8,
+                                device=A.device)
     _check(lib().metis_split_quantize(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
-                                      out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None))
+                                      out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None,
+                                      workspace.data_ptr(), workspace.numel()))
 
 
 def linear_workspace_bytes(L, N, K, k):

@@ -1,0 +1,90 @@
+"""GPU parity: fprop / dgrad / wgrad on split FP4 operands against the oracle's fp64
+product of the SAME quantized operands (tolerance from the benchmark spec: 2e-2 relative
+Frobenius error)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import linear as olin
+from gpu_helpers import make_split, rel_fro, split_to_oracle
+
+pytestmark = pytest.mark.gpu
+
+GEMM_RTOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def metis():
+    from paper_2509_00404_amd import metis as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _three(metis, X, W, G, kx, kw, kg, p, rho, out_dtype=torch.bfloat16):
+    L, K = X.shape
+    N = W.shape[0]
+    xs = make_split(metis, X, kx, p, rho, 11)[0]
+    ws = make_split(metis, W, kw, p, 1.0, 12)[0]
+    gs = make_split(metis, G, kg, p, rho, 13)[0]
+    kmax = max(kx, kw, kg)
+    wsb = torch.empty((max(metis.linear_workspace_bytes(L, N, K, kmax), 256),), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((L, N), dtype=out_dtype, device="cuda")
+    dX = torch.empty((L, K), dtype=out_dtype, device="cuda")
+    dW = torch.empty((N, K), dtype=out_dtype, device="cuda")
+    metis.fp4_linear_fwd(xs, ws, Y, wsb)
+    metis.fp4_linear_dgrad(gs, ws, dX, wsb)
+    metis.fp4_linear_wgrad(gs, xs, dW, wsb)
+    torch.cuda.synchronize()
+    xo, wo, go = split_to_oracle(xs), split_to_oracle(ws), split_to_oracle(gs)
+    e = (rel_fro(Y.double().cpu().numpy(), olin.linear_fwd(xo, wo)),
+         rel_fro(dX.double().cpu().numpy(), olin.linear_dgrad(go, wo)),
+         rel_fro(dW.double().cpu().numpy(), olin.linear_wgrad(go, xo)))
+    return e, (Y, dX, dW), (xo, wo, go)
+
+
+def test_config1_forward(metis):
+    from paper_2509_00404_amd import workloads
+    t = workloads.config(1)
+    W, X = t["W"], t["X"]                       # W 256x512 split (k=8), X 128x512 plain
+    ws = make_split(metis, W, 8, 8, 0.25, workloads.seed_for(1, 0) + 7, want_t=False)[0]
+    xs = make_split(metis, X, 0, 0, 1.0, 0, want_t=False)[0]
+    wsb = torch.empty((metis.linear_workspace_bytes(128, 256, 512, 8),), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((128, 256), dtype=torch.bfloat16, device="cuda")
+    metis.fp4_linear_fwd(xs, ws, Y, wsb)
+    torch.cuda.synchronize()
+    ref = olin.linear_fwd(split_to_oracle(xs), split_to_oracle(ws))
+    assert rel_fro(Y.double().cpu().numpy(), ref) < GEMM_RTOL
+    # and the quantized product is a faithful approximation of the bf16 one (FP4: ~10 %)
+    exact = X.double().numpy() @ W.double().numpy().T
+    assert rel_fro(ref, exact) < 0.2
+
+
+@pytest.mark.parametrize("L,N,K,kx,kw,kg", [(128, 256, 512, 8, 8, 8), (208, 144, 272, 5, 12, 7),
+                                            (512, 384, 1024, 64, 64, 64), (256, 128, 128, 0, 16, 16),
+                                            (144, 160, 256, 16, 0, 0), (96, 80, 112, 0, 0, 0)])
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_all_three_products(metis, L, N, K, kx, kw, kg, out_dtype):
+    from paper_2509_00404_amd import workloads
+    X = workloads.planted(L, K, workloads.power_law(min(L, K), 1.2), 1, rms=1.0, outlier_cols=1)
+    W = workloads.planted(N, K, workloads.power_law(min(N, K), 1.0), 2, noise_top=0.01, rms=0.02)
+    G = workloads.planted(L, N, workloads.power_law(min(L, N), 2.0, head=4, head_gain=100.0), 3, rms=1e-3)
+    e, _, _ = _three(metis, X, W, G, kx, kw, kg, 8, 0.5, out_dtype)
+    tol = GEMM_RTOL if out_dtype == torch.bfloat16 else 5e-3
+    assert max(e) < tol, e
+
+
+def test_workspace_and_shape_errors(metis):
+    from paper_2509_00404_amd import workloads
+    X = workloads.gaussian(64, 128, 1)
+    W = workloads.gaussian(32, 128, 2)
+    xs = make_split(metis, X, 4, 4, 1.0, 1)[0]
+    ws = make_split(metis, W, 4, 4, 1.0, 2)[0]
+    Y = torch.empty((64, 32), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_fwd(xs, ws, Y, None)                       # split operands need workspace
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_fwd(xs, ws, torch.empty((64, 48), dtype=torch.bfloat16, device="cuda"),
+                             torch.empty((1 << 20,), dtype=torch.uint8, device="cuda"))
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_dgrad(xs, ws, Y, torch.empty((1 << 20,), dtype=torch.uint8, device="cuda"))

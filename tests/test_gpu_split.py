@@ -1,0 +1,85 @@
+"""GPU parity: metis_split_quantize. The residual against an fp64 evaluation of
+A - U S V^T from the same factors; codes and scales bit-exact against the oracle
+quantizer fed the kernel's own (dumped) fp32 quantizer input."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decompose as odec
+from oracle import quant as oq
+from gpu_helpers import make_split
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def metis():
+    from paper_2509_00404_amd import metis as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _check(metis, A, k, p, rho, seed, want_t=True):
+    sp, U, S, V, Rd = make_split(metis, A, k, p, rho, seed, want_t)
+    An = A.double().numpy()
+    Un, Sn, Vn = U.double().cpu().numpy(), S.double().cpu().numpy(), V.double().cpu().numpy()
+    R = Rd.double().cpu().numpy()
+    Rref = odec.residual(An, Un, Sn, Vn)
+    # low-rank product carried by two bf16 parts per factor: ~2^-16 of the low-rank magnitude
+    assert np.linalg.norm(R - Rref) <= 1e-4 * np.linalg.norm(An)
+    assert np.abs(R - Rref).max() <= 2e-4 * np.abs(An).max()
+    # identity A = U S V^T + R (Sec. 3.2)
+    assert np.linalg.norm((Un * Sn) @ Vn.T + R - An) <= 1e-4 * np.linalg.norm(An)
+    g = sp.R.tscale
+    c, s = oq.quantize(R, g)
+    assert np.array_equal(sp.R.scales.cpu().numpy(), s)
+    assert np.array_equal(sp.R.codes.cpu().numpy(), c)
+    if want_t:
+        c, s = oq.quantize(R.T, g)
+        assert np.array_equal(sp.Rt.scales.cpu().numpy(), s)
+        assert np.array_equal(sp.Rt.codes.cpu().numpy(), c)
+    c, s = oq.quantize(Un.T, sp.Ut.tscale)
+    assert np.array_equal(sp.Ut.scales.cpu().numpy(), s) and np.array_equal(sp.Ut.codes.cpu().numpy(), c)
+    c, s = oq.quantize(Vn.T, sp.Vt.tscale)
+    assert np.array_equal(sp.Vt.scales.cpu().numpy(), s) and np.array_equal(sp.Vt.codes.cpu().numpy(), c)
+    assert np.array_equal(sp.S[:k].cpu().numpy(), S.cpu().numpy())
+    # the premise of the method (Sec. 2.2): the residual is much narrower than A
+    return np.abs(R).max() / np.abs(An).max()
+
+
+def test_config1(metis):
+    from paper_2509_00404_amd import workloads
+    A = workloads.tiny_planted(workloads.seed_for(1, 0))
+    ratio = _check(metis, A, 8, 8, 0.25, workloads.seed_for(1, 0) + 7)
+    assert ratio < 0.2
+
+
+@pytest.mark.parametrize("M,N,k,p,rho", [(208, 96, 12, 4, 0.5), (336, 272, 5, 3, 0.1), (1008, 528, 33, 7, 0.25),
+                                         (96, 1024, 16, 16, 1.0), (2048, 1024, 64, 16, 0.125)])
+def test_ragged_shapes(metis, M, N, k, p, rho):
+    from paper_2509_00404_amd import workloads
+    q = min(M, N)
+    A = workloads.planted(M, N, 50.0 * np.arange(1, q + 1) ** -1.3 + 0.02, seed=M + N)
+    _check(metis, A, k, p, rho, seed=31)
+
+
+def test_without_transposed_residual(metis):
+    from paper_2509_00404_amd import workloads
+    A = workloads.planted(144, 80, 10.0 * np.arange(1, 81) ** -1.0, seed=8)
+    _check(metis, A, 8, 8, 1.0, seed=2, want_t=False)
+
+
+def test_argument_errors(metis):
+    A = torch.zeros((64, 48), dtype=torch.bfloat16, device="cuda")
+    U = torch.zeros((64, 4), device="cuda")
+    S = torch.zeros((4,), device="cuda")
+    V = torch.zeros((48, 4), device="cuda")
+    good = metis.SplitTensor(64, 48, 4, 2.0 ** -11, 2.0 ** -11, 1.0)
+    metis.split_quantize(A, U, S, V, good)
+    bad = metis.SplitTensor(64, 64, 4, 2.0 ** -11, 2.0 ** -11, 1.0)
+    with pytest.raises(metis.MetisError):
+        metis.split_quantize(A, U, S, V, bad)
+    with pytest.raises(metis.MetisError):
+        metis.split_quantize(A, U, S, V, good, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
