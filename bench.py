@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the Metis split-FP4 linear hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input
+already resident in HBM.  Default workload "c2": the LLaMA-3-8B attention projection
+(W 4096x4096 decomposed with k=64, p=16 and split-quantized; X 8192x4096 quantized;
+forward X W^T on the FP4 operands).  "c4" is the full W4A4G4 step of the FFN down
+projection (three decompositions, three split-quantizations with both block
+orientations, fprop + dgrad + wgrad).
+
+Prints ONE JSON line: whole-step throughput (useful GEMM flops / step time), the
+roofline of the dominant kernel (the FP4 GEMM, measured with HIP events around each of
+its launches inside the timed region), per-pass HBM rates, and the fp64 oracle timed on
+the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 2500.0     # MI355X dense fp16/bf16 matrix peak
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class Operand:
+    """One matrix of the layer with everything its decomposition and split need, preallocated."""
+
+    def __init__(self, metis, torch, A, k, p, rho, seed, want_t, oq):
+        self.A = A.cuda()
+        self.M, self.N = A.shape
+        self.k, self.p, self.rho, self.seed = k, p, rho, seed
+        g_r = oq.tensor_scale_for(float(A.abs().max()))         # delayed scaling: amax known from setup
+        dev = "cuda"
+        if k:
+            self.U = torch.empty((self.M, k), dtype=torch.float32, device=dev)
+            self.S = torch.empty((k,), dtype=torch.float32, device=dev)
+            self.V = torch.empty((self.N, k), dtype=torch.float32, device=dev)
+            self.ws_dec = torch.empty((metis.decompose_workspace_bytes(self.M, self.N, k, p, rho),),
+                                      dtype=torch.uint8, device=dev)
+            self.ws_split = torch.empty((metis.split_workspace_bytes(self.M, self.N, k),), dtype=torch.uint8, device=dev)
+        self.q = metis.SplitTensor(self.M, self.N, k, 2.0 ** -11, 2.0 ** -11, g_r, want_t)
+        self.metis = metis
+
+    def prepare(self):
+        m = self.metis
+        if self.k:
+            m.decompose(self.A, self.k, self.p, self.rho, self.seed, workspace=self.ws_dec, out=(self.U, self.S, self.V))
+            m.split_quantize(self.A, self.U, self.S, self.V, self.q, workspace=self.ws_split)
+        else:
+            m.quantize(self.A, self.q.R, self.q.Rt)
+
+    def bytes_read_once(self):
+        return 2 * self.M * self.N
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2509_00404_amd import metis, workloads
+    from oracle import quant as oq                    # only tensor_scale_for (setup) and the cpu_baseline leg
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    metis.lib()
+
+    c = int(args.workload[1])
+    prm = workloads.PARAMS[c]
+    t0 = time.time()
+    T = workloads.config(c)
+    k, p = prm["k"], prm["p"]
+    split_x = c >= 3
+    full = c == 4
+    W = Operand(metis, torch, T["W"], k, p, prm["rho_w"], workloads.seed_for(c, 0) + 7, full, oq)
+    X = Operand(metis, torch, T["X"], k if split_x else 0, p, prm["rho_x"], workloads.seed_for(c, 1) + 7, full, oq)
+    G = Operand(metis, torch, T["G"], k, p, prm["rho_x"], workloads.seed_for(c, 2) + 7, True, oq) if full else None
+    L, K = X.M, X.N
+    N = W.M
+    ws_lin = torch.empty((max(metis.linear_workspace_bytes(L, N, K, k), 256),), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((L, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((L, K), dtype=torch.bfloat16, device="cuda") if full else None
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device="cuda") if full else None
+    setup_s = time.time() - t0
+    ops = [W, X] + ([G] if full else [])
+    n_gemm = 3 if full else 1
+
+    def step():
+        for o in ops:
+            o.prepare()
+        metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin)
+        if full:
+            metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin)
+            metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    n_split = sum(1 for o in ops if o.k)
+    timers = {
+        "gemm": metis.KernelTimer(metis.PROF_GEMM, args.steps * n_gemm),
+        "broadcast": metis.KernelTimer(metis.PROF_BROADCAST, max(1, args.steps * n_split)),
+        "residual_quant": metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, max(1, args.steps * n_split)),
+        "quantize": metis.KernelTimer(metis.PROF_QUANTIZE, max(1, args.steps)),
+    }
+    for t in timers.values():
+        t.__enter__()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    for t in timers.values():
+        t.__exit__()
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    useful_flops = 2.0 * L * K * N * n_gemm
+    value = useful_flops / (ms_per_step * 1e-3) / 1e12
+
+    def avg(name, count):
+        d = timers[name].durations_ms(count)
+        return sum(d) / len(d) if d else None
+
+    gemm_ms = avg("gemm", args.steps * n_gemm)
+    gemm_tflops = 2.0 * L * K * N / (gemm_ms * 1e-3) / 1e12
+    roofline = {"kernel": "k_fp4_gemm_nt", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+                "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_TFLOPS, 4),
+                "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
+
+    passes = {}
+    if n_split:
+        bc_ms = avg("broadcast", args.steps * n_split)
+        rq_ms = avg("residual_quant", args.steps * n_split)
+        mn = sum(o.M * o.N for o in ops if o.k) / n_split
+        orient = 2 if full else 1
+        passes["broadcast"] = {"avg_ms": round(bc_ms, 4), "GB/s": round(2 * mn / bc_ms / 1e6, 1),
+                               "frac_hbm": round(2 * mn / bc_ms / 1e6 / PEAK_HBM_GBS, 4)}
+        rq_bytes = (2 + 0.5625 * orient) * mn
+        passes["residual_quant"] = {"avg_ms": round(rq_ms, 4), "GB/s": round(rq_bytes / rq_ms / 1e6, 1),
+                                    "frac_hbm": round(rq_bytes / rq_ms / 1e6 / PEAK_HBM_GBS, 4)}
+    if not split_x:
+        q_ms = avg("quantize", args.steps)
+        qb = 2.5625 * L * K
+        passes["quantize"] = {"avg_ms": round(q_ms, 4), "GB/s": round(qb / q_ms / 1e6, 1),
+                              "frac_hbm": round(qb / q_ms / 1e6 / PEAK_HBM_GBS, 4)}
+
+    out = {
+        "metric": "split-FP4 linear TFLOP/s + decompose/quantize GB/s (frac of roofline), 1 GPU",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4(e2m1)+e4m3 block scales, fp16 MFMA, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": {"c1": "config 1: tiny planted 256x512, X 128x512, k=8",
+                                "c2": "config 2: LLaMA-3-8B attention projection W 4096x4096 (k=64,p=16) x X 8192x4096, "
+                                      "decompose+split_quantize(W), quantize(X), fwd",
+                                "c3": "config 3: FFN up W 14336x4096, X 8192x4096 both split, fwd",
+                                "c4": "config 4: FFN down W 4096x14336, X 8192x14336, G 8192x4096, full W4A4G4 step"}[args.workload],
+                   "L": L, "K": K, "N": N, "k": k, "p": p, "gemms_per_step": n_gemm, "setup_s": round(setup_s, 1)},
+        "roofline": roofline,
+        "passes": passes,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(np, torch, T, c, prm, oq)
+    print(json.dumps(out))
+
+
+def cpu_baseline(np, torch, T, c, prm, oq):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import decompose as odec
+    from oracle import linear as olin
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    k, p = prm["k"], prm["p"]
+    rows = 4096 if c >= 2 else T["X"].shape[0]
+    Wn = T["W"].double().numpy()
+    Xn = T["X"][:rows].double().numpy()
+    t0 = time.perf_counter()
+    U, S, V = odec.decompose(Wn, k, p, prm["rho_w"], 1)
+    wq = olin.split_quantize(Wn, U, S, V, 2.0 ** -11, 2.0 ** -11, oq.tensor_scale_for(np.abs(Wn).max()), want_t=False)
+    xq = olin.split_quantize(Xn, None, None, None, 1.0, 1.0, oq.tensor_scale_for(np.abs(Xn).max()), want_t=False)
+    Yo = olin.linear_fwd(xq, wq)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * rows * Wn.shape[0] * Wn.shape[1]
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"full decompose+split_quantize of W {Wn.shape[0]}x{Wn.shape[1]}, quantize + fwd of the first "
+                      f"{rows} of {T['X'].shape[0]} rows of X (useful flops of those rows / oracle seconds)"}
+
+
+if __name__ == "__main__":
+    main()

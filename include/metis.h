@@ -164,6 +164,18 @@ int metis_fp4_linear_dgrad(void* stream, const metis_split* G, const metis_split
 int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const metis_split* X, metis_mat* dW,
                            void* workspace, size_t workspace_bytes);
 
+/* ---- measurement aid ---------------------------------------------------------------------- */
+
+/*
+ * Bracket every launch of one hot kernel with caller-owned HIP events (hipEvent_t passed as
+ * void*), recorded on the stream the kernel is launched on: launch i uses start[i % n] and
+ * stop[i % n].  kernel_id: 0 main FP4 GEMM kernel of the three linear calls (the kernel that
+ * writes Y / dX / dW), 1 broadcast C = A V0, 2 fused residual + quantize, 3 plain row
+ * quantizer.  n = 0 switches it off.  The arrays (host memory) must stay valid while set.
+ * Host-side state, not thread-safe; for benchmarks only.
+ */
+int metis_profile_events(int kernel_id, void** start, void** stop, int n);
+
 #ifdef __cplusplus
 }
 #endif

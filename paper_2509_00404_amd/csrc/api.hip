@@ -14,3 +14,16 @@ extern "C" const char* metis_status_string(int status) {
 }
 
 extern "C" int metis_version(void) { return 1; }
+
+MetisProfSlot g_metis_prof[METIS_PROF_COUNT] = {};
+
+extern "C" int metis_profile_events(int kernel_id, void** start, void** stop, int n) {
+    if (kernel_id < 0 || kernel_id >= METIS_PROF_COUNT || n < 0) return METIS_INVALID_ARG;
+    if (n > 0 && (!start || !stop)) return METIS_INVALID_ARG;
+    MetisProfSlot& p = g_metis_prof[kernel_id];
+    p.start = (hipEvent_t*)start;
+    p.stop = (hipEvent_t*)stop;
+    p.n = n;
+    p.next = 0;
+    return METIS_OK;
+}

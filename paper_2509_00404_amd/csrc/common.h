@@ -13,6 +13,29 @@
 
 typedef uint16_t bf16_t;   // raw bfloat16 bits
 
+// ---- optional event bracketing of the hot kernels (see metis_profile_events) ----
+enum { METIS_PROF_GEMM = 0, METIS_PROF_BROADCAST = 1, METIS_PROF_RESIDUAL_QUANT = 2, METIS_PROF_QUANTIZE = 3,
+       METIS_PROF_COUNT = 4 };
+struct MetisProfSlot {
+    hipEvent_t* start;
+    hipEvent_t* stop;
+    int n, next;
+};
+extern MetisProfSlot g_metis_prof[METIS_PROF_COUNT];
+static inline int metis_prof_begin(int id, hipStream_t s) {
+    MetisProfSlot& p = g_metis_prof[id];
+    if (p.n <= 0) return -1;
+    int i = p.next % p.n;
+    (void)hipEventRecord(p.start[i], s);
+    return i;
+}
+static inline void metis_prof_end(int id, int i, hipStream_t s) {
+    if (i < 0) return;
+    MetisProfSlot& p = g_metis_prof[id];
+    (void)hipEventRecord(p.stop[i], s);
+    p.next++;
+}
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 // low / high half of a dword holding two bf16
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }

@@ -177,7 +177,10 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
                                                      epi(V0f, k, V0hi, V0lo, N));
     METIS_LAUNCH_CHECK();
     // broadcast to the full batch: C = A V0
-    if ((st = launch_broadcast(s, Ap, lda, M, N, V0hi, V0lo, k, C, (uint32_t*)amax_out)) != METIS_OK) return st;
+    const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
+    st = launch_broadcast(s, Ap, lda, M, N, V0hi, V0lo, k, C, (uint32_t*)amax_out);
+    metis_prof_end(METIS_PROF_BROADCAST, pi, s);
+    if (st != METIS_OK) return st;
     // singular-value form: C = U S W^T, V = V0 W
     const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
     launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op(C, 1, k), op(C, 1, k), k, k, M, split_for(M, tiles_kk),

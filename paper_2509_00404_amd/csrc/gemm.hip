@@ -339,9 +339,13 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         Aext = ae;
         Bext = be;
     }
+    const int pi = metis_prof_begin(METIS_PROF_GEMM, s);
     if (out->dtype == METIS_BF16)
-        return launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld);
-    return launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld);
+        st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld);
+    else
+        st = launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld);
+    metis_prof_end(METIS_PROF_GEMM, pi, s);
+    return st;
 }
 
 NtOperand nt(const metis_fp4& R, const metis_fp4& Ut, const metis_fp4& Vt, const float* S, int k) {

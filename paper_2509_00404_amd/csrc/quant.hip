@@ -95,9 +95,11 @@ extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, 
                         (reinterpret_cast<uintptr_t>(A->ptr) % 16 == 0);
     if (vec_ok) {
         int64_t nb = M * (N / 16);
+        const int pi = metis_prof_begin(METIS_PROF_QUANTIZE, s);
         hipLaunchKernelGGL(k_quantize_rows_bf16, dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
                            (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale),
                            out->codes, out->scales);
+        metis_prof_end(METIS_PROF_QUANTIZE, pi, s);
         METIS_LAUNCH_CHECK();
         return METIS_OK;
     }

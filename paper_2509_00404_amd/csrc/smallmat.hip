@@ -7,50 +7,85 @@
 // Cholesky G = L L^T and Linv = L^-1 (lower triangular), n <= SM_MAX_N.
 // LDS: L [n][n+1] doubles, X [n][n+1] doubles.
 // ---------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+__device__ __forceinline__ double chol_rsqrt(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y;
+}
+
+__device__ __forceinline__ double chol_group8_sum(double x) {
+    int lo, hi;
+    double y;
+    lo = __builtin_amdgcn_update_dpp(__double2loint(x), __double2loint(x), 0xB1, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(__double2hiint(x), __double2hiint(x), 0xB1, 0xF, 0xF, false);
+    y = x + __hiloint2double(hi, lo);
+    lo = __builtin_amdgcn_update_dpp(__double2loint(y), __double2loint(y), 0x4E, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(__double2hiint(y), __double2hiint(y), 0x4E, 0xF, 0xF, false);
+    y = y + __hiloint2double(hi, lo);
+    lo = __builtin_amdgcn_update_dpp(__double2loint(y), __double2loint(y), 0x141, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(__double2hiint(y), __double2hiint(y), 0x141, 0xF, 0xF, false);
+    return y + __hiloint2double(hi, lo);
+}
+
+__global__ void __launch_bounds__(1024)
 k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32_t* __restrict__ info) {
     extern __shared__ double sm[];
     const int ld = n + 1;
     double* L = sm;
     double* X = sm + (size_t)n * ld;
+    __shared__ double dinv[SM_MAX_CHOL];
     const int tid = threadIdx.x;
-    for (int e = tid; e < n * n; e += 256) {
+    for (int e = tid; e < n * n; e += 1024) {
         int i = e / n, j = e - i * n;
         L[i * ld + j] = G[e];
         X[i * ld + j] = 0.0;
     }
     __syncthreads();
+    // right-looking Cholesky, one barrier per column: the trailing update uses the unscaled
+    // column and 1/pivot; the columns are scaled by 1/sqrt(pivot) in one pass at the end
+    const int ti = tid >> 5, tc = tid & 31;
     for (int j = 0; j < n; ++j) {
-        if (tid == 0) {
-            double d = L[j * ld + j];
-            if (!(d > 0.0)) {               // rank-deficient sketch: flag it, keep going finitely
-                if (info) *info = j + 1;
-                d = 1e-300;
-            }
-            L[j * ld + j] = sqrt(d);
+        double d = L[j * ld + j];
+        if (!(d > 0.0)) {                   // rank-deficient sketch: flag it, keep going finitely
+            if (tid == 0 && info) *info = j + 1;
+            d = 1e-300;
         }
-        __syncthreads();
-        double djj = L[j * ld + j];
-        for (int i = j + 1 + tid; i < n; i += 256) L[i * ld + j] /= djj;
-        __syncthreads();
-        const int ti = tid >> 4, tc = tid & 15;
-        for (int i = j + 1 + ti; i < n; i += 16) {
-            double lij = L[i * ld + j];
-            for (int c = j + 1 + tc; c <= i; c += 16) L[i * ld + c] -= lij * L[c * ld + j];
+        const double r = chol_rsqrt(d);
+        if (tid == 0) dinv[j] = r;
+        const double r2 = r * r;
+        for (int i = j + 1 + ti; i < n; i += 32) {
+            double lij = L[i * ld + j] * r2;
+            for (int c = j + 1 + tc; c <= i; c += 32) L[i * ld + c] -= lij * L[c * ld + j];
         }
         __syncthreads();
     }
-    // forward substitution, one column of L^-1 per thread; X[t][c] keeps lanes conflict-free
-    if (tid < n) {
-        const int c = tid;
-        for (int i = 0; i < n; ++i) {
-            double s = (i == c) ? 1.0 : 0.0;
-            for (int t = 0; t < i; ++t) s -= L[i * ld + t] * X[t * ld + c];
-            X[i * ld + c] = (i < c) ? 0.0 : s / L[i * ld + i];
+    for (int e = tid; e < n * n; e += 1024) {
+        int i = e / n, j = e - i * n;
+        if (j <= i) {
+            double v = L[i * ld + j];
+            if (i == j && !(v > 0.0)) v = 1e-300;
+            L[i * ld + j] = v * dinv[j];
         }
     }
     __syncthreads();
-    for (int e = tid; e < n * n; e += 256) {
+    // forward substitution: column c of L^-1 by a group of 8 lanes (same wave, so the group's own
+    // LDS writes are visible to it without a workgroup barrier); X[t][c] keeps groups conflict-free
+    {
+        const int c = tid >> 3, gl = tid & 7;
+        if (c < n) {
+            for (int i = c; i < n; ++i) {
+                double s = 0.0;
+                for (int t = c + gl; t < i; t += 8) s -= L[i * ld + t] * X[t * ld + c];
+                s = chol_group8_sum(s);
+                if (gl == 0) X[i * ld + c] = ((i == c ? 1.0 : 0.0) + s) * dinv[i];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < n * n; e += 1024) {
         int i = e / n, j = e - i * n;
         Linv[e] = X[i * ld + j];
     }
@@ -60,78 +95,148 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
 // One-sided Jacobi on a symmetric positive semi-definite G (n <= SM_MAX_N):
 // rotate the columns of W = G until they are mutually orthogonal; then column j is
 // lambda_j v_j.  1024 threads = 64 groups of 16 lanes, one column pair per group and
-// step, round-robin ordering; dot products by 16-lane shuffles.
+// step, round-robin ordering; dot products by 16-lane DPP rotations.
 // Outputs (eigenvalues descending):
 //   lam  [n]            eigenvalues
 //   vec  [n][n]         vec[i*n + j] = component i of eigenvector j          (optional)
 //   tmat [n][kk]        tmat[i*kk + c] = vec[i][c] / sqrt(lam_c), c < kk     (optional)
 //   sval [kk]           (float) sqrt(lam_c)                                  (optional)
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ double group16_sum(double x) {
-    x += __shfl_xor(x, 8, 16);
-    x += __shfl_xor(x, 4, 16);
-    x += __shfl_xor(x, 2, 16);
-    x += __shfl_xor(x, 1, 16);
+// ---- 8-lane all-reduce of a double with DPP (no LDS traffic) ----
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov64(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double group8_sum(double x) {
+    x += dpp_mov64<0xB1>(x);      // quad_perm [1,0,3,2]
+    x += dpp_mov64<0x4E>(x);      // quad_perm [2,3,0,1]
+    x += dpp_mov64<0x141>(x);     // row_half_mirror: lane i <-> 7-i within each 8 lanes
     return x;
 }
 
-__global__ void __launch_bounds__(1024)
+// 1/sqrt(x) for x > 0: hardware seed + two Newton steps (full fp64 accuracy)
+__device__ __forceinline__ double rsqrt_nr(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y;
+}
+__device__ __forceinline__ double rcp_nr(double x) {
+    double y = __builtin_amdgcn_rcp(x);
+    y = y * (2.0 - x * y);
+    y = y * (2.0 - x * y);
+    return y;
+}
+
+#define JG 8      // lanes per column pair
+
+__host__ __device__ static inline int jacobi_ld(int n) { return ((n + 7) / 16) * 16 + 8; }
+
+// NE = ceil(n / 8): elements of one column held by each of the 8 lanes of a group.
+// blockDim = 64 * ceil(ceil(n/2) / 8): one group of 8 lanes per column pair.
+template <int NE>
+__global__ void __launch_bounds__(512)
 k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ lam, double* __restrict__ vec,
              double* __restrict__ tmat, float* __restrict__ sval) {
     extern __shared__ double sm[];
     const int ne = n + (n & 1);             // even number of columns (a zero column pads odd n)
-    const int ld = n + 1;
+    // Column stride = 8 (mod 16) doubles: the 8 groups of a wave touch 8 consecutive columns in
+    // one LDS instruction, and this stride spreads them evenly over the banks.
+    const int ld = jacobi_ld(n);
     double* W = sm;                         // column-major: W[p*ld + i] = element i of column p
-    double* nrm = sm + (size_t)ne * ld;     // [ne]
+    double* nrm = sm + (size_t)ne * ld;     // [ne] squared column norms during the sweeps
     int* order = (int*)(nrm + ne);          // [ne]
     __shared__ int rotated;
-    const int tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
+    __shared__ double amax_sh;
+    const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JG, gl = tid % JG;
 
-    for (int e = tid; e < ne * ld; e += 1024) {
+    for (int e = tid; e < ne * ld; e += nthr) {
         int p = e / ld, i = e - p * ld;
         W[e] = (p < n && i < n) ? G[(size_t)i * n + p] : 0.0;
     }
     __syncthreads();
 
     const int npairs = ne / 2, nm1 = ne - 1;
-    const double tol = 1e-15;
+    const bool active = grp < npairs;
+
+    // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta).  The second term is
+    // the rounding floor of a dot product of two columns that each carry an absolute error of
+    // ~eps * lambda_max (the columns are lambda_j v_j, formed from O(lambda_max) entries): below it
+    // a rotation only reshuffles noise and the sweeps would never end.
+    const double tol2 = 1e-26, floor2 = 1e-28;
     for (int sweep = 0; sweep < 40; ++sweep) {
+        // exact squared norms at the start of every sweep (the in-sweep updates only track them)
+        if (active) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int p = 2 * grp + h;
+                double s = 0.0;
+#pragma unroll
+                for (int e = 0; e < NE; ++e) {
+                    int i = gl + JG * e;
+                    double x = i < n ? W[(size_t)p * ld + i] : 0.0;
+                    s += x * x;
+                }
+                s = group8_sum(s);
+                if (gl == 0) nrm[p] = s;
+            }
+        }
         if (tid == 0) rotated = 0;
         __syncthreads();
+        if (tid == 0) {
+            double m = 0.0;
+            for (int j = 0; j < ne; ++j) m = fmax(m, nrm[j]);
+            amax_sh = m;
+        }
+        __syncthreads();
+        const double amax = amax_sh;
+        // round-robin pairing: column nm1 stays, the others rotate through the slots
+        int p = grp == 0 ? nm1 : grp % nm1;
+        int q = grp == 0 ? 0 : (nm1 - grp % nm1) % nm1;
         for (int step = 0; step < nm1; ++step) {
-            if (grp < npairs) {
-                int p, q;
-                if (grp == 0) { p = nm1; q = step; }
-                else { p = (step + grp) % nm1; q = (step - grp + nm1) % nm1; }
+            if (active) {
                 double* wp = W + (size_t)p * ld;
                 double* wq = W + (size_t)q * ld;
-                double a[SM_MAX_N / 16], b[SM_MAX_N / 16];
-                double alpha = 0.0, beta = 0.0, gamma = 0.0;
+                double a[NE], b[NE];
+                double g0 = 0.0, g1 = 0.0;
 #pragma unroll
-                for (int e = 0; e < SM_MAX_N / 16; ++e) {
-                    int i = gl + 16 * e;
+                for (int e = 0; e < NE; ++e) {
+                    int i = gl + JG * e;
                     a[e] = i < n ? wp[i] : 0.0;
                     b[e] = i < n ? wq[i] : 0.0;
-                    alpha += a[e] * a[e];
-                    beta += b[e] * b[e];
-                    gamma += a[e] * b[e];
+                    if (e & 1) g1 += a[e] * b[e]; else g0 += a[e] * b[e];
                 }
-                alpha = group16_sum(alpha);
-                beta = group16_sum(beta);
-                gamma = group16_sum(gamma);
-                if (fabs(gamma) > tol * sqrt(alpha * beta) && alpha > 0.0 && beta > 0.0) {
-                    double zeta = (beta - alpha) / (2.0 * gamma);
-                    double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    double c = 1.0 / sqrt(1.0 + t * t), s = c * t;
+                const double alpha = nrm[p], beta = nrm[q];
+                const double gamma = group8_sum(g0 + g1);
+                if (gamma * gamma > tol2 * alpha * beta + floor2 * amax * (alpha + beta) && alpha > 0.0 && beta > 0.0) {
+                    // t = tan(theta) of the rotation that orthogonalises the pair (smaller root)
+                    const double tau = beta - alpha;
+                    const double hh = tau * tau + 4.0 * gamma * gamma;
+                    const double hyp = hh * rsqrt_nr(hh);
+                    const double t = (tau < 0.0 ? -2.0 : 2.0) * gamma * rcp_nr(fabs(tau) + hyp);
+                    const double c = rsqrt_nr(1.0 + t * t), s = c * t;
 #pragma unroll
-                    for (int e = 0; e < SM_MAX_N / 16; ++e) {
-                        int i = gl + 16 * e;
+                    for (int e = 0; e < NE; ++e) {
+                        int i = gl + JG * e;
                         if (i < n) {
                             wp[i] = c * a[e] - s * b[e];
                             wq[i] = s * a[e] + c * b[e];
                         }
                     }
-                    if (gl == 0) rotated = 1;
+                    if (gl == 0) {
+                        nrm[p] = alpha - t * gamma;
+                        nrm[q] = beta + t * gamma;
+                        rotated = 1;
+                    }
+                }
+                if (grp == 0) {
+                    q = q + 1;
+                } else {
+                    p = p + 1 == nm1 ? 0 : p + 1;
+                    q = q + 1 == nm1 ? 0 : q + 1;
                 }
             }
             __syncthreads();
@@ -141,13 +246,13 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         if (!any) break;
     }
     // column norms = eigenvalues
-    if (grp < npairs) {
+    if (active) {
         for (int h = 0; h < 2; ++h) {
-            int p = 2 * grp + h;
+            int pp = 2 * grp + h;
             double s = 0.0;
-            for (int i = gl; i < n; i += 16) s += W[(size_t)p * ld + i] * W[(size_t)p * ld + i];
-            s = group16_sum(s);
-            if (gl == 0) nrm[p] = (p < n) ? sqrt(s) : -1.0;
+            for (int i = gl; i < n; i += JG) s += W[(size_t)pp * ld + i] * W[(size_t)pp * ld + i];
+            s = group8_sum(s);
+            if (gl == 0) nrm[pp] = (pp < n) ? sqrt(s) : -1.0;
         }
     }
     __syncthreads();
@@ -158,11 +263,11 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         order[r] = tid;
     }
     __syncthreads();
-    for (int e = tid; e < n * n; e += 1024) {
+    for (int e = tid; e < n * n; e += nthr) {
         int i = e / n, j = e - i * n;
-        int p = order[j];
-        double l = nrm[p];
-        double v = l > 0.0 ? W[(size_t)p * ld + i] / l : (i == j ? 1.0 : 0.0);
+        int pp = order[j];
+        double l = nrm[pp];
+        double v = l > 0.0 ? W[(size_t)pp * ld + i] / l : (i == j ? 1.0 : 0.0);
         if (vec) vec[e] = v;
         if (tmat && j < kk) tmat[(size_t)i * kk + j] = l > 0.0 ? v / sqrt(l) : 0.0;
     }
@@ -177,7 +282,7 @@ int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t
     size_t lds = 2 * (size_t)n * (n + 1) * sizeof(double);
     if (hipFuncSetAttribute((const void*)k_chol_inv, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(256), lds, s, G, n, Linv, info);
+    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), lds, s, G, n, Linv, info);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
@@ -185,10 +290,27 @@ int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t
 int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
                       float* sval) {
     int ne = n + (n & 1);
-    size_t lds = ((size_t)ne * (n + 1) + ne) * sizeof(double) + (size_t)ne * sizeof(int);
-    if (hipFuncSetAttribute((const void*)k_jacobi_eig, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(k_jacobi_eig, dim3(1), dim3(1024), lds, s, G, n, kk, lam, vec, tmat, sval);
+    size_t lds = ((size_t)ne * jacobi_ld(n) + ne) * sizeof(double) + (size_t)ne * sizeof(int);
+const int npairs = ne / 2;
+    const int threads = 64 * ((npairs + 7) / 8);          // one 8-lane group per column pair
+    if (threads > 512 || ne > threads) return METIS_UNSUPPORTED;
+#define JACOBI_CASE(NE)                                                                                       \
+    {                                                                                                         \
+        if (hipFuncSetAttribute((const void*)k_jacobi_eig<NE>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                (int)lds) != hipSuccess)                                                      \
+            return METIS_HIP_ERROR;                                                                           \
+        hipLaunchKernelGGL(k_jacobi_eig<NE>, dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval); \
+    }
+    const int need = (n + 7) / 8;
+    if (need <= 1) JACOBI_CASE(1)
+    else if (need <= 2) JACOBI_CASE(2)
+    else if (need <= 4) JACOBI_CASE(4)
+    else if (need <= 8) JACOBI_CASE(8)
+    else if (need <= 10) JACOBI_CASE(10)
+    else if (need <= 12) JACOBI_CASE(12)
+    else if (need <= 16) JACOBI_CASE(16)
+    else return METIS_UNSUPPORTED;
+#undef JACOBI_CASE
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }

@@ -158,9 +158,11 @@ extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const floa
     hipLaunchKernelGGL(k_split_factors, dim3((unsigned)ceil_div64(tot, 256)), dim3(256), 0, s, U, S, V, M, N, k, kp,
                        us_hi, us_lo, v_hi, v_lo, out->S);
     dim3 grid((unsigned)ceil_div64(N, RQ_T), (unsigned)ceil_div64(M, RQ_T));
+    const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
     hipLaunchKernelGGL(k_residual_quant, grid, dim3(256), 0, s, (const bf16_t*)A->ptr, A->ld, M, N, kp, us_hi, us_lo,
                        v_hi, v_lo, make_quant_params(out->R.tscale), out->R.codes, out->R.scales,
                        want_t ? out->Rt.codes : nullptr, want_t ? out->Rt.scales : nullptr, R_debug);
+    metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
     METIS_LAUNCH_CHECK();
     // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
     metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};

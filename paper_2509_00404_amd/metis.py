@@ -49,6 +49,7 @@ _SIGNATURES = {
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
+    "metis_profile_events": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_int]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                        C.c_void_p, C.c_size_t]),
@@ -212,3 +213,42 @@ def fp4_linear_dgrad(G, W, dX, workspace):
 
 def fp4_linear_wgrad(G, X, dW, workspace):
     return _linear(lib().metis_fp4_linear_wgrad, G, X, dW, workspace)
+
+
+PROF_GEMM, PROF_BROADCAST, PROF_RESIDUAL_QUANT, PROF_QUANTIZE = 0, 1, 2, 3
+
+
+class KernelTimer:
+    """HIP events around every launch of one hot kernel (metis_profile_events)."""
+
+    def __init__(self, kernel_id, n):
+        self.kernel_id, self.n = kernel_id, n
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventCreate.restype = C.c_int
+        self.hip.hipEventElapsedTime.restype = C.c_int
+        self.start = (C.c_void_p * n)()
+        self.stop = (C.c_void_p * n)()
+        for arr in (self.start, self.stop):
+            for i in range(n):
+                ev = C.c_void_p()
+                if self.hip.hipEventCreate(C.byref(ev)) != 0:
+                    raise MetisError("hipEventCreate failed")
+                arr[i] = ev
+
+    def __enter__(self):
+        _check(lib().metis_profile_events(self.kernel_id, self.start, self.stop, self.n))
+        return self
+
+    def __exit__(self, *exc):
+        _check(lib().metis_profile_events(self.kernel_id, None, None, 0))
+
+    def durations_ms(self, count):
+        """Durations of the last `count` (<= n) bracketed launches; call after a device sync."""
+        out = []
+        for i in range(min(count, self.n)):
+            ms = C.c_float()
+            if self.hip.hipEventElapsedTime(C.byref(ms), self.start[i], self.stop[i]) == 0:
+                out.append(ms.value)
+        return out
