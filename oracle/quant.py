@@ -10,7 +10,11 @@ round(e / (s*g)) * (s*g) on the grid +-{0, .5, 1, 1.5, 2, 3, 4, 6}.
 
 Readings of this build where the paper is silent:
   * g is a per-tensor power-of-two scale (g = 1 is the paper's text verbatim);
-  * round() is round-to-nearest, ties to the even E2M1 code;
+  * the quotient e/s is the IEEE fp32 quotient y = fl32(e / (s*g)) (the precision of the
+    kernels; the paper's own emulation evaluates it in floating point as well); inputs are
+    taken as fp32 values.  y is exact whenever it is representable, so a value that sits
+    exactly on a rounding midpoint stays there;
+  * round() is round-to-nearest of y, ties to the even E2M1 code;
   * a block whose amax exceeds 6*448*g saturates (scale 448, elements clamp to 6);
   * an all-zero block gets scale byte 0 and codes that keep only the sign bit.
 
@@ -50,18 +54,18 @@ def quantize(x, g=1.0):
     cover = 6.0 * E4M3_POS * g
     sidx = np.searchsorted(cover, amax, side="left")
     sidx = np.minimum(sidx, 126)                    # saturate at 448
-    s = E4M3_POS[sidx] * g                          # effective step per block
-    a = np.abs(xb)
-    step = s[:, :, None]
+    step = (E4M3_POS[sidx] * g).astype(np.float32)  # s*g: at most 4 significant bits, exact in fp32
+    # e/s as the IEEE fp32 quotient; an all-zero block (step 0) maps to +-0
+    safe = np.where(step > 0, step, np.float32(1.0)).astype(np.float32)
+    y = (xb.astype(np.float32) / safe[:, :, None]).astype(np.float32).astype(np.float64)
+    a = np.abs(y)
     mag = np.zeros(xb.shape, dtype=np.int64)
     for j, mid in enumerate(E2M1_MID):
-        bound = mid * step
         # a tie goes to the even code: boundary j separates codes j and j+1
         if (j + 1) % 2 == 0:
-            mag += (a >= bound)
+            mag += (a >= mid)
         else:
-            mag += (a > bound)
-    mag = np.where(step == 0, 0, mag)
+            mag += (a > mid)
     sign = np.signbit(xb).astype(np.int64)
     nib = (sign << 3) | mag
     nib = nib.reshape(rows, cols)

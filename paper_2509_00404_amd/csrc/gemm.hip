@@ -16,8 +16,8 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 namespace {
 
 #define G_KI 128                    // contraction elements per LDS stage
-#define G_CROW (G_KI / 2 + 4)       // padded code row in LDS (bytes): dword stride 17
-#define G_SROW 16                   // 8 fp16 block scales per row and stage
+#define G_CROW (G_KI / 2 + 4)       // padded code row in LDS (bytes): dword stride 17, conflict-free
+#define G_SROW 36                   // 8 block scales per row and stage, each as a duplicated fp16 pair, + pad
 
 struct Fp4Operand {
     const uint8_t* codes;           // [rows, K/2]
@@ -25,62 +25,88 @@ struct Fp4Operand {
     int64_t rows;
 };
 
-__device__ __forceinline__ uint16_t e4m3_to_f16_bits(uint32_t b) {
+__device__ __forceinline__ uint32_t e4m3_to_f16_pair(uint32_t b) {
     // normal: exponent rebias 7 -> 15, mantissa left-aligned; subnormal b*2^-9 is a normal fp16
-    if (b >= 8u) return (uint16_t)((b << 7) + 0x2000u);
-    _Float16 h = (_Float16)((float)b * 0.001953125f);
-    return __builtin_bit_cast(uint16_t, h);
+    uint32_t h;
+    if (b >= 8u) {
+        h = (b << 7) + 0x2000u;
+    } else {
+        _Float16 f = (_Float16)((float)b * 0.001953125f);
+        h = __builtin_bit_cast(uint16_t, f);
+    }
+    return h | (h << 16);
 }
 
-// Stage `rows` rows of codes/scales for contraction range [k0, k0+128) into LDS.
-template <int ROWS, bool VEC>
-__device__ __forceinline__ void stage_operand(const Fp4Operand& op, int64_t r0, int64_t K, int64_t k0,
-                                              uint8_t* __restrict__ lc, uint16_t* __restrict__ ls, int tid) {
+// One thread's share of a stage of ROWS rows x 64 B of codes: V = ROWS*4/NT 16-byte code vectors and
+// (threads below ROWS) the 8 scale bytes of one row.  NT = threads per workgroup.
+template <int V>
+struct StageRegs {
+    uint4 c[V];
+    uint2 s;
+};
+
+template <int ROWS, int NT, bool VEC>
+__device__ __forceinline__ void stage_load(const Fp4Operand& op, int64_t r0, int64_t K, int64_t k0,
+                                           StageRegs<ROWS * 4 / NT>& rg, int tid) {
+    constexpr int T = ROWS * 4 / NT;
     const int64_t cstride = K / 2, sstride = K / 16;
-    for (int e = tid; e < ROWS * 4; e += 256) {
+#pragma unroll
+    for (int v = 0; v < T; ++v) {
+        int e = tid + NT * v;
         int row = e >> 2, seg = e & 3;
         int64_t gr = r0 + row;
         if (gr >= op.rows) gr = op.rows - 1;
         const uint8_t* src = op.codes + gr * cstride + k0 / 2 + 16 * seg;
-        uint4 v = make_uint4(0, 0, 0, 0);
         if (VEC) {
-            v = *reinterpret_cast<const uint4*>(src);
+            rg.c[v] = *reinterpret_cast<const uint4*>(src);
         } else {
             uint32_t w[4] = {0, 0, 0, 0};
             for (int b = 0; b < 16; ++b) {
                 int64_t kb = k0 / 2 + 16 * seg + b;
                 if (kb < cstride) w[b >> 2] |= (uint32_t)src[b] << (8 * (b & 3));
             }
-            v = make_uint4(w[0], w[1], w[2], w[3]);
+            rg.c[v] = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
-        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
-    for (int e = tid; e < ROWS; e += 256) {
-        int64_t gr = r0 + e;
+    if (tid < ROWS) {
+        int64_t gr = r0 + tid;
         if (gr >= op.rows) gr = op.rows - 1;
         const uint8_t* src = op.scales + gr * sstride + k0 / 16;
-        uint32_t b[8];
         if (VEC) {
-            uint2 v = *reinterpret_cast<const uint2*>(src);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { b[i] = (v.x >> (8 * i)) & 0xFFu; b[4 + i] = (v.y >> (8 * i)) & 0xFFu; }
+            rg.s = *reinterpret_cast<const uint2*>(src);
         } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) b[i] = (k0 / 16 + i < sstride) ? src[i] : 0u;
+            uint32_t w[2] = {0, 0};
+            for (int i = 0; i < 8; ++i)
+                if (k0 / 16 + i < sstride) w[i >> 2] |= (uint32_t)src[i] << (8 * (i & 3));
+            rg.s = make_uint2(w[0], w[1]);
         }
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)e4m3_to_f16_bits(b[2 * i]) | ((uint32_t)e4m3_to_f16_bits(b[2 * i + 1]) << 16);
-        *reinterpret_cast<uint4*>(ls + e * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
-// 8 codes (one dword) times one fp16 block scale -> 8 fp16
-__device__ __forceinline__ half8_t dequant8(uint32_t cw, uint16_t sbits) {
-    _Float16 s = __builtin_bit_cast(_Float16, sbits);
-    half2_t s2 = {s, s};
+template <int ROWS, int NT>
+__device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, uint8_t* __restrict__ lc,
+                                            uint8_t* __restrict__ ls, int tid) {
+    constexpr int T = ROWS * 4 / NT;
+#pragma unroll
+    for (int v = 0; v < T; ++v) {
+        int e = tid + NT * v;
+        int row = e >> 2, seg = e & 3;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
+        dst[0] = rg.c[v].x; dst[1] = rg.c[v].y; dst[2] = rg.c[v].z; dst[3] = rg.c[v].w;
+    }
+    if (tid < ROWS) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(ls + tid * G_SROW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dst[i] = e4m3_to_f16_pair((rg.s.x >> (8 * i)) & 0xFFu);
+            dst[4 + i] = e4m3_to_f16_pair((rg.s.y >> (8 * i)) & 0xFFu);
+        }
+    }
+}
+
+// 8 codes (one dword) times one block scale (fp16, duplicated in both halves of `s2`) -> 8 fp16
+__device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t s2bits) {
+    half2_t s2 = __builtin_bit_cast(half2_t, s2bits);
     half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0) * s2;
     half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1) * s2;
     half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2) * s2;
@@ -98,19 +124,32 @@ template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
 template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16_rne(v); }
 
-// grid: (ceil(N / (64*TN)), ceil(M / (64*TM))); block 256 = 2x2 waves, each wave TM x TN tiles of 32x32.
-template <int TM, int TN, bool VEC, typename OUT>
-__global__ void __launch_bounds__(256)
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes() {
+    return 2 * ((size_t)BM * (G_CROW + G_SROW) + (size_t)BN * (G_CROW + G_SROW));
+}
+
+// 1-D grid of ceil(M / BM) * ceil(N / BN) workgroups of WMW x WNW waves, each wave TM x TN tiles of
+// 32x32 (BM = 32 TM WMW, BN = 32 TN WNW).  Workgroup ids are dealt round-robin to the 8 XCDs by the
+// hardware; the remap below hands each XCD a contiguous run of tiles so that its L2 sees few
+// distinct rows of A.
+template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
+__global__ void __launch_bounds__(64 * WMW * WNW)
 k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    __shared__ __attribute__((aligned(16))) uint8_t lcA[2][BM * G_CROW];
-    __shared__ __attribute__((aligned(16))) uint8_t lcB[2][BN * G_CROW];
-    __shared__ __attribute__((aligned(16))) uint16_t lsA[2][BM * 8];
-    __shared__ __attribute__((aligned(16))) uint16_t lsB[2][BN * 8];
+              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n) {
+    constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    // LDS: [buffer][codes A | codes B | scales A | scales B]
+    constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
+                  BUF = OFF_SB + BN * G_SROW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
-    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    int tile = blockIdx.x;
+    {
+        const int total = gridDim.x;
+        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
+    }
+    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    const int wm = (wave / WNW) * 32 * TM, wn = (wave % WNW) * 32 * TN;
     const int li = lane & 31, half = lane >> 5;
 
     float16_t acc[TM][TN];
@@ -122,40 +161,46 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const int64_t niter = (K + G_KI - 1) / G_KI;
-    stage_operand<BM, VEC>(A, m0, K, 0, lcA[0], lsA[0], tid);
-    stage_operand<BN, VEC>(B, n0, K, 0, lcB[0], lsB[0], tid);
+    StageRegs<BM * 4 / NT> ra;
+    StageRegs<BN * 4 / NT> rb;
+    stage_load<BM, NT, VEC>(A, m0, K, 0, ra, tid);
+    stage_load<BN, NT, VEC>(B, n0, K, 0, rb, tid);
+    stage_store<BM, NT>(ra, lds, lds + OFF_SA, tid);
+    stage_store<BN, NT>(rb, lds + OFF_CB, lds + OFF_SB, tid);
     __syncthreads();
     for (int64_t it = 0; it < niter; ++it) {
         const int cur = (int)(it & 1);
-        if (it + 1 < niter) {
-            stage_operand<BM, VEC>(A, m0, K, (it + 1) * G_KI, lcA[cur ^ 1], lsA[cur ^ 1], tid);
-            stage_operand<BN, VEC>(B, n0, K, (it + 1) * G_KI, lcB[cur ^ 1], lsB[cur ^ 1], tid);
+        const bool more = it + 1 < niter;
+        if (more) {
+            stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
+            stage_load<BN, NT, VEC>(B, n0, K, (it + 1) * G_KI, rb, tid);
         }
-        uint4 sa[TM], sb[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint4*>(&lsA[cur][(wm + 32 * i + li) * 8]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint4*>(&lsB[cur][(wn + 32 * j + li) * 8]);
+        const uint8_t* bufc = lds + cur * BUF;
+        uint8_t* bufn = lds + (cur ^ 1) * BUF;
+        const uint8_t* ca = bufc + (wm + li) * G_CROW + 4 * half;
+        const uint8_t* cb = bufc + OFF_CB + (wn + li) * G_CROW + 4 * half;
+        const uint8_t* sa = bufc + OFF_SA + (wm + li) * G_SROW;
+        const uint8_t* sb = bufc + OFF_SB + (wn + li) * G_SROW;
 #pragma unroll
         for (int s = 0; s < G_KI / 16; ++s) {
             half8_t fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                uint32_t cw = *reinterpret_cast<const uint32_t*>(&lcA[cur][(wm + 32 * i + li) * G_CROW + 8 * s + 4 * half]);
-                uint32_t sw = (&sa[i].x)[s >> 1];
-                fa[i] = dequant8(cw, (uint16_t)((s & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-            }
+            for (int i = 0; i < TM; ++i)
+                fa[i] = dequant8(*reinterpret_cast<const uint32_t*>(ca + 32 * i * G_CROW + 8 * s),
+                                 *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * s));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                uint32_t cw = *reinterpret_cast<const uint32_t*>(&lcB[cur][(wn + 32 * j + li) * G_CROW + 8 * s + 4 * half]);
-                uint32_t sw = (&sb[j].x)[s >> 1];
-                fb[j] = dequant8(cw, (uint16_t)((s & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-            }
+            for (int j = 0; j < TN; ++j)
+                fb[j] = dequant8(*reinterpret_cast<const uint32_t*>(cb + 32 * j * G_CROW + 8 * s),
+                                 *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * s));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            stage_store<BM, NT>(ra, bufn, bufn + OFF_SA, tid);
+            stage_store<BN, NT>(rb, bufn + OFF_CB, bufn + OFF_SB, tid);
         }
         __syncthreads();
     }
@@ -196,6 +241,30 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
         }
 }
 
+template <int TM, int TN, int WMW, int WNW, typename OUT>
+int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
+                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
+    constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
+    static_assert(BM * 4 >= NT && BN * 4 >= NT, "every thread stages at least one code vector");
+    const int64_t tm = ceil_div64(a.rows, BM), tn = ceil_div64(b.rows, BN);
+    if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    dim3 grid((unsigned)(tm * tn));
+    if (vec) {
+        auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, true, OUT>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+    } else {
+        auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, false, OUT>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+    }
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
 template <typename OUT>
 int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf16_t* Aext, const bf16_t* Bext, int Ke,
                 float alpha, OUT* C, int64_t ldc) {
@@ -204,21 +273,11 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
     const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
                      reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
-    if (N > 64 && M > 64) {
-        dim3 grid((unsigned)ceil_div64(N, 128), (unsigned)ceil_div64(M, 128));
-        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<2, 2, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-        else hipLaunchKernelGGL((k_fp4_gemm_nt<2, 2, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-    } else if (N <= 64) {
-        dim3 grid((unsigned)ceil_div64(N, 64), (unsigned)ceil_div64(M, 128));
-        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<2, 1, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-        else hipLaunchKernelGGL((k_fp4_gemm_nt<2, 1, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-    } else {
-        dim3 grid((unsigned)ceil_div64(N, 128), (unsigned)ceil_div64(M, 64));
-        if (vec) hipLaunchKernelGGL((k_fp4_gemm_nt<1, 2, true, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-        else hipLaunchKernelGGL((k_fp4_gemm_nt<1, 2, false, OUT>), grid, dim3(256), 0, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
-    }
-    METIS_LAUNCH_CHECK();
-    return METIS_OK;
+    if (M >= 1024 && N >= 1024)      // 256x256 tile, 8 waves of 128x64: two waves per SIMD hide each other's latencies
+        return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
 }
 
 // value of one FP4 element without the tensor scale: grid[code] * e4m3(scale)

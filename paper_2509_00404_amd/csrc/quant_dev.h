@@ -1,6 +1,7 @@
 // NVFP4 block quantizer (Sec. 2.3; value set App. C.1), device side.
-// One block = 16 values held by one lane; every comparison is exact in fp32 because
-// 6*s, midpoint*s need at most 7 significand bits and the tensor scale g is a power of two.
+// One block = 16 values held by one lane.  The scale choice compares exactly (6*s needs at
+// most 6 significand bits and the tensor scale g is a power of two); the quotient e/s of the
+// element rule is the IEEE fp32 quotient.
 #pragma once
 #include "common.h"
 
@@ -34,33 +35,41 @@ __device__ __forceinline__ uint32_t e4m3_scale_round_up(float amax, QuantParams 
     return c;
 }
 
-// magnitude code 0..7 of |x| for block step `step` (= e4m3(scale)*g), ties to the even code
-__device__ __forceinline__ uint32_t e2m1_code(float a, float step) {
-    uint32_t c = (a > 0.25f * step) ? 1u : 0u;
-    c += (a >= 0.75f * step) ? 1u : 0u;
-    c += (a > 1.25f * step) ? 1u : 0u;
-    c += (a >= 1.75f * step) ? 1u : 0u;
-    c += (a > 2.5f * step) ? 1u : 0u;
-    c += (a >= 3.5f * step) ? 1u : 0u;
-    c += (a > 5.0f * step) ? 1u : 0u;
-    return c;
+// y = fl32(x / step), correctly rounded, from r = fl32(1/step): one product, the exact remainder by
+// fma, one correction (Markstein: correct unless the divisor's significand is all ones; a step has
+// at most 4 significant bits).  Keeps the sign of x for zeros and for r = 0.
+__device__ __forceinline__ float quot_rn(float x, float step, float r) {
+    float q = x * r;
+    float e = __builtin_fmaf(-q, step, x);
+    // (+0) + (-0) rounds to +0: restore the sign of x, which the IEEE quotient carries
+    return __builtin_copysignf(__builtin_fmaf(e, r, q), x);
 }
 
 // Quantize 16 values; returns the scale byte, writes 8 code bytes (low nibble = even element).
+// Element rule: y = fl32(x / (e4m3(scale) * g)) (IEEE fp32 quotient), code = nearest E2M1 value
+// of y, ties to the even code, magnitudes above 6 saturate, sign bit of x kept (also for zeros).
+// The packed converter of gfx950 does the rounding, saturation and nibble packing for two values.
 __device__ __forceinline__ uint32_t quantize_block16(const float (&v)[16], QuantParams qp, uint2& codes) {
     float amax = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
-    uint32_t sc = e4m3_scale_round_up(amax, qp);
-    float step = e4m3_decode(sc) * qp.g;
-    uint32_t w[2] = {0u, 0u};
+    for (int i = 0; i < 16; i += 2) amax = fmaxf(amax, fmaxf(fabsf(v[i]), fabsf(v[i + 1])));
+    const uint32_t sc = e4m3_scale_round_up(amax, qp);
+    // an all-zero block (scale byte 0) keeps only the signs: r = 0 maps every element to +-0
+    const float step = e4m3_decode(sc) * qp.g;
+    const float r = sc == 0u ? 0.0f : 1.0f / step;
+    float y[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        uint32_t mag = sc == 0u ? 0u : e2m1_code(fabsf(v[i]), step);
-        uint32_t nib = ((__float_as_uint(v[i]) >> 28) & 8u) | mag;
-        w[i >> 3] |= nib << (4 * (i & 7));
-    }
-    codes.x = w[0];
-    codes.y = w[1];
+    for (int i = 0; i < 16; ++i) y[i] = quot_rn(v[i], step, r);
+    uint32_t w0 = 0u, w1 = 0u;
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[0], y[1], 1.0f, 0);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[2], y[3], 1.0f, 1);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[4], y[5], 1.0f, 2);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[6], y[7], 1.0f, 3);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[8], y[9], 1.0f, 0);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[10], y[11], 1.0f, 1);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[12], y[13], 1.0f, 2);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[14], y[15], 1.0f, 3);
+    codes.x = w0;
+    codes.y = w1;
     return sc;
 }

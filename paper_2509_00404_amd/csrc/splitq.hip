@@ -16,7 +16,7 @@ union Frag {
     bf16x8_t v;
 };
 
-// (U diag(S)) and V as bf16 hi/lo, row-major with the rank padded to a multiple of 16
+// -(U diag(S)) and V as bf16 hi/lo, row-major with the rank padded to kp (a multiple of 16)
 __global__ void k_split_factors(const float* __restrict__ U, const float* __restrict__ S, const float* __restrict__ V,
                                 int64_t M, int64_t N, int k, int kp, bf16_t* __restrict__ us_hi,
                                 bf16_t* __restrict__ us_lo, bf16_t* __restrict__ v_hi, bf16_t* __restrict__ v_lo,
@@ -29,7 +29,7 @@ __global__ void k_split_factors(const float* __restrict__ U, const float* __rest
     float x = 0.0f;
     bf16_t *hi, *lo;
     if (row < M) {
-        if (c < k) x = U[row * k + c] * S[c];
+        if (c < k) x = -(U[row * k + c] * S[c]);
         hi = us_hi + row * kp + c;
         lo = us_lo + row * kp + c;
     } else {
@@ -43,73 +43,184 @@ __global__ void k_split_factors(const float* __restrict__ U, const float* __rest
     *lo = f32_to_bf16_rne(x - bf16_to_f32(h));
 }
 
-#define RQ_T 64
+#define RQ_ROWS 128              // rows per workgroup (4 waves x 32)
+#define RQ_COLS 64               // columns per step
+#define RQ_LDR 68                // padded fp32 row of the per-wave residual tile (16-byte aligned rows)
 
-// grid (ceil(N/64), ceil(M/64)); block 256: 4 waves, each one 32x32 MFMA tile of the residual
+// Residual + quantize.  One workgroup = 4 waves = 128 rows x a run of 64-column steps.
+// Per step and wave: R[32 x 64] = A + (-U S) V^T entirely on the matrix cores (A enters through an
+// identity operand, so the bf16 values are added exactly into the fp32 accumulators); the
+// -U S fragments of the wave's rows stay in registers for the whole run, V is staged through
+// double-buffered LDS, A for the next step is in flight while the current one is processed.
+// Blocks along the rows of A (transposed output) are quantized straight from the accumulators
+// after a half-wave swap; blocks along the columns go through a per-wave LDS tile.
+// grid: (ceil(M/128), csplit); block 256.  KS = kp / 16.
+template <int KS>
 __global__ void __launch_bounds__(256)
-k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, int kp,
+k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, int64_t cchunk,
                  const bf16_t* __restrict__ us_hi, const bf16_t* __restrict__ us_lo,
                  const bf16_t* __restrict__ v_hi, const bf16_t* __restrict__ v_lo, QuantParams qp,
                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint8_t* __restrict__ codes_t,
                  uint8_t* __restrict__ scales_t, float* __restrict__ R_debug) {
-    __shared__ float tile[RQ_T][RQ_T + 1];
+    constexpr int KP = 16 * KS, LDV = KP + 8;
+    constexpr int VVEC = (2 * RQ_COLS * (KP / 8) + 255) / 256;                  // 16-byte V vectors per thread
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][2][RQ_COLS][LDV];      // [buffer][hi/lo][column][k]
+    __shared__ __attribute__((aligned(16))) float Rt[4][32][RQ_LDR];           // per-wave residual tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t m0 = (int64_t)blockIdx.y * RQ_T, n0 = (int64_t)blockIdx.x * RQ_T;
-    const int rt = (wave >> 1) * 32, ct = (wave & 1) * 32;
-    const int half = lane >> 5;
-    int64_t arow = m0 + rt + (lane & 31), bcol = n0 + ct + (lane & 31);
-    if (arow >= M) arow = M - 1;            // in-bounds loads; the products are discarded below
-    if (bcol >= N) bcol = N - 1;
-    float16_t acc;
+    const int li = lane & 31, half = lane >> 5;
+    const int64_t wr0 = (int64_t)blockIdx.x * RQ_ROWS + 32 * wave;
+    const int64_t cbeg = (int64_t)blockIdx.y * cchunk;
+    const int64_t cend = cbeg + cchunk < N ? cbeg + cchunk : N;
+    if (cbeg >= N) return;
+    int64_t arow = wr0 + li;
+    if (arow >= M) arow = M - 1;              // in-bounds loads; results for such rows are not stored
+
+    // persistent -U S fragments of this wave's 32 rows
+    Frag ush[KS], usl[KS];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    for (int ks = 0; ks < kp; ks += 16) {
-        Frag ah, al, bh, bl;
-        ah.u = *reinterpret_cast<const uint4*>(us_hi + arow * kp + ks + 8 * half);
-        al.u = *reinterpret_cast<const uint4*>(us_lo + arow * kp + ks + 8 * half);
-        bh.u = *reinterpret_cast<const uint4*>(v_hi + bcol * kp + ks + 8 * half);
-        bl.u = *reinterpret_cast<const uint4*>(v_lo + bcol * kp + ks + 8 * half);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah.v, bh.v, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah.v, bl.v, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al.v, bh.v, acc, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) {
+        ush[ks].u = *reinterpret_cast<const uint4*>(us_hi + arow * KP + 16 * ks + 8 * half);
+        usl[ks].u = *reinterpret_cast<const uint4*>(us_lo + arow * KP + 16 * ks + 8 * half);
     }
-    // residual: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the wave tile
+    // identity operand: contraction slot (half h, step s, element e) stands for column 16h + 8s + e of a tile
+    Frag idf[2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        int rl = rt + 8 * (v >> 2) + 4 * half + (v & 3), cl = ct + (lane & 31);
-        int64_t m = m0 + rl, n = n0 + cl;
-        float r = 0.0f;
-        if (m < M && n < N) {
-            r = bf16_to_f32(A[m * lda + n]) - acc[v];
-            if (R_debug) R_debug[m * N + n] = r;
+    for (int s2 = 0; s2 < 2; ++s2) {
+        uint32_t w[4] = {0, 0, 0, 0};
+        int e = li - 8 * s2 - 16 * half;
+        if (e >= 0 && e < 8) w[e >> 1] = (e & 1) ? 0x3F800000u : 0x00003F80u;
+        idf[s2].u = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    const bf16_t* abase = A + arow * lda + 16 * half;
+    auto load_a = [&](int64_t n0, Frag (&a)[2][2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                int64_t n = n0 + 32 * t + 16 * half + 8 * s2;
+                a[t][s2].u = n < cend ? *reinterpret_cast<const uint4*>(abase + n0 + 32 * t + 8 * s2) : make_uint4(0, 0, 0, 0);
+            }
+    };
+    auto load_v = [&](int64_t n0, uint4 (&b)[VVEC]) {
+#pragma unroll
+        for (int v = 0; v < VVEC; ++v) {
+            int e = tid + 256 * v;
+            int part = e / (RQ_COLS * (KP / 8));
+            int r = e % (RQ_COLS * (KP / 8));
+            int c = r / (KP / 8), seg = r % (KP / 8);
+            b[v] = make_uint4(0, 0, 0, 0);
+            if (part < 2 && n0 + c < cend)
+                b[v] = *reinterpret_cast<const uint4*>((part ? v_lo : v_hi) + (n0 + c) * KP + seg * 8);
         }
-        tile[rl][cl] = r;
-    }
+    };
+    auto store_v = [&](int buf, const uint4 (&b)[VVEC]) {
+#pragma unroll
+        for (int v = 0; v < VVEC; ++v) {
+            int e = tid + 256 * v;
+            int part = e / (RQ_COLS * (KP / 8));
+            int r = e % (RQ_COLS * (KP / 8));
+            int c = r / (KP / 8), seg = r % (KP / 8);
+            if (part < 2) *reinterpret_cast<uint4*>(&Vs[buf][part][c][seg * 8]) = b[v];
+        }
+    };
+
+    Frag a_cur[2][2], a_nxt[2][2];
+    uint4 v_nxt[VVEC];
+    load_a(cbeg, a_cur);
+    load_v(cbeg, v_nxt);
+    store_v(0, v_nxt);
     __syncthreads();
-    const int line = tid >> 2, blk = tid & 3;
-    if (codes) {
-        int64_t m = m0 + line, n = n0 + blk * 16;
-        if (m < M && n < N) {
-            float x[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) x[i] = tile[line][blk * 16 + i];
-            uint2 c;
-            uint32_t sc = quantize_block16(x, qp, c);
-            *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
-            scales[m * (N / 16) + n / 16] = (uint8_t)sc;
+    int buf = 0;
+    for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) {
+        const bool more = n0 + RQ_COLS < cend;
+        if (more) {
+            load_a(n0 + RQ_COLS, a_nxt);
+            load_v(n0 + RQ_COLS, v_nxt);
         }
-    }
-    if (codes_t) {
-        int64_t n = n0 + line, m = m0 + blk * 16;
-        if (n < N && m < M) {
-            float x[16];
+        float16_t acc[2];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) x[i] = tile[blk * 16 + i][line];
-            uint2 c;
-            uint32_t sc = quantize_block16(x, qp, c);
-            *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
-            scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[t][0].v, idf[0].v, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[t][1].v, idf[1].v, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                Frag bh, bl;
+                bh.u = *reinterpret_cast<const uint4*>(&Vs[buf][0][32 * t + li][16 * ks + 8 * half]);
+                bl.u = *reinterpret_cast<const uint4*>(&Vs[buf][1][32 * t + li][16 * ks + 8 * half]);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ush[ks].v, bh.v, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ush[ks].v, bl.v, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(usl[ks].v, bh.v, acc[t], 0, 0, 0);
+            }
         }
+        // accumulator layout: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32 of tile t
+        // ---- blocks along the columns: through the wave's LDS tile ----
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Rt[wave][8 * (v >> 2) + 4 * half + (v & 3)][32 * t + li] = acc[t][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        {
+            const int64_t m = wr0 + li;
+#pragma unroll
+            for (int bb = 0; bb < 2; ++bb) {
+                const int blk = 2 * half + bb;
+                const int64_t n = n0 + 16 * blk;
+                float x[16];
+                const float4* src = reinterpret_cast<const float4*>(&Rt[wave][li][16 * blk]);
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 f = src[q4];
+                    x[4 * q4] = f.x; x[4 * q4 + 1] = f.y; x[4 * q4 + 2] = f.z; x[4 * q4 + 3] = f.w;
+                }
+                if (m < M && n < cend) {
+                    if (codes) {
+                        uint2 c;
+                        uint32_t sc = quantize_block16(x, qp, c);
+                        *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
+                        scales[m * (N / 16) + n / 16] = (uint8_t)sc;
+                    }
+                    if (R_debug) {
+                        float4* dst = reinterpret_cast<float4*>(R_debug + m * N + n);
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) dst[q4] = make_float4(x[4 * q4], x[4 * q4 + 1], x[4 * q4 + 2], x[4 * q4 + 3]);
+                    }
+                }
+            }
+        }
+        // ---- blocks along the rows (transposed output): half-wave swap, then in-lane ----
+        if (codes_t) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                float x[16];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    // swap the upper half of element i with the lower half of element i+8
+                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][i]), __float_as_uint(acc[t][i + 8]), false, false);
+                    // lower lanes: rows 0-15 of the tile, upper lanes: rows 16-31
+                    x[(i & 3) + 8 * (i >> 2)] = __uint_as_float(sw[0]);
+                    x[(i & 3) + 8 * (i >> 2) + 4] = __uint_as_float(sw[1]);
+                }
+                const int64_t n = n0 + 32 * t + li, m = wr0 + 16 * half;
+                if (n < cend && m < M) {
+                    uint2 c;
+                    uint32_t sc = quantize_block16(x, qp, c);
+                    *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
+                    scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
+                }
+            }
+        }
+        if (more) {
+            store_v(buf ^ 1, v_nxt);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) a_cur[t][s2] = a_nxt[t][s2];
+        }
+        __syncthreads();
+        buf ^= 1;
     }
 }
 
@@ -125,9 +236,11 @@ bool fp4_ok(const metis_fp4& f, int64_t rows, int64_t cols) {
 
 }  // namespace
 
+static int padded_rank(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : k <= 64 ? 64 : 128; }
+
 extern "C" size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k) {
-    if (M < 1 || N < 1 || k < 1) return 0;
-    int64_t kp = (k + 15) / 16 * 16;
+    if (M < 1 || N < 1 || k < 1 || k > 128) return 0;
+    int64_t kp = padded_rank(k);
     return align_up((size_t)M * kp * 2, 256) * 2 + align_up((size_t)N * kp * 2, 256) * 2;
 }
 
@@ -139,6 +252,7 @@ extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const floa
     if (A->dtype != METIS_BF16 || k > 128) return METIS_UNSUPPORTED;
     const int64_t M = A->rows, N = A->cols;
     if (M < 1 || N < 1 || A->ld < N) return METIS_BAD_SHAPE;
+    if (N % 16 || A->ld % 8 || reinterpret_cast<uintptr_t>(A->ptr) % 16) return METIS_BAD_SHAPE;   // 16-byte row loads
     const bool want_t = out->Rt.codes != nullptr;
     if (!fp4_ok(out->R, M, N)) return METIS_BAD_SHAPE;
     if (want_t && (!fp4_ok(out->Rt, N, M) || out->Rt.tscale != out->R.tscale)) return METIS_BAD_SHAPE;
@@ -147,7 +261,7 @@ extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const floa
     if (reinterpret_cast<uintptr_t>(workspace) % 16) return METIS_INVALID_ARG;
 
     hipStream_t s = (hipStream_t)stream;
-    const int kp = (k + 15) / 16 * 16;
+    const int kp = padded_rank(k);
     char* ws = (char*)workspace;
     const size_t ub = align_up((size_t)M * kp * 2, 256), vb = align_up((size_t)N * kp * 2, 256);
     bf16_t* us_hi = (bf16_t*)ws;
@@ -157,11 +271,23 @@ extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const floa
     int64_t tot = (M + N) * kp;
     hipLaunchKernelGGL(k_split_factors, dim3((unsigned)ceil_div64(tot, 256)), dim3(256), 0, s, U, S, V, M, N, k, kp,
                        us_hi, us_lo, v_hi, v_lo, out->S);
-    dim3 grid((unsigned)ceil_div64(N, RQ_T), (unsigned)ceil_div64(M, RQ_T));
+    // about two workgroups per CU; every workgroup walks at least four 64-column steps
+    const int64_t row_blocks = ceil_div64(M, RQ_ROWS);
+    int64_t want = ceil_div64(512, row_blocks);
+    int64_t cchunk = ceil_div64(ceil_div64(N, want), RQ_COLS) * RQ_COLS;
+    if (cchunk < 4 * RQ_COLS) cchunk = 4 * RQ_COLS;
+    dim3 grid((unsigned)row_blocks, (unsigned)ceil_div64(N, cchunk));
+    const QuantParams qp = make_quant_params(out->R.tscale);
+    uint8_t* ct = want_t ? out->Rt.codes : nullptr;
+    uint8_t* st_ = want_t ? out->Rt.scales : nullptr;
+    const bf16_t* Ap = (const bf16_t*)A->ptr;
     const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
-    hipLaunchKernelGGL(k_residual_quant, grid, dim3(256), 0, s, (const bf16_t*)A->ptr, A->ld, M, N, kp, us_hi, us_lo,
-                       v_hi, v_lo, make_quant_params(out->R.tscale), out->R.codes, out->R.scales,
-                       want_t ? out->Rt.codes : nullptr, want_t ? out->Rt.scales : nullptr, R_debug);
+    switch (kp / 16) {
+        case 1: hipLaunchKernelGGL(k_residual_quant<1>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
+        case 2: hipLaunchKernelGGL(k_residual_quant<2>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
+        case 4: hipLaunchKernelGGL(k_residual_quant<4>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
+        default: hipLaunchKernelGGL(k_residual_quant<8>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
+    }
     metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
     METIS_LAUNCH_CHECK();
     // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis

@@ -68,9 +68,17 @@ def test_against_exact_rational_rounding_random():
         nib = _nibbles(codes)
         for i in range(x.shape[0]):
             for b in range(2):
-                sidx, mags = _exact_quantize_block(x[i, 16 * b:16 * b + 16], g)
+                blk = x[i, 16 * b:16 * b + 16]
+                sidx, mags = _exact_quantize_block(blk, g)
                 assert scales[i, b] == sidx
-                assert list(nib[i, 16 * b:16 * b + 16] & 7) == mags
+                got = list(nib[i, 16 * b:16 * b + 16] & 7)
+                # the quotient is taken in fp32: it can only disagree with exact arithmetic when the
+                # exact quotient lies within an fp32 ulp of a rounding midpoint
+                step = quant.E4M3_POS[sidx] * g
+                for v, c_got, c_ref in zip(blk, got, mags):
+                    if c_got != c_ref:
+                        t = abs(v) / step
+                        assert min(abs(t - m) / m for m in quant.E2M1_MID) < 2.0 ** -22
         assert np.array_equal(nib >> 3, np.signbit(x).astype(np.int64))
 
 
@@ -102,7 +110,7 @@ def test_ties_go_to_even_code():
     assert list(d[8:15]) == [-0.0, -1.0, -1.0, -2.0, -2.0, -4.0, -4.0]
     assert d[0] == 6.0
     # just above / below a midpoint
-    blk[1:3] = [np.nextafter(0.25, 1), np.nextafter(0.75, 0)]
+    blk[1:3] = [np.nextafter(np.float32(0.25), np.float32(1)), np.nextafter(np.float32(0.75), np.float32(0))]
     d = quant.dequantize(*quant.quantize(blk[None, :]))[0]
     assert list(d[1:3]) == [0.5, 0.5]
 
@@ -174,3 +182,29 @@ def test_packing_layout():
     blk[0, 0], blk[0, 1] = 6.0, -3.0       # codes 7 and 8|5
     codes, _ = quant.quantize(blk)
     assert codes[0, 0] == (7 | (13 << 4))
+
+
+def test_ties_to_even_with_every_scale_mantissa():
+    # values exactly on a midpoint stay there under the fp32 quotient, for any scale mantissa
+    for sidx in (0x38, 0x39, 0x3B, 0x3F, 0x45, 0x12, 0x05):
+        s = quant.E4M3_POS[sidx]
+        blk = np.zeros(16)
+        blk[0] = 6.0 * s
+        blk[1:8] = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0]) * s
+        codes, scales = quant.quantize(blk[None, :])
+        assert scales[0, 0] == sidx
+        d = quant.dequantize(codes, scales)[0] / s
+        assert list(d[:8]) == [6.0, 0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
+
+
+def test_quotient_is_ieee_fp32_division():
+    # decision on y = fl32(x / step): place x one fp32 ulp around midpoint * step for a scale with mantissa
+    s = np.float32(quant.E4M3_POS[0x3B])             # 1.375
+    mid = np.float32(2.5) * s
+    for x in (np.nextafter(mid, np.float32(0)), mid, np.nextafter(mid, np.float32(10))):
+        blk = np.zeros(16, dtype=np.float32)
+        blk[0], blk[1] = np.float32(6) * s, x
+        codes, _ = quant.quantize(blk[None, :].astype(np.float64))
+        y = np.float32(x) / s
+        want = 4 if y <= np.float32(2.5) else 5          # 2.5 itself ties to the even code 4
+        assert (int(codes[0, 0]) >> 4) == want
