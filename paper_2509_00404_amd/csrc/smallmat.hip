@@ -92,9 +92,9 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
 }
 
 // ---------------------------------------------------------------------------------------
-// One-sided Jacobi on a symmetric positive semi-definite G (n <= SM_MAX_N):
-// rotate the columns of W = G until they are mutually orthogonal; then column j is
-// lambda_j v_j.  1024 threads = 64 groups of 16 lanes, one column pair per group and
+// One-sided Jacobi on a symmetric positive semi-definite G (n <= SM_MAX_N), applied to its
+// Cholesky factor: rotate the columns of W = L until they are mutually orthogonal; then
+// column j is sqrt(lambda_j) v_j.  1024 threads = 64 groups of 16 lanes, one column pair per group and
 // step, round-robin ordering; dot products by 16-lane DPP rotations.
 // Outputs (eigenvalues descending):
 //   lam  [n]            eigenvalues
@@ -117,18 +117,15 @@ __device__ __forceinline__ double group8_sum(double x) {
     return x;
 }
 
-// 1/sqrt(x) for x > 0: hardware seed + two Newton steps (full fp64 accuracy)
+// 1/sqrt(x), 1/x for x > 0: hardware seed + one Newton step.  The rotation only has to be
+// orthogonal to ~1e-13 (c and s come from the same t, so c^2 + s^2 = 1 up to the error of one rsqrt).
 __device__ __forceinline__ double rsqrt_nr(double x) {
     double y = __builtin_amdgcn_rsq(x);
-    y = y * (1.5 - 0.5 * x * y * y);
-    y = y * (1.5 - 0.5 * x * y * y);
-    return y;
+    return y * (1.5 - 0.5 * x * y * y);
 }
 __device__ __forceinline__ double rcp_nr(double x) {
     double y = __builtin_amdgcn_rcp(x);
-    y = y * (2.0 - x * y);
-    y = y * (2.0 - x * y);
-    return y;
+    return y * (2.0 - x * y);
 }
 
 #define JG 8      // lanes per column pair
@@ -158,15 +155,48 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         W[e] = (p < n && i < n) ? G[(size_t)i * n + p] : 0.0;
     }
     __syncthreads();
+    // Precondition: replace G by its Cholesky factor L (G = L L^T, column j of L in column j of W).
+    // The columns of L are far closer to orthogonal than those of G (one Cholesky-LR step), the
+    // rotations then converge in about half the sweeps, and column j ends as sigma_j u_j with
+    // sigma_j^2 = lambda_j, u_j the eigenvector of G.  A pivot at rounding level (semi-definite G)
+    // zeroes its column.
+    {
+        __shared__ double piv_floor;
+        if (tid == 0) {
+            double m = 0.0;
+            for (int j = 0; j < n; ++j) m = fmax(m, W[(size_t)j * ld + j]);
+            piv_floor = m * 1e-30;
+        }
+        __syncthreads();
+        for (int j = 0; j < n; ++j) {
+            const double d = W[(size_t)j * ld + j];
+            const bool ok = d > piv_floor;
+            const double r = ok ? rsqrt_nr(d) : 0.0, r2 = r * r;
+            // trailing update with the unscaled column j: L[i][c] -= L[i][j] L[c][j] / d   (i >= c > j)
+            for (int e = tid; e < (n - j - 1) * (n - j - 1); e += nthr) {
+                int c = j + 1 + e / (n - j - 1), i = j + 1 + e % (n - j - 1);
+                if (i >= c) W[(size_t)c * ld + i] -= W[(size_t)j * ld + i] * W[(size_t)j * ld + c] * r2;
+            }
+            __syncthreads();
+            // scale column j, clear the part above the diagonal (row index < column index)
+            for (int i = tid; i < n; i += nthr) {
+                double v = i >= j ? W[(size_t)j * ld + i] * r : 0.0;
+                W[(size_t)j * ld + i] = v;
+            }
+            // (column j is not read again by later steps, no barrier needed before the next pivot read:
+            //  the next pivot W[j+1][j+1] was finalised by the update above)
+        }
+        __syncthreads();
+    }
 
     const int npairs = ne / 2, nm1 = ne - 1;
     const bool active = grp < npairs;
 
-    // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta).  The second term is
+    // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-11.  The second term is
     // the rounding floor of a dot product of two columns that each carry an absolute error of
     // ~eps * lambda_max (the columns are lambda_j v_j, formed from O(lambda_max) entries): below it
     // a rotation only reshuffles noise and the sweeps would never end.
-    const double tol2 = 1e-26, floor2 = 1e-28;
+    const double tol2 = 1e-22, floor2 = 1e-28;
     for (int sweep = 0; sweep < 40; ++sweep) {
         // exact squared norms at the start of every sweep (the in-sweep updates only track them)
         if (active) {
@@ -269,12 +299,12 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         double l = nrm[pp];
         double v = l > 0.0 ? W[(size_t)pp * ld + i] / l : (i == j ? 1.0 : 0.0);
         if (vec) vec[e] = v;
-        if (tmat && j < kk) tmat[(size_t)i * kk + j] = l > 0.0 ? v / sqrt(l) : 0.0;
+        if (tmat && j < kk) tmat[(size_t)i * kk + j] = l > 0.0 ? v / l : 0.0;
     }
     if (tid < n) {
-        double l = nrm[order[tid]];
-        lam[tid] = l;
-        if (sval && tid < kk) sval[tid] = (float)sqrt(l);
+        double l = nrm[order[tid]];              // sigma_j = sqrt(lambda_j)
+        lam[tid] = l * l;
+        if (sval && tid < kk) sval[tid] = (float)l;
     }
 }
 
