@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -112,6 +114,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     n_split = sum(1 for o in ops if o.k)
     timers = {
@@ -145,6 +153,33 @@ def main():
                 "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_TFLOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
 
+    # per-call wall time of each entry point, measured after the timed region (5 repetitions)
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) / 5, 4)
+
+    phases = {}
+    for name, o in (("W", W), ("X", X), ("G", G)):
+        if o is None:
+            continue
+        if o.k:
+            phases[f"decompose_{name}_ms"] = timed(lambda: metis.decompose(o.A, o.k, o.p, o.rho, o.seed, workspace=o.ws_dec,
+                                                                        out=(o.U, o.S, o.V)))
+            phases[f"split_quantize_{name}_ms"] = timed(lambda: metis.split_quantize(o.A, o.U, o.S, o.V, o.q,
+                                                                                  workspace=o.ws_split))
+        else:
+            phases[f"quantize_{name}_ms"] = timed(lambda: metis.quantize(o.A, o.q.R, o.q.Rt))
+    phases["linear_fwd_ms"] = timed(lambda: metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin))
+    if full:
+        phases["linear_dgrad_ms"] = timed(lambda: metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin))
+        phases["linear_wgrad_ms"] = timed(lambda: metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin))
+    roofline["traffic"] = traffic_from_profile(args.workload)
+
     passes = {}
     if n_split:
         bc_ms = avg("broadcast", args.steps * n_split)
@@ -175,11 +210,26 @@ def main():
                    "L": L, "K": K, "N": N, "k": k, "p": p, "gemms_per_step": n_gemm, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "passes": passes,
+        "phases": phases,
     }
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, torch, T, c, prm, oq)
     print(json.dumps(out))
+
+
+def traffic_from_profile(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"bench_config{workload[1]}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("k_fp4_gemm_nt<4, 2, 2, 4"):
+                tail = line[52:].split()
+                return round((float(tail[0]) + float(tail[1])) * 2 ** 20)
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(np, torch, T, c, prm, oq):
