@@ -14,8 +14,8 @@ namespace {
 struct Layout {
     int64_t M, N, Ms;
     int k, r;
-    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_c, zero_bytes;
-    size_t off_idx, off_omega, off_linv, off_h1, off_h, off_b, off_lam, off_t, off_v0f, off_v0hi, off_v0lo,
+    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_c, off_b, zero_bytes;
+    size_t off_idx, off_omega, off_linv, off_h1, off_h, off_lam, off_t, off_v0f, off_v0hi, off_v0lo,
         off_lam3, off_w3, off_t3, total;
 };
 
@@ -31,13 +31,13 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     L.off_g2 = take(r * r * 8);
     L.off_g3 = take(kk * kk * 8);
     L.off_c = take((size_t)M * kk * 4);
+    L.off_b = take(r * (size_t)N * 8);
     L.zero_bytes = o;
     L.off_idx = take((size_t)Ms * 4);
     L.off_omega = take((size_t)N * r * 2);
     L.off_linv = take(r * r * 8);
     L.off_h1 = take((size_t)Ms * r * 8);
     L.off_h = take((size_t)Ms * r * 8);
-    L.off_b = take(r * (size_t)N * 8);
     L.off_lam = take(r * 8);
     L.off_t = take(r * kk * 8);
     L.off_v0f = take((size_t)N * kk * 4);
@@ -166,8 +166,8 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     if ((st = launch_chol_inv(s, G1b, r, Linv, info)) != METIS_OK) return st;
     launch_dgemm<double, double, EPI_STORE_F64>(s, op(H1, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi(H, r));
     // reduced matrix B = H^T A_s  (r x N)
-    launch_dgemm<double, bf16_t, EPI_STORE_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms, 1,
-                                                 epi(B, N));
+    launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms,
+                                                  split_for(Ms, ceil_div64(r, 32) * ceil_div64(N, 32)), epi(B, N));
     // top-k right singular vectors of B from the eigen-decomposition of B B^T
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(B, N, 1), op(B, N, 1), r, r, N, split_for(N, tiles_rr),
                                                   epi(G2, r));

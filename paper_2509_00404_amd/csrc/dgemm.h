@@ -115,10 +115,137 @@ k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk,
     }
 }
 
+// Epilogue shared by both kernels.
+template <int EPI>
+__device__ __forceinline__ void dgemm_store(const DEpilogue& ep, int64_t m, int64_t n, double x) {
+    if (EPI == EPI_STORE_F64) {
+        ((double*)ep.c)[m * ep.ldc + n] = x;
+    } else if (EPI == EPI_ATOMIC_F64) {
+        unsafeAtomicAdd(&((double*)ep.c)[m * ep.ldc + n], x);
+    } else if (EPI == EPI_STORE_F32) {
+        ((float*)ep.c)[m * ep.ldc + n] = (float)x;
+    } else {
+        float f = (float)x;
+        bf16_t hi = f32_to_bf16_rne(f);
+        float rem = f - bf16_to_f32(hi);
+        bf16_t lo = f32_to_bf16_rne(rem);
+        ep.hi_t[n * ep.ld_t + m] = hi;
+        ep.lo_t[n * ep.ld_t + m] = lo;
+        ((float*)ep.c)[m * ep.ldc + n] = bf16_to_f32(hi) + bf16_to_f32(lo);
+    }
+}
+
+// Larger variant for the two contractions that touch every sampled row (sketch, projection):
+// 64x64 block tile, each of the 4 waves a 32x32 tile (2x2 MFMA tiles), 32-deep stages, the next
+// stage's operands in flight (registers) while the current one is multiplied, double-buffered LDS.
+#define DGB_T 64
+#define DGB_K 32
+template <typename TA, typename TB, int EPI>
+__global__ void __launch_bounds__(256)
+k_dgemm_big(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
+    __shared__ double As[2][DGB_K][DGB_T + DG_PAD];
+    __shared__ double Bs[2][DGB_K][DGB_T + DG_PAD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t m0 = (int64_t)blockIdx.y * DGB_T, n0 = (int64_t)blockIdx.x * DGB_T;
+    const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
+    const int64_t kend = kbeg + kchunk < K ? kbeg + kchunk : K;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    double4_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (double4_t){0.0, 0.0, 0.0, 0.0};
+    const bool a_kfast = A.s_k == 1 && !A.map_k, b_kfast = B.s_k == 1 && !B.map_k;
+    // element e of a 64 x 32 stage: (outer, k) = (e/32, e%32) when k is the contiguous axis, else (e%64, e/64)
+    double ra[8], rb[8];
+    auto fetch = [&](int64_t kt) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int e = tid + 256 * i;
+            {
+                int mm = a_kfast ? e >> 5 : e & 63, kk = a_kfast ? e & 31 : e >> 6;
+                int64_t m = m0 + mm, k = kt + kk;
+                double v = 0.0;
+                if (m < M && k < kend) {
+                    int64_t mo = A.map_outer ? (int64_t)A.map_outer[m] : m;
+                    int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
+                    v = dload<TA>(A.p, mo * A.s_outer + ko * A.s_k);
+                }
+                ra[i] = v;
+            }
+            {
+                int nn = b_kfast ? e >> 5 : e & 63, kk = b_kfast ? e & 31 : e >> 6;
+                int64_t n = n0 + nn, k = kt + kk;
+                double v = 0.0;
+                if (n < N && k < kend) {
+                    int64_t no = B.map_outer ? (int64_t)B.map_outer[n] : n;
+                    int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
+                    v = dload<TB>(B.p, no * B.s_outer + ko * B.s_k);
+                }
+                rb[i] = v;
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int e = tid + 256 * i;
+            As[buf][a_kfast ? e & 31 : e >> 6][a_kfast ? e >> 5 : e & 63] = ra[i];
+            Bs[buf][b_kfast ? e & 31 : e >> 6][b_kfast ? e >> 5 : e & 63] = rb[i];
+        }
+    };
+    fetch(kbeg);
+    stash(0);
+    __syncthreads();
+    int buf = 0;
+    for (int64_t kt = kbeg; kt < kend; kt += DGB_K) {
+        const bool more = kt + DGB_K < kend;
+        if (more) fetch(kt + DGB_K);
+#pragma unroll
+        for (int s = 0; s < DGB_K / 4; ++s) {
+            const int kr = 4 * s + (lane >> 4);
+            double a0 = As[buf][kr][wm + (lane & 15)], a1 = As[buf][kr][wm + 16 + (lane & 15)];
+            double b0 = Bs[buf][kr][wn + (lane & 15)], b1 = Bs[buf][kr][wn + 16 + (lane & 15)];
+            acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                int64_t m = m0 + wm + 16 * i + 4 * v + (lane >> 4), n = n0 + wn + 16 * j + (lane & 15);
+                if (m < M && n < N) dgemm_store<EPI>(ep, m, n, acc[i][j][v]);
+            }
+}
+
 template <typename TA, typename TB, int EPI>
 static inline void launch_dgemm(hipStream_t s, DOperand A, DOperand B, int64_t M, int64_t N, int64_t K,
                                 int ksplit, DEpilogue ep) {
     if (ksplit < 1) ksplit = 1;
+    const bool big = M * N * K >= ((int64_t)1 << 26) && M >= 48 && N >= 48;
+    if (big) {
+        // split the contraction only as far as needed for ~512 workgroups (atomic epilogue only)
+        int64_t tiles = ceil_div64(M, DGB_T) * ceil_div64(N, DGB_T);
+        if (EPI == EPI_ATOMIC_F64) {
+            int64_t want = ceil_div64(512, tiles), maxs = K / 128 > 0 ? K / 128 : 1;
+            ksplit = (int)(want < maxs ? want : maxs);
+        } else {
+            ksplit = 1;
+        }
+        int64_t kchunk = ceil_div64(ceil_div64(K, ksplit), DGB_K) * DGB_K;
+        ksplit = (int)ceil_div64(K, kchunk);
+        dim3 grid((unsigned)ceil_div64(N, DGB_T), (unsigned)ceil_div64(M, DGB_T), (unsigned)ksplit);
+        hipLaunchKernelGGL((k_dgemm_big<TA, TB, EPI>), grid, dim3(256), 0, s, A, B, M, N, K, kchunk, ep);
+        return;
+    }
     int64_t kchunk = ceil_div64(ceil_div64(K, ksplit), DG_BK) * DG_BK;
     ksplit = (int)ceil_div64(K, kchunk);
     dim3 grid((unsigned)ceil_div64(N, DG_BN), (unsigned)ceil_div64(M, DG_BM), (unsigned)ksplit);

@@ -192,11 +192,12 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     const int npairs = ne / 2, nm1 = ne - 1;
     const bool active = grp < npairs;
 
-    // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-11.  The second term is
+    // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-7: the
+    // eigenvectors are then accurate to ~1e-7 / (relative gap), far inside the 1e-2 rad the split needs.  The second term is
     // the rounding floor of a dot product of two columns that each carry an absolute error of
     // ~eps * lambda_max (the columns are lambda_j v_j, formed from O(lambda_max) entries): below it
     // a rotation only reshuffles noise and the sweeps would never end.
-    const double tol2 = 1e-22, floor2 = 1e-28;
+    const double tol2 = 1e-14, floor2 = 1e-28;
     for (int sweep = 0; sweep < 40; ++sweep) {
         // exact squared norms at the start of every sweep (the in-sweep updates only track them)
         if (active) {
