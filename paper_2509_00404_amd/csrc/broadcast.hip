@@ -4,7 +4,7 @@
 // contraction runs twice per tile.  By-product: max|A|.
 //
 // One workgroup = 8 waves = 256 rows of A and one contraction range; each wave keeps its
-// 32 rows x 128 contraction elements of A for the NEXT stage in flight (registers) while it
+// 32 rows x 64 contraction elements of A for the NEXT stage in flight (registers) while it
 // multiplies the current one; the V0 stage is shared through double-buffered LDS.
 #include "broadcast.h"
 
@@ -13,39 +13,43 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 #define BC_WAVES 8
 #define BC_ROWS (32 * BC_WAVES)   // rows per workgroup
-#define BC_NC 128                 // contraction elements per stage
-#define BC_LDB (BC_NC + 8)        // padded LDS row (bf16 elements): +16 B keeps b128 reads conflict-free
+#define BC_NC 64                  // contraction elements per stage
+#define BC_LDB (BC_NC + 8)        // padded LDS row (bf16 elements): 144 B keeps b128 accesses conflict-free
 #define BC_KS (BC_NC / 16)        // MFMA steps per stage
+#define BC_DEPTH 3                // stages of A and V0 kept in flight in registers
 
 union Frag {
     uint4 u;
     bf16x8_t v;
 };
 
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+// max of two packed pairs of 16-bit magnitudes: one v_pk_max_u16
 __device__ __forceinline__ uint32_t pk_umax16(uint32_t a, uint32_t b) {
-    uint32_t lo = (a & 0xFFFFu) > (b & 0xFFFFu) ? (a & 0xFFFFu) : (b & 0xFFFFu);
-    uint32_t hi = (a >> 16) > (b >> 16) ? (a >> 16) : (b >> 16);
-    return lo | (hi << 16);
+    ushort2_t r = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a), __builtin_bit_cast(ushort2_t, b));
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // grid: (ceil(M/256), nsplit); block 512.  KT = number of 32-column tiles of V0 (k <= 32*KT).
+// A is read with fully coalesced 16-byte loads (8 lanes cover one 128-byte row piece) and passes
+// through a per-wave LDS slice to reach the MFMA operand layout; loading each lane's operand
+// fragment directly would touch every cache line 4-8 times with 16 bytes each.
 template <int KT>
 __global__ void __launch_bounds__(64 * BC_WAVES)
 k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, const bf16_t* __restrict__ V0hi,
-            const bf16_t* __restrict__ V0lo, int k, int64_t nchunk, float* __restrict__ C,
-            uint32_t* __restrict__ amax_bits) {
+            const bf16_t* __restrict__ V0lo, int k, float* __restrict__ Cpart, uint32_t* __restrict__ amax_bits) {
     constexpr int NT = 64 * BC_WAVES;
     constexpr int BVEC = (2 * 32 * KT * (BC_NC / 8) + NT - 1) / NT;          // 16-byte V0 vectors per thread
     __shared__ __attribute__((aligned(16))) bf16_t Bs[2][2][32 * KT][BC_LDB];  // [buffer][hi/lo][column][n]
+    __shared__ __attribute__((aligned(16))) bf16_t As[BC_WAVES][32][BC_LDB];   // per-wave slice of A
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * BC_ROWS + wave * 32;
-    const int64_t nbeg = (int64_t)blockIdx.y * nchunk;
-    const int64_t nend = nbeg + nchunk < N ? nbeg + nchunk : N;
-    const int half = lane >> 5;
-    int64_t row = row0 + (lane & 31);
-    const bool row_ok = row < M;
-    if (!row_ok) row = M - 1;                 // keep loads in bounds, result discarded
-    const bf16_t* arow = A + row * lda + (BC_NC / 2) * half;   // each lane reads BC_NC bytes contiguous per stage
+    // contraction stages are dealt round-robin to the gridDim.y workgroups of a row block, so that the
+    // workgroups running side by side read neighbouring pieces of the same rows (DRAM page locality)
+    const int64_t nstride = (int64_t)gridDim.y * BC_NC;
+    const int64_t nbeg = (int64_t)blockIdx.y * BC_NC;
+    const int li = lane & 31, half = lane >> 5;
+    const int lrow = lane >> 3, piece = lane & 7;           // coalesced load: 8 rows x 128 B per instruction
 
     float16_t acc[KT];
 #pragma unroll
@@ -54,13 +58,18 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
     uint32_t amax2 = 0;                       // two 15-bit magnitudes tracked as packed u16 maxima
 
-    // this lane's BC_KS x 16 B of A per stage: contraction slots of half h are n0 + 64h + 8s .. +7
-    auto load_a = [&](int64_t n0, Frag (&a)[BC_KS]) {
+    const bf16_t* aptr[4];
+    bool aok[4];
 #pragma unroll
-        for (int s = 0; s < BC_KS; ++s) {
-            int64_t n = n0 + (BC_NC / 2) * half + 8 * s;
-            a[s].u = n < nend ? *reinterpret_cast<const uint4*>(arow + n0 + 8 * s) : make_uint4(0, 0, 0, 0);
-        }
+    for (int q = 0; q < 4; ++q) {
+        int64_t r = row0 + 8 * q + lrow;
+        aok[q] = r < M;
+        aptr[q] = A + (aok[q] ? r : M - 1) * lda + 8 * piece;
+    }
+    auto load_a = [&](int64_t n0, uint4 (&a)[4]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            a[q] = (aok[q] && n0 + 8 * piece < N) ? *reinterpret_cast<const uint4*>(aptr[q] + n0) : make_uint4(0, 0, 0, 0);
     };
     auto load_b = [&](int64_t n0, uint4 (&b)[BVEC]) {
 #pragma unroll
@@ -71,7 +80,7 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
             int c = r / (BC_NC / 8), seg = r % (BC_NC / 8);
             int64_t n = n0 + seg * 8;
             b[v] = make_uint4(0, 0, 0, 0);
-            if (part < 2 && c < k && n < nend)
+            if (part < 2 && c < k && n < N)
                 b[v] = *reinterpret_cast<const uint4*>((part ? V0lo : V0hi) + (int64_t)c * N + n);
         }
     };
@@ -85,56 +94,74 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
             if (part < 2) *reinterpret_cast<uint4*>(&Bs[buf][part][c][seg * 8]) = b[v];
         }
     };
+    auto store_a = [&](const uint4 (&a)[4]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            *reinterpret_cast<uint4*>(&As[wave][8 * q + lrow][8 * piece]) = a[q];
+            // |x| as 15-bit patterns, compared as unsigned 16-bit integers
+            amax2 = pk_umax16(amax2, pk_umax16(a[q].x & 0x7FFF7FFFu, a[q].y & 0x7FFF7FFFu));
+            amax2 = pk_umax16(amax2, pk_umax16(a[q].z & 0x7FFF7FFFu, a[q].w & 0x7FFF7FFFu));
+        }
+    };
 
-    Frag a_cur[BC_KS], a_nxt[BC_KS];
-    uint4 b_nxt[BVEC];
-    load_a(nbeg, a_cur);
-    load_b(nbeg, b_nxt);
-    store_b(0, b_nxt);
+    // Register ring: the loads of stages i+1 .. i+BC_DEPTH are in flight while stage i is multiplied.
+    uint4 ra[BC_DEPTH][4], rb[BC_DEPTH][BVEC];
+    const int64_t nst = nbeg < N ? (N - nbeg + nstride - 1) / nstride : 0;     // stages of this workgroup
+#pragma unroll
+    for (int j = 0; j < BC_DEPTH; ++j) {
+        load_a(nbeg + j * nstride, ra[j]);       // out-of-range stages load zeros
+        load_b(nbeg + j * nstride, rb[j]);
+    }
+    store_a(ra[0]);
+    store_b(0, rb[0]);
     __syncthreads();
     int buf = 0;
-    for (int64_t n0 = nbeg; n0 < nend; n0 += BC_NC) {
-        const bool more = n0 + BC_NC < nend;
-        if (more) {
-            load_a(n0 + BC_NC, a_nxt);
-            load_b(n0 + BC_NC, b_nxt);
-        }
+    for (int64_t base = 0; base < nst; base += BC_DEPTH) {
 #pragma unroll
-        for (int s = 0; s < BC_KS; ++s) {
-            amax2 = pk_umax16(amax2, a_cur[s].u.x & 0x7FFF7FFFu);
-            amax2 = pk_umax16(amax2, a_cur[s].u.y & 0x7FFF7FFFu);
-            amax2 = pk_umax16(amax2, a_cur[s].u.z & 0x7FFF7FFFu);
-            amax2 = pk_umax16(amax2, a_cur[s].u.w & 0x7FFF7FFFu);
+        for (int j = 0; j < BC_DEPTH; ++j) {
+            const int64_t i = base + j;
+            if (i < nst) {
+                // slot j held stage i (now in LDS): refill it with stage i + BC_DEPTH
+                load_a(nbeg + (i + BC_DEPTH) * nstride, ra[j]);
+                load_b(nbeg + (i + BC_DEPTH) * nstride, rb[j]);
 #pragma unroll
-            for (int t = 0; t < KT; ++t) {
-                Frag bh, bl;
-                bh.u = *reinterpret_cast<const uint4*>(&Bs[buf][0][32 * t + (lane & 31)][(BC_NC / 2) * half + 8 * s]);
-                bl.u = *reinterpret_cast<const uint4*>(&Bs[buf][1][32 * t + (lane & 31)][(BC_NC / 2) * half + 8 * s]);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[s].v, bh.v, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[s].v, bl.v, acc[t], 0, 0, 0);
+                for (int s = 0; s < BC_KS; ++s) {
+                    Frag a;
+                    a.u = *reinterpret_cast<const uint4*>(&As[wave][li][16 * s + 8 * half]);
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) {
+                        Frag bh, bl;
+                        bh.u = *reinterpret_cast<const uint4*>(&Bs[buf][0][32 * t + li][16 * s + 8 * half]);
+                        bl.u = *reinterpret_cast<const uint4*>(&Bs[buf][1][32 * t + li][16 * s + 8 * half]);
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bh.v, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bl.v, acc[t], 0, 0, 0);
+                    }
+                }
+                if (i + 1 < nst) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    store_a(ra[(j + 1) % BC_DEPTH]);
+                    store_b(buf ^ 1, rb[(j + 1) % BC_DEPTH]);
+                }
+                __syncthreads();
+                buf ^= 1;
             }
         }
-        if (more) {
-            store_b(buf ^ 1, b_nxt);
-#pragma unroll
-            for (int s = 0; s < BC_KS; ++s) a_cur[s] = a_nxt[s];
-        }
-        __syncthreads();
-        buf ^= 1;
     }
-    // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    // Each contraction split writes its own partial C (plain stores); the consumers add the parts.
+    float* __restrict__ P = Cpart + (size_t)blockIdx.y * (size_t)M * k;
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-        int c = 32 * t + (lane & 31);
+        int c = 32 * t + li;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             int64_t r = row0 + 8 * (v >> 2) + 4 * half + (v & 3);
-            if (r < M && c < k) unsafeAtomicAdd(&C[r * k + c], acc[t][v]);
+            if (r < M && c < k) P[r * k + c] = acc[t][v];
         }
     }
     if (amax_bits) {
         uint32_t m = (amax2 & 0xFFFFu) > (amax2 >> 16) ? (amax2 & 0xFFFFu) : (amax2 >> 16);
-        if (!row_ok) m = 0;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             uint32_t other = __shfl_xor(m, o);
@@ -144,23 +171,27 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
     }
 }
 
-int launch_broadcast(hipStream_t s, const bf16_t* A, int64_t lda, int64_t M, int64_t N, const bf16_t* V0hi,
-                     const bf16_t* V0lo, int k, float* C, uint32_t* amax_bits) {
-    const int kt = (k + 31) / 32;
+int broadcast_splits(int64_t M, int64_t N) {
     int64_t row_blocks = ceil_div64(M, BC_ROWS);
-    // about 1.5 workgroups (12 waves) per CU, but at least four stages per workgroup: every extra
-    // contraction split costs one more fp32 atomic per output element
-    int64_t want = ceil_div64(384, row_blocks);
-    int64_t nchunk = ceil_div64(ceil_div64(N, want), BC_NC) * BC_NC;
-    if (nchunk < 4 * BC_NC) nchunk = 4 * BC_NC;
-    int nsplit = (int)ceil_div64(N, nchunk);
-    dim3 grid((unsigned)row_blocks, (unsigned)nsplit);
+    // about one workgroup (8 waves) per CU, at least two stages each, at most 16 partial results
+    int64_t stages = ceil_div64(N, BC_NC);
+    int64_t nsplit = ceil_div64(256, row_blocks);
+    if (nsplit > stages / 2) nsplit = stages / 2;
+    if (nsplit > 16) nsplit = 16;
+    if (nsplit < 1) nsplit = 1;
+    return (int)nsplit;
+}
+
+int launch_broadcast(hipStream_t s, const bf16_t* A, int64_t lda, int64_t M, int64_t N, const bf16_t* V0hi,
+                     const bf16_t* V0lo, int k, float* Cpart, uint32_t* amax_bits) {
+    const int kt = (k + 31) / 32;
+    dim3 grid((unsigned)ceil_div64(M, BC_ROWS), (unsigned)broadcast_splits(M, N));
     dim3 block(64 * BC_WAVES);
     switch (kt) {
-        case 1: hipLaunchKernelGGL(k_broadcast<1>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, nchunk, C, amax_bits); break;
-        case 2: hipLaunchKernelGGL(k_broadcast<2>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, nchunk, C, amax_bits); break;
-        case 3: hipLaunchKernelGGL(k_broadcast<3>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, nchunk, C, amax_bits); break;
-        case 4: hipLaunchKernelGGL(k_broadcast<4>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, nchunk, C, amax_bits); break;
+        case 1: hipLaunchKernelGGL(k_broadcast<1>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, Cpart, amax_bits); break;
+        case 2: hipLaunchKernelGGL(k_broadcast<2>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, Cpart, amax_bits); break;
+        case 3: hipLaunchKernelGGL(k_broadcast<3>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, Cpart, amax_bits); break;
+        case 4: hipLaunchKernelGGL(k_broadcast<4>, grid, block, 0, s, A, lda, M, N, V0hi, V0lo, k, Cpart, amax_bits); break;
         default: return METIS_UNSUPPORTED;
     }
     METIS_LAUNCH_CHECK();

@@ -30,9 +30,9 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     L.off_g1b = take(r * r * 8);
     L.off_g2 = take(r * r * 8);
     L.off_g3 = take(kk * kk * 8);
-    L.off_c = take((size_t)M * kk * 4);
     L.off_b = take(r * (size_t)N * 8);
     L.zero_bytes = o;
+    L.off_c = take((size_t)broadcast_splits(M, N) * (size_t)M * kk * 4);
     L.off_idx = take((size_t)Ms * 4);
     L.off_omega = take((size_t)N * r * 2);
     L.off_linv = take(r * r * 8);
@@ -60,6 +60,13 @@ DOperand op(const void* p, int64_t s_outer, int64_t s_k, const uint32_t* map_out
             const uint32_t* map_k = nullptr) {
     DOperand o;
     o.p = p; o.s_outer = s_outer; o.s_k = s_k; o.map_outer = map_outer; o.map_k = map_k;
+    o.nparts = 1; o.part_stride = 0;
+    return o;
+}
+
+DOperand op_parts(const void* p, int64_t s_outer, int64_t s_k, int nparts, int64_t part_stride) {
+    DOperand o = op(p, s_outer, s_k);
+    o.nparts = nparts; o.part_stride = part_stride;
     return o;
 }
 
@@ -183,11 +190,13 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     if (st != METIS_OK) return st;
     // singular-value form: C = U S W^T, V = V0 W
     const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
-    launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op(C, 1, k), op(C, 1, k), k, k, M, split_for(M, tiles_kk),
-                                                epi(G3, k));
+    const int cparts = broadcast_splits(M, N);
+    const int64_t cstride = M * (int64_t)k;
+    launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(C, 1, k, cparts, cstride), op_parts(C, 1, k, cparts, cstride),
+                                                k, k, M, split_for(M, tiles_kk), epi(G3, k));
     METIS_LAUNCH_CHECK();
     if ((st = launch_jacobi_eig(s, G3, k, k, lam3, W3, T3, S)) != METIS_OK) return st;
-    launch_dgemm<float, double, EPI_STORE_F32>(s, op(C, k, 1), op(T3, 1, k), M, k, k, 1, epi(U, k));
+    launch_dgemm<float, double, EPI_STORE_F32>(s, op_parts(C, k, 1, cparts, cstride), op(T3, 1, k), M, k, k, 1, epi(U, k));
     launch_dgemm<float, double, EPI_STORE_F32>(s, op(V0f, k, 1), op(W3, 1, k), N, k, k, 1, epi(V, k));
     METIS_LAUNCH_CHECK();
     return METIS_OK;

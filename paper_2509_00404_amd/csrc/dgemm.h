@@ -13,6 +13,8 @@ struct DOperand {
     int64_t s_k;                 // element stride between consecutive k
     const uint32_t* map_outer;   // optional gather on the outer index
     const uint32_t* map_k;       // optional gather on the contraction index
+    int nparts;                  // the operand is the sum of nparts arrays ...
+    int64_t part_stride;         // ... part_stride elements apart (nparts <= 1: a single array)
 };
 
 enum { EPI_STORE_F64 = 0, EPI_ATOMIC_F64 = 1, EPI_STORE_F32 = 2, EPI_STORE_SPLIT_T = 3 };
@@ -34,6 +36,13 @@ template <> __device__ __forceinline__ double dload<float>(const void* p, int64_
 }
 template <> __device__ __forceinline__ double dload<double>(const void* p, int64_t off) {
     return ((const double*)p)[off];
+}
+
+template <typename T>
+__device__ __forceinline__ double dload_sum(const DOperand& o, int64_t off) {
+    double v = dload<T>(o.p, off);
+    for (int p = 1; p < o.nparts; ++p) v += dload<T>(o.p, off + p * o.part_stride);
+    return v;
 }
 
 #define DG_BM 32
@@ -66,7 +75,7 @@ k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk,
                 if (m < M && k < kend) {
                     int64_t mo = A.map_outer ? (int64_t)A.map_outer[m] : m;
                     int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
-                    v = dload<TA>(A.p, mo * A.s_outer + ko * A.s_k);
+                    v = dload_sum<TA>(A, mo * A.s_outer + ko * A.s_k);
                 }
                 As[kk][mm] = v;
             }
@@ -77,7 +86,7 @@ k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk,
                 if (n < N && k < kend) {
                     int64_t no = B.map_outer ? (int64_t)B.map_outer[n] : n;
                     int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
-                    v = dload<TB>(B.p, no * B.s_outer + ko * B.s_k);
+                    v = dload_sum<TB>(B, no * B.s_outer + ko * B.s_k);
                 }
                 Bs[kk][nn] = v;
             }
@@ -169,7 +178,7 @@ k_dgemm_big(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kch
                 if (m < M && k < kend) {
                     int64_t mo = A.map_outer ? (int64_t)A.map_outer[m] : m;
                     int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
-                    v = dload<TA>(A.p, mo * A.s_outer + ko * A.s_k);
+                    v = dload_sum<TA>(A, mo * A.s_outer + ko * A.s_k);
                 }
                 ra[i] = v;
             }
@@ -180,7 +189,7 @@ k_dgemm_big(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kch
                 if (n < N && k < kend) {
                     int64_t no = B.map_outer ? (int64_t)B.map_outer[n] : n;
                     int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
-                    v = dload<TB>(B.p, no * B.s_outer + ko * B.s_k);
+                    v = dload_sum<TB>(B, no * B.s_outer + ko * B.s_k);
                 }
                 rb[i] = v;
             }

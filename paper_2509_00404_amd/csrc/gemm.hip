@@ -6,6 +6,7 @@
 // significant bits: exact) and multiplied on the fp16 matrix cores with fp32 accumulation.
 // The low-rank terms of the split enter as extra contraction columns (bf16, same
 // accumulators):  Abar Bbar^T = Ra Rb^T + [(Ra Vb + Ua Sa Va^T Vb) Sb] Ub^T + (Ua Sa)(Rb Va)^T.
+#include <stdlib.h>
 #include "common.h"
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -241,6 +242,161 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
         }
 }
 
+// Software-pipelined variant: 256 x 256 tile, 4 waves of 128 x 128 (16 accumulator tiles per wave,
+// one wave per SIMD).  Half as many code expansions per MFMA as the 8-wave kernel, so the matrix
+// cores rather than the vector ALUs bound it -- provided nothing waits: the raw codes/scales of
+// contraction step s+2 are read from LDS and step s+1 is expanded to fp16 while the 16 MFMAs of
+// step s run (explicit register double-buffering, interleaving pinned with sched_group_barrier).
+template <bool VEC, typename OUT>
+__global__ void __launch_bounds__(256)
+k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
+                   const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n) {
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
+                  BUF = OFF_SB + BN * G_SROW;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int tile = blockIdx.x;
+    {
+        const int total = gridDim.x;
+        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
+    }
+    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+    const int li = lane & 31, half = lane >> 5;
+
+    float16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int64_t niter = (K + G_KI - 1) / G_KI;
+    StageRegs<BM * 4 / NT> ra;
+    StageRegs<BN * 4 / NT> rb;
+    stage_load<BM, NT, VEC>(A, m0, K, 0, ra, tid);
+    stage_load<BN, NT, VEC>(B, n0, K, 0, rb, tid);
+    stage_store<BM, NT>(ra, lds, lds + OFF_SA, tid);
+    stage_store<BN, NT>(rb, lds + OFF_CB, lds + OFF_SB, tid);
+    __syncthreads();
+    for (int64_t it = 0; it < niter; ++it) {
+        const int cur = (int)(it & 1);
+        const bool more = it + 1 < niter;
+        if (more) {
+            stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
+            stage_load<BN, NT, VEC>(B, n0, K, (it + 1) * G_KI, rb, tid);
+        }
+        const uint8_t* bufc = lds + cur * BUF;
+        uint8_t* bufn = lds + (cur ^ 1) * BUF;
+        const uint8_t* ca = bufc + (wm + li) * G_CROW + 4 * half;
+        const uint8_t* cb = bufc + OFF_CB + (wn + li) * G_CROW + 4 * half;
+        const uint8_t* sa = bufc + OFF_SA + (wm + li) * G_SROW;
+        const uint8_t* sb = bufc + OFF_SB + (wn + li) * G_SROW;
+        uint32_t rawc[2][TM + TN], raws[2][TM + TN];
+        half8_t frag[2][TM + TN];
+        auto read_raw = [&](int s, int slot) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                rawc[slot][i] = *reinterpret_cast<const uint32_t*>(ca + 32 * i * G_CROW + 8 * s);
+                raws[slot][i] = *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * s);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                rawc[slot][TM + j] = *reinterpret_cast<const uint32_t*>(cb + 32 * j * G_CROW + 8 * s);
+                raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * s);
+            }
+        };
+        read_raw(0, 0);
+        read_raw(1, 1);
+#pragma unroll
+        for (int t = 0; t < TM + TN; ++t) frag[0][t] = dequant8(rawc[0][t], raws[0][t]);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int c = s & 1, n = c ^ 1;
+            // expand step s+1 (its raw words arrived during step s-1), then refill that raw slot with s+2
+            if (s + 1 < KS) {
+#pragma unroll
+                for (int t = 0; t < TM + TN; ++t) frag[n][t] = dequant8(rawc[n][t], raws[n][t]);
+            }
+            if (s + 2 < KS) read_raw(s + 2, c);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(frag[c][i], frag[c][TM + j], acc[i][j], 0, 0, 0);
+            // one MFMA, then its share of the vector work: 4 of the 64 expansion ops and 1 of the 16 LDS reads
+#pragma unroll
+            for (int m = 0; m < TM * TN; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        if (more) {
+            stage_store<BM, NT>(ra, bufn, bufn + OFF_SA, tid);
+            stage_store<BN, NT>(rb, bufn + OFF_CB, bufn + OFF_SB, tid);
+        }
+        __syncthreads();
+    }
+    if (Ke > 0) {
+        for (int ks = 0; ks < Ke; ks += 16) {
+            BFrag fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                int64_t r = m0 + wm + 32 * i + li;
+                if (r >= A.rows) r = A.rows - 1;
+                fa[i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + ks + 8 * half);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int64_t r = n0 + wn + 32 * j + li;
+                if (r >= B.rows) r = B.rows - 1;
+                fb[j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + ks + 8 * half);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int64_t c = n0 + wn + 32 * j + li;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int64_t r = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+            }
+        }
+}
+
+template <typename OUT>
+int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
+                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
+    const int64_t tm = ceil_div64(a.rows, 256), tn = ceil_div64(b.rows, 256);
+    if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+    constexpr size_t lds = gemm_lds_bytes<256, 256>();
+    dim3 grid((unsigned)(tm * tn));
+    if (vec) {
+        auto kern = k_fp4_gemm_nt_pipe<true, OUT>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+    } else {
+        auto kern = k_fp4_gemm_nt_pipe<false, OUT>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+    }
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
 template <int TM, int TN, int WMW, int WNW, typename OUT>
 int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
                      const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
@@ -273,8 +429,12 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
     const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
                      reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
-    if (M >= 1024 && N >= 1024)      // 256x256 tile, 8 waves of 128x64: two waves per SIMD hide each other's latencies
+    if (M >= 1024 && N >= 1024) {
+        static const bool use_pipe = getenv("METIS_GEMM_PIPE") != nullptr;
+        if (use_pipe) return launch_gemm_pipe<OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+        // 256x256 tile, 8 waves of 128x64: two waves per SIMD hide each other's latencies
         return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    }
     if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
