@@ -13,26 +13,34 @@ struct QuantParams {
 static inline QuantParams make_quant_params(float g) {
     QuantParams q;
     q.g = g;
-    q.inv6g = 1.0f / (6.0f * g);
+    q.inv6g = (1.0f / (6.0f * g)) * (1.0f - 4.0f * 1.1920929e-07f);   // biased low: see e4m3_scale_round_up
     return q;
 }
 
 // smallest E4M3 byte c (0..126) with 6*e4m3(c)*g >= amax, saturating at 126 (=448)
 __device__ __forceinline__ uint32_t e4m3_scale_round_up(float amax, QuantParams qp) {
+    // first guess from a product that is biased low by a few ulp: rounding up is monotone, so the guess
+    // is the answer or one below it, and a single exact comparison settles it
     float q = amax * qp.inv6g;
     uint32_t c;
     if (q >= 0.015625f) {                       // normal range: keep 3 mantissa bits, round up
         uint32_t u = __float_as_uint(q) + 0xFFFFFu;
         uint32_t e = u >> 23;                   // biased fp32 exponent (q > 0: sign bit clear)
-        c = e >= 120u + 16u ? 126u : ((e - 120u) << 3) | ((u >> 20) & 7u);
-        c = c > 126u ? 126u : c;
+        c = ((e - 120u) << 3) | ((u >> 20) & 7u);
+        c = e >= 136u ? 126u : (c > 126u ? 126u : c);
     } else {                                    // subnormal range: steps of 2^-9
         c = (uint32_t)ceilf(q * 512.0f);
     }
-    // the guess came from an inexact product: settle it with exact comparisons
     if (c < 126u && 6.0f * e4m3_decode(c) * qp.g < amax) ++c;
-    else if (c > 0u && 6.0f * e4m3_decode(c - 1u) * qp.g >= amax) --c;
     return c;
+}
+
+// fl32(1/step), correctly rounded, from the hardware reciprocal and one fma correction
+// (step has at most 4 significant bits; checked against IEEE division for every scale in the tests)
+__device__ __forceinline__ float recip_rn(float step) {
+    float r0 = __builtin_amdgcn_rcpf(step);
+    float e = __builtin_fmaf(-step, r0, 1.0f);
+    return __builtin_fmaf(e, r0, r0);
 }
 
 // y = fl32(x / step), correctly rounded, from r = fl32(1/step): one product, the exact remainder by
@@ -56,7 +64,7 @@ __device__ __forceinline__ uint32_t quantize_block16(const float (&v)[16], Quant
     const uint32_t sc = e4m3_scale_round_up(amax, qp);
     // an all-zero block (scale byte 0) keeps only the signs: r = 0 maps every element to +-0
     const float step = e4m3_decode(sc) * qp.g;
-    const float r = sc == 0u ? 0.0f : 1.0f / step;
+    const float r = sc == 0u ? 0.0f : recip_rn(step);
     float y[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) y[i] = quot_rn(v[i], step, r);

@@ -66,6 +66,10 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
     constexpr int VVEC = (2 * RQ_COLS * (KP / 8) + 255) / 256;                  // 16-byte V vectors per thread
     __shared__ __attribute__((aligned(16))) bf16_t Vs[2][2][RQ_COLS][LDV];      // [buffer][hi/lo][column][k]
     __shared__ __attribute__((aligned(16))) float Rt[4][32][RQ_LDR];           // per-wave residual tile
+    // per-wave bf16 slice of A, overlaid on the wave's residual tile: it is consumed (operand reads)
+    // before the tile is written and refilled after the tile has been read
+    typedef bf16_t ASlice[32][RQ_COLS + 8];
+    static_assert(sizeof(ASlice) <= sizeof(float) * 32 * RQ_LDR, "A slice must fit in the residual tile");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, half = lane >> 5;
     const int64_t wr0 = (int64_t)blockIdx.x * RQ_ROWS + 32 * wave;
@@ -82,24 +86,32 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         ush[ks].u = *reinterpret_cast<const uint4*>(us_hi + arow * KP + 16 * ks + 8 * half);
         usl[ks].u = *reinterpret_cast<const uint4*>(us_lo + arow * KP + 16 * ks + 8 * half);
     }
-    // identity operand: contraction slot (half h, step s, element e) stands for column 16h + 8s + e of a tile
+    // identity operand: contraction slot (step s, half h, element e) stands for column 16s + 8h + e of a tile
     Frag idf[2];
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
         uint32_t w[4] = {0, 0, 0, 0};
-        int e = li - 8 * s2 - 16 * half;
+        int e = li - 16 * s2 - 8 * half;
         if (e >= 0 && e < 8) w[e >> 1] = (e & 1) ? 0x3F800000u : 0x00003F80u;
         idf[s2].u = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    const bf16_t* abase = A + arow * lda + 16 * half;
-    auto load_a = [&](int64_t n0, Frag (&a)[2][2]) {
+    // A is read with coalesced 16-byte loads (8 lanes cover the 128 bytes one row contributes to a
+    // step) and reaches the MFMA operand layout through the wave's LDS slice
+    const int lrow = lane >> 3, piece = lane & 7;
+    const bf16_t* aptr[4];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+    for (int q = 0; q < 4; ++q) {
+        int64_t r = wr0 + 8 * q + lrow;
+        aptr[q] = A + (r < M ? r : M - 1) * lda + 8 * piece;
+    }
+    auto load_a = [&](int64_t n0, uint4 (&a)[4]) {
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                int64_t n = n0 + 32 * t + 16 * half + 8 * s2;
-                a[t][s2].u = n < cend ? *reinterpret_cast<const uint4*>(abase + n0 + 32 * t + 8 * s2) : make_uint4(0, 0, 0, 0);
-            }
+        for (int q = 0; q < 4; ++q)
+            a[q] = n0 + 8 * piece < cend ? *reinterpret_cast<const uint4*>(aptr[q] + n0) : make_uint4(0, 0, 0, 0);
+    };
+    auto store_a = [&](const uint4 (&a)[4]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[8 * q + lrow][8 * piece]) = a[q];
     };
     auto load_v = [&](int64_t n0, uint4 (&b)[VVEC]) {
 #pragma unroll
@@ -124,10 +136,11 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         }
     };
 
-    Frag a_cur[2][2], a_nxt[2][2];
+    uint4 a_nxt[4];
     uint4 v_nxt[VVEC];
-    load_a(cbeg, a_cur);
+    load_a(cbeg, a_nxt);
     load_v(cbeg, v_nxt);
+    store_a(a_nxt);
     store_v(0, v_nxt);
     __syncthreads();
     int buf = 0;
@@ -142,8 +155,11 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         for (int t = 0; t < 2; ++t) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[t][0].v, idf[0].v, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[t][1].v, idf[1].v, acc[t], 0, 0, 0);
+            Frag a0, a1;
+            a0.u = *reinterpret_cast<const uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[li][32 * t + 8 * half]);
+            a1.u = *reinterpret_cast<const uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[li][32 * t + 16 + 8 * half]);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, idf[0].v, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, idf[1].v, acc[t], 0, 0, 0);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 Frag bh, bl;
@@ -155,7 +171,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             }
         }
         // accumulator layout: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32 of tile t
-        // ---- blocks along the columns: through the wave's LDS tile ----
+        // ---- blocks along the columns: through the wave's LDS tile (this overwrites the A slice) ----
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -214,10 +232,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         }
         if (more) {
             store_v(buf ^ 1, v_nxt);
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) a_cur[t][s2] = a_nxt[t][s2];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            store_a(a_nxt);
         }
         __syncthreads();
         buf ^= 1;
