@@ -125,6 +125,10 @@ template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
 template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16_rne(v); }
 
+template <typename T> __device__ __forceinline__ void atomic_out(T* p, float v);
+template <> __device__ __forceinline__ void atomic_out<float>(float* p, float v) { unsafeAtomicAdd(p, v); }
+template <> __device__ __forceinline__ void atomic_out<bf16_t>(bf16_t*, float) {}   // splits are only used with fp32 output
+
 template <int BM, int BN>
 constexpr size_t gemm_lds_bytes() {
     return 2 * ((size_t)BM * (G_CROW + G_SROW) + (size_t)BN * (G_CROW + G_SROW));
@@ -137,7 +141,8 @@ constexpr size_t gemm_lds_bytes() {
 template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
 __global__ void __launch_bounds__(64 * WMW * WNW)
 k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n) {
+              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n,
+              int iters_per_split) {
     constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // LDS: [buffer][codes A | codes B | scales A | scales B]
@@ -161,16 +166,20 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int64_t niter = (K + G_KI - 1) / G_KI;
+    // blockIdx.y = contraction split: stages [it0, it1); more than one split accumulates with fp32 atomics
+    const int64_t niter_all = (K + G_KI - 1) / G_KI;
+    const int64_t it0 = (int64_t)blockIdx.y * iters_per_split;
+    const int64_t niter = it0 + iters_per_split < niter_all ? it0 + iters_per_split : niter_all;
+    const bool split = gridDim.y > 1;
     StageRegs<BM * 4 / NT> ra;
     StageRegs<BN * 4 / NT> rb;
-    stage_load<BM, NT, VEC>(A, m0, K, 0, ra, tid);
-    stage_load<BN, NT, VEC>(B, n0, K, 0, rb, tid);
+    stage_load<BM, NT, VEC>(A, m0, K, it0 * G_KI, ra, tid);
+    stage_load<BN, NT, VEC>(B, n0, K, it0 * G_KI, rb, tid);
     stage_store<BM, NT>(ra, lds, lds + OFF_SA, tid);
     stage_store<BN, NT>(rb, lds + OFF_CB, lds + OFF_SB, tid);
     __syncthreads();
-    for (int64_t it = 0; it < niter; ++it) {
-        const int cur = (int)(it & 1);
+    for (int64_t it = it0; it < niter; ++it) {
+        const int cur = (int)((it - it0) & 1);
         const bool more = it + 1 < niter;
         if (more) {
             stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
@@ -206,7 +215,7 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
         __syncthreads();
     }
     // low-rank terms: extra contraction columns in bf16, read straight from global memory
-    if (Ke > 0) {
+    if (Ke > 0 && blockIdx.y == 0) {
         for (int ks = 0; ks < Ke; ks += 16) {
             BFrag fa[TM], fb[TN];
 #pragma unroll
@@ -237,7 +246,10 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 int64_t r = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+                if (r < A.rows && c < B.rows) {
+                    if (split) atomic_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+                    else store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+                }
             }
         }
 }
@@ -399,31 +411,35 @@ int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
 
 template <int TM, int TN, int WMW, int WNW, typename OUT>
 int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
-                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
+                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc, int ksplit = 1) {
     constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
     static_assert(BM * 4 >= NT && BN * 4 >= NT, "every thread stages at least one code vector");
     const int64_t tm = ceil_div64(a.rows, BM), tn = ceil_div64(b.rows, BN);
     if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-    dim3 grid((unsigned)(tm * tn));
+    const int64_t niter = ceil_div64(K, G_KI);
+    if (ksplit < 1 || sizeof(OUT) != 4) ksplit = 1;
+    const int ips = (int)ceil_div64(niter, ksplit);
+    dim3 grid((unsigned)(tm * tn), (unsigned)ceil_div64(niter, ips));
     if (vec) {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, true, OUT>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn, ips);
     } else {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, false, OUT>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn, ips);
     }
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
 
+// ksplit > 1: C (fp32, zero on entry) accumulates the contraction splits with atomics
 template <typename OUT>
 int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf16_t* Aext, const bf16_t* Bext, int Ke,
-                float alpha, OUT* C, int64_t ldc) {
+                float alpha, OUT* C, int64_t ldc, int ksplit = 1) {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
     Fp4Operand a = {A.codes, A.scales, M}, b = {B.codes, B.scales, N};
     const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
@@ -435,9 +451,9 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
         // 256x256 tile, 8 waves of 128x64: two waves per SIMD hide each other's latencies
         return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     }
-    if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
-    if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
-    return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
+    if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
+    return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
 }
 
 // value of one FP4 element without the tensor scale: grid[code] * e4m3(scale)
@@ -486,6 +502,11 @@ __global__ void k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, 
         }
         Bext[row * Kep + c] = f32_to_bf16_rne(v);
     }
+}
+
+__global__ void k_zero_f32(float* __restrict__ p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, st = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += st) p[i] = 0.0f;
 }
 
 struct NtOperand {            // one side of Abar Bbar^T: Abar = U diag(S) V^T + R, R [rows, Kc]
@@ -542,9 +563,20 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         float* E2 = (float*)(ws + w.off_e2);
         bf16_t* ae = (bf16_t*)(ws + w.off_aext);
         bf16_t* be = (bf16_t*)(ws + w.off_bext);
-        if (kb > 0 && (st = launch_gemm<float>(s, a.R, b.Vt, nullptr, nullptr, 0, a.R.tscale * b.Vt.tscale, T1, kb)))
+        // skinny products: few output tiles, long contraction -> split it over workgroups
+        auto splits = [&](int64_t rows, int64_t cols) {
+            int64_t tiles = ceil_div64(rows, 128) * ceil_div64(cols, 64), iters = ceil_div64(Kc, G_KI);
+            int64_t want = ceil_div64(512, tiles), maxs = iters / 2 > 0 ? iters / 2 : 1;
+            return (int)(want < maxs ? want : maxs);
+        };
+        const int s1 = kb > 0 ? splits(Ma, kb) : 1, s2 = ka > 0 ? splits(Nb, ka) : 1;
+        if (s1 > 1 || s2 > 1) {     // T1, Mk, E2 are contiguous at the start of the workspace
+            hipLaunchKernelGGL(k_zero_f32, dim3(256), dim3(256), 0, s, (float*)ws, w.off_aext / 4);
+            METIS_LAUNCH_CHECK();
+        }
+        if (kb > 0 && (st = launch_gemm<float>(s, a.R, b.Vt, nullptr, nullptr, 0, a.R.tscale * b.Vt.tscale, T1, kb, s1)))
             return st;
-        if (ka > 0 && (st = launch_gemm<float>(s, b.R, a.Vt, nullptr, nullptr, 0, b.R.tscale * a.Vt.tscale, E2, ka)))
+        if (ka > 0 && (st = launch_gemm<float>(s, b.R, a.Vt, nullptr, nullptr, 0, b.R.tscale * a.Vt.tscale, E2, ka, s2)))
             return st;
         if (ka > 0 && kb > 0 &&
             (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb)))
