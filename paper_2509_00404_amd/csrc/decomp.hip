@@ -7,6 +7,7 @@
 // (C = A V0) runs on the bf16 matrix cores with V0 split in two bf16 parts.
 #include "broadcast.h"
 #include "dgemm.h"
+#include "dgemm_skinny.h"
 #include "smallmat.h"
 
 namespace {
@@ -159,8 +160,13 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     const int64_t tiles_zr = ceil_div64(Ms, 32) * ceil_div64(r, 32);
     const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
     // sketch Z = A_s Omega
-    launch_dgemm<bf16_t, bf16_t, EPI_ATOMIC_F64>(s, op(Ap, lda, 1, idx_use), op(om_use, 1, r), Ms, r, N,
-                                                  split_for(N, tiles_zr), epi(Zacc, r));
+    const bool fast = skinny_ok(Ap, lda, N, r) && reinterpret_cast<uintptr_t>(om_use) % 16 == 0;
+    if (fast) {
+        if ((st = launch_sketch(s, Ap, lda, idx_use, Ms, N, om_use, r, Zacc)) != METIS_OK) return st;
+    } else {
+        launch_dgemm<bf16_t, bf16_t, EPI_ATOMIC_F64>(s, op(Ap, lda, 1, idx_use), op(om_use, 1, r), Ms, r, N,
+                                                      split_for(N, tiles_zr), epi(Zacc, r));
+    }
     // CholeskyQR2: Z = H R
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(Zacc, 1, r), op(Zacc, 1, r), r, r, Ms,
                                                   split_for(Ms, tiles_rr), epi(G1, r));
@@ -173,8 +179,12 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     if ((st = launch_chol_inv(s, G1b, r, Linv, info)) != METIS_OK) return st;
     launch_dgemm<double, double, EPI_STORE_F64>(s, op(H1, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi(H, r));
     // reduced matrix B = H^T A_s  (r x N)
-    launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms,
-                                                  split_for(Ms, ceil_div64(r, 32) * ceil_div64(N, 32)), epi(B, N));
+    if (fast) {
+        if ((st = launch_project(s, H, r, Ap, lda, idx_use, Ms, N, B)) != METIS_OK) return st;
+    } else {
+        launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms,
+                                                      split_for(Ms, ceil_div64(r, 32) * ceil_div64(N, 32)), epi(B, N));
+    }
     // top-k right singular vectors of B from the eigen-decomposition of B B^T
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(B, N, 1), op(B, N, 1), r, r, N, split_for(N, tiles_rr),
                                                   epi(G2, r));

@@ -2,6 +2,7 @@
 // (Sec. 3.1): Cholesky + triangular inverse for CholeskyQR2 (thin QR Z = H R), and a
 // one-sided Jacobi eigensolver for the Gram matrices of the reduced problem.
 #include "smallmat.h"
+#include <cstdlib>
 
 // ---------------------------------------------------------------------------------------
 // Cholesky G = L L^T and Linv = L^-1 (lower triangular), n <= SM_MAX_N.
@@ -106,8 +107,8 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
 template <int CTRL>
 __device__ __forceinline__ double dpp_mov64(double x) {
     int lo = __double2loint(x), hi = __double2hiint(x);
-    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
-    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    lo = __builtin_amdgcn_mov_dpp(lo, CTRL, 0xF, 0xF, true);
+    hi = __builtin_amdgcn_mov_dpp(hi, CTRL, 0xF, 0xF, true);
     return __hiloint2double(hi, lo);
 }
 __device__ __forceinline__ double group8_sum(double x) {
@@ -128,32 +129,67 @@ __device__ __forceinline__ double rcp_nr(double x) {
     return y * (2.0 - x * y);
 }
 
-#define JG 8      // lanes per column pair
+template <int JGL> __device__ __forceinline__ double group_sum(double x);
+template <> __device__ __forceinline__ double group_sum<4>(double x) {
+    x += dpp_mov64<0xB1>(x);      // quad_perm [1,0,3,2]
+    x += dpp_mov64<0x4E>(x);      // quad_perm [2,3,0,1]
+    return x;
+}
+template <> __device__ __forceinline__ double group_sum<8>(double x) { return group8_sum(x); }
+template <> __device__ __forceinline__ double group_sum<16>(double x) {
+    x = group8_sum(x);
+    x += dpp_mov64<0x140>(x);     // row_mirror: lane i <-> 15-i within each 16 lanes
+    return x;
+}
 
-__host__ __device__ static inline int jacobi_ld(int n) { return ((n + 7) / 16) * 16 + 8; }
+// lanes per column pair: a step is bound by the latency of its chain of dependent operations, so the
+// widest group (shortest per-lane column pieces) wins even though it needs the most waves
+__host__ __device__ static inline int jacobi_lanes(int n) { (void)n; return 16; }
+// Column stride in doubles: at least n rounded up to 16 (the rows from n up exist and stay zero, so the
+// column loads and stores need no bounds checks), and = l (mod 2 l), which shifts neighbouring columns
+// by one group's width in the banks.
+__host__ __device__ static inline int jacobi_ld(int n, int l) {
+    const int rows = (n + 15) / 16 * 16;
+    return rows % (2 * l) == l ? rows : rows + l;
+}
 
-// NE = ceil(n / 8): elements of one column held by each of the 8 lanes of a group.
-// blockDim = 64 * ceil(ceil(n/2) / 8): one group of 8 lanes per column pair.
-template <int NE>
-__global__ void __launch_bounds__(512)
+// One-sided Jacobi on the Cholesky factor of G.  JGL lanes share a pair of columns, NE = ceil(n / JGL)
+// elements of each column per lane; the two columns of a group live in registers for a whole sweep.
+//
+// Ordering: odd-even transposition.  The active columns sit in slots 0 .. m-1; on even steps group g
+// rotates slots (2g, 2g+1), on odd steps slots (2g+1, 2g+2), and after every rotation the two
+// columns trade slots, so in m steps every pair of columns meets exactly once.  Between steps a
+// group keeps one column and passes the other to a neighbour through an LDS mailbox (one column
+// written and one read per group and step, one barrier per step).
+//
+// Deflation: a column that met every partner of a sweep without rotating is orthogonal (to tol)
+// to all the others, and rotations among the others keep it so; it leaves the tournament, and
+// the later sweeps run over the columns that still move.
+template <int NE, int JGL>
+__global__ void __launch_bounds__(1024)
 k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ lam, double* __restrict__ vec,
              double* __restrict__ tmat, float* __restrict__ sval) {
     extern __shared__ double sm[];
     const int ne = n + (n & 1);             // even number of columns (a zero column pads odd n)
-    // Column stride = 8 (mod 16) doubles: the 8 groups of a wave touch 8 consecutive columns in
-    // one LDS instruction, and this stride spreads them evenly over the banks.
-    const int ld = jacobi_ld(n);
-    double* W = sm;                         // column-major: W[p*ld + i] = element i of column p
-    double* nrm = sm + (size_t)ne * ld;     // [ne] squared column norms during the sweeps
-    int* order = (int*)(nrm + ne);          // [ne]
-    __shared__ int rotated;
+    // Column stride = 8 (mod 16) doubles spreads the columns that one LDS instruction touches over the banks.
+    const int ld = jacobi_ld(n, JGL);
+    double* W = sm;                              // column-major: W[p*ld + i] = element i of column p; column ne is a spare zero column
+    double* mailn = W + (size_t)(ne + 1) * ld;   // [ne/2] squared norm of the column in transit to even slot 2j
+    double* nrm = mailn + ne / 2;                // [ne + 1]
+    int* order = (int*)(nrm + ne + 1);           // [ne]
+    int* colmap = order + ne;                    // [ne + 1] slot -> column of the columns still rotating
+    int* rotf = colmap + ne + 1;                 // [ne + 1] column took part in a rotation this sweep
+    int* mailid = rotf + ne + 1;                 // [ne/2] column index of the column in transit
+    __shared__ int nact_sh, wcnt[2];
     __shared__ double amax_sh;
-    const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JG, gl = tid % JG;
+    const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JGL, gl = tid % JGL;
 
-    for (int e = tid; e < ne * ld; e += nthr) {
+    for (int e = tid; e < (ne + 1) * ld; e += nthr) {
         int p = e / ld, i = e - p * ld;
         W[e] = (p < n && i < n) ? G[(size_t)i * n + p] : 0.0;
     }
+    if (tid <= ne) { colmap[tid] = tid; rotf[tid] = 0; nrm[tid] = 0.0; }
+    if (tid == 0) { nact_sh = ne; wcnt[0] = 0; wcnt[1] = 0; }
     __syncthreads();
     // Precondition: replace G by its Cholesky factor L (G = L L^T, column j of L in column j of W).
     // The columns of L are far closer to orthogonal than those of G (one Cholesky-LR step), the
@@ -172,10 +208,11 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             const double d = W[(size_t)j * ld + j];
             const bool ok = d > piv_floor;
             const double r = ok ? rsqrt_nr(d) : 0.0, r2 = r * r;
-            // trailing update with the unscaled column j: L[i][c] -= L[i][j] L[c][j] / d   (i >= c > j)
-            for (int e = tid; e < (n - j - 1) * (n - j - 1); e += nthr) {
-                int c = j + 1 + e / (n - j - 1), i = j + 1 + e % (n - j - 1);
-                if (i >= c) W[(size_t)c * ld + i] -= W[(size_t)j * ld + i] * W[(size_t)j * ld + c] * r2;
+            // trailing update with the unscaled column j: L[i][c] -= L[i][j] L[c][j] / d   (i >= c > j);
+            // 16 threads walk down each column
+            for (int c = j + 1 + (tid >> 4); c < n; c += nthr >> 4) {
+                const double f = W[(size_t)j * ld + c] * r2;
+                for (int i = c + (tid & 15); i < n; i += 16) W[(size_t)c * ld + i] -= W[(size_t)j * ld + i] * f;
             }
             __syncthreads();
             // scale column j, clear the part above the diagonal (row index < column index)
@@ -189,102 +226,161 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         __syncthreads();
     }
 
-    const int npairs = ne / 2, nm1 = ne - 1;
-    const bool active = grp < npairs;
-
     // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-7: the
     // eigenvectors are then accurate to ~1e-7 / (relative gap), far inside the 1e-2 rad the split needs.  The second term is
     // the rounding floor of a dot product of two columns that each carry an absolute error of
     // ~eps * lambda_max (the columns are lambda_j v_j, formed from O(lambda_max) entries): below it
     // a rotation only reshuffles noise and the sweeps would never end.
     const double tol2 = 1e-14, floor2 = 1e-28;
-    for (int sweep = 0; sweep < 40; ++sweep) {
-        // exact squared norms at the start of every sweep (the in-sweep updates only track them)
-        if (active) {
+    double amax = 0.0;
+    double X[NE], Y[NE];
+    double nX = 0.0, nY = 0.0;
+    int idX = ne, idY = ne;
+
+    // rows n .. JGL*NE-1 of every column are zero padding: no bounds checks
+    auto load_col = [&](double* dst, const double* src) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                int p = 2 * grp + h;
-                double s = 0.0;
+        for (int e = 0; e < NE; ++e) dst[e] = src[gl + JGL * e];
+    };
+    auto store_col = [&](double* dst, const double* src) {
 #pragma unroll
-                for (int e = 0; e < NE; ++e) {
-                    int i = gl + JG * e;
-                    double x = i < n ? W[(size_t)p * ld + i] : 0.0;
-                    s += x * x;
-                }
-                s = group8_sum(s);
-                if (gl == 0) nrm[p] = s;
+        for (int e = 0; e < NE; ++e) dst[gl + JGL * e] = src[e];
+    };
+    // orthogonalise the pair in registers: X <- c X - s Y, Y <- s X + c Y
+    auto rotate = [&]() {
+        double g0 = 0.0, g1 = 0.0;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            if (e & 1) g1 += X[e] * Y[e]; else g0 += X[e] * Y[e];
+        }
+        const double gamma = group_sum<JGL>(g0 + g1);
+        if (gamma * gamma > tol2 * nX * nY + floor2 * amax * (nX + nY) && nX > 0.0 && nY > 0.0) {
+            // With tau = beta - alpha and hyp = sqrt(tau^2 + 4 gamma^2) the rotation that zeroes the pair
+            // (angle at most 45 degrees) has c^2 = (1 + |tau| / hyp) / 2 and s c = sign(tau) gamma / hyp.
+            // The hardware reciprocal square roots are good to ~1e-7, which only steers the angle; the
+            // pair (c, s) is then rescaled to unit length to second order (error ~1e-21).
+            const double tau = nY - nX;
+            const double hh = tau * tau + 4.0 * gamma * gamma;
+            const double rh = __builtin_amdgcn_rsq(hh);
+            const double c2 = 0.5 + 0.5 * fabs(tau) * rh;
+            const double rc = __builtin_amdgcn_rsq(c2);
+            double c = c2 * rc;
+            double s = (tau < 0.0 ? -gamma : gamma) * rh * rc;
+            const double d = c * c + (s * s - 1.0);
+            const double f = 1.0 + d * (0.375 * d - 0.5);
+            c *= f;
+            s *= f;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const double x = X[e], y = Y[e];
+                X[e] = c * x - s * y;
+                Y[e] = s * x + c * y;
+            }
+            // squared norms after the rotation; their sum is preserved
+            const double na = c * c * nX - 2.0 * c * s * gamma + s * s * nY;
+            nY = (nX + nY) - na;
+            nX = na;
+            if (gl == 0) {
+                rotf[idX] = 1;
+                rotf[idY] = 1;
             }
         }
-        if (tid == 0) rotated = 0;
-        __syncthreads();
-        if (tid == 0) {
-            double m = 0.0;
-            for (int j = 0; j < ne; ++j) m = fmax(m, nrm[j]);
-            amax_sh = m;
+    };
+
+    for (int sweep = 0; sweep < 40; ++sweep) {
+        const int m = nact_sh, gs = m / 2;           // even number of slots, groups this sweep
+        const bool act = grp < gs, inner = grp < gs - 1;
+        if (act) {
+            idX = colmap[2 * grp];
+            idY = colmap[2 * grp + 1];
+            load_col(X, W + (size_t)idX * ld);
+            load_col(Y, W + (size_t)idY * ld);
+            double sx = 0.0, sy = 0.0;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                sx += X[e] * X[e];
+                sy += Y[e] * Y[e];
+            }
+            nX = group_sum<JGL>(sx);              // exact squared norms at the start of every sweep
+            nY = group_sum<JGL>(sy);
         }
-        __syncthreads();
-        const double amax = amax_sh;
-        // round-robin pairing: column nm1 stays, the others rotate through the slots
-        int p = grp == 0 ? nm1 : grp % nm1;
-        int q = grp == 0 ? 0 : (nm1 - grp % nm1) % nm1;
-        for (int step = 0; step < nm1; ++step) {
-            if (active) {
-                double* wp = W + (size_t)p * ld;
-                double* wq = W + (size_t)q * ld;
-                double a[NE], b[NE];
-                double g0 = 0.0, g1 = 0.0;
-#pragma unroll
-                for (int e = 0; e < NE; ++e) {
-                    int i = gl + JG * e;
-                    a[e] = i < n ? wp[i] : 0.0;
-                    b[e] = i < n ? wq[i] : 0.0;
-                    if (e & 1) g1 += a[e] * b[e]; else g0 += a[e] * b[e];
-                }
-                const double alpha = nrm[p], beta = nrm[q];
-                const double gamma = group8_sum(g0 + g1);
-                if (gamma * gamma > tol2 * alpha * beta + floor2 * amax * (alpha + beta) && alpha > 0.0 && beta > 0.0) {
-                    // t = tan(theta) of the rotation that orthogonalises the pair (smaller root)
-                    const double tau = beta - alpha;
-                    const double hh = tau * tau + 4.0 * gamma * gamma;
-                    const double hyp = hh * rsqrt_nr(hh);
-                    const double t = (tau < 0.0 ? -2.0 : 2.0) * gamma * rcp_nr(fabs(tau) + hyp);
-                    const double c = rsqrt_nr(1.0 + t * t), s = c * t;
-#pragma unroll
-                    for (int e = 0; e < NE; ++e) {
-                        int i = gl + JG * e;
-                        if (i < n) {
-                            wp[i] = c * a[e] - s * b[e];
-                            wq[i] = s * a[e] + c * b[e];
-                        }
-                    }
-                    if (gl == 0) {
-                        nrm[p] = alpha - t * gamma;
-                        nrm[q] = beta + t * gamma;
-                        rotated = 1;
-                    }
-                }
-                if (grp == 0) {
-                    q = q + 1;
-                } else {
-                    p = p + 1 == nm1 ? 0 : p + 1;
-                    q = q + 1 == nm1 ? 0 : q + 1;
-                }
+        double* const mail_lo = W + (size_t)idX * ld;                                  // mailbox of slot 2g
+        double* const mail_hi = W + (size_t)(inner ? colmap[2 * grp + 2] : ne) * ld;   // mailbox of slot 2g + 2
+        __syncthreads();                          // every column is in registers before the first mailbox write
+        if (sweep == 0) {
+            if (act && gl == 0) { nrm[idX] = nX; nrm[idY] = nY; }
+            __syncthreads();
+            if (tid == 0) {
+                double mx = 0.0;
+                for (int j = 0; j < ne; ++j) mx = fmax(mx, nrm[j]);
+                amax_sh = mx;
             }
             __syncthreads();
+            amax = amax_sh;
         }
-        int any = rotated;
+        for (int s2 = 0; s2 < gs; ++s2) {
+            // even step: slots (2g, 2g+1) are (X, Y); afterwards Y moves down to group g-1
+            if (act) {
+                rotate();
+                store_col(mail_lo, Y);
+                if (gl == 0) { mailn[grp] = nY; mailid[grp] = idY; }
+            }
+            __syncthreads();
+            if (inner) {
+                load_col(Y, mail_hi);
+                nY = mailn[grp + 1];
+                idY = mailid[grp + 1];
+            }
+            // odd step: slots (2g+1, 2g+2) are (X, Y); afterwards X moves up to group g+1.  The last
+            // group holds the unpaired top slot and only renames it.
+            if (inner) {
+                rotate();
+                store_col(mail_hi, X);
+                if (gl == 0) { mailn[grp + 1] = nX; mailid[grp + 1] = idX; }
+            } else if (act) {
+#pragma unroll
+                for (int e = 0; e < NE; ++e) Y[e] = X[e];
+                nY = nX;
+                idY = idX;
+            }
+            __syncthreads();
+            if (act) {
+                load_col(X, mail_lo);
+                nX = mailn[grp];
+                idX = mailid[grp];
+            }
+        }
+        __syncthreads();                          // the last mailbox reads are done
+        if (act) {
+            store_col(W + (size_t)idX * ld, X);
+            store_col(W + (size_t)idY * ld, Y);
+        }
+        // keep the columns that rotated, in slot order
+        int myc = -1, f = 0;
         __syncthreads();
-        if (!any) break;
-    }
-    // column norms = eigenvalues
-    if (active) {
-        for (int h = 0; h < 2; ++h) {
-            int pp = 2 * grp + h;
-            double s = 0.0;
-            for (int i = gl; i < n; i += JG) s += W[(size_t)pp * ld + i] * W[(size_t)pp * ld + i];
-            s = group8_sum(s);
-            if (gl == 0) nrm[pp] = (pp < n) ? sqrt(s) : -1.0;
+        if (tid < m) { myc = colmap[tid]; f = rotf[myc]; }
+        const unsigned long long bal = __ballot(f);
+        const int wv = tid >> 6, ln = tid & 63;
+        if (ln == 0 && wv < 2) wcnt[wv] = __popcll(bal);
+        __syncthreads();
+        const int total = wcnt[0] + wcnt[1];
+        if (f) {
+            colmap[__popcll(bal & ((1ull << ln) - 1ull)) + (wv == 1 ? wcnt[0] : 0)] = myc;
+            rotf[myc] = 0;
         }
+        if (tid == 0) {
+            if (total & 1) colmap[total] = ne;
+            nact_sh = total + (total & 1);
+        }
+        __syncthreads();
+        if (total == 0) break;
+    }
+    // column norms = singular values of L = square roots of the eigenvalues
+    for (int pp = grp; pp < ne; pp += nthr / JGL) {
+        double s = 0.0;
+        for (int i = gl; i < n; i += JGL) s += W[(size_t)pp * ld + i] * W[(size_t)pp * ld + i];
+        s = group_sum<JGL>(s);
+        if (gl == 0) nrm[pp] = (pp < n) ? sqrt(s) : -1.0;
     }
     __syncthreads();
     if (tid < ne) {                          // rank by counting: descending, ties by index
@@ -320,27 +416,58 @@ int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t
 
 int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
                       float* sval) {
-    int ne = n + (n & 1);
-    size_t lds = ((size_t)ne * jacobi_ld(n) + ne) * sizeof(double) + (size_t)ne * sizeof(int);
-const int npairs = ne / 2;
-    const int threads = 64 * ((npairs + 7) / 8);          // one 8-lane group per column pair
-    if (threads > 512 || ne > threads) return METIS_UNSUPPORTED;
-#define JACOBI_CASE(NE)                                                                                       \
+    if (n < 1 || n > 128) return METIS_UNSUPPORTED;
+    int jgl = jacobi_lanes(n);
+    if (const char* e = getenv("METIS_JACOBI_LANES")) jgl = atoi(e);
+    const int ne = n + (n & 1), ld = jacobi_ld(n, jgl);
+    const size_t lds = ((size_t)(ne + 1) * ld + ne / 2 + ne + 1) * sizeof(double) +
+                       (size_t)(3 * ne + 2 + ne / 2) * sizeof(int);
+    // one group of jgl lanes per column pair; the Cholesky pre-pass and the bookkeeping use all 512 threads
+    const int threads = ne / 2 * jgl > 512 ? 1024 : 512;
+    if (ne / 2 * jgl > threads) return METIS_UNSUPPORTED;
+#define JACOBI_CASE(NE, JGL)                                                                                  \
     {                                                                                                         \
-        if (hipFuncSetAttribute((const void*)k_jacobi_eig<NE>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
+        if (hipFuncSetAttribute((const void*)k_jacobi_eig<NE, JGL>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                      \
             return METIS_HIP_ERROR;                                                                           \
-        hipLaunchKernelGGL(k_jacobi_eig<NE>, dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval); \
+        hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval); \
     }
-    const int need = (n + 7) / 8;
-    if (need <= 1) JACOBI_CASE(1)
-    else if (need <= 2) JACOBI_CASE(2)
-    else if (need <= 4) JACOBI_CASE(4)
-    else if (need <= 8) JACOBI_CASE(8)
-    else if (need <= 10) JACOBI_CASE(10)
-    else if (need <= 12) JACOBI_CASE(12)
-    else if (need <= 16) JACOBI_CASE(16)
-    else return METIS_UNSUPPORTED;
+    if (jgl == 4) {
+        switch ((n + 15) / 16) {
+            case 1: JACOBI_CASE(4, 4) break;
+            case 2: JACOBI_CASE(8, 4) break;
+            case 3: JACOBI_CASE(12, 4) break;
+            case 4: JACOBI_CASE(16, 4) break;
+            case 5: JACOBI_CASE(20, 4) break;
+            case 6: JACOBI_CASE(24, 4) break;
+            case 7: JACOBI_CASE(28, 4) break;
+            default: JACOBI_CASE(32, 4) break;
+        }
+    } else if (jgl == 8) {
+        switch ((n + 15) / 16) {
+            case 1: JACOBI_CASE(2, 8) break;
+            case 2: JACOBI_CASE(4, 8) break;
+            case 3: JACOBI_CASE(6, 8) break;
+            case 4: JACOBI_CASE(8, 8) break;
+            case 5: JACOBI_CASE(10, 8) break;
+            case 6: JACOBI_CASE(12, 8) break;
+            case 7: JACOBI_CASE(14, 8) break;
+            default: JACOBI_CASE(16, 8) break;
+        }
+    } else if (jgl == 16) {
+        switch ((n + 15) / 16) {
+            case 1: JACOBI_CASE(1, 16) break;
+            case 2: JACOBI_CASE(2, 16) break;
+            case 3: JACOBI_CASE(3, 16) break;
+            case 4: JACOBI_CASE(4, 16) break;
+            case 5: JACOBI_CASE(5, 16) break;
+            case 6: JACOBI_CASE(6, 16) break;
+            case 7: JACOBI_CASE(7, 16) break;
+            default: JACOBI_CASE(8, 16) break;
+        }
+    } else {
+        return METIS_UNSUPPORTED;
+    }
 #undef JACOBI_CASE
     METIS_LAUNCH_CHECK();
     return METIS_OK;
