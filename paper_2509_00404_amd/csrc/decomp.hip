@@ -202,11 +202,20 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
     const int cparts = broadcast_splits(M, N);
     const int64_t cstride = M * (int64_t)k;
-    launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(C, 1, k, cparts, cstride), op_parts(C, 1, k, cparts, cstride),
-                                                k, k, M, split_for(M, tiles_kk), epi(G3, k));
+    const bool gram_fast = k % 4 == 0;
+    if (gram_fast) {
+        // sums the broadcast's partial products into C (part 0) on the way
+        if ((st = launch_gram_parts(s, C, k, M, cparts, cstride, C, G3)) != METIS_OK) return st;
+    } else {
+        launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(C, 1, k, cparts, cstride), op_parts(C, 1, k, cparts, cstride),
+                                                    k, k, M, split_for(M, tiles_kk), epi(G3, k));
+    }
     METIS_LAUNCH_CHECK();
     if ((st = launch_jacobi_eig(s, G3, k, k, lam3, W3, T3, S)) != METIS_OK) return st;
-    launch_dgemm<float, double, EPI_STORE_F32>(s, op_parts(C, k, 1, cparts, cstride), op(T3, 1, k), M, k, k, 1, epi(U, k));
+    if (gram_fast)
+        launch_dgemm<float, double, EPI_STORE_F32>(s, op(C, k, 1), op(T3, 1, k), M, k, k, 1, epi(U, k));
+    else
+        launch_dgemm<float, double, EPI_STORE_F32>(s, op_parts(C, k, 1, cparts, cstride), op(T3, 1, k), M, k, k, 1, epi(U, k));
     launch_dgemm<float, double, EPI_STORE_F32>(s, op(V0f, k, 1), op(W3, 1, k), N, k, k, 1, epi(V, k));
     METIS_LAUNCH_CHECK();
     return METIS_OK;

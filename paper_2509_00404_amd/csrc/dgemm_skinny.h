@@ -303,3 +303,122 @@ static inline int launch_project(hipStream_t s, const double* H, int r, const bf
 #undef PROJECT_CASE
     return METIS_OK;
 }
+
+// ---------------------------------------------------------------------------------------
+// Gram matrix of a tall skinny matrix given as a sum of partial arrays (the broadcast's per-split
+// partial products):  S = sum_p C_p  (M x r, fp32),  G += S^T S  (r x r, fp64, zeroed by the caller).
+// The summed matrix is written back as fp32 (sum_out, may alias part 0) for the later U = S T.
+//   r % 4 == 0, C 16-byte aligned.
+// grid (ceil(M / GR_ROWS)), block 256; wave w owns row tiles w, w+4 of G and all NT column tiles.
+// ---------------------------------------------------------------------------------------
+#define GR_ROWS 32                    // rows of C per workgroup
+#define GR_KS 32                      // rows per stage
+template <int NT>
+__global__ void __launch_bounds__(256)
+k_gram_parts(const float* C, int r, int64_t M, int nparts, int64_t part_stride, float* sum_out,
+             double* __restrict__ G) {
+    constexpr int LDC = NT * 16 + ((NT * 16) % 32 == 16 ? 0 : 16);      // doubles, = 16 (mod 32)
+    constexpr int PIECES = (GR_KS * NT * 4 + 255) / 256;                // float4 pieces per thread and stage
+    constexpr int RT = (NT + 3) / 4;                                     // row tiles per wave
+    __shared__ double Cs[GR_KS * LDC];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t m0 = (int64_t)blockIdx.x * GR_ROWS;
+    const int rc = r >> 2;
+    for (int e = tid; e < GR_KS * LDC; e += 256) Cs[e] = 0.0;           // pad columns r .. 16 NT stay zero
+    double4_t acc[RT][NT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = (double4_t){0.0, 0.0, 0.0, 0.0};
+    __syncthreads();
+    for (int64_t mt = m0; mt < m0 + GR_ROWS && mt < M; mt += GR_KS) {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int c = tid + 256 * i, row = c / rc, col = 4 * (c - row * rc);
+            if (row < GR_KS) {
+                const int64_t m = mt + row;
+                double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+                if (m < M) {
+                    const float* src = C + m * r + col;
+                    int p = 0;
+                    for (; p + 4 <= nparts; p += 4) {          // four loads in flight
+                        float4 v[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(src + (p + u) * part_stride);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            s0 += (double)v[u].x;
+                            s1 += (double)v[u].y;
+                            s2 += (double)v[u].z;
+                            s3 += (double)v[u].w;
+                        }
+                    }
+                    for (; p < nparts; ++p) {
+                        const float4 v = *reinterpret_cast<const float4*>(src + p * part_stride);
+                        s0 += (double)v.x;
+                        s1 += (double)v.y;
+                        s2 += (double)v.z;
+                        s3 += (double)v.w;
+                    }
+                    if (sum_out) {
+                        // the Gram matrix is taken of the rounded sums, the same matrix the caller multiplies later
+                        const float4 o = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+                        *reinterpret_cast<float4*>(sum_out + m * r + col) = o;
+                        s0 = o.x; s1 = o.y; s2 = o.z; s3 = o.w;
+                    }
+                }
+                double* d = &Cs[row * LDC + col];
+                d[0] = s0; d[1] = s1; d[2] = s2; d[3] = s3;
+            }
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int s = 0; s < GR_KS / 4; ++s) {
+            const int kr = 4 * s + (lane >> 4);
+            double b[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = Cs[kr * LDC + 16 * j + (lane & 15)];
+            // no branch around the matrix instructions: a wave whose row tile does not exist recomputes
+            // tile 0 and drops the result in the epilogue
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                const int it = wave + 4 * i < NT ? wave + 4 * i : 0;
+                const double a = Cs[kr * LDC + 16 * it + (lane & 15)];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        const int it = wave + 4 * i;
+        if (it >= NT) continue;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int a = 16 * it + 4 * v + (lane >> 4), b = 16 * j + (lane & 15);
+                if (a < r && b < r) unsafeAtomicAdd(&G[(int64_t)a * r + b], acc[i][j][v]);
+            }
+    }
+}
+
+static inline int launch_gram_parts(hipStream_t s, const float* C, int r, int64_t M, int nparts, int64_t part_stride,
+                                    float* sum_out, double* G) {
+    dim3 grid((unsigned)ceil_div64(M, GR_ROWS));
+#define GRAM_CASE(NT) hipLaunchKernelGGL(k_gram_parts<NT>, grid, dim3(256), 0, s, C, r, M, nparts, part_stride, sum_out, G);
+    switch ((r + 15) / 16) {
+        case 1: GRAM_CASE(1) break;
+        case 2: GRAM_CASE(2) break;
+        case 3: GRAM_CASE(3) break;
+        case 4: GRAM_CASE(4) break;
+        case 5: GRAM_CASE(5) break;
+        case 6: GRAM_CASE(6) break;
+        case 7: GRAM_CASE(7) break;
+        case 8: GRAM_CASE(8) break;
+        default: return METIS_UNSUPPORTED;
+    }
+#undef GRAM_CASE
+    return METIS_OK;
+}
