@@ -5,9 +5,19 @@
 #include <cstdlib>
 
 // ---------------------------------------------------------------------------------------
-// Cholesky G = L L^T and Linv = L^-1 (lower triangular), n <= SM_MAX_N.
-// LDS: L [n][n+1] doubles, X [n][n+1] doubles.
+// Blocked Cholesky in LDS, shared by both kernels below.  On entry W holds the lower triangle of a
+// symmetric matrix column-major (element (i, c), i >= c, at W[c*ld + i]); on exit the same places
+// hold L, and rinv[c] = 1 / L[c][c].  Blocks of 4 columns, two workgroup barriers per block:
+//   1  one thread per row at or below the block reads the 4x4 diagonal block (LDS broadcast), factors
+//      it on its own (every thread repeats the same ~30 operations: cheaper than a barrier and a round
+//      trip through LDS) and solves its row's four entries against it,
+//   2  the trailing matrix takes the rank-4 update on the fp64 matrix cores: one
+//      v_mfma_f64_16x16x4_f64 per 16x16 tile, the block width being exactly the instruction's depth.
+// BAD_PIVOT_ZEROES: a pivot <= floor zeroes its column (semi-definite input, eigensolver); otherwise it is
+// replaced by 1e-300 and its 1-based index is written to *info (CholeskyQR2's rank check).
 // ---------------------------------------------------------------------------------------
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ double chol_rsqrt(double x) {
     double y = __builtin_amdgcn_rsq(x);
     y = y * (1.5 - 0.5 * x * y * y);
@@ -15,6 +25,111 @@ __device__ __forceinline__ double chol_rsqrt(double x) {
     return y;
 }
 
+template <bool BAD_PIVOT_ZEROES>
+__device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __restrict__ rinv, double floor_,
+                             int32_t* __restrict__ info) {
+    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
+#ifdef JAC_PROF
+    long long ca = 0, cc = 0, c0 = clock64();
+#define CH_MARK(acc) { long long c1 = clock64(); acc += c1 - c0; c0 = c1; }
+#else
+#define CH_MARK(acc)
+#endif
+    for (int k0 = 0; k0 < n; k0 += 4) {
+        // ---- 1: diagonal block (entries past n act as an identity block) and the rows below ----
+        double d[4][4];                                  // lower triangle of the diagonal block
+        double r[4];
+        if (tid < n - k0) {
+            const int i = k0 + tid;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int c = 0; c <= q; ++c)
+                    d[q][c] = (k0 + q < n) ? W[(size_t)(k0 + c) * ld + k0 + q] : (q == c ? 1.0 : 0.0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                double piv = d[c][c];
+#pragma unroll
+                for (int t = 0; t < c; ++t) piv -= d[c][t] * d[c][t];
+                if (BAD_PIVOT_ZEROES) {
+                    r[c] = piv > floor_ ? chol_rsqrt(piv) : 0.0;
+                } else {
+                    if (!(piv > 0.0)) {
+                        if (tid == 0 && info && k0 + c < n) *info = k0 + c + 1;
+                        piv = 1e-300;
+                    }
+                    r[c] = chol_rsqrt(piv);
+                }
+                d[c][c] = piv * r[c];                    // sqrt(pivot), or 0 for a zeroed column
+#pragma unroll
+                for (int q = c + 1; q < 4; ++q) {
+                    double v = d[q][c];
+#pragma unroll
+                    for (int t = 0; t < c; ++t) v -= d[q][t] * d[c][t];
+                    d[q][c] = v * r[c];
+                }
+            }
+            if (tid >= 4) {
+                double x[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    double v = W[(size_t)(k0 + c) * ld + i];
+#pragma unroll
+                    for (int t = 0; t < c; ++t) v -= x[t] * d[c][t];
+                    x[c] = v * r[c];
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) W[(size_t)(k0 + c) * ld + i] = x[c];
+            }
+        }
+        __syncthreads();
+        // the block's own rows are written once every thread has read the unfactored block; nothing
+        // reads them again before the next barrier
+        if (tid < 4 && tid < n - k0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (tid == q) {
+                    rinv[k0 + q] = r[q];
+#pragma unroll
+                    for (int c = 0; c <= q; ++c) W[(size_t)(k0 + c) * ld + k0 + q] = d[q][c];
+                }
+        }
+        CH_MARK(ca)
+        if (n - k0 <= 4) break;
+        // ---- 2: trailing update A22 -= L21 L21^T over the 16-aligned lower tiles that reach past k0 + 4 ----
+        const int t0 = (k0 + 4) & ~15;
+        const int T = (n - t0 + 15) / 16, ntiles = T * (T + 1) / 2;
+        for (int tile = wave; tile < ntiles; tile += nwaves) {
+            int ti = 0, rem = tile;
+            while (rem > ti) { rem -= ti + 1; ++ti; }       // tile -> (ti, tc), tc <= ti
+            const int i0 = t0 + 16 * ti, c0 = t0 + 16 * rem;
+            const int ia = i0 + (lane & 15), cb = c0 + (lane & 15);
+            const size_t col = (size_t)(k0 + (lane >> 4)) * ld;
+            const double av = (ia < n && ia >= k0 + 4) ? W[col + ia] : 0.0;
+            const double bv = (cb < n && cb >= k0 + 4) ? W[col + cb] : 0.0;
+            double4_t acc = {0.0, 0.0, 0.0, 0.0};
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            // D: lane l, element v -> (row 4 v + l / 16, column l % 16) of the tile
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + 4 * v + (lane >> 4), c = cb;
+                if (i < n && c < n && c >= k0 + 4 && i >= c) W[(size_t)c * ld + i] -= acc[v];
+            }
+        }
+        __syncthreads();
+        CH_MARK(cc)
+    }
+    __syncthreads();                                     // the last block's rows are visible to the caller
+#ifdef JAC_PROF
+    if (tid == 0) printf("chol n=%d: phase1 %lld trailing %lld\n", n, ca, cc);
+#endif
+}
+
+// ---------------------------------------------------------------------------------------
+// Cholesky G = L L^T and Linv = L^-1 (lower triangular), n <= SM_MAX_N.
+// LDS: L [n][n+1] doubles, X [n][n+1] doubles.
+// ---------------------------------------------------------------------------------------
 __device__ __forceinline__ double chol_group8_sum(double x) {
     int lo, hi;
     double y;
@@ -33,43 +148,17 @@ __global__ void __launch_bounds__(1024)
 k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32_t* __restrict__ info) {
     extern __shared__ double sm[];
     const int ld = n + 1;
-    double* L = sm;
-    double* X = sm + (size_t)n * ld;
+    double* L = sm;                              // column-major: L(i, c) at L[c*ld + i]
+    double* X = sm + (size_t)n * ld;             // L^-1, row-major: X(t, c) at X[t*ld + c]
     __shared__ double dinv[SM_MAX_CHOL];
     const int tid = threadIdx.x;
     for (int e = tid; e < n * n; e += 1024) {
         int i = e / n, j = e - i * n;
-        L[i * ld + j] = G[e];
+        L[j * ld + i] = G[e];
         X[i * ld + j] = 0.0;
     }
     __syncthreads();
-    // right-looking Cholesky, one barrier per column: the trailing update uses the unscaled
-    // column and 1/pivot; the columns are scaled by 1/sqrt(pivot) in one pass at the end
-    const int ti = tid >> 5, tc = tid & 31;
-    for (int j = 0; j < n; ++j) {
-        double d = L[j * ld + j];
-        if (!(d > 0.0)) {                   // rank-deficient sketch: flag it, keep going finitely
-            if (tid == 0 && info) *info = j + 1;
-            d = 1e-300;
-        }
-        const double r = chol_rsqrt(d);
-        if (tid == 0) dinv[j] = r;
-        const double r2 = r * r;
-        for (int i = j + 1 + ti; i < n; i += 32) {
-            double lij = L[i * ld + j] * r2;
-            for (int c = j + 1 + tc; c <= i; c += 32) L[i * ld + c] -= lij * L[c * ld + j];
-        }
-        __syncthreads();
-    }
-    for (int e = tid; e < n * n; e += 1024) {
-        int i = e / n, j = e - i * n;
-        if (j <= i) {
-            double v = L[i * ld + j];
-            if (i == j && !(v > 0.0)) v = 1e-300;
-            L[i * ld + j] = v * dinv[j];
-        }
-    }
-    __syncthreads();
+    chol_blocked<false>(L, ld, n, dinv, 0.0, info);
     // forward substitution: column c of L^-1 by a group of 8 lanes (same wave, so the group's own
     // LDS writes are visible to it without a workgroup barrier); X[t][c] keeps groups conflict-free
     {
@@ -77,7 +166,7 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
         if (c < n) {
             for (int i = c; i < n; ++i) {
                 double s = 0.0;
-                for (int t = c + gl; t < i; t += 8) s -= L[i * ld + t] * X[t * ld + c];
+                for (int t = c + gl; t < i; t += 8) s -= L[t * ld + i] * X[t * ld + c];
                 s = chol_group8_sum(s);
                 if (gl == 0) X[i * ld + c] = ((i == c ? 1.0 : 0.0) + s) * dinv[i];
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -179,11 +268,13 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     int* order = (int*)(nrm + ne + 1);           // [ne]
     int* colmap = order + ne;                    // [ne + 1] slot -> column of the columns still rotating
     int* rotf = colmap + ne + 1;                 // [ne + 1] column took part in a rotation this sweep
-    int* mailid = rotf + ne + 1;                 // [ne/2] column index of the column in transit
     __shared__ int nact_sh, wcnt[2];
     __shared__ double amax_sh;
     const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JGL, gl = tid % JGL;
 
+#ifdef JAC_PROF
+    const long long pt0 = clock64();
+#endif
     for (int e = tid; e < (ne + 1) * ld; e += nthr) {
         int p = e / ld, i = e - p * ld;
         W[e] = (p < n && i < n) ? G[(size_t)i * n + p] : 0.0;
@@ -198,30 +289,24 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     // zeroes its column.
     {
         __shared__ double piv_floor;
+        __shared__ double rinv_sh[SM_MAX_N];
         if (tid == 0) {
             double m = 0.0;
             for (int j = 0; j < n; ++j) m = fmax(m, W[(size_t)j * ld + j]);
             piv_floor = m * 1e-30;
         }
         __syncthreads();
-        for (int j = 0; j < n; ++j) {
-            const double d = W[(size_t)j * ld + j];
-            const bool ok = d > piv_floor;
-            const double r = ok ? rsqrt_nr(d) : 0.0, r2 = r * r;
-            // trailing update with the unscaled column j: L[i][c] -= L[i][j] L[c][j] / d   (i >= c > j);
-            // 16 threads walk down each column
-            for (int c = j + 1 + (tid >> 4); c < n; c += nthr >> 4) {
-                const double f = W[(size_t)j * ld + c] * r2;
-                for (int i = c + (tid & 15); i < n; i += 16) W[(size_t)c * ld + i] -= W[(size_t)j * ld + i] * f;
-            }
-            __syncthreads();
-            // scale column j, clear the part above the diagonal (row index < column index)
-            for (int i = tid; i < n; i += nthr) {
-                double v = i >= j ? W[(size_t)j * ld + i] * r : 0.0;
-                W[(size_t)j * ld + i] = v;
-            }
-            // (column j is not read again by later steps, no barrier needed before the next pivot read:
-            //  the next pivot W[j+1][j+1] was finalised by the update above)
+#ifdef JAC_PROF
+        const long long pt1 = clock64();
+#endif
+        chol_blocked<true>(W, ld, n, rinv_sh, piv_floor, nullptr);
+#ifdef JAC_PROF
+        if (tid == 0) printf("jacobi n=%d: load %lld chol %lld\n", n, pt1 - pt0, (long long)(clock64() - pt1));
+#endif
+        // the rotations work on whole columns: clear the part above the diagonal
+        for (int e = tid; e < n * n; e += nthr) {
+            const int c = e / n, i = e - c * n;
+            if (i < c) W[(size_t)c * ld + i] = 0.0;
         }
         __syncthreads();
     }
@@ -235,7 +320,6 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     double amax = 0.0;
     double X[NE], Y[NE];
     double nX = 0.0, nY = 0.0;
-    int idX = ne, idY = ne;
 
     // rows n .. JGL*NE-1 of every column are zero padding: no bounds checks
     auto load_col = [&](double* dst, const double* src) {
@@ -246,7 +330,8 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
 #pragma unroll
         for (int e = 0; e < NE; ++e) dst[gl + JGL * e] = src[e];
     };
-    // orthogonalise the pair in registers: X <- c X - s Y, Y <- s X + c Y
+    // orthogonalise the pair in registers: X <- c X - s Y, Y <- s X + c Y.  The squared norms travel with
+    // their columns; a set sign bit marks a column that has rotated in this sweep.
     auto rotate = [&]() {
         double g0 = 0.0, g1 = 0.0;
 #pragma unroll
@@ -254,12 +339,14 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             if (e & 1) g1 += X[e] * Y[e]; else g0 += X[e] * Y[e];
         }
         const double gamma = group_sum<JGL>(g0 + g1);
-        if (gamma * gamma > tol2 * nX * nY + floor2 * amax * (nX + nY) && nX > 0.0 && nY > 0.0) {
+        const double a = fabs(nX), b = fabs(nY);
+        // (a zero column gives gamma = 0 and never passes the test)
+        if (gamma * gamma > tol2 * a * b + floor2 * amax * (a + b)) {
             // With tau = beta - alpha and hyp = sqrt(tau^2 + 4 gamma^2) the rotation that zeroes the pair
             // (angle at most 45 degrees) has c^2 = (1 + |tau| / hyp) / 2 and s c = sign(tau) gamma / hyp.
             // The hardware reciprocal square roots are good to ~1e-7, which only steers the angle; the
             // pair (c, s) is then rescaled to unit length to second order (error ~1e-21).
-            const double tau = nY - nX;
+            const double tau = b - a;
             const double hh = tau * tau + 4.0 * gamma * gamma;
             const double rh = __builtin_amdgcn_rsq(hh);
             const double c2 = 0.5 + 0.5 * fabs(tau) * rh;
@@ -276,20 +363,17 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
                 X[e] = c * x - s * y;
                 Y[e] = s * x + c * y;
             }
-            // squared norms after the rotation; their sum is preserved
-            const double na = c * c * nX - 2.0 * c * s * gamma + s * s * nY;
-            nY = (nX + nY) - na;
-            nX = na;
-            if (gl == 0) {
-                rotf[idX] = 1;
-                rotf[idY] = 1;
-            }
+            // squared norms after the rotation (their sum is preserved), flagged as rotated
+            const double na = fabs(a + (s * s) * tau - 2.0 * (c * s) * gamma);
+            nX = -na;
+            nY = -fabs((a + b) - na);
         }
     };
 
     for (int sweep = 0; sweep < 40; ++sweep) {
         const int m = nact_sh, gs = m / 2;           // even number of slots, groups this sweep
         const bool act = grp < gs, inner = grp < gs - 1;
+        int idX = ne, idY = ne;
         if (act) {
             idX = colmap[2 * grp];
             idY = colmap[2 * grp + 1];
@@ -306,6 +390,8 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         }
         double* const mail_lo = W + (size_t)idX * ld;                                  // mailbox of slot 2g
         double* const mail_hi = W + (size_t)(inner ? colmap[2 * grp + 2] : ne) * ld;   // mailbox of slot 2g + 2
+        // a full sweep reverses the slot order: the columns this group ends up with
+        const int endX = act ? colmap[m - 1 - 2 * grp] : ne, endY = act ? colmap[m - 2 - 2 * grp] : ne;
         __syncthreads();                          // every column is in registers before the first mailbox write
         if (sweep == 0) {
             if (act && gl == 0) { nrm[idX] = nX; nrm[idY] = nY; }
@@ -323,37 +409,38 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             if (act) {
                 rotate();
                 store_col(mail_lo, Y);
-                if (gl == 0) { mailn[grp] = nY; mailid[grp] = idY; }
+                mailn[grp] = nY;                  // all lanes of the group write the same value
             }
             __syncthreads();
             if (inner) {
                 load_col(Y, mail_hi);
                 nY = mailn[grp + 1];
-                idY = mailid[grp + 1];
             }
             // odd step: slots (2g+1, 2g+2) are (X, Y); afterwards X moves up to group g+1.  The last
             // group holds the unpaired top slot and only renames it.
             if (inner) {
                 rotate();
                 store_col(mail_hi, X);
-                if (gl == 0) { mailn[grp + 1] = nX; mailid[grp + 1] = idX; }
+                mailn[grp + 1] = nX;
             } else if (act) {
 #pragma unroll
                 for (int e = 0; e < NE; ++e) Y[e] = X[e];
                 nY = nX;
-                idY = idX;
             }
             __syncthreads();
             if (act) {
                 load_col(X, mail_lo);
                 nX = mailn[grp];
-                idX = mailid[grp];
             }
         }
         __syncthreads();                          // the last mailbox reads are done
         if (act) {
-            store_col(W + (size_t)idX * ld, X);
-            store_col(W + (size_t)idY * ld, Y);
+            store_col(W + (size_t)endX * ld, X);
+            store_col(W + (size_t)endY * ld, Y);
+            if (gl == 0) {
+                if (__double2hiint(nX) < 0) rotf[endX] = 1;
+                if (__double2hiint(nY) < 0) rotf[endY] = 1;
+            }
         }
         // keep the columns that rotated, in slot order
         int myc = -1, f = 0;
