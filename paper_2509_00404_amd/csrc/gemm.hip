@@ -18,7 +18,7 @@ namespace {
 
 #define G_KI 128                    // contraction elements per LDS stage
 #define G_CROW (G_KI / 2 + 4)       // padded code row in LDS (bytes): dword stride 17, conflict-free
-#define G_SROW 36                   // 8 block scales per row and stage, each as a duplicated fp16 pair, + pad
+#define G_SROW 20                   // 8 block scales per row and stage as fp16, + pad (dword stride 5: conflict-free)
 
 struct Fp4Operand {
     const uint8_t* codes;           // [rows, K/2]
@@ -26,25 +26,64 @@ struct Fp4Operand {
     int64_t rows;
 };
 
-__device__ __forceinline__ uint32_t e4m3_to_f16_pair(uint32_t b) {
-    // normal: exponent rebias 7 -> 15, mantissa left-aligned; subnormal b*2^-9 is a normal fp16
-    uint32_t h;
-    if (b >= 8u) {
-        h = (b << 7) + 0x2000u;
-    } else {
-        _Float16 f = (_Float16)((float)b * 0.001953125f);
-        h = __builtin_bit_cast(uint16_t, f);
-    }
-    return h | (h << 16);
-}
-
-// One thread's share of a stage of ROWS rows x 64 B of codes: V = ROWS*4/NT 16-byte code vectors and
-// (threads below ROWS) the 8 scale bytes of one row.  NT = threads per workgroup.
+// One thread's share of a stage of ROWS rows x 64 B of codes: V = ROWS*4/NT 16-byte code vectors.
+// NT = threads per workgroup.
 template <int V>
 struct StageRegs {
     uint4 c[V];
-    uint2 s;
 };
+
+// The 8 scale bytes per row and stage of both operands, dealt over all threads of the workgroup:
+// thread t takes rows t, t + NT, ... of the BM + BN staged rows (A's rows first).
+template <int V>
+struct ScaleRegs {
+    uint2 s[V];
+};
+
+template <int BM, int BN, int NT, bool VEC>
+__device__ __forceinline__ void scale_load(const Fp4Operand& A, const Fp4Operand& B, int64_t m0, int64_t n0, int64_t K,
+                                           int64_t k0, ScaleRegs<(BM + BN + NT - 1) / NT>& rg, int tid) {
+    constexpr int V = (BM + BN + NT - 1) / NT;
+    const int64_t sstride = K / 16;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int e = tid + NT * v;
+        if ((BM + BN) % NT == 0 || e < BM + BN) {
+            const bool isa = e < BM;
+            const Fp4Operand& op = isa ? A : B;
+            int64_t gr = isa ? m0 + e : n0 + (e - BM);
+            if (gr >= op.rows) gr = op.rows - 1;
+            const uint8_t* src = op.scales + gr * sstride + k0 / 16;
+            if (VEC) {
+                rg.s[v] = *reinterpret_cast<const uint2*>(src);
+            } else {
+                uint32_t w[2] = {0, 0};
+                for (int i = 0; i < 8; ++i)
+                    if (k0 / 16 + i < sstride) w[i >> 2] |= (uint32_t)src[i] << (8 * (i & 3));
+                rg.s[v] = make_uint2(w[0], w[1]);
+            }
+        }
+    }
+}
+
+// E4M3 bytes -> fp16 with the hardware FP8 converter (exact; checked against the format's
+// definition for all 256 bytes), 8 scales = 16 bytes per row
+template <int BM, int BN, int NT>
+__device__ __forceinline__ void scale_store(const ScaleRegs<(BM + BN + NT - 1) / NT>& rg, uint8_t* __restrict__ lsa,
+                                            uint8_t* __restrict__ lsb, int tid) {
+    constexpr int V = (BM + BN + NT - 1) / NT;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int e = tid + NT * v;
+        if ((BM + BN) % NT == 0 || e < BM + BN) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(e < BM ? lsa + e * G_SROW : lsb + (e - BM) * G_SROW);
+            dst[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rg.s[v].x, 1.0f, false));
+            dst[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rg.s[v].x, 1.0f, true));
+            dst[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rg.s[v].y, 1.0f, false));
+            dst[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rg.s[v].y, 1.0f, true));
+        }
+    }
+}
 
 template <int ROWS, int NT, bool VEC>
 __device__ __forceinline__ void stage_load(const Fp4Operand& op, int64_t r0, int64_t K, int64_t k0,
@@ -69,24 +108,10 @@ __device__ __forceinline__ void stage_load(const Fp4Operand& op, int64_t r0, int
             rg.c[v] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
-    if (tid < ROWS) {
-        int64_t gr = r0 + tid;
-        if (gr >= op.rows) gr = op.rows - 1;
-        const uint8_t* src = op.scales + gr * sstride + k0 / 16;
-        if (VEC) {
-            rg.s = *reinterpret_cast<const uint2*>(src);
-        } else {
-            uint32_t w[2] = {0, 0};
-            for (int i = 0; i < 8; ++i)
-                if (k0 / 16 + i < sstride) w[i >> 2] |= (uint32_t)src[i] << (8 * (i & 3));
-            rg.s = make_uint2(w[0], w[1]);
-        }
-    }
 }
 
 template <int ROWS, int NT>
-__device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, uint8_t* __restrict__ lc,
-                                            uint8_t* __restrict__ ls, int tid) {
+__device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, uint8_t* __restrict__ lc, int tid) {
     constexpr int T = ROWS * 4 / NT;
 #pragma unroll
     for (int v = 0; v < T; ++v) {
@@ -95,19 +120,13 @@ __device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, 
         uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
         dst[0] = rg.c[v].x; dst[1] = rg.c[v].y; dst[2] = rg.c[v].z; dst[3] = rg.c[v].w;
     }
-    if (tid < ROWS) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(ls + tid * G_SROW);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            dst[i] = e4m3_to_f16_pair((rg.s.x >> (8 * i)) & 0xFFu);
-            dst[4 + i] = e4m3_to_f16_pair((rg.s.y >> (8 * i)) & 0xFFu);
-        }
-    }
 }
 
-// 8 codes (one dword) times one block scale (fp16, duplicated in both halves of `s2`) -> 8 fp16
-__device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t s2bits) {
-    half2_t s2 = __builtin_bit_cast(half2_t, s2bits);
+// 8 codes (one dword) times one block scale -> 8 fp16.  `spair` holds the fp16 scales of two
+// consecutive blocks; `hi` picks the second (the splat folds into the packed multiply's operand select).
+__device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t spair, bool hi) {
+    const half2_t sp = __builtin_bit_cast(half2_t, spair);
+    const half2_t s2 = hi ? (half2_t){sp[1], sp[1]} : (half2_t){sp[0], sp[0]};
     half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0) * s2;
     half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1) * s2;
     half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2) * s2;
@@ -173,10 +192,13 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
     const bool split = gridDim.y > 1;
     StageRegs<BM * 4 / NT> ra;
     StageRegs<BN * 4 / NT> rb;
+    ScaleRegs<(BM + BN + NT - 1) / NT> rs;
     stage_load<BM, NT, VEC>(A, m0, K, it0 * G_KI, ra, tid);
     stage_load<BN, NT, VEC>(B, n0, K, it0 * G_KI, rb, tid);
-    stage_store<BM, NT>(ra, lds, lds + OFF_SA, tid);
-    stage_store<BN, NT>(rb, lds + OFF_CB, lds + OFF_SB, tid);
+    scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, it0 * G_KI, rs, tid);
+    stage_store<BM, NT>(ra, lds, tid);
+    stage_store<BN, NT>(rb, lds + OFF_CB, tid);
+    scale_store<BM, BN, NT>(rs, lds + OFF_SA, lds + OFF_SB, tid);
     __syncthreads();
     for (int64_t it = it0; it < niter; ++it) {
         const int cur = (int)((it - it0) & 1);
@@ -184,6 +206,7 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
         if (more) {
             stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
             stage_load<BN, NT, VEC>(B, n0, K, (it + 1) * G_KI, rb, tid);
+            scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, (it + 1) * G_KI, rs, tid);
         }
         const uint8_t* bufc = lds + cur * BUF;
         uint8_t* bufn = lds + (cur ^ 1) * BUF;
@@ -197,11 +220,11 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 fa[i] = dequant8(*reinterpret_cast<const uint32_t*>(ca + 32 * i * G_CROW + 8 * s),
-                                 *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * s));
+                                 *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * (s >> 1)), s & 1);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 fb[j] = dequant8(*reinterpret_cast<const uint32_t*>(cb + 32 * j * G_CROW + 8 * s),
-                                 *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * s));
+                                 *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * (s >> 1)), s & 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -209,8 +232,9 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
         if (more) {
-            stage_store<BM, NT>(ra, bufn, bufn + OFF_SA, tid);
-            stage_store<BN, NT>(rb, bufn + OFF_CB, bufn + OFF_SB, tid);
+            stage_store<BM, NT>(ra, bufn, tid);
+            stage_store<BN, NT>(rb, bufn + OFF_CB, tid);
+            scale_store<BM, BN, NT>(rs, bufn + OFF_SA, bufn + OFF_SB, tid);
         }
         __syncthreads();
     }
@@ -288,10 +312,13 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     const int64_t niter = (K + G_KI - 1) / G_KI;
     StageRegs<BM * 4 / NT> ra;
     StageRegs<BN * 4 / NT> rb;
+    ScaleRegs<(BM + BN + NT - 1) / NT> rs;
     stage_load<BM, NT, VEC>(A, m0, K, 0, ra, tid);
     stage_load<BN, NT, VEC>(B, n0, K, 0, rb, tid);
-    stage_store<BM, NT>(ra, lds, lds + OFF_SA, tid);
-    stage_store<BN, NT>(rb, lds + OFF_CB, lds + OFF_SB, tid);
+    scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, 0, rs, tid);
+    stage_store<BM, NT>(ra, lds, tid);
+    stage_store<BN, NT>(rb, lds + OFF_CB, tid);
+    scale_store<BM, BN, NT>(rs, lds + OFF_SA, lds + OFF_SB, tid);
     __syncthreads();
     for (int64_t it = 0; it < niter; ++it) {
         const int cur = (int)(it & 1);
@@ -299,6 +326,7 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         if (more) {
             stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
             stage_load<BN, NT, VEC>(B, n0, K, (it + 1) * G_KI, rb, tid);
+            scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, (it + 1) * G_KI, rs, tid);
         }
         const uint8_t* bufc = lds + cur * BUF;
         uint8_t* bufn = lds + (cur ^ 1) * BUF;
@@ -312,25 +340,25 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 rawc[slot][i] = *reinterpret_cast<const uint32_t*>(ca + 32 * i * G_CROW + 8 * s);
-                raws[slot][i] = *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * s);
+                raws[slot][i] = *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * (s >> 1));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 rawc[slot][TM + j] = *reinterpret_cast<const uint32_t*>(cb + 32 * j * G_CROW + 8 * s);
-                raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * s);
+                raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * (s >> 1));
             }
         };
         read_raw(0, 0);
         read_raw(1, 1);
 #pragma unroll
-        for (int t = 0; t < TM + TN; ++t) frag[0][t] = dequant8(rawc[0][t], raws[0][t]);
+        for (int t = 0; t < TM + TN; ++t) frag[0][t] = dequant8(rawc[0][t], raws[0][t], false);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const int c = s & 1, n = c ^ 1;
             // expand step s+1 (its raw words arrived during step s-1), then refill that raw slot with s+2
             if (s + 1 < KS) {
 #pragma unroll
-                for (int t = 0; t < TM + TN; ++t) frag[n][t] = dequant8(rawc[n][t], raws[n][t]);
+                for (int t = 0; t < TM + TN; ++t) frag[n][t] = dequant8(rawc[n][t], raws[n][t], (s + 1) & 1);
             }
             if (s + 2 < KS) read_raw(s + 2, c);
 #pragma unroll
@@ -347,8 +375,9 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
             }
         }
         if (more) {
-            stage_store<BM, NT>(ra, bufn, bufn + OFF_SA, tid);
-            stage_store<BN, NT>(rb, bufn + OFF_CB, bufn + OFF_SB, tid);
+            stage_store<BM, NT>(ra, bufn, tid);
+            stage_store<BN, NT>(rb, bufn + OFF_CB, tid);
+            scale_store<BM, BN, NT>(rs, bufn + OFF_SA, bufn + OFF_SB, tid);
         }
         __syncthreads();
     }
