@@ -149,7 +149,7 @@ def main():
 
     gemm_ms = avg("gemm", args.steps * n_gemm)
     gemm_tflops = 2.0 * L * K * N / (gemm_ms * 1e-3) / 1e12
-    roofline = {"kernel": "k_fp4_gemm_nt", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+    roofline = {"kernel": "k_fp4_gemm_nt_pipe", "bound": "mfma", "achieved": round(gemm_tflops, 2),
                 "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_TFLOPS, 4),
                 "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
 
@@ -224,7 +224,7 @@ def traffic_from_profile(workload):
     path = os.path.join(ROOT, "profiles", f"bench_config{workload[1]}_hbm_traffic.txt")
     try:
         for line in open(path):
-            if line.startswith("k_fp4_gemm_nt<4, 2, 2, 4"):
+            if line.startswith("k_fp4_gemm_nt_pipe<unsigned short>"):
                 tail = line[52:].split()
                 return round((float(tail[0]) + float(tail[1])) * 2 ** 20)
     except OSError:

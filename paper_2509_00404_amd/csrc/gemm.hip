@@ -122,6 +122,13 @@ __device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, 
     }
 }
 
+// one 16-byte code vector (element e of the stage: row e/4, 16-byte segment e%4) into the padded LDS rows
+__device__ __forceinline__ void stage_store_one(const uint4& v, uint8_t* __restrict__ lc, int e) {
+    const int row = e >> 2, seg = e & 3;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+}
+
 // 8 codes (one dword) times one block scale -> 8 fp16.  `spair` holds the fp16 scales of two
 // consecutive blocks; `hi` picks the second (the splat folds into the packed multiply's operand select).
 __device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t spair, bool hi) {
@@ -143,6 +150,26 @@ union BFrag {
 template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
 template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16_rne(v); }
+
+// one lane's 16 values of a 32x32 accumulator tile: rows 8 (v/4) + v%4 from p, one column
+template <typename T> __device__ __forceinline__ void store_tile16(T* p, int64_t ldc, const float16_t& a, float alpha);
+template <> __device__ __forceinline__ void store_tile16<float>(float* p, int64_t ldc, const float16_t& a, float alpha) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) p[(8 * (v >> 2) + (v & 3)) * ldc] = alpha * a[v];
+}
+template <> __device__ __forceinline__ void store_tile16<bf16_t>(bf16_t* p, int64_t ldc, const float16_t& a, float alpha) {
+    typedef __bf16 bf2_t __attribute__((ext_vector_type(2)));
+    typedef float f2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+        // hardware packed conversion (round to nearest even), then the two halves go to consecutive rows
+        const f2_t x = {alpha * a[v], alpha * a[v + 1]};
+        const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf2_t));
+        bf16_t* q = p + (8 * (v >> 2) + (v & 3)) * ldc;
+        q[0] = (bf16_t)(w & 0xFFFFu);
+        q[ldc] = (bf16_t)(w >> 16);
+    }
+}
 
 template <typename T> __device__ __forceinline__ void atomic_out(T* p, float v);
 template <> __device__ __forceinline__ void atomic_out<float>(float* p, float v) { unsafeAtomicAdd(p, v); }
@@ -280,10 +307,17 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 
 // Software-pipelined variant: 256 x 256 tile, 4 waves of 128 x 128 (16 accumulator tiles per wave,
 // one wave per SIMD).  Half as many code expansions per MFMA as the 8-wave kernel, so the matrix
-// cores rather than the vector ALUs bound it -- provided nothing waits: the raw codes/scales of
-// contraction step s+2 are read from LDS and step s+1 is expanded to fp16 while the 16 MFMAs of
-// step s run (explicit register double-buffering, interleaving pinned with sched_group_barrier).
-template <bool VEC, typename OUT>
+// cores rather than the vector ALUs bound it -- provided the matrix pipe never drains:
+//  * within a stage, the raw codes/scales of contraction step s+2 are read from LDS and step s+1
+//    is expanded to fp16 between the 16 MFMAs of step s (register double-buffering, interleaving
+//    pinned with sched_group_barrier);
+//  * across stages, the next stage's global data is written to the other LDS buffer during steps
+//    0-4 (each staging register is refilled with the stage after next right after its write), the
+//    workgroup barrier sits at the start of step 6, and steps 6 and 7 already read and expand the
+//    next stage's first two steps, so no MFMA waits for a barrier, an LDS round trip or a global load.
+// The stage body is branch-free and the same for every stage (the last one stages and expands data
+// that nobody uses), which keeps the whole loop one scheduling region.  Needs K % 128 == 0.
+template <typename OUT>
 __global__ void __launch_bounds__(256)
 k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
                    const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n) {
@@ -309,131 +343,197 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int64_t niter = (K + G_KI - 1) / G_KI;
-    StageRegs<BM * 4 / NT> ra;
-    StageRegs<BN * 4 / NT> rb;
-    ScaleRegs<(BM + BN + NT - 1) / NT> rs;
-    stage_load<BM, NT, VEC>(A, m0, K, 0, ra, tid);
-    stage_load<BN, NT, VEC>(B, n0, K, 0, rb, tid);
-    scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, 0, rs, tid);
-    stage_store<BM, NT>(ra, lds, tid);
-    stage_store<BN, NT>(rb, lds + OFF_CB, tid);
-    scale_store<BM, BN, NT>(rs, lds + OFF_SA, lds + OFF_SB, tid);
+    const int niter = (int)(K / G_KI);
+    // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/4 + 64 v, 16-byte
+    // segment tid%4) and the scale rows tid (A) and tid (B); rows past the operand's end re-read its last row
+    const uint8_t* pa[4];
+    const uint8_t* pb[4];
+    const int64_t cstride = K / 2, sstride = K / 16;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        int64_t ga = m0 + (tid >> 2) + 64 * v, gb = n0 + (tid >> 2) + 64 * v;
+        if (ga >= A.rows) ga = A.rows - 1;
+        if (gb >= B.rows) gb = B.rows - 1;
+        pa[v] = A.codes + ga * cstride + 16 * (tid & 3);
+        pb[v] = B.codes + gb * cstride + 16 * (tid & 3);
+    }
+    const uint8_t* psa;
+    const uint8_t* psb;
+    {
+        int64_t ga = m0 + tid, gb = n0 + tid;
+        if (ga >= A.rows) ga = A.rows - 1;
+        if (gb >= B.rows) gb = B.rows - 1;
+        psa = A.scales + ga * sstride;
+        psb = B.scales + gb * sstride;
+    }
+    uint4 ra[4], rb[4];
+    uint2 rsa, rsb;
+    // st = stage index, clamped by the caller
+    auto load_codes = [&](int st, int v) {
+        ra[v] = *reinterpret_cast<const uint4*>(pa[v] + st * (G_KI / 2));
+        rb[v] = *reinterpret_cast<const uint4*>(pb[v] + st * (G_KI / 2));
+    };
+    auto load_scales = [&](int st) {
+        rsa = *reinterpret_cast<const uint2*>(psa + st * (G_KI / 16));
+        rsb = *reinterpret_cast<const uint2*>(psb + st * (G_KI / 16));
+    };
+    auto load_stage = [&](int st) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) load_codes(st, v);
+        load_scales(st);
+    };
+    auto store_codes = [&](uint8_t* buf, int v) {
+        stage_store_one(ra[v], buf, tid + NT * v);
+        stage_store_one(rb[v], buf + OFF_CB, tid + NT * v);
+    };
+    auto store_scales = [&](uint8_t* buf) {
+        uint32_t* da = reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * G_SROW);
+        uint32_t* db = reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * G_SROW);
+        da[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, false));
+        da[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, true));
+        da[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, false));
+        da[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, true));
+        db[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, false));
+        db[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, true));
+        db[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, false));
+        db[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, true));
+    };
+    load_stage(0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) store_codes(lds, v);
+    store_scales(lds);
     __syncthreads();
-    for (int64_t it = 0; it < niter; ++it) {
-        const int cur = (int)(it & 1);
-        const bool more = it + 1 < niter;
-        if (more) {
-            stage_load<BM, NT, VEC>(A, m0, K, (it + 1) * G_KI, ra, tid);
-            stage_load<BN, NT, VEC>(B, n0, K, (it + 1) * G_KI, rb, tid);
-            scale_load<BM, BN, NT, VEC>(A, B, m0, n0, K, (it + 1) * G_KI, rs, tid);
+    load_stage(niter > 1 ? 1 : 0);
+
+    // per-lane byte offsets of this wave's fragment rows inside a buffer
+    const int oca = (wm + li) * G_CROW + 4 * half, ocb = OFF_CB + (wn + li) * G_CROW + 4 * half;
+    const int osa = OFF_SA + (wm + li) * G_SROW, osb = OFF_SB + (wn + li) * G_SROW;
+    uint32_t rawc[2][TM + TN], raws[2][TM + TN];
+    half8_t frag[2][TM + TN];
+    auto read_raw = [&](const uint8_t* buf, int s, int slot) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            rawc[slot][i] = *reinterpret_cast<const uint32_t*>(buf + oca + 32 * i * G_CROW + 8 * s);
+            raws[slot][i] = *reinterpret_cast<const uint32_t*>(buf + osa + 32 * i * G_SROW + 4 * (s >> 1));
         }
-        const uint8_t* bufc = lds + cur * BUF;
-        uint8_t* bufn = lds + (cur ^ 1) * BUF;
-        const uint8_t* ca = bufc + (wm + li) * G_CROW + 4 * half;
-        const uint8_t* cb = bufc + OFF_CB + (wn + li) * G_CROW + 4 * half;
-        const uint8_t* sa = bufc + OFF_SA + (wm + li) * G_SROW;
-        const uint8_t* sb = bufc + OFF_SB + (wn + li) * G_SROW;
-        uint32_t rawc[2][TM + TN], raws[2][TM + TN];
-        half8_t frag[2][TM + TN];
-        auto read_raw = [&](int s, int slot) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                rawc[slot][i] = *reinterpret_cast<const uint32_t*>(ca + 32 * i * G_CROW + 8 * s);
-                raws[slot][i] = *reinterpret_cast<const uint32_t*>(sa + 32 * i * G_SROW + 4 * (s >> 1));
-            }
+        for (int j = 0; j < TN; ++j) {
+            rawc[slot][TM + j] = *reinterpret_cast<const uint32_t*>(buf + ocb + 32 * j * G_CROW + 8 * s);
+            raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(buf + osb + 32 * j * G_SROW + 4 * (s >> 1));
+        }
+    };
+    read_raw(lds, 0, 0);
+    read_raw(lds, 1, 1);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                rawc[slot][TM + j] = *reinterpret_cast<const uint32_t*>(cb + 32 * j * G_CROW + 8 * s);
-                raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(sb + 32 * j * G_SROW + 4 * (s >> 1));
-            }
-        };
-        read_raw(0, 0);
-        read_raw(1, 1);
-#pragma unroll
-        for (int t = 0; t < TM + TN; ++t) frag[0][t] = dequant8(rawc[0][t], raws[0][t], false);
+    for (int t = 0; t < TM + TN; ++t) frag[0][t] = dequant8(rawc[0][t], raws[0][t], false);
+
+#pragma unroll 1
+    for (int it = 0; it < niter; ++it) {
+        const uint8_t* bufc = lds + (it & 1) * BUF;
+        uint8_t* bufn = lds + ((it & 1) ^ 1) * BUF;
+        const int stn = it + 2 < niter ? it + 2 : niter - 1;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const int c = s & 1, n = c ^ 1;
+            if (s + 2 == KS) __syncthreads();     // next stage is in LDS, this stage's raw words are all read
             // expand step s+1 (its raw words arrived during step s-1), then refill that raw slot with s+2
-            if (s + 1 < KS) {
 #pragma unroll
-                for (int t = 0; t < TM + TN; ++t) frag[n][t] = dequant8(rawc[n][t], raws[n][t], (s + 1) & 1);
-            }
-            if (s + 2 < KS) read_raw(s + 2, c);
+            for (int t = 0; t < TM + TN; ++t) frag[n][t] = dequant8(rawc[n][t], raws[n][t], (s + 1) & 1);
+            if (s + 2 < KS) read_raw(bufc, s + 2, c);
+            else read_raw(bufn, s + 2 - KS, c);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(frag[c][i], frag[c][TM + j], acc[i][j], 0, 0, 0);
-            // one MFMA, then its share of the vector work: 4 of the 64 expansion ops and 1 of the 16 LDS reads
+            // a staging register is refilled with the stage after next as soon as it has been written
+            // to LDS, which gives every global load a whole stage to arrive
+            if (s < 4) {
+                store_codes(bufn, s);
+                load_codes(stn, s);
+            }
+            if (s == 4) {
+                store_scales(bufn);
+                load_scales(stn);
+            }
+            // one MFMA, then its share of the other work: 4 of the 64 expansion ops, 1 of the 16 LDS reads,
+            // and where the step has them an LDS write or a global load
 #pragma unroll
             for (int m = 0; m < TM * TN; ++m) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (s <= 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                if (s <= 4 && m >= 8 && m < 10) {                      // the step's two global loads, after its LDS writes
+                    __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
             }
         }
-        if (more) {
-            stage_store<BM, NT>(ra, bufn, tid);
-            stage_store<BN, NT>(rb, bufn + OFF_CB, tid);
-            scale_store<BM, BN, NT>(rs, bufn + OFF_SA, bufn + OFF_SB, tid);
-        }
-        __syncthreads();
     }
-    if (Ke > 0) {
-        for (int ks = 0; ks < Ke; ks += 16) {
-            BFrag fa[TM], fb[TN];
+
+    // low-rank terms: extra contraction columns in bf16, read straight from global memory, four steps
+    // (64 columns) of fragments in flight at a time
+    for (int ks = 0; ks < Ke; ks += 64) {
+        BFrag fa[4][TM], fb[4][TN];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int kc = ks + 16 * u < Ke ? ks + 16 * u : ks;      // a short last batch re-reads its first step (unused)
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 int64_t r = m0 + wm + 32 * i + li;
                 if (r >= A.rows) r = A.rows - 1;
-                fa[i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + ks + 8 * half);
+                fa[u][i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + kc + 8 * half);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 int64_t r = n0 + wn + 32 * j + li;
                 if (r >= B.rows) r = B.rows - 1;
-                fb[j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + ks + 8 * half);
+                fb[u][j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + kc + 8 * half);
             }
+        }
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int u = 0; u < 4; ++u) {
+            if (ks + 16 * u < Ke) {                                   // uniform (kernel argument)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][i].v, fb[u][j].v, acc[i][j], 0, 0, 0);
+            }
         }
     }
+    // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            int64_t c = n0 + wn + 32 * j + li;
+            const int64_t c = n0 + wn + 32 * j + li;
+            const int64_t rbase = m0 + wm + 32 * i + 4 * half;
+            if (interior) {
+                store_tile16<OUT>(C + rbase * ldc + c, ldc, acc[i][j], alpha);
+            } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int64_t r = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
+                }
             }
         }
 }
 
 template <typename OUT>
-int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
+int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, const bf16_t* Aext,
                      const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
     const int64_t tm = ceil_div64(a.rows, 256), tn = ceil_div64(b.rows, 256);
     if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
     constexpr size_t lds = gemm_lds_bytes<256, 256>();
     dim3 grid((unsigned)(tm * tn));
-    if (vec) {
-        auto kern = k_fp4_gemm_nt_pipe<true, OUT>;
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
-    } else {
-        auto kern = k_fp4_gemm_nt_pipe<false, OUT>;
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
-    }
+    auto kern = k_fp4_gemm_nt_pipe<OUT>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return METIS_HIP_ERROR;
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
@@ -475,9 +575,9 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
                      reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
     if (M >= 1024 && N >= 1024) {
-        static const bool use_pipe = getenv("METIS_GEMM_PIPE") != nullptr;
-        if (use_pipe) return launch_gemm_pipe<OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
-        // 256x256 tile, 8 waves of 128x64: two waves per SIMD hide each other's latencies
+        // 256x256 tile, 4 waves of 128x128, software-pipelined (needs whole 128-deep stages and aligned rows)
+        if (vec) return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+        // otherwise 8 waves of 128x64 with bounds-checked staging
         return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     }
     if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
