@@ -77,9 +77,11 @@ DEpilogue epi(void* c, int64_t ldc, bf16_t* hi_t = nullptr, bf16_t* lo_t = nullp
     return e;
 }
 
-int split_for(int64_t K, int64_t tiles) {      // contraction chunks so that ~512 workgroups exist
-    int64_t s = 512 / (tiles > 512 ? 512 : tiles);
-    int64_t maxs = K / 64;
+// contraction chunks so that ~2048 workgroups exist: the generic kernel does not prefetch, so a workgroup
+// should own one or two 32-deep stages and the grid, not the loop, should cover the contraction
+int split_for(int64_t K, int64_t tiles) {
+    int64_t s = 2048 / (tiles > 2048 ? 2048 : tiles);
+    int64_t maxs = K / 32;
     if (s > maxs) s = maxs;
     return (int)(s < 1 ? 1 : s);
 }

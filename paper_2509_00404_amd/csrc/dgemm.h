@@ -64,31 +64,46 @@ k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk,
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
     const bool a_kfast = A.s_k == 1 && !A.map_k, b_kfast = B.s_k == 1 && !B.map_k;
 
+    // per-thread element slots of a stage: the outer-index part of every address is fixed for the whole
+    // contraction, only the k part moves (unless k is gathered)
+    int a_mm[4], a_kk[4], b_nn[4], b_kk[4];
+    int64_t a_off[4], b_off[4];
+    bool a_ok[4], b_ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = tid + 256 * i;
+        a_mm[i] = a_kfast ? e >> 5 : e & 31;
+        a_kk[i] = a_kfast ? e & 31 : e >> 5;
+        b_nn[i] = b_kfast ? e >> 5 : e & 31;
+        b_kk[i] = b_kfast ? e & 31 : e >> 5;
+        const int64_t m = m0 + a_mm[i], n = n0 + b_nn[i];
+        a_ok[i] = m < M;
+        b_ok[i] = n < N;
+        const int64_t mo = a_ok[i] ? (A.map_outer ? (int64_t)A.map_outer[m] : m) : 0;
+        const int64_t no = b_ok[i] ? (B.map_outer ? (int64_t)B.map_outer[n] : n) : 0;
+        a_off[i] = mo * A.s_outer;
+        b_off[i] = no * B.s_outer;
+    }
     for (int64_t kt = kbeg; kt < kend; kt += DG_BK) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int e = tid + 256 * i;
             {
-                int mm = a_kfast ? e >> 5 : e & 31, kk = a_kfast ? e & 31 : e >> 5;
-                int64_t m = m0 + mm, k = kt + kk;
+                const int64_t k = kt + a_kk[i];
                 double v = 0.0;
-                if (m < M && k < kend) {
-                    int64_t mo = A.map_outer ? (int64_t)A.map_outer[m] : m;
-                    int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
-                    v = dload_sum<TA>(A, mo * A.s_outer + ko * A.s_k);
+                if (a_ok[i] && k < kend) {
+                    const int64_t ko = A.map_k ? (int64_t)A.map_k[k] : k;
+                    v = dload_sum<TA>(A, a_off[i] + ko * A.s_k);
                 }
-                As[kk][mm] = v;
+                As[a_kk[i]][a_mm[i]] = v;
             }
             {
-                int nn = b_kfast ? e >> 5 : e & 31, kk = b_kfast ? e & 31 : e >> 5;
-                int64_t n = n0 + nn, k = kt + kk;
+                const int64_t k = kt + b_kk[i];
                 double v = 0.0;
-                if (n < N && k < kend) {
-                    int64_t no = B.map_outer ? (int64_t)B.map_outer[n] : n;
-                    int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
-                    v = dload_sum<TB>(B, no * B.s_outer + ko * B.s_k);
+                if (b_ok[i] && k < kend) {
+                    const int64_t ko = B.map_k ? (int64_t)B.map_k[k] : k;
+                    v = dload_sum<TB>(B, b_off[i] + ko * B.s_k);
                 }
-                Bs[kk][nn] = v;
+                Bs[b_kk[i]][b_nn[i]] = v;
             }
         }
         __syncthreads();
