@@ -15,7 +15,7 @@ namespace {
 struct Layout {
     int64_t M, N, Ms;
     int k, r;
-    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_c, off_b, zero_bytes;
+    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_flag, off_c, off_b, zero_bytes;
     size_t off_idx, off_omega, off_linv, off_h1, off_h, off_lam, off_t, off_v0f, off_v0hi, off_v0lo,
         off_lam3, off_w3, off_t3, total;
 };
@@ -31,6 +31,7 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     L.off_g1b = take(r * r * 8);
     L.off_g2 = take(r * r * 8);
     L.off_g3 = take(kk * kk * 8);
+    L.off_flag = take(4);
     L.off_b = take(r * (size_t)N * 8);
     L.zero_bytes = o;
     L.off_c = take((size_t)broadcast_splits(M, N) * (size_t)M * kk * 4);
@@ -73,7 +74,12 @@ DOperand op_parts(const void* p, int64_t s_outer, int64_t s_k, int nparts, int64
 
 DEpilogue epi(void* c, int64_t ldc, bf16_t* hi_t = nullptr, bf16_t* lo_t = nullptr, int64_t ld_t = 0) {
     DEpilogue e;
-    e.c = c; e.ldc = ldc; e.hi_t = hi_t; e.lo_t = lo_t; e.ld_t = ld_t;
+    e.c = c; e.ldc = ldc; e.hi_t = hi_t; e.lo_t = lo_t; e.ld_t = ld_t; e.skip = nullptr;
+    return e;
+}
+DEpilogue epi_skip(void* c, int64_t ldc, const int32_t* skip) {
+    DEpilogue e = epi(c, ldc);
+    e.skip = skip;
     return e;
 }
 
@@ -173,16 +179,20 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(Zacc, 1, r), op(Zacc, 1, r), r, r, Ms,
                                                   split_for(Ms, tiles_rr), epi(G1, r));
     METIS_LAUNCH_CHECK();
-    if ((st = launch_chol_inv(s, G1, r, Linv, info)) != METIS_OK) return st;
+    // The second pass only repairs the orthogonality the first one lost to cond(Z)^2 eps.  When the first
+    // factor's diagonal shows a well-conditioned sketch the first pass's H1 is orthonormal to ~1e-10 already:
+    // a device flag then turns the second pass's kernels into no-ops and the projection reads H1.
+    int32_t* wellcond = fast ? (int32_t*)(ws + L.off_flag) : nullptr;
+    if ((st = launch_chol_inv(s, G1, r, Linv, info, wellcond, nullptr)) != METIS_OK) return st;
     launch_dgemm<double, double, EPI_STORE_F64>(s, op(Zacc, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi(H1, r));
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(H1, 1, r), op(H1, 1, r), r, r, Ms,
-                                                  split_for(Ms, tiles_rr), epi(G1b, r));
+                                                  split_for(Ms, tiles_rr), epi_skip(G1b, r, wellcond));
     METIS_LAUNCH_CHECK();
-    if ((st = launch_chol_inv(s, G1b, r, Linv, info)) != METIS_OK) return st;
-    launch_dgemm<double, double, EPI_STORE_F64>(s, op(H1, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi(H, r));
+    if ((st = launch_chol_inv(s, G1b, r, Linv, info, nullptr, wellcond)) != METIS_OK) return st;
+    launch_dgemm<double, double, EPI_STORE_F64>(s, op(H1, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi_skip(H, r, wellcond));
     // reduced matrix B = H^T A_s  (r x N)
     if (fast) {
-        if ((st = launch_project(s, H, r, Ap, lda, idx_use, Ms, N, B)) != METIS_OK) return st;
+        if ((st = launch_project(s, H, H1, wellcond, r, Ap, lda, idx_use, Ms, N, B)) != METIS_OK) return st;
     } else {
         launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms,
                                                       split_for(Ms, ceil_div64(r, 32) * ceil_div64(N, 32)), epi(B, N));

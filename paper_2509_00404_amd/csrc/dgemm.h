@@ -25,6 +25,7 @@ struct DEpilogue {
     bf16_t* hi_t;                // SPLIT_T: bf16 hi/lo parts stored transposed, (m,n) at [n*ld_t + m]
     bf16_t* lo_t;
     int64_t ld_t;
+    const int32_t* skip;         // optional device flag: nonzero -> the kernel returns at once
 };
 
 template <typename T> __device__ __forceinline__ double dload(const void* p, int64_t off);
@@ -56,6 +57,7 @@ __global__ void __launch_bounds__(256)
 k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
     __shared__ double As[DG_BK][DG_BM + DG_PAD];
     __shared__ double Bs[DG_BK][DG_BN + DG_PAD];
+    if (ep.skip && *ep.skip) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t m0 = (int64_t)blockIdx.y * DG_BM, n0 = (int64_t)blockIdx.x * DG_BN;
     const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
@@ -169,6 +171,7 @@ __global__ void __launch_bounds__(256)
 k_dgemm_big(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
     __shared__ double As[2][DGB_K][DGB_T + DG_PAD];
     __shared__ double Bs[2][DGB_K][DGB_T + DG_PAD];
+    if (ep.skip && *ep.skip) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t m0 = (int64_t)blockIdx.y * DGB_T, n0 = (int64_t)blockIdx.x * DGB_T;
     const int64_t kbeg = (int64_t)blockIdx.z * kchunk;

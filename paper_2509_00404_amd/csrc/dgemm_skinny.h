@@ -152,8 +152,11 @@ struct ProjectCfg {
 
 template <int NT>
 __global__ void __launch_bounds__(256)
-k_project(const double* __restrict__ H, int r, const bf16_t* __restrict__ A, int64_t lda,
-          const uint32_t* __restrict__ rowmap, int64_t Ms, int64_t N, int64_t kchunk, double* __restrict__ B) {
+k_project(const double* __restrict__ H_main, const double* __restrict__ H_alt, const int32_t* __restrict__ use_alt, int r,
+          const bf16_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ rowmap, int64_t Ms, int64_t N,
+          int64_t kchunk, double* __restrict__ B) {
+    // the orthonormal basis: the second CholeskyQR pass's output, or the first pass's when that was enough
+    const double* __restrict__ H = (use_alt && *use_alt) ? H_alt : H_main;
     constexpr int LDH = ProjectCfg<NT>::LDH;
     constexpr int HL = ProjectCfg<NT>::H_LOADS;
     extern __shared__ __align__(16) unsigned char pj_smem[];
@@ -277,8 +280,8 @@ static inline int launch_sketch(hipStream_t s, const bf16_t* A, int64_t lda, con
     return METIS_OK;
 }
 
-static inline int launch_project(hipStream_t s, const double* H, int r, const bf16_t* A, int64_t lda,
-                                 const uint32_t* rowmap, int64_t Ms, int64_t N, double* B) {
+static inline int launch_project(hipStream_t s, const double* H, const double* H_alt, const int32_t* use_alt, int r,
+                                 const bf16_t* A, int64_t lda, const uint32_t* rowmap, int64_t Ms, int64_t N, double* B) {
     const int64_t kchunk = skinny_kchunk(Ms, ceil_div64(N, PJ_COLS), PJ_KS);
     dim3 grid((unsigned)ceil_div64(N, PJ_COLS), 1, (unsigned)ceil_div64(Ms, kchunk));
 #define PROJECT_CASE(NT)                                                                                         \
@@ -287,7 +290,7 @@ static inline int launch_project(hipStream_t s, const double* H, int r, const bf
         if (hipFuncSetAttribute((const void*)k_project<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != \
             hipSuccess)                                                                                          \
             return METIS_HIP_ERROR;                                                                              \
-        hipLaunchKernelGGL(k_project<NT>, grid, dim3(256), lds, s, H, r, A, lda, rowmap, Ms, N, kchunk, B);      \
+        hipLaunchKernelGGL(k_project<NT>, grid, dim3(256), lds, s, H, H_alt, use_alt, r, A, lda, rowmap, Ms, N, kchunk, B);      \
     }
     switch ((r + 15) / 16) {
         case 1: PROJECT_CASE(1) break;

@@ -145,8 +145,13 @@ __device__ __forceinline__ double chol_group8_sum(double x) {
 }
 
 __global__ void __launch_bounds__(1024)
-k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32_t* __restrict__ info) {
+k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32_t* __restrict__ info,
+           int32_t* __restrict__ wellcond_out, const int32_t* __restrict__ skip_in) {
     extern __shared__ double sm[];
+    if (skip_in && *skip_in) {
+        for (int e = threadIdx.x; e < n * n; e += 1024) Linv[e] = (e / n == e % n) ? 1.0 : 0.0;
+        return;
+    }
     const int ld = n + 1;
     double* L = sm;                              // column-major: L(i, c) at L[c*ld + i]
     double* X = sm + (size_t)n * ld;             // L^-1, row-major: X(t, c) at X[t*ld + c]
@@ -159,6 +164,11 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
     }
     __syncthreads();
     chol_blocked<false>(L, ld, n, dinv, 0.0, info);
+    if (wellcond_out && tid == 0) {
+        double lo = dinv[0], hi = dinv[0];
+        for (int j = 1; j < n; ++j) { lo = fmin(lo, dinv[j]); hi = fmax(hi, dinv[j]); }
+        *wellcond_out = (hi <= 1e3 * lo) ? 1 : 0;        // a replaced pivot has dinv = 1e150 and fails this
+    }
     // forward substitution: column c of L^-1 by a group of 8 lanes (same wave, so the group's own
     // LDS writes are visible to it without a workgroup barrier); X[t][c] keeps groups conflict-free
     {
@@ -492,11 +502,12 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     }
 }
 
-int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info) {
+int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info, int32_t* wellcond_out,
+                    const int32_t* skip_in) {
     size_t lds = 2 * (size_t)n * (n + 1) * sizeof(double);
     if (hipFuncSetAttribute((const void*)k_chol_inv, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), lds, s, G, n, Linv, info);
+    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), lds, s, G, n, Linv, info, wellcond_out, skip_in);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
