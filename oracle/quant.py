@@ -73,6 +73,53 @@ def quantize(x, g=1.0):
     return codes, sidx.astype(np.uint8)
 
 
+STREAM_SR = 3          # Philox stream of the stochastic-rounding draws (row orientation)
+STREAM_SR_T = 4        # ... of the transposed orientation
+
+
+def quantize_sr(x, g, seed, stream=STREAM_SR, words=None):
+    """Stochastically rounded variant (Sec. 4, FP4 Training: SR is the default of every FP4 run).
+
+    The paper names the rounding mode and nothing else; readings of this build:
+      * block scale exactly as in quantize(): chosen from the block's amax, rounded up;
+      * y = fl32(x / (s*g)) as in quantize(), a = min(|y|, 6);
+      * with lo <= a <= hi the two neighbouring E2M1 magnitudes, the element goes to hi with
+        probability t = (a - lo) / (hi - lo) and to lo otherwise (so its expectation is a);
+        a value on the grid stays where it is;
+      * the draw: u = (w >> 8) * 2^-24 with w the Philox4x32-10 word whose index is the
+        element's row-major position in x, stream 3 (4 for a transposed copy); go up iff u < t.
+        t is exact in fp32 (a - lo is exact and hi - lo is a power of two), so the comparison
+        is the same on every machine.
+    words (optional, uint32 of x's shape) replaces the Philox draws -- for tests.
+    Returns (codes, scales) in the storage layout of quantize().
+    """
+    from . import rng
+    x = np.asarray(x, dtype=np.float64)
+    rows, cols = x.shape
+    assert cols % BLOCK == 0
+    xb = x.reshape(rows, cols // BLOCK, BLOCK)
+    amax = np.abs(xb).max(axis=2)
+    cover = 6.0 * E4M3_POS * g
+    sidx = np.minimum(np.searchsorted(cover, amax, side="left"), 126)
+    step = (E4M3_POS[sidx] * g).astype(np.float32)
+    safe = np.where(step > 0, step, np.float32(1.0)).astype(np.float32)
+    y = (xb.astype(np.float32) / safe[:, :, None]).astype(np.float32).astype(np.float64)
+    a = np.minimum(np.abs(y), 6.0).reshape(rows, cols)
+    if words is None:
+        words = rng.philox_words(seed, stream, 0, rows * cols).reshape(rows, cols)
+    u = (np.asarray(words, dtype=np.uint64) >> np.uint64(8)).astype(np.float64) * 2.0 ** -24
+    lo_i = np.searchsorted(E2M1_GRID, a, side="right") - 1          # largest grid value <= a
+    hi_i = np.minimum(lo_i + 1, 7)
+    lo, hi = E2M1_GRID[lo_i], E2M1_GRID[hi_i]
+    width = np.where(hi > lo, hi - lo, 1.0)
+    t = (a - lo) / width
+    mag = np.where(u < t, hi_i, lo_i).astype(np.int64)
+    sign = np.signbit(x).astype(np.int64)
+    nib = (sign << 3) | mag
+    codes = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    return codes, sidx.astype(np.uint8)
+
+
 def dequantize(codes, scales, g=1.0):
     """Inverse map: fp64 matrix [rows, cols] of grid * s * g."""
     codes = np.asarray(codes, dtype=np.int64)

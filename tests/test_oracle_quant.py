@@ -7,6 +7,8 @@ import numpy as np
 import torch
 
 from oracle import quant
+from oracle import quant as oq
+from oracle import rng as orng
 
 
 def test_grid_matches_paper_table(golden_dir):
@@ -208,3 +210,84 @@ def test_quotient_is_ieee_fp32_division():
         y = np.float32(x) / s
         want = 4 if y <= np.float32(2.5) else 5          # 2.5 itself ties to the even code 4
         assert (int(codes[0, 0]) >> 4) == want
+
+
+# ---------------------------------------------------------------------------------------------
+# Stochastic rounding (Sec. 4, FP4 Training): pins of oracle.quant.quantize_sr
+# ---------------------------------------------------------------------------------------------
+def _deq_mag(codes, scales, g):
+    return np.abs(oq.dequantize(codes, scales, g))
+
+
+def test_sr_scale_choice_is_the_rne_quantizers_and_signs_kept():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((8, 64)) * np.exp(rng.uniform(-6, 6, (8, 1)))
+    x[0, :16] = 0.0
+    x[1, 3] = -0.0
+    c0, s0 = oq.quantize(x, 0.25)
+    c1, s1 = oq.quantize_sr(x, 0.25, seed=11)
+    assert np.array_equal(s0, s1)
+    assert np.array_equal((c0 & 0x88), (c1 & 0x88))          # sign bits of both nibbles
+
+
+def test_sr_result_is_one_of_the_two_neighbours_and_grid_points_stay():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((16, 128)).astype(np.float32).astype(np.float64)
+    g = 2.0 ** -3
+    codes, scales = oq.quantize_sr(x, g, seed=3)
+    step = np.repeat(oq.e4m3_value(scales) * g, 16, axis=1)
+    y = np.abs((x.astype(np.float32) / step.astype(np.float32)).astype(np.float64))
+    q = _deq_mag(codes, scales, g) / step
+    lo = oq.E2M1_GRID[np.searchsorted(oq.E2M1_GRID, np.minimum(y, 6.0), side="right") - 1]
+    hi = oq.E2M1_GRID[np.minimum(np.searchsorted(oq.E2M1_GRID, np.minimum(y, 6.0), side="left"), 7)]
+    assert np.all((q == lo) | (q == hi))
+    # values that already sit on the grid never move, whatever the draw
+    grid_vals = np.tile(np.concatenate([oq.E2M1_GRID, -oq.E2M1_GRID]), (4, 1))     # amax 6 -> scale 1
+    for seed in range(5):
+        c, s = oq.quantize_sr(grid_vals, 1.0, seed=seed)
+        assert np.array_equal(oq.dequantize(c, s, 1.0), grid_vals)
+
+
+def test_sr_threshold_is_exact():
+    # one block with amax 6 (scale 1): element 1 is 2.25 -> between 2 and 3, t = 0.25 exactly
+    x = np.zeros((1, 16)); x[0, 0] = 6.0; x[0, 1] = 2.25; x[0, 2] = -0.125; x[0, 3] = 5.0
+    def run(word):
+        w = np.full((1, 16), word, dtype=np.uint32)
+        c, s = oq.quantize_sr(x, 1.0, seed=0, words=w)
+        return oq.dequantize(c, s, 1.0)[0]
+    t_quarter = int(0.25 * 2 ** 24)
+    assert run((t_quarter - 1) << 8)[1] == 3.0          # u just below t: up
+    assert run(t_quarter << 8)[1] == 2.0                # u == t: down (strict comparison)
+    assert run((t_quarter << 8) | 0xFF)[1] == 2.0       # the low 8 bits of the word are not used
+    assert run(0)[2] == -0.5 and run(0)[3] == 6.0       # u = 0 < t: up, sign kept
+    assert run(0xFFFFFFFF)[2] == -0.0 and run(0xFFFFFFFF)[3] == 4.0
+    assert run(0)[0] == 6.0 and run(0xFFFFFFFF)[0] == 6.0
+
+
+def test_sr_is_unbiased_and_uses_the_pinned_philox_stream():
+    # the same value in every position: the mean over 2^16 independent draws approaches the value
+    val = 2.6
+    x = np.full((4096, 16), val); x[:, 0] = 6.0          # keeps every block's scale at 1
+    codes, scales = oq.quantize_sr(x, 1.0, seed=2024)
+    d = oq.dequantize(codes, scales, 1.0)[:, 1:]
+    n = d.size
+    p = 0.6                                              # (2.6 - 2) / (3 - 2)
+    assert set(np.unique(d)) == {2.0, 3.0}
+    assert abs(d.mean() - val) < 5 * np.sqrt(p * (1 - p) / n)
+    # draws are the words of stream 3 at the elements' row-major positions
+    w = orng.philox_words(2024, oq.STREAM_SR, 0, x.size).reshape(x.shape)
+    u = (w >> 8) * 2.0 ** -24
+    assert np.array_equal(d == 3.0, (u < np.float64(np.float32(val) - 2.0))[:, 1:])
+    # another seed or the transposed copy's stream gives other draws
+    c2, _ = oq.quantize_sr(x, 1.0, seed=2025)
+    c3, _ = oq.quantize_sr(x, 1.0, seed=2024, stream=oq.STREAM_SR_T)
+    assert not np.array_equal(c2, codes) and not np.array_equal(c3, codes)
+
+
+def test_sr_expected_error_beats_rne_bias_on_a_constant():
+    # RNE maps 2.4 to 2 every time (bias -0.4); SR's mean stays at 2.4
+    x = np.full((2048, 16), 2.4); x[:, 0] = 6.0
+    c_rne, s_rne = oq.quantize(x, 1.0)
+    c_sr, s_sr = oq.quantize_sr(x, 1.0, seed=9)
+    assert np.all(oq.dequantize(c_rne, s_rne, 1.0)[:, 1:] == 2.0)
+    assert abs(oq.dequantize(c_sr, s_sr, 1.0)[:, 1:].mean() - 2.4) < 0.01
