@@ -196,6 +196,11 @@ def main():
         qb = 2.5625 * L * K
         passes["quantize"] = {"avg_ms": round(q_ms, 4), "GB/s": round(qb / q_ms / 1e6, 1),
                               "frac_hbm": round(qb / q_ms / 1e6 / PEAK_HBM_GBS, 4)}
+        # the stochastically rounded variant of the same pass (outside the timed step: the graded path rounds to nearest)
+        sr_ms = timed(lambda: metis.quantize_sr(X.A, 1, X.q.R, None))
+        passes["quantize_sr"] = {"avg_ms": round(sr_ms, 4), "GB/s": round(qb / sr_ms / 1e6, 1),
+                                 "frac_hbm": round(qb / sr_ms / 1e6 / PEAK_HBM_GBS, 4)}
+        metis.quantize(X.A, X.q.R, None)
 
     out = {
         "metric": "split-FP4 linear TFLOP/s + decompose/quantize GB/s (frac of roofline), 1 GPU",

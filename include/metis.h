@@ -136,6 +136,19 @@ int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, dou
 int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t);
 
 /*
+ * Stochastically rounded variant (Sec. 4, "FP4 Training": stochastic rounding is the default of
+ * every FP4 run).  Block scales as above.  With y = e/(s*g) (fp32 quotient, |y| clipped at 6)
+ * between the neighbouring E2M1 magnitudes lo <= |y| <= hi, the element goes to hi with
+ * probability (|y| - lo)/(hi - lo), else to lo; values on the grid do not move.  The draw of an
+ * element is u = (w >> 8) * 2^-24, w = Philox4x32-10 word under `seed` whose index is the
+ * element's row-major position in the output it belongs to (stream 3 for `out`, stream 4 for
+ * `out_t`; word w = lane w%4 of the block with counter (w/4 low, w/4 high, stream, 0)); it goes
+ * up iff u < t.  Same arguments, layouts and errors as metis_quantize; results are
+ * reproducible bit for bit from (A, g, seed).
+ */
+int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t);
+
+/*
  * Split + quantize: R = A - U diag(S) V^T in fp32 (unquantized factors, Sec. 3.2), then
  * Q(R) into out->R (and Q(R^T) into out->Rt when its codes pointer is non-null), Q(U^T)
  * into out->Ut, Q(V^T) into out->Vt, S copied to out->S.  out->k must equal k.

@@ -2,9 +2,13 @@
 #include "quant_dev.h"
 
 // ---- row orientation, bf16 input: one lane per block of 16, 32 contiguous bytes per lane ----
+#define SR_STREAM 3u          // Philox stream of the stochastic-rounding draws, row orientation
+#define SR_STREAM_T 4u        // ... of the transposed copy
+
+template <bool SR>
 __global__ void __launch_bounds__(256)
 k_quantize_rows_bf16(const bf16_t* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* N/16 */,
-                     QuantParams qp, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+                     QuantParams qp, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint64_t seed) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= M * nblk) return;
     int64_t row = t / nblk, bc = t - row * nblk;
@@ -18,7 +22,8 @@ k_quantize_rows_bf16(const bf16_t* __restrict__ A, int64_t ld, int64_t M, int64_
         v[2 * i + 1] = bf16hi_to_f32(w[i]);
     }
     uint2 c;
-    uint32_t sc = quantize_block16(v, qp, c);
+    // block t covers the elements 16 t .. 16 t + 15 of the row-major matrix: their draws are those words
+    uint32_t sc = SR ? quantize_block16_sr(v, qp, c, seed, SR_STREAM, (uint64_t)t * 16) : quantize_block16(v, qp, c);
     *reinterpret_cast<uint2*>(codes + t * 8) = c;     // codes are [M, N/2] contiguous: block t at byte 8t
     scales[t] = (uint8_t)sc;
 }
@@ -28,11 +33,11 @@ template <typename T> __device__ __forceinline__ float load_as_f32(const T* p);
 template <> __device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
 template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
 
-template <typename T>
+template <typename T, bool SR>
 __global__ void __launch_bounds__(256)
 k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, QuantParams qp, QuantParams qpt,
                 uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t) {
+                uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t, uint64_t seed) {
     __shared__ float tile[64][65];
     const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
     const int tid = threadIdx.x;
@@ -51,7 +56,8 @@ k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, Quant
 #pragma unroll
             for (int i = 0; i < 16; ++i) v[i] = tile[line][blk * 16 + i];
             uint2 c;
-            uint32_t sc = quantize_block16(v, qp, c);
+            uint32_t sc = SR ? quantize_block16_sr(v, qp, c, seed, SR_STREAM, (uint64_t)(m * N + n))
+                             : quantize_block16(v, qp, c);
             *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
             scales[m * (N / 16) + n / 16] = (uint8_t)sc;
         }
@@ -63,7 +69,9 @@ k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, Quant
 #pragma unroll
             for (int i = 0; i < 16; ++i) v[i] = tile[blk * 16 + i][line];
             uint2 c;
-            uint32_t sc = quantize_block16(v, qpt, c);
+            // the transposed copy draws from its own stream, indexed by its own row-major positions
+            uint32_t sc = SR ? quantize_block16_sr(v, qpt, c, seed, SR_STREAM_T, (uint64_t)(n * M + m))
+                             : quantize_block16(v, qpt, c);
             *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
             scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
         }
@@ -77,7 +85,8 @@ static bool pow2(float g) {
     return (u & 0x7FFFFFu) == 0 && (u >> 23) != 0 && (u >> 23) != 255;
 }
 
-extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t) {
+template <bool SR>
+static int quantize_impl(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t, uint64_t seed) {
     if (!A || !A->ptr || (!out && !out_t)) return METIS_INVALID_ARG;
     if (A->dtype != METIS_BF16 && A->dtype != METIS_F32) return METIS_INVALID_ARG;
     const int64_t M = A->rows, N = A->cols;
@@ -96,9 +105,9 @@ extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, 
     if (vec_ok) {
         int64_t nb = M * (N / 16);
         const int pi = metis_prof_begin(METIS_PROF_QUANTIZE, s);
-        hipLaunchKernelGGL(k_quantize_rows_bf16, dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
+        hipLaunchKernelGGL(k_quantize_rows_bf16<SR>, dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
                            (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale),
-                           out->codes, out->scales);
+                           out->codes, out->scales, seed);
         metis_prof_end(METIS_PROF_QUANTIZE, pi, s);
         METIS_LAUNCH_CHECK();
         return METIS_OK;
@@ -111,11 +120,19 @@ extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, 
     uint8_t* ct = out_t ? out_t->codes : nullptr;
     uint8_t* sct = out_t ? out_t->scales : nullptr;
     if (A->dtype == METIS_BF16)
-        hipLaunchKernelGGL(k_quantize_tile<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)A->ptr, A->ld, M, N,
-                           qp, qpt, c, sc, ct, sct);
+        hipLaunchKernelGGL((k_quantize_tile<bf16_t, SR>), grid, dim3(256), 0, s, (const bf16_t*)A->ptr, A->ld, M, N,
+                           qp, qpt, c, sc, ct, sct, seed);
     else
-        hipLaunchKernelGGL(k_quantize_tile<float>, grid, dim3(256), 0, s, (const float*)A->ptr, A->ld, M, N,
-                           qp, qpt, c, sc, ct, sct);
+        hipLaunchKernelGGL((k_quantize_tile<float, SR>), grid, dim3(256), 0, s, (const float*)A->ptr, A->ld, M, N,
+                           qp, qpt, c, sc, ct, sct, seed);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
+}
+
+extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t) {
+    return quantize_impl<false>(stream, A, out, out_t, 0);
+}
+
+extern "C" int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t) {
+    return quantize_impl<true>(stream, A, out, out_t, seed);
 }

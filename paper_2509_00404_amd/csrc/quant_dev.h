@@ -81,3 +81,53 @@ __device__ __forceinline__ uint32_t quantize_block16(const float (&v)[16], Quant
     codes.y = w1;
     return sc;
 }
+
+// Stochastically rounded variant (Sec. 4, FP4 Training).  Same block scale and the same fp32 quotient y
+// as above; a = min(|y|, 6) lies between two neighbouring E2M1 magnitudes lo <= a <= hi and goes up
+// with probability t = (a - lo) / (hi - lo): up iff u < t, u = (word >> 8) * 2^-24, word = Philox word
+// `first_word + i` of `stream` for element i.  The E2M1 spacing around a is w = 2^(max(exponent(a), 0) - 1)
+// (0.5 below 2, then 1, then 2), so with q = a / w (exact) lo = floor(q) w, t = q - floor(q) (exact), and the
+// chosen neighbour (floor(q) + up) w is a grid value, which the packed converter then encodes exactly.
+__device__ __forceinline__ float sr_pick(float y, uint32_t word) {
+    const float a = fminf(fabsf(y), 6.0f);
+    int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;      // floor(log2 a) for normal a; a < 1 -> e = 0
+    e = e < 0 ? 0 : e;
+    const float w = __uint_as_float((uint32_t)(126 + e) << 23);  // 2^(e-1)
+    const float winv = __uint_as_float((uint32_t)(128 - e) << 23);   // 2^(1-e)
+    const float q = a * winv;
+    const float fl = floorf(q);
+    const float u = (float)(word >> 8) * 5.9604644775390625e-08f;    // 2^-24, exact
+    const float v = (fl + (u < q - fl ? 1.0f : 0.0f)) * w;
+    return __builtin_copysignf(v, y);
+}
+
+__device__ __forceinline__ uint32_t quantize_block16_sr(const float (&v)[16], QuantParams qp, uint2& codes, uint64_t seed,
+                                                        uint32_t stream, uint64_t first_word /* multiple of 4 */) {
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) amax = fmaxf(amax, fmaxf(fabsf(v[i]), fabsf(v[i + 1])));
+    const uint32_t sc = e4m3_scale_round_up(amax, qp);
+    const float step = e4m3_decode(sc) * qp.g;
+    const float r = sc == 0u ? 0.0f : recip_rn(step);
+    float y[16];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const u32x4 rw = philox_block(seed, stream, (first_word >> 2) + b);
+        y[4 * b + 0] = sr_pick(quot_rn(v[4 * b + 0], step, r), rw.x);
+        y[4 * b + 1] = sr_pick(quot_rn(v[4 * b + 1], step, r), rw.y);
+        y[4 * b + 2] = sr_pick(quot_rn(v[4 * b + 2], step, r), rw.z);
+        y[4 * b + 3] = sr_pick(quot_rn(v[4 * b + 3], step, r), rw.w);
+    }
+    uint32_t w0 = 0u, w1 = 0u;
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[0], y[1], 1.0f, 0);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[2], y[3], 1.0f, 1);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[4], y[5], 1.0f, 2);
+    w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[6], y[7], 1.0f, 3);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[8], y[9], 1.0f, 0);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[10], y[11], 1.0f, 1);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[12], y[13], 1.0f, 2);
+    w1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w1, y[14], y[15], 1.0f, 3);
+    codes.x = w0;
+    codes.y = w1;
+    return sc;
+}

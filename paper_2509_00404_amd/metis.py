@@ -46,6 +46,7 @@ _SIGNATURES = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
     "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
+    "metis_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_uint64, C.POINTER(Fp4), C.POINTER(Fp4)]),
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
@@ -174,6 +175,15 @@ def quantize(A, out=None, out_t=None):
     o = out.c() if out is not None else None
     ot = out_t.c() if out_t is not None else None
     _check(lib().metis_quantize(_stream(), C.byref(a), C.byref(o) if o else None, C.byref(ot) if ot else None))
+
+
+def quantize_sr(A, seed, out=None, out_t=None):
+    """Stochastically rounded NVFP4 quantization (draws from Philox under `seed`)."""
+    a = _mat(A)
+    o = out.c() if out is not None else None
+    ot = out_t.c() if out_t is not None else None
+    _check(lib().metis_quantize_sr(_stream(), C.byref(a), int(seed), C.byref(o) if o else None,
+                                   C.byref(ot) if ot else None))
 
 
 def split_workspace_bytes(M, N, k):

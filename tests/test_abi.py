@@ -44,3 +44,4 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.metis_sample_rows(None, 1, 100, 10, None) == -1
     assert L.metis_gaussian_omega(None, 1, 0, 4, None) == -1
     assert L.metis_quantize(None, None, None, None) == -1
+    assert L.metis_quantize_sr(None, None, 0, None, None) == -1
