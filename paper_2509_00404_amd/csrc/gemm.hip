@@ -600,33 +600,65 @@ __device__ __forceinline__ float fp4_elem_nog(const uint8_t* codes, const uint8_
 //   Aext[m, kb:kb+ka] = Ua[m,:] without its tensor scale (exact in bf16)
 //   Bext[n, 0:kb]     = Ub[n,:] without its tensor scale (exact in bf16)
 //   Bext[n, kb:kb+ka] = E2[n,:] * Sa * gUa / (gRa gRb)
-__global__ void k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1,
-                               const float* __restrict__ Mk, const float* __restrict__ E2,
-                               const uint8_t* __restrict__ ua_codes, const uint8_t* __restrict__ ua_scales, float g_ua,
-                               const float* __restrict__ Sa, const uint8_t* __restrict__ ub_codes,
-                               const uint8_t* __restrict__ ub_scales, float g_ub, const float* __restrict__ Sb,
-                               float inv_grr, bf16_t* __restrict__ Aext, bf16_t* __restrict__ Bext) {
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (Ma + Nb) * Kep) return;
-    int64_t row = t / Kep;
-    int c = (int)(t - row * Kep);
-    float v = 0.0f;
-    if (row < Ma) {
-        if (c < kb) {
-            float acc = T1[row * kb + c];
-            for (int j = 0; j < ka; ++j)
-                acc += fp4_elem_nog(ua_codes, ua_scales, Ma, j, row) * g_ua * Sa[j] * Mk[(int64_t)j * kb + c];
-            v = acc * Sb[c] * g_ub * inv_grr;
-        } else if (c < kb + ka) {
-            v = fp4_elem_nog(ua_codes, ua_scales, Ma, c - kb, row);
+// Blocks [0, ceil(Ma/64)) build 64 rows of Aext each: the dequantized factor rows U_a S_a and the small
+// matrix Mk sit in LDS, so the k_a-term sum of the first kb columns reads global memory once.  The
+// remaining blocks build 64 rows of Bext each the same way.
+#define AX_ROWS 64
+__global__ void __launch_bounds__(256)
+k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1,
+               const float* __restrict__ Mk, const float* __restrict__ E2,
+               const uint8_t* __restrict__ ua_codes, const uint8_t* __restrict__ ua_scales, float g_ua,
+               const float* __restrict__ Sa, const uint8_t* __restrict__ ub_codes,
+               const uint8_t* __restrict__ ub_scales, float g_ub, const float* __restrict__ Sb,
+               float inv_grr, bf16_t* __restrict__ Aext, bf16_t* __restrict__ Bext) {
+    extern __shared__ float ax_sm[];
+    const int nblk_a = (int)((Ma + AX_ROWS - 1) / AX_ROWS);
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x < nblk_a) {
+        float* ua = ax_sm;                          // [AX_ROWS][ka + 1]: factor entries without tensor scale
+        float* mk = ax_sm + AX_ROWS * (ka + 1);     // [ka][kb]
+        const int64_t r0 = (int64_t)blockIdx.x * AX_ROWS;
+        for (int e = tid; e < AX_ROWS * ka; e += 256) {
+            const int j = e / AX_ROWS, rr = e - j * AX_ROWS;      // consecutive threads walk along a stored factor row
+            const int64_t row = r0 + rr;
+            ua[rr * (ka + 1) + j] = row < Ma ? fp4_elem_nog(ua_codes, ua_scales, Ma, j, row) : 0.0f;
         }
-        Aext[row * Kep + c] = f32_to_bf16_rne(v);
-    } else {
-        row -= Ma;
+        for (int e = tid; e < ka * kb; e += 256) mk[e] = Mk[e] * g_ua * Sa[e / kb];
+        __syncthreads();
+        for (int e = tid; e < AX_ROWS * Kep; e += 256) {
+            const int rr = e / Kep, c = e - rr * Kep;
+            const int64_t row = r0 + rr;
+            if (row >= Ma) continue;
+            float v = 0.0f;
+            if (c < kb) {
+                float acc = T1[row * kb + c];
+                for (int j = 0; j < ka; ++j) acc += ua[rr * (ka + 1) + j] * mk[j * kb + c];
+                v = acc * Sb[c] * g_ub * inv_grr;
+            } else if (c < kb + ka) {
+                v = ua[rr * (ka + 1) + (c - kb)];
+            }
+            Aext[row * Kep + c] = f32_to_bf16_rne(v);
+        }
+        return;
+    }
+    // Bext: 64 rows per block; the stored factor rows of U_b are decoded along their contiguous axis into LDS
+    float* ub = ax_sm;                              // [AX_ROWS][kb + 1]
+    const int64_t r0 = ((int64_t)blockIdx.x - nblk_a) * AX_ROWS;
+    for (int e = tid; e < AX_ROWS * kb; e += 256) {
+        const int j = e / AX_ROWS, rr = e - j * AX_ROWS;
+        const int64_t row = r0 + rr;
+        ub[rr * (kb + 1) + j] = row < Nb ? fp4_elem_nog(ub_codes, ub_scales, Nb, j, row) : 0.0f;
+    }
+    __syncthreads();
+    for (int e = tid; e < AX_ROWS * Kep; e += 256) {
+        const int rr = e / Kep, c = e - rr * Kep;
+        const int64_t row = r0 + rr;
+        if (row >= Nb) continue;
+        float v = 0.0f;
         if (c < kb) {
-            v = fp4_elem_nog(ub_codes, ub_scales, Nb, c, row);
+            v = ub[rr * (kb + 1) + c];
         } else if (c < kb + ka) {
-            int j = c - kb;
+            const int j = c - kb;
             v = E2[row * ka + j] * Sa[j] * g_ua * inv_grr;
         }
         Bext[row * Kep + c] = f32_to_bf16_rne(v);
@@ -710,8 +742,12 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         if (ka > 0 && kb > 0 &&
             (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb)))
             return st;
-        int64_t tot = (Ma + Nb) * w.Kep;
-        hipLaunchKernelGGL(k_assemble_ext, dim3((unsigned)ceil_div64(tot, 256)), dim3(256), 0, s, Ma, Nb, ka, kb, w.Kep,
+        const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
+        const size_t ax_lds = ((size_t)AX_ROWS * ((ka > kb ? ka : kb) + 1) + (size_t)ka * kb) * sizeof(float);
+        if (ax_lds > 48 * 1024 &&
+            hipFuncSetAttribute((const void*)k_assemble_ext, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ax_lds) != hipSuccess)
+            return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(k_assemble_ext, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
                            T1, Mk, E2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
                            b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);
         METIS_LAUNCH_CHECK();
