@@ -103,9 +103,30 @@ def main():
     ops = [W, X] + ([G] if full else [])
     n_gemm = 3 if full else 1
 
+    # The operands' preparations (decompose + split_quantize, or quantize) are independent of each other, and
+    # the decomposition's small-matrix kernels occupy one CU each: one stream per operand lets them overlap.
+    # Every entry point only enqueues on the caller's current stream, so this is plain caller-side concurrency.
+    main_stream = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in ops]                 # default priority
+    ev_fork = torch.cuda.Event()
+    ev_join = [torch.cuda.Event() for _ in ops]
+
+    multi = sum(1 for o in ops if o.k) >= 2                   # worth a fork/join only with two or more decompositions
+
     def step():
-        for o in ops:
-            o.prepare()
+        if not multi:
+            for o in ops:
+                o.prepare()
+            metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin)
+            return
+        ev_fork.record(main_stream)
+        for o, st, ev in zip(ops, side, ev_join):
+            st.wait_event(ev_fork)
+            with torch.cuda.stream(st):
+                o.prepare()
+                ev.record(st)
+        for ev in ev_join:
+            main_stream.wait_event(ev)
         metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin)
         if full:
             metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin)
