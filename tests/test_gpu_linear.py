@@ -74,6 +74,22 @@ def test_all_three_products(metis, L, N, K, kx, kw, kg, out_dtype):
     assert max(e) < tol, e
 
 
+@pytest.mark.parametrize("L,N,K,k", [(1104, 1040, 1280, 16),      # fwd: pipelined kernel with ragged edge tiles
+                                     (1280, 1152, 1024, 16),      # all three products on the pipelined kernel
+                                     (1024, 1024, 384, 0)])       # no factors, three 128-deep stages
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_large_tiles_pipelined_kernel(metis, L, N, K, k, out_dtype):
+    """Shapes of at least 1024 x 1024 outputs take the 256x256-tile software-pipelined kernel when the
+    contraction is a multiple of 128, the 8-wave kernel otherwise; both with edge tiles."""
+    from paper_2509_00404_amd import workloads
+    X = workloads.planted(L, K, workloads.power_law(min(L, K, 256), 1.2), 4, rms=1.0, outlier_cols=1)
+    W = workloads.planted(N, K, workloads.power_law(min(N, K, 256), 1.0), 5, noise_top=0.01, rms=0.02)
+    G = workloads.planted(L, N, workloads.power_law(min(L, N, 256), 2.0, head=4, head_gain=100.0), 6, rms=1e-3)
+    e, _, _ = _three(metis, X, W, G, k, k, k, 8, 0.25, out_dtype)
+    tol = GEMM_RTOL if out_dtype == torch.bfloat16 else 5e-3
+    assert max(e) < tol, e
+
+
 def test_workspace_and_shape_errors(metis):
     from paper_2509_00404_amd import workloads
     X = workloads.gaussian(64, 128, 1)
