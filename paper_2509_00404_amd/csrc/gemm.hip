@@ -175,19 +175,56 @@ template <typename T> __device__ __forceinline__ void atomic_out(T* p, float v);
 template <> __device__ __forceinline__ void atomic_out<float>(float* p, float v) { unsafeAtomicAdd(p, v); }
 template <> __device__ __forceinline__ void atomic_out<bf16_t>(bf16_t*, float) {}   // splits are only used with fp32 output
 
+// Workgroup ids are dealt round-robin to the 8 XCDs by the hardware, and each XCD has its own L2.
+// XCD x therefore gets one RM x RN region of the tile grid (when the grid splits that way) and walks it
+// row-major, so the ~32 tiles it runs at a time form a block of few distinct A and B panels; without a
+// fitting region every XCD takes a contiguous run of row-major tiles.
+struct TileMap {
+    int tiles_n;     // tiles along N
+    int rm, rn;      // region shape in tiles, 0 = no regions
+};
+
+static inline TileMap make_tile_map(int64_t tiles_m, int64_t tiles_n) {
+    TileMap t = {(int)tiles_n, 0, 0};
+    const int64_t total = tiles_m * tiles_n;
+    if (total % 8) return t;
+    const int64_t per = total / 8;
+    int64_t best = 0;
+    for (int64_t rn = 1; rn <= tiles_n; ++rn) {          // the most square region that tiles the grid
+        if (per % rn || tiles_n % rn) continue;
+        const int64_t rm = per / rn;
+        if (tiles_m % rm) continue;
+        const int64_t cur = rn < rm ? rn : rm;
+        if (cur > best) { best = cur; t.rm = (int)rm; t.rn = (int)rn; }
+    }
+    return t;
+}
+
+__device__ __forceinline__ void tile_coords(const TileMap& t, int& tm, int& tn) {
+    const int total = gridDim.x, b = blockIdx.x;
+    if (t.rm > 0) {
+        const int xcd = b & 7, local = b >> 3, regions_n = t.tiles_n / t.rn;
+        tm = (xcd / regions_n) * t.rm + local / t.rn;
+        tn = (xcd % regions_n) * t.rn + local % t.rn;
+    } else {
+        int tile = b;
+        if ((total & 7) == 0) tile = (b & 7) * (total >> 3) + (b >> 3);
+        tm = tile / t.tiles_n;
+        tn = tile % t.tiles_n;
+    }
+}
+
 template <int BM, int BN>
 constexpr size_t gemm_lds_bytes() {
     return 2 * ((size_t)BM * (G_CROW + G_SROW) + (size_t)BN * (G_CROW + G_SROW));
 }
 
 // 1-D grid of ceil(M / BM) * ceil(N / BN) workgroups of WMW x WNW waves, each wave TM x TN tiles of
-// 32x32 (BM = 32 TM WMW, BN = 32 TN WNW).  Workgroup ids are dealt round-robin to the 8 XCDs by the
-// hardware; the remap below hands each XCD a contiguous run of tiles so that its L2 sees few
-// distinct rows of A.
+// 32x32 (BM = 32 TM WMW, BN = 32 TN WNW); workgroup -> tile by TileMap.
 template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
 __global__ void __launch_bounds__(64 * WMW * WNW)
 k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n,
+              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap,
               int iters_per_split) {
     constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -195,12 +232,9 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
     constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
                   BUF = OFF_SB + BN * G_SROW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int tile = blockIdx.x;
-    {
-        const int total = gridDim.x;
-        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
-    }
-    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    int tile_m, tile_n;
+    tile_coords(tmap, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int wm = (wave / WNW) * 32 * TM, wn = (wave % WNW) * 32 * TN;
     const int li = lane & 31, half = lane >> 5;
 
@@ -320,18 +354,15 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 template <typename OUT>
 __global__ void __launch_bounds__(256)
 k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-                   const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tiles_n) {
+                   const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
     constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
                   BUF = OFF_SB + BN * G_SROW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int tile = blockIdx.x;
-    {
-        const int total = gridDim.x;
-        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
-    }
-    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+    int tile_m, tile_n;
+    tile_coords(tmap, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
     const int li = lane & 31, half = lane >> 5;
 
@@ -533,7 +564,7 @@ int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
     auto kern = k_fp4_gemm_nt_pipe<OUT>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn));
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
@@ -554,12 +585,12 @@ int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, true, OUT>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn, ips);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
     } else {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, false, OUT>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, (int)tn, ips);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
     }
     METIS_LAUNCH_CHECK();
     return METIS_OK;
