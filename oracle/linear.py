@@ -52,6 +52,26 @@ def split_quantize(A, U, S, V, g_u, g_v, g_r, want_t=True):
     return SplitQ(Ut, np.asarray(S, dtype=np.float64), Vt, Rq, Rtq)
 
 
+def split_quantize_sr(A, U, S, V, g_u, g_v, g_r, seed, want_t=True):
+    """split_quantize with the stochastically rounded quantizer (Sec. 4: SR is the default of the FP4
+    runs).  Readings of this build: the residual draws from `seed` (stream 3 for R, stream 4 for the
+    transposed copy), Q(U^T) from `seed + 1` and Q(V^T) from `seed + 2` (both transposed copies, stream 4),
+    so that no two tensors share draws."""
+    from .decompose import residual
+    A = np.asarray(A, dtype=np.float64)
+    if U is None or U.shape[1] == 0:
+        R = A
+        Ut = Vt = None
+        S = np.zeros(0)
+    else:
+        R = residual(A, U, S, V)
+        Ut = quant.quantize_sr(np.ascontiguousarray(U.T), g_u, seed + 1, quant.STREAM_SR_T) + (g_u,)
+        Vt = quant.quantize_sr(np.ascontiguousarray(V.T), g_v, seed + 2, quant.STREAM_SR_T) + (g_v,)
+    Rq = quant.quantize_sr(R, g_r, seed, quant.STREAM_SR) + (g_r,)
+    Rtq = quant.quantize_sr(np.ascontiguousarray(R.T), g_r, seed, quant.STREAM_SR_T) + (g_r,) if want_t else None
+    return SplitQ(Ut, np.asarray(S, dtype=np.float64), Vt, Rq, Rtq)
+
+
 def assemble(sq, transposed_residual=False):
     """Abar [M,N] from a SplitQ, using R (blocks along N) or Rt (blocks along M)."""
     if transposed_residual:

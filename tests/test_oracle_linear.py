@@ -118,3 +118,33 @@ def test_residual_is_narrower_and_quantizes_with_less_error():
     err_r = np.linalg.norm(quant.dequantize(*quant.quantize(R, g), g) - R)
     err_a = np.linalg.norm(quant.dequantize(*quant.quantize(A, g), g) - A)
     assert err_r < 0.2 * err_a
+
+
+def test_split_quantize_sr_is_unbiased_where_nearest_rounding_is_not():
+    """Sec. 4: stochastic rounding removes the quantization bias.  Averaged over seeds, the split
+    quantized with SR reproduces A far better than any single draw and than nearest rounding's
+    systematic error allows."""
+    odec, olin, oq = dec, lin, quant
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((64, 8)) @ rng.standard_normal((8, 96)) + 0.3 * rng.standard_normal((64, 96))
+    U, S, V = odec.decompose(A, 8, 8, 1.0, 5)
+    g = oq.tensor_scale_for(np.abs(A).max())
+    one = olin.assemble(olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=0))
+    mean = np.zeros_like(A)
+    n = 48
+    for seed in range(n):
+        sq = olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=10 * seed)
+        # the residual part alone is unbiased; factors enter as a product, so average the residual term
+        mean += oq.dequantize(*sq.R)
+    mean /= n
+    R = odec.residual(A, U, S, V)
+    rne = oq.dequantize(*(oq.quantize(R, g) + (g,)))
+    err_one = np.linalg.norm(oq.dequantize(*olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=0).R) - R)
+    err_mean = np.linalg.norm(mean - R)
+    assert err_mean < err_one / 4                   # ~1/sqrt(48) of a single draw
+    assert err_mean < np.linalg.norm(rne - R) / 2   # below what deterministic rounding leaves
+    assert np.isfinite(one).all()
+    # distinct tensors draw from distinct keys: U^T and R^T codes are not produced from shared words
+    a = olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=1)
+    b = olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=2)
+    assert not np.array_equal(a.R[0], b.R[0]) and not np.array_equal(a.Ut[0], b.Ut[0])
