@@ -162,6 +162,16 @@ int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const
                          const float* V, int k, metis_split* out, float* R_debug,
                          void* workspace, size_t workspace_bytes);
 
+/*
+ * Stochastically rounded split (Sec. 4, "FP4 Training"): as metis_split_quantize, with every
+ * quantizer replaced by the rule of metis_quantize_sr.  Draws: R from `seed` (stream 3), R^T from
+ * `seed` (stream 4), Q(U^T) from `seed + 1` and Q(V^T) from `seed + 2` (stream 4 each), the word
+ * index being the element's row-major position in the tensor it is written to.
+ */
+int metis_split_quantize_sr(void* stream, const metis_mat* A, const float* U, const float* S,
+                            const float* V, int k, uint64_t seed, metis_split* out, float* R_debug,
+                            void* workspace, size_t workspace_bytes);
+
 /* ---- FP4 GEMMs on split operands (Eq. 2, Eq. 3, and the W_R gradient after Eq. 3) ------ */
 
 /* Bytes of device workspace the three GEMM calls need (max over them). */

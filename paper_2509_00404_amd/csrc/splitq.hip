@@ -55,13 +55,13 @@ __global__ void k_split_factors(const float* __restrict__ U, const float* __rest
 // Blocks along the rows of A (transposed output) are quantized straight from the accumulators
 // after a half-wave swap; blocks along the columns go through a per-wave LDS tile.
 // grid: (ceil(M/128), csplit); block 256.  KS = kp / 16.
-template <int KS>
+template <int KS, bool SR>
 __global__ void __launch_bounds__(256)
 k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, int64_t cchunk,
                  const bf16_t* __restrict__ us_hi, const bf16_t* __restrict__ us_lo,
                  const bf16_t* __restrict__ v_hi, const bf16_t* __restrict__ v_lo, QuantParams qp,
                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint8_t* __restrict__ codes_t,
-                 uint8_t* __restrict__ scales_t, float* __restrict__ R_debug) {
+                 uint8_t* __restrict__ scales_t, float* __restrict__ R_debug, uint64_t seed) {
     constexpr int KP = 16 * KS, LDV = KP + 8;
     constexpr int VVEC = (2 * RQ_COLS * (KP / 8) + 255) / 256;                  // 16-byte V vectors per thread
     __shared__ __attribute__((aligned(16))) bf16_t Vs[2][2][RQ_COLS][LDV];      // [buffer][hi/lo][column][k]
@@ -196,7 +196,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 if (m < M && n < cend) {
                     if (codes) {
                         uint2 c;
-                        uint32_t sc = quantize_block16(x, qp, c);
+                        // stochastic rounding draws: stream 3, word = row-major position in R
+                        uint32_t sc = SR ? quantize_block16_sr(x, qp, c, seed, 3u, (uint64_t)(m * N + n))
+                                         : quantize_block16(x, qp, c);
                         *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
                         scales[m * (N / 16) + n / 16] = (uint8_t)sc;
                     }
@@ -224,7 +226,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 const int64_t n = n0 + 32 * t + li, m = wr0 + 16 * half;
                 if (n < cend && m < M) {
                     uint2 c;
-                    uint32_t sc = quantize_block16(x, qp, c);
+                    // transposed copy: stream 4, word = row-major position in R^T
+                    uint32_t sc = SR ? quantize_block16_sr(x, qp, c, seed, 4u, (uint64_t)(n * M + m))
+                                     : quantize_block16(x, qp, c);
                     *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
                     scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
                 }
@@ -261,9 +265,12 @@ extern "C" size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k) {
     return align_up((size_t)M * kp * 2, 256) * 2 + align_up((size_t)N * kp * 2, 256) * 2;
 }
 
-extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,
-                                    int k, metis_split* out, float* R_debug, void* workspace,
-                                    size_t workspace_bytes) {
+extern "C" int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t);
+
+template <bool SR>
+static int split_quantize_impl(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,
+                               int k, uint64_t seed, metis_split* out, float* R_debug, void* workspace,
+                               size_t workspace_bytes) {
     if (!A || !A->ptr || !U || !S || !V || !out || !workspace) return METIS_INVALID_ARG;
     if (k < 1 || out->k != k || !out->S) return METIS_INVALID_ARG;
     if (A->dtype != METIS_BF16 || k > 128) return METIS_UNSUPPORTED;
@@ -300,16 +307,34 @@ extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const floa
     const bf16_t* Ap = (const bf16_t*)A->ptr;
     const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
     switch (kp / 16) {
-        case 1: hipLaunchKernelGGL(k_residual_quant<1>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
-        case 2: hipLaunchKernelGGL(k_residual_quant<2>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
-        case 4: hipLaunchKernelGGL(k_residual_quant<4>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
-        default: hipLaunchKernelGGL(k_residual_quant<8>, grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug); break;
+        case 1: hipLaunchKernelGGL((k_residual_quant<1, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
+        case 2: hipLaunchKernelGGL((k_residual_quant<2, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
+        case 4: hipLaunchKernelGGL((k_residual_quant<4, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
+        default: hipLaunchKernelGGL((k_residual_quant<8, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
     }
     metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
     METIS_LAUNCH_CHECK();
     // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
     metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
+    if (SR) {
+        // the factors draw under their own keys so that no two tensors share draws
+        int st = metis_quantize_sr(stream, &um, seed + 1, nullptr, &out->Ut);
+        if (st != METIS_OK) return st;
+        return metis_quantize_sr(stream, &vm, seed + 2, nullptr, &out->Vt);
+    }
     int st = metis_quantize(stream, &um, nullptr, &out->Ut);
     if (st != METIS_OK) return st;
     return metis_quantize(stream, &vm, nullptr, &out->Vt);
+}
+
+extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,
+                                    int k, metis_split* out, float* R_debug, void* workspace,
+                                    size_t workspace_bytes) {
+    return split_quantize_impl<false>(stream, A, U, S, V, k, 0, out, R_debug, workspace, workspace_bytes);
+}
+
+extern "C" int metis_split_quantize_sr(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,
+                                       int k, uint64_t seed, metis_split* out, float* R_debug, void* workspace,
+                                       size_t workspace_bytes) {
+    return split_quantize_impl<true>(stream, A, U, S, V, k, seed, out, R_debug, workspace, workspace_bytes);
 }

@@ -50,6 +50,8 @@ _SIGNATURES = {
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
+    "metis_split_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int, C.c_uint64, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
     "metis_profile_events": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_int]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
@@ -199,6 +201,19 @@ def split_quantize(A, U, S, V, out, R_debug=None, workspace=None):
     _check(lib().metis_split_quantize(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
                                       out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None,
                                       workspace.data_ptr(), workspace.numel()))
+
+
+def split_quantize_sr(A, U, S, V, seed, out, R_debug=None, workspace=None):
+    """split_quantize with stochastically rounded quantizers (draws from Philox under `seed`)."""
+    a = _mat(A)
+    s = out.c()
+    if workspace is None:
+        workspace = torch.empty((split_workspace_bytes(A.shape[0], A.shape[1], out.k),), dtype=torch.uint8,
+                                device=A.device)
+    _check(lib().metis_split_quantize_sr(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
+                                         out.k, int(seed), C.byref(s),
+                                         R_debug.data_ptr() if R_debug is not None else None,
+                                         workspace.data_ptr(), workspace.numel()))
 
 
 def linear_workspace_bytes(L, N, K, k):

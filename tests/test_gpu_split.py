@@ -83,3 +83,37 @@ def test_argument_errors(metis):
     with pytest.raises(metis.MetisError):
         metis.split_quantize(A, U, S, V, good, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
+
+
+# ---- stochastically rounded split (Sec. 4): bit-exact against the oracle on the dumped quantizer input ----
+@pytest.mark.parametrize("M,N,k,p,rho,want_t", [(208, 96, 12, 4, 0.5, True), (1008, 528, 33, 7, 0.25, True),
+                                                (96, 1024, 16, 16, 1.0, False), (2048, 1024, 64, 16, 0.125, True)])
+def test_split_quantize_sr(metis, M, N, k, p, rho, want_t):
+    from paper_2509_00404_amd import workloads
+    q = min(M, N)
+    A = workloads.planted(M, N, 50.0 * np.arange(1, q + 1) ** -1.3 + 0.02, seed=M + N + 1)
+    Ad = A.cuda()
+    U, S, V = metis.decompose(Ad, k, p, rho, 31)
+    g = oq.tensor_scale_for(float(A.abs().max()))
+    sp = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+    Rd = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    seed = 1000 + M
+    metis.split_quantize_sr(Ad, U, S, V, seed, sp, R_debug=Rd)
+    torch.cuda.synchronize()
+    R = Rd.double().cpu().numpy()
+    Un, Vn = U.double().cpu().numpy(), V.double().cpu().numpy()
+    c, s = oq.quantize_sr(R, g, seed, oq.STREAM_SR)
+    assert np.array_equal(sp.R.scales.cpu().numpy(), s) and np.array_equal(sp.R.codes.cpu().numpy(), c)
+    if want_t:
+        c, s = oq.quantize_sr(np.ascontiguousarray(R.T), g, seed, oq.STREAM_SR_T)
+        assert np.array_equal(sp.Rt.scales.cpu().numpy(), s) and np.array_equal(sp.Rt.codes.cpu().numpy(), c)
+    c, s = oq.quantize_sr(np.ascontiguousarray(Un.T), sp.Ut.tscale, seed + 1, oq.STREAM_SR_T)
+    assert np.array_equal(sp.Ut.scales.cpu().numpy(), s) and np.array_equal(sp.Ut.codes.cpu().numpy(), c)
+    c, s = oq.quantize_sr(np.ascontiguousarray(Vn.T), sp.Vt.tscale, seed + 2, oq.STREAM_SR_T)
+    assert np.array_equal(sp.Vt.scales.cpu().numpy(), s) and np.array_equal(sp.Vt.codes.cpu().numpy(), c)
+    # and it differs from the nearest-rounding split only in codes, never in scales
+    sp0 = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+    metis.split_quantize(Ad, U, S, V, sp0)
+    torch.cuda.synchronize()
+    assert np.array_equal(sp0.R.scales.cpu().numpy(), sp.R.scales.cpu().numpy())
+    assert not np.array_equal(sp0.R.codes.cpu().numpy(), sp.R.codes.cpu().numpy())
