@@ -101,6 +101,26 @@ def linear_wgrad(gq, xq):
     return assemble(gq, transposed_residual=True).T @ assemble(xq, transposed_residual=True)
 
 
+def factor_grads(dW, wq):
+    """Gradients of the weight's low-rank factors (Sec. 3.2, backward pass, the formulas after Eq. 3).
+
+    Layout of this build: W[N,K] = U S V^T + W_R with U [N,k], V [K,k] (the paper writes Y = X W with
+    W [m,n], so its U_k is this V and its V_k is this U), dW[N,K] = dL/dW = Gbar^T Xbar as returned
+    by linear_wgrad.  With the quantized factors Ubar, Vbar and the unquantized S:
+        dL/dU = dW Vbar S          [N,k]
+        dL/dS = Ubar^T dW Vbar     [k,k]   (the paper's k x k expression, transposed to this layout)
+        dL/dV = dW^T Ubar S        [K,k]
+    which are the paper's four-term sums with Xbar^T (P T Q^T + D_R) collected into dW.
+    Returns (dU, dS, dV) in fp64.
+    """
+    dW = np.asarray(dW, dtype=np.float64)
+    Ub = quant.dequantize(*wq.Ut).T          # [N,k]
+    Vb = quant.dequantize(*wq.Vt).T          # [K,k]
+    S = np.asarray(wq.S, dtype=np.float64)
+    T = dW @ Vb
+    return T * S, Ub.T @ T, (dW.T @ Ub) * S
+
+
 def linear_fwd_expanded(xq, wq):
     """Eq. 2 written out term by term (used only to pin linear_fwd)."""
     XR = quant.dequantize(*xq.R)

@@ -148,3 +148,38 @@ def test_split_quantize_sr_is_unbiased_where_nearest_rounding_is_not():
     a = olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=1)
     b = olin.split_quantize_sr(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, seed=2)
     assert not np.array_equal(a.R[0], b.R[0]) and not np.array_equal(a.Ut[0], b.Ut[0])
+
+
+def test_factor_grads_match_finite_differences_of_the_quantized_forward():
+    """L(U, S, V) = <G, X (U S V^T + R)^T> is linear in each factor: its gradient at the dequantized
+    factors must equal factor_grads fed dW = G^T X (central differences are exact for a bilinear form up
+    to rounding)."""
+    rng = np.random.default_rng(11)
+    L_, N, K, k = 24, 32, 48, 4
+    X = rng.standard_normal((L_, K)); G = rng.standard_normal((L_, N))
+    W = rng.standard_normal((N, k)) @ rng.standard_normal((k, K)) + 0.1 * rng.standard_normal((N, K))
+    U, S, V = dec.decompose(W, k, 4, 1.0, 3)
+    wq = lin.split_quantize(W, U, S, V, 2.0 ** -11, 2.0 ** -11, quant.tensor_scale_for(np.abs(W).max()))
+    Ub, Vb = quant.dequantize(*wq.Ut).T, quant.dequantize(*wq.Vt).T
+    Rb = quant.dequantize(*wq.R)
+    dW = G.T @ X
+    dU, dS, dV = lin.factor_grads(dW, wq)
+    assert dU.shape == (N, k) and dS.shape == (k, k) and dV.shape == (K, k)
+
+    def loss(Uc, Sm, Vc):
+        return float(np.sum(G * (X @ (Uc @ Sm @ Vc.T + Rb).T)))
+    Sm = np.diag(wq.S)
+    h = 1e-3
+    for (i, j) in [(0, 0), (5, 2), (N - 1, k - 1)]:
+        E = np.zeros_like(Ub); E[i, j] = h
+        assert np.isclose((loss(Ub + E, Sm, Vb) - loss(Ub - E, Sm, Vb)) / (2 * h), dU[i, j], rtol=1e-8, atol=1e-9)
+    for (i, j) in [(0, 0), (7, 1), (K - 1, k - 1)]:
+        E = np.zeros_like(Vb); E[i, j] = h
+        assert np.isclose((loss(Ub, Sm, Vb + E) - loss(Ub, Sm, Vb - E)) / (2 * h), dV[i, j], rtol=1e-8, atol=1e-9)
+    for (i, j) in [(0, 0), (1, 3), (k - 1, k - 1)]:
+        E = np.zeros_like(Sm); E[i, j] = h
+        assert np.isclose((loss(Ub, Sm + E, Vb) - loss(Ub, Sm - E, Vb)) / (2 * h), dS[i, j], rtol=1e-8, atol=1e-9)
+    # and dW itself is the gradient with respect to the residual (the hot path's wgrad)
+    E = np.zeros_like(Rb); E[3, 9] = h
+    f = lambda Rm: float(np.sum(G * (X @ (Ub @ Sm @ Vb.T + Rm).T)))
+    assert np.isclose((f(Rb + E) - f(Rb - E)) / (2 * h), dW[3, 9], rtol=1e-8)
