@@ -196,6 +196,14 @@ def main():
         else:
             phases[f"quantize_{name}_ms"] = timed(lambda: metis.quantize(o.A, o.q.R, o.q.Rt))
     phases["linear_fwd_ms"] = timed(lambda: metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin))
+    if W.k:
+        # gradients of W's factors from a dense dW (outside the timed step: an extra output of the backward pass)
+        dWf = dW if full else torch.randn((N, K), dtype=torch.bfloat16, device="cuda")
+        gU = torch.empty((N, W.k), dtype=torch.float32, device="cuda")
+        gS = torch.empty((W.k, W.k), dtype=torch.float32, device="cuda")
+        gV = torch.empty((K, W.k), dtype=torch.float32, device="cuda")
+        ws_fg = torch.empty((metis.factor_grads_workspace_bytes(N, K, W.k),), dtype=torch.uint8, device="cuda")
+        phases["factor_grads_W_ms"] = timed(lambda: metis.fp4_factor_grads(dWf, W.q, gU, gS, gV, ws_fg))
     if full:
         phases["linear_dgrad_ms"] = timed(lambda: metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin))
         phases["linear_wgrad_ms"] = timed(lambda: metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin))

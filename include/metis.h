@@ -187,6 +187,31 @@ int metis_fp4_linear_dgrad(void* stream, const metis_split* G, const metis_split
 int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const metis_split* X, metis_mat* dW,
                            void* workspace, size_t workspace_bytes);
 
+/* ---- gradients of the weight's low-rank factors (Sec. 3.2, backward formulas after Eq. 3) --- */
+
+/* Bytes of device workspace metis_fp4_factor_grads needs for W[N,K] split at rank k. */
+size_t metis_factor_grads_workspace_bytes(int64_t N, int64_t K, int k);
+
+/*
+ * Gradients with respect to the factors of W[N,K] = U diag(S) V^T + W_R, given the dense
+ * dW[N,K] = Gbar^T Xbar that metis_fp4_linear_wgrad wrote (which is also dL/dW_R).  The
+ * paper's sums over the split terms of X and of the output gradient collect into dW:
+ *     dU[N,k] = dW Vbar diag(S)      dS[k,k] = Ubar^T dW Vbar      dV[K,k] = dW^T Ubar diag(S)
+ * Ubar, Vbar are the dequantized W->Ut [k,N], W->Vt [k,K]; S = W->S stays fp32.  (This
+ * build's U [N,k] holds the paper's V_k and its V [K,k] the paper's U_k, because W is stored
+ * [out, in].)  dS is the full k x k matrix, row-major; a diagonal S takes its diagonal.
+ *   dW   device, fp32 or bf16, [N,K] with row stride ld >= K
+ *   W    only Ut, Vt, S and k are read; 1 <= k <= 128; N, K multiples of 16
+ *   dU, dS, dV   device fp32, caller-owned, contiguous row-major, overwritten
+ *   workspace    device, 16-byte aligned, >= metis_factor_grads_workspace_bytes(N, K, k)
+ * Products accumulate in fp64 and round once to fp32.  Asynchronous on `stream`.
+ * Errors: METIS_INVALID_ARG (null pointer, dtype, k out of range, misaligned workspace),
+ * METIS_BAD_SHAPE (factor shapes do not match dW), METIS_WORKSPACE_TOO_SMALL.
+ */
+int metis_fp4_factor_grads(void* stream, const metis_mat* dW, const metis_split* W,
+                           float* dU, float* dS, float* dV,
+                           void* workspace, size_t workspace_bytes);
+
 /* ---- measurement aid ---------------------------------------------------------------------- */
 
 /*

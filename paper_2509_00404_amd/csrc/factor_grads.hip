@@ -1,0 +1,144 @@
+// Gradients of the weight's low-rank factors (Sec. 3.2, backward pass: the formulas after Eq. 3).
+// Layout of this build: W[N,K] = U S V^T + W_R, U [N,k], V [K,k]; dW[N,K] = Gbar^T Xbar is the output
+// of metis_fp4_linear_wgrad.  With the quantized factors Ubar, Vbar and the unquantized S:
+//     dL/dU = dW Vbar S [N,k],   dL/dS = Ubar^T dW Vbar [k,k],   dL/dV = dW^T Ubar S [K,k]
+// (the paper's four-term sums with Xbar^T (P T Q^T + D_R) collected into dW).  Three skinny products of the
+// dense dW with the dequantized factors on the fp64 matrix cores, contraction split over workgroups.
+#include "common.h"
+#include "dgemm.h"
+#include "../../include/metis.h"
+
+namespace {
+
+// out[j][c] = value of the FP4 factor entry (j, c), times scale[j] when given
+__global__ void k_dequant_factor(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int k, int64_t cols,
+                                 float g, const float* __restrict__ rowscale, float* __restrict__ out) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)k * cols) return;
+    const int64_t j = t / cols, c = t - j * cols;
+    const uint32_t byte = codes[j * (cols / 2) + c / 2];
+    const uint32_t nib = (c & 1) ? (byte >> 4) : (byte & 15u);
+    const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    float v = grid[nib & 7u] * e4m3_decode(scales[j * (cols / 16) + c / 16]) * g;
+    if (nib & 8u) v = -v;
+    out[t] = rowscale ? v * rowscale[j] : v;
+}
+
+__global__ void k_zero_f64(double* __restrict__ p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t st = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += st) p[i] = 0.0;
+}
+
+// out[r][j] = (float)(in[r][j] * colscale[j])  (colscale optional)
+__global__ void k_f64_to_f32_cols(const double* __restrict__ in, int64_t rows, int k, const float* __restrict__ colscale,
+                                  float* __restrict__ out) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * k) return;
+    const int j = (int)(t % k);
+    out[t] = (float)(colscale ? in[t] * (double)colscale[j] : in[t]);
+}
+
+struct FgLayout {
+    size_t off_t, off_dv, off_ds, zero_bytes, off_vd, off_ud, off_uds, total;
+};
+
+FgLayout fg_layout(int64_t N, int64_t K, int k) {
+    FgLayout L;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.off_t = take((size_t)N * k * 8);
+    L.off_dv = take((size_t)K * k * 8);
+    L.off_ds = take((size_t)k * k * 8);
+    L.zero_bytes = o;
+    L.off_vd = take((size_t)k * K * 4);
+    L.off_ud = take((size_t)k * N * 4);
+    L.off_uds = take((size_t)k * N * 4);
+    L.total = o;
+    return L;
+}
+
+DOperand opnd(const void* p, int64_t s_outer, int64_t s_k) {
+    DOperand o;
+    o.p = p; o.s_outer = s_outer; o.s_k = s_k; o.map_outer = nullptr; o.map_k = nullptr; o.nparts = 1; o.part_stride = 0;
+    return o;
+}
+
+DEpilogue epi64(double* c, int64_t ldc) {
+    DEpilogue e;
+    e.c = c; e.ldc = ldc; e.hi_t = nullptr; e.lo_t = nullptr; e.ld_t = 0; e.skip = nullptr;
+    return e;
+}
+
+int splits_for(int64_t Kc, int64_t tiles) {
+    int64_t s = 1024 / (tiles > 1024 ? 1024 : tiles), maxs = Kc / 64;
+    if (s > maxs) s = maxs;
+    return (int)(s < 1 ? 1 : s);
+}
+
+bool fp4_ok(const metis_fp4& f, int64_t rows, int64_t cols) {
+    return f.codes && f.scales && f.rows == rows && f.cols == cols && cols % 16 == 0 && f.tscale > 0.0f;
+}
+
+template <typename TW>
+int run(hipStream_t s, const TW* dW, int64_t ld, int64_t N, int64_t K, int k, const metis_split* W, float* dU, float* dS,
+        float* dV, char* ws, const FgLayout& L) {
+    double* T = (double*)(ws + L.off_t);
+    double* dV64 = (double*)(ws + L.off_dv);
+    double* dS64 = (double*)(ws + L.off_ds);
+    float* Vd = (float*)(ws + L.off_vd);
+    float* Ud = (float*)(ws + L.off_ud);
+    float* UdS = (float*)(ws + L.off_uds);
+    hipLaunchKernelGGL(k_zero_f64, dim3(256), dim3(256), 0, s, (double*)ws, L.zero_bytes / 8);
+    hipLaunchKernelGGL(k_dequant_factor, dim3((unsigned)ceil_div64((int64_t)k * K, 256)), dim3(256), 0, s, W->Vt.codes,
+                       W->Vt.scales, k, K, W->Vt.tscale, (const float*)nullptr, Vd);
+    hipLaunchKernelGGL(k_dequant_factor, dim3((unsigned)ceil_div64((int64_t)k * N, 256)), dim3(256), 0, s, W->Ut.codes,
+                       W->Ut.scales, k, N, W->Ut.tscale, (const float*)nullptr, Ud);
+    hipLaunchKernelGGL(k_dequant_factor, dim3((unsigned)ceil_div64((int64_t)k * N, 256)), dim3(256), 0, s, W->Ut.codes,
+                       W->Ut.scales, k, N, W->Ut.tscale, W->S, UdS);
+    METIS_LAUNCH_CHECK();
+    const int64_t tk = ceil_div64(k, 32);
+    // T = dW Vbar                      [N,k], contraction over K
+    launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, ld, 1), opnd(Vd, K, 1), N, k, K,
+                                            splits_for(K, ceil_div64(N, 32) * tk), epi64(T, k));
+    // dV = dW^T (Ubar S)               [K,k], contraction over N
+    launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, 1, ld), opnd(UdS, N, 1), K, k, N,
+                                            splits_for(N, ceil_div64(K, 32) * tk), epi64(dV64, k));
+    METIS_LAUNCH_CHECK();
+    // dS = Ubar^T T                    [k,k], contraction over N
+    launch_dgemm<float, double, EPI_ATOMIC_F64>(s, opnd(Ud, N, 1), opnd(T, 1, k), k, k, N, splits_for(N, tk * tk),
+                                                epi64(dS64, k));
+    METIS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(N * k, 256)), dim3(256), 0, s, T, N, k, W->S, dU);
+    hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(K * k, 256)), dim3(256), 0, s, dV64, K, k,
+                       (const float*)nullptr, dV);
+    hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64((int64_t)k * k, 256)), dim3(256), 0, s, dS64,
+                       (int64_t)k, k, (const float*)nullptr, dS);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+}  // namespace
+
+extern "C" size_t metis_factor_grads_workspace_bytes(int64_t N, int64_t K, int k) {
+    if (N < 1 || K < 1 || k < 1) return 0;
+    return fg_layout(N, K, k).total;
+}
+
+extern "C" int metis_fp4_factor_grads(void* stream, const metis_mat* dW, const metis_split* W, float* dU, float* dS,
+                                      float* dV, void* workspace, size_t workspace_bytes) {
+    if (!dW || !dW->ptr || !W || !dU || !dS || !dV || !workspace) return METIS_INVALID_ARG;
+    if (dW->dtype != METIS_F32 && dW->dtype != METIS_BF16) return METIS_INVALID_ARG;
+    const int64_t N = dW->rows, K = dW->cols;
+    const int k = W->k;
+    if (N < 1 || K < 1 || dW->ld < K) return METIS_BAD_SHAPE;
+    if (k < 1 || k > 128 || !W->S) return METIS_INVALID_ARG;
+    if (!fp4_ok(W->Ut, k, N) || !fp4_ok(W->Vt, k, K)) return METIS_BAD_SHAPE;
+    const FgLayout L = fg_layout(N, K, k);
+    if (workspace_bytes < L.total) return METIS_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16) return METIS_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (dW->dtype == METIS_F32)
+        return run<float>(s, (const float*)dW->ptr, dW->ld, N, K, k, W, dU, dS, dV, (char*)workspace, L);
+    return run<bf16_t>(s, (const bf16_t*)dW->ptr, dW->ld, N, K, k, W, dU, dS, dV, (char*)workspace, L);
+}

@@ -60,6 +60,9 @@ _SIGNATURES = {
                                          C.c_void_p, C.c_size_t]),
     "metis_fp4_linear_wgrad": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                          C.c_void_p, C.c_size_t]),
+    "metis_factor_grads_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
+    "metis_fp4_factor_grads": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Split), C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_size_t]),
 }
 
 
@@ -238,6 +241,21 @@ def fp4_linear_dgrad(G, W, dX, workspace):
 
 def fp4_linear_wgrad(G, X, dW, workspace):
     return _linear(lib().metis_fp4_linear_wgrad, G, X, dW, workspace)
+
+
+def factor_grads_workspace_bytes(N, K, k):
+    return int(lib().metis_factor_grads_workspace_bytes(N, K, k))
+
+
+def fp4_factor_grads(dW, W, dU, dS, dV, workspace=None):
+    """dU [N,k], dS [k,k], dV [K,k] (fp32, overwritten) from dW [N,K] and the quantized factors of W."""
+    m, w = _mat(dW), W.c()
+    if workspace is None:
+        workspace = torch.empty((factor_grads_workspace_bytes(dW.shape[0], dW.shape[1], W.k),), dtype=torch.uint8,
+                                device=dW.device)
+    _check(lib().metis_fp4_factor_grads(_stream(), C.byref(m), C.byref(w), dU.data_ptr(), dS.data_ptr(),
+                                        dV.data_ptr(), workspace.data_ptr(), workspace.numel()))
+    return dU, dS, dV
 
 
 PROF_GEMM, PROF_BROADCAST, PROF_RESIDUAL_QUANT, PROF_QUANTIZE = 0, 1, 2, 3
