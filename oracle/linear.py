@@ -72,6 +72,27 @@ def split_quantize_sr(A, U, S, V, g_u, g_v, g_r, seed, want_t=True):
     return SplitQ(Ut, np.asarray(S, dtype=np.float64), Vt, Rq, Rtq)
 
 
+def split_from_parts(W_R, U, S, V, g_u, g_v, g_r, want_t=True, seed=None):
+    """Quantized split of a weight whose parts are stored, not recomputed (Sec. 3.2: for parameters the
+    low-rank factors and the residual are separate trainable variables): Q_b on U, V and the given W_R,
+    S untouched.  No subtraction happens here, W_R is taken as it is.  seed = None rounds to nearest;
+    otherwise the stochastic quantizer with the same keys as split_quantize_sr."""
+    W_R = np.asarray(W_R, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    if seed is None:
+        Ut = quant.quantize(U.T, g_u) + (g_u,)
+        Vt = quant.quantize(V.T, g_v) + (g_v,)
+        Rq = quant.quantize(W_R, g_r) + (g_r,)
+        Rtq = quant.quantize(W_R.T, g_r) + (g_r,) if want_t else None
+    else:
+        Ut = quant.quantize_sr(np.ascontiguousarray(U.T), g_u, seed + 1, quant.STREAM_SR_T) + (g_u,)
+        Vt = quant.quantize_sr(np.ascontiguousarray(V.T), g_v, seed + 2, quant.STREAM_SR_T) + (g_v,)
+        Rq = quant.quantize_sr(W_R, g_r, seed, quant.STREAM_SR) + (g_r,)
+        Rtq = quant.quantize_sr(np.ascontiguousarray(W_R.T), g_r, seed, quant.STREAM_SR_T) + (g_r,) if want_t else None
+    return SplitQ(Ut, np.asarray(S, dtype=np.float64), Vt, Rq, Rtq)
+
+
 def assemble(sq, transposed_residual=False):
     """Abar [M,N] from a SplitQ, using R (blocks along N) or Rt (blocks along M)."""
     if transposed_residual:

@@ -183,3 +183,47 @@ def test_factor_grads_match_finite_differences_of_the_quantized_forward():
     E = np.zeros_like(Rb); E[3, 9] = h
     f = lambda Rm: float(np.sum(G * (X @ (Ub @ Sm @ Vb.T + Rm).T)))
     assert np.isclose((f(Rb + E) - f(Rb - E)) / (2 * h), dW[3, 9], rtol=1e-8)
+
+
+def test_split_from_parts_stores_the_parts_it_is_given():
+    # Sec. 3.2: a weight's factors and residual are stored variables.  Pins: (i) parts on the
+    # E2M1 grid come back exactly, in both orientations of the residual and with each factor
+    # transposed (a swapped U/V or a missing transpose changes the assembled matrix);
+    # (ii) with W_R = W - U S V^T it is the same split as split_quantize of W;
+    # (iii) for general parts every assembled element is within the quantizer's half-step bound.
+    rs = np.random.default_rng(11)
+    grid = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+
+    def lossless(m, n):
+        a = grid[rs.integers(0, 8, (m, n))] * rs.choice([-1, 1], (m, n))
+        a[:, ::16] = 6.0
+        a[::16, :] = 6.0
+        return a
+    N, K, k = 48, 32, 16
+    U, V, WR = lossless(N, k), lossless(K, k), lossless(N, K) * 0.5
+    S = rs.uniform(0.5, 2.0, k)
+    sq = lin.split_from_parts(WR, U, S, V, 1.0, 1.0, 1.0)
+    ref = (U * S) @ V.T + WR
+    assert np.array_equal(lin.assemble(sq), ref) and np.array_equal(lin.assemble(sq, True), ref)
+    assert sq.Ut[0].shape == (k, N // 2) and sq.Vt[0].shape == (k, K // 2)
+    assert sq.R[0].shape == (N, K // 2) and sq.Rt[0].shape == (K, N // 2)
+
+    W = rs.standard_normal((N, K))
+    Uo, So, Vo = dec.decompose(W, 8, 8, 1.0, seed=2)
+    a = lin.split_quantize(W, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, 2.0 ** -6)
+    b = lin.split_from_parts(dec.residual(W, Uo, So, Vo), Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, 2.0 ** -6)
+    for x, y in ((a.Ut, b.Ut), (a.Vt, b.Vt), (a.R, b.R), (a.Rt, b.Rt)):
+        assert np.array_equal(x[0], y[0]) and np.array_equal(x[1], y[1]) and x[2] == y[2]
+
+    g = 2.0 ** -6
+    WR2 = 0.05 * rs.standard_normal((N, K))
+    c = lin.split_from_parts(WR2, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, g, seed=None)
+    err = np.abs(quant.dequantize(*c.R) - WR2)
+    amax = np.abs(WR2).reshape(N, K // 16, 16).max(axis=2)
+    # step of a block <= its amax/6 rounded up to the next E4M3 value (<= 1.125x, or the smallest scale);
+    # the widest grid gap is 2 steps
+    bound = np.maximum(amax / 6.0 * 1.125, 2.0 ** -9 * g)
+    assert (err.reshape(N, K // 16, 16) <= bound[:, :, None] + 1e-15).all()
+    d = lin.split_from_parts(WR2, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, g, seed=5)
+    e = lin.split_quantize_sr(WR2 + (Uo * So) @ Vo.T, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, g, 5)
+    assert np.array_equal(d.Ut[0], e.Ut[0]) and np.array_equal(d.Vt[0], e.Vt[0])   # same keys as the recomputed split
