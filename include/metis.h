@@ -172,6 +172,22 @@ int metis_split_quantize_sr(void* stream, const metis_mat* A, const float* U, co
                             const float* V, int k, uint64_t seed, metis_split* out, float* R_debug,
                             void* workspace, size_t workspace_bytes);
 
+/*
+ * Split of a weight whose parts are stored, not recomputed (Sec. 3.2: for parameters the low-rank
+ * factors and the residual are separate trainable variables, updated independently).  Q_b on
+ * U, V and W_R as given; S copied to out->S; no subtraction and no workspace.
+ *   W_R  device, bf16 or fp32, [M,N] row stride ld >= N (N % 16 == 0; M % 16 == 0 when out->Rt is wanted)
+ *   U [M,k], S [k], V [N,k]  device fp32, contiguous; 1 <= k <= 128, k == out->k
+ *   out  as for metis_split_quantize (Rt all-null: that orientation is skipped)
+ * The _sr form rounds stochastically with the keys of metis_split_quantize_sr
+ * (W_R: seed, U: seed+1, V: seed+2).  Asynchronous on `stream`.
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE (as metis_quantize).
+ */
+int metis_split_from_parts(void* stream, const metis_mat* W_R, const float* U, const float* S,
+                           const float* V, int k, metis_split* out);
+int metis_split_from_parts_sr(void* stream, const metis_mat* W_R, const float* U, const float* S,
+                              const float* V, int k, uint64_t seed, metis_split* out);
+
 /* ---- FP4 GEMMs on split operands (Eq. 2, Eq. 3, and the W_R gradient after Eq. 3) ------ */
 
 /* Bytes of device workspace the three GEMM calls need (max over them). */

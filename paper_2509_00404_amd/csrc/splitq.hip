@@ -257,6 +257,13 @@ bool fp4_ok(const metis_fp4& f, int64_t rows, int64_t cols) {
 
 }  // namespace
 
+namespace {
+__global__ void k_copy_f32(const float* __restrict__ src, float* __restrict__ dst, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+}  // namespace
+
 static int padded_rank(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : k <= 64 ? 64 : 128; }
 
 extern "C" size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k) {
@@ -337,4 +344,41 @@ extern "C" int metis_split_quantize_sr(void* stream, const metis_mat* A, const f
                                        int k, uint64_t seed, metis_split* out, float* R_debug, void* workspace,
                                        size_t workspace_bytes) {
     return split_quantize_impl<true>(stream, A, U, S, V, k, seed, out, R_debug, workspace, workspace_bytes);
+}
+
+// Split of a weight whose factors and residual are stored variables (Sec. 3.2): nothing is subtracted,
+// the three parts go through the quantizer as they are and S is copied.
+template <bool SR>
+static int split_from_parts_impl(void* stream, const metis_mat* W_R, const float* U, const float* S, const float* V,
+                                 int k, uint64_t seed, metis_split* out) {
+    if (!W_R || !W_R->ptr || !U || !S || !V || !out) return METIS_INVALID_ARG;
+    if (k < 1 || k > 128 || out->k != k || !out->S) return METIS_INVALID_ARG;
+    const int64_t M = W_R->rows, N = W_R->cols;
+    const bool want_t = out->Rt.codes != nullptr;
+    if (!fp4_ok(out->R, M, N)) return METIS_BAD_SHAPE;
+    if (want_t && (!fp4_ok(out->Rt, N, M) || out->Rt.tscale != out->R.tscale)) return METIS_BAD_SHAPE;
+    if (!fp4_ok(out->Ut, k, M) || !fp4_ok(out->Vt, k, N)) return METIS_BAD_SHAPE;
+    metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
+    metis_fp4* rt = want_t ? &out->Rt : nullptr;
+    int st = SR ? metis_quantize_sr(stream, W_R, seed, &out->R, rt) : metis_quantize(stream, W_R, &out->R, rt);
+    if (st != METIS_OK) return st;
+    st = SR ? metis_quantize_sr(stream, &um, seed + 1, nullptr, &out->Ut) : metis_quantize(stream, &um, nullptr, &out->Ut);
+    if (st != METIS_OK) return st;
+    st = SR ? metis_quantize_sr(stream, &vm, seed + 2, nullptr, &out->Vt) : metis_quantize(stream, &vm, nullptr, &out->Vt);
+    if (st != METIS_OK) return st;
+    if (out->S != S) {
+        hipLaunchKernelGGL(k_copy_f32, dim3(1), dim3(128), 0, (hipStream_t)stream, S, out->S, k);
+        METIS_LAUNCH_CHECK();
+    }
+    return METIS_OK;
+}
+
+extern "C" int metis_split_from_parts(void* stream, const metis_mat* W_R, const float* U, const float* S,
+                                      const float* V, int k, metis_split* out) {
+    return split_from_parts_impl<false>(stream, W_R, U, S, V, k, 0, out);
+}
+
+extern "C" int metis_split_from_parts_sr(void* stream, const metis_mat* W_R, const float* U, const float* S,
+                                         const float* V, int k, uint64_t seed, metis_split* out) {
+    return split_from_parts_impl<true>(stream, W_R, U, S, V, k, seed, out);
 }

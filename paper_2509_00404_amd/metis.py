@@ -52,6 +52,10 @@ _SIGNATURES = {
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
     "metis_split_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_int, C.c_uint64, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
+    "metis_split_from_parts": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                         C.POINTER(Split)]),
+    "metis_split_from_parts_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                            C.c_uint64, C.POINTER(Split)]),
     "metis_profile_events": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_int]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
@@ -219,6 +223,20 @@ def split_quantize_sr(A, U, S, V, seed, out, R_debug=None, workspace=None):
                                          workspace.data_ptr(), workspace.numel()))
 
 
+def split_from_parts(W_R, U, S, V, out, seed=None):
+    """Quantize a weight's stored parts (factors U, V, residual W_R; S copied) into the split `out`;
+    seed = None rounds to nearest, otherwise stochastically under that key."""
+    a = _mat(W_R)
+    s = out.c()
+    assert all(t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 for t in (U, S, V))
+    if seed is None:
+        _check(lib().metis_split_from_parts(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
+                                            out.k, C.byref(s)))
+    else:
+        _check(lib().metis_split_from_parts_sr(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
+                                               out.k, int(seed), C.byref(s)))
+
+
 def linear_workspace_bytes(L, N, K, k):
     return int(lib().metis_linear_workspace_bytes(L, N, K, k))
 
@@ -250,6 +268,7 @@ def factor_grads_workspace_bytes(N, K, k):
 def fp4_factor_grads(dW, W, dU, dS, dV, workspace=None):
     """dU [N,k], dS [k,k], dV [K,k] (fp32, overwritten) from dW [N,K] and the quantized factors of W."""
     m, w = _mat(dW), W.c()
+    assert all(t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 for t in (dU, dS, dV))
     if workspace is None:
         workspace = torch.empty((factor_grads_workspace_bytes(dW.shape[0], dW.shape[1], W.k),), dtype=torch.uint8,
                                 device=dW.device)
