@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipeline-depth", type=int, default=3,
+                    help="extra measurement: independent steps in flight at once, one stream and one set of "
+                         "buffers each (0 or 1 = skip); never enters `value`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
@@ -42,8 +45,8 @@ def parse():
 class Operand:
     """One matrix of the layer with everything its decomposition and split need, preallocated."""
 
-    def __init__(self, metis, torch, A, k, p, rho, seed, want_t, oq):
-        self.A = A.cuda()
+    def __init__(self, metis, torch, A, k, p, rho, seed, want_t, oq, share=None):
+        self.A = share.A if share is not None else A.cuda()       # a pipeline slot reads the same input
         self.M, self.N = A.shape
         self.k, self.p, self.rho, self.seed = k, p, rho, seed
         g_r = oq.tensor_scale_for(float(A.abs().max()))         # delayed scaling: amax known from setup
@@ -209,6 +212,18 @@ def main():
         phases["linear_wgrad_ms"] = timed(lambda: metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin))
     roofline["traffic"] = traffic_from_profile(args.workload)
 
+    # Throughput with several independent steps in flight (different layers or micro-batches of a training
+    # job): each slot has its own stream and its own outputs and workspaces, the inputs are shared.  A step's
+    # decomposition is a chain of small single-workgroup kernels that leaves the chip idle; steps in other slots
+    # fill it.  Reported beside `value`, which stays the one-step-at-a-time figure.
+    pipelined = None
+    depth = args.pipeline_depth
+    if depth > 1 and not multi:
+        try:
+            pipelined = pipelined_throughput(args, torch, metis, oq, T, W, X, Y, ws_lin, p, full, depth, useful_flops)
+        except Exception as e:                                     # an extra figure must never cost the main line
+            pipelined = {"depth": depth, "error": repr(e)[:200]}
+
     passes = {}
     if n_split:
         bc_ms = avg("broadcast", args.steps * n_split)
@@ -243,6 +258,7 @@ def main():
                                 "c4": "config 4: FFN down W 4096x14336, X 8192x14336, G 8192x4096, full W4A4G4 step"}[args.workload],
                    "L": L, "K": K, "N": N, "k": k, "p": p, "gemms_per_step": n_gemm, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
+        "pipelined": pipelined,
         "passes": passes,
         "phases": phases,
     }
@@ -250,6 +266,58 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, torch, T, c, prm, oq)
     print(json.dumps(out))
+
+
+def pipelined_throughput(args, torch, metis, oq, T, W, X, Y, ws_lin, p, full, depth, useful_flops):
+    """Steps per second with `depth` independent steps in flight, each slot a HIP graph on its own stream."""
+    slots = []
+    for d in range(depth):
+        Wd = Operand(metis, torch, T["W"], W.k, p, W.rho, W.seed, full, oq, share=W)
+        Xd = Operand(metis, torch, T["X"], X.k, p, X.rho, X.seed, full, oq, share=X)
+        slots.append((Wd, Xd, torch.empty_like(Y), torch.empty_like(ws_lin), torch.cuda.Stream()))
+
+    def slot_step(sl):
+        Wd, Xd, Yd, wsd, st = sl
+        with torch.cuda.stream(st):
+            Wd.prepare()
+            Xd.prepare()
+            metis.fp4_linear_fwd(Xd.q, Wd.q, Yd, wsd)
+
+    for i in range(max(args.warmup, depth)):
+        slot_step(slots[i % depth])
+    torch.cuda.synchronize()
+    # one HIP graph per slot: a step is ~35 launches, and with several steps in flight the host would
+    # otherwise be the limit.  The library records kernels only (its buffers are cleared by fill kernels).
+    graphs = []
+    for sl in slots:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=sl[4]):
+            sl[0].prepare()
+            sl[1].prepare()
+            metis.fp4_linear_fwd(sl[1].q, sl[0].q, sl[2], sl[3])
+        graphs.append(g)
+    torch.cuda.synchronize()
+
+    def replay(i):
+        with torch.cuda.stream(slots[i % depth][4]):
+            graphs[i % depth].replay()
+
+    for i in range(depth):
+        slots[i][2].zero_()
+        replay(i)
+    torch.cuda.synchronize()
+    t_p = time.perf_counter()
+    for i in range(args.steps):
+        replay(i)
+    torch.cuda.synchronize()
+    ms_p = (time.perf_counter() - t_p) * 1e3 / args.steps
+    ref = Y.float()                                            # every slot reproduces the serial step's output
+    same = all(((sl[2].float() - ref).abs().max() <= 1e-3 * ref.abs().max()).item() for sl in slots)
+    pipelined = {"depth": depth, "ms_per_step": round(ms_p, 4),
+                 "value": round(useful_flops / (ms_p * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
+                 "outputs_match_serial": bool(same)}
+    del graphs, slots
+    return pipelined
 
 
 def traffic_from_profile(workload):

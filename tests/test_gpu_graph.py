@@ -1,0 +1,92 @@
+"""The whole step (decompose, split_quantize, quantize, forward GEMM, and the backward products with the
+factor gradients) recorded into a HIP graph: every replay, with eager work and synchronisations between
+the replays, must reproduce the eager result.  The entry points allocate nothing, never
+synchronise and clear their buffers with fill kernels, which is what makes them recordable."""
+import pytest
+import torch
+
+from oracle import quant as oq
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def metis():
+    from paper_2509_00404_amd import metis as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+class _Step:
+    def __init__(self, metis, W, X, G, k, p):
+        self.m = metis
+        self.W, self.X, self.G = W.cuda(), X.cuda(), G.cuda()
+        L, K = X.shape
+        N = W.shape[0]
+        self.k, self.p = k, p
+        dev = "cuda"
+        self.U = torch.empty((N, k), dtype=torch.float32, device=dev)
+        self.S = torch.empty((k,), dtype=torch.float32, device=dev)
+        self.V = torch.empty((K, k), dtype=torch.float32, device=dev)
+        self.ws_dec = torch.empty((metis.decompose_workspace_bytes(N, K, k, p, 1.0),), dtype=torch.uint8, device=dev)
+        self.ws_split = torch.empty((metis.split_workspace_bytes(N, K, k),), dtype=torch.uint8, device=dev)
+        self.wq = metis.SplitTensor(N, K, k, 2.0 ** -11, 2.0 ** -11, oq.tensor_scale_for(float(W.abs().max())), True)
+        self.xq = metis.SplitTensor(L, K, 0, 1.0, 1.0, oq.tensor_scale_for(float(X.abs().max())), True)
+        self.gq = metis.SplitTensor(L, N, 0, 1.0, 1.0, oq.tensor_scale_for(float(G.abs().max())), True)
+        self.ws_lin = torch.empty((metis.linear_workspace_bytes(L, N, K, k),), dtype=torch.uint8, device=dev)
+        self.ws_fg = torch.empty((metis.factor_grads_workspace_bytes(N, K, k),), dtype=torch.uint8, device=dev)
+        self.Y = torch.empty((L, N), dtype=torch.bfloat16, device=dev)
+        self.dX = torch.empty((L, K), dtype=torch.bfloat16, device=dev)
+        self.dW = torch.empty((N, K), dtype=torch.float32, device=dev)
+        self.dU = torch.empty((N, k), dtype=torch.float32, device=dev)
+        self.dS = torch.empty((k, k), dtype=torch.float32, device=dev)
+        self.dV = torch.empty((K, k), dtype=torch.float32, device=dev)
+
+    def run(self):
+        m = self.m
+        m.decompose(self.W, self.k, self.p, 1.0, 5, workspace=self.ws_dec, out=(self.U, self.S, self.V))
+        m.split_quantize(self.W, self.U, self.S, self.V, self.wq, workspace=self.ws_split)
+        m.quantize(self.X, self.xq.R, self.xq.Rt)
+        m.quantize_sr(self.G, 9, self.gq.R, self.gq.Rt)
+        m.fp4_linear_fwd(self.xq, self.wq, self.Y, self.ws_lin)
+        m.fp4_linear_dgrad(self.gq, self.wq, self.dX, self.ws_lin)
+        m.fp4_linear_wgrad(self.gq, self.xq, self.dW, self.ws_lin)
+        m.fp4_factor_grads(self.dW, self.wq, self.dU, self.dS, self.dV, self.ws_fg)
+
+    def outputs(self):
+        return [self.S, self.U, self.V, self.wq.R.codes, self.wq.Rt.scales, self.gq.R.codes, self.Y, self.dX, self.dW,
+                self.dU, self.dS, self.dV]
+
+
+def test_step_replays_from_a_graph(metis):
+    from paper_2509_00404_amd import workloads
+    L, N, K, k, p = 1152, 1024, 1280, 16, 8
+    W = workloads.planted(N, K, workloads.power_law(min(N, K), 1.0), 2, noise_top=0.01, rms=0.02)
+    X = workloads.planted(L, K, workloads.power_law(min(L, K), 1.2), 1, rms=1.0, outlier_cols=1)
+    G = workloads.planted(L, N, workloads.power_law(min(L, N), 2.0, head=4, head_gain=100.0), 3, rms=1e-3)
+    st = _Step(metis, W, X, G, k, p)
+    st.run()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in st.outputs()]
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st.run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in st.outputs():
+            t.zero_()                                   # eager work between the replays, and proof that the replay wrote
+        other = torch.randn((512, 512), device="cuda") @ torch.randn((512, 512), device="cuda")
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(st.outputs(), eager)):
+            # the split contractions add their partial sums with fp64 atomics in arrival order, so a last
+            # fp64 bit, and once in a long while an fp32 rounding or an FP4 code behind it, may differ
+            if a.dtype == torch.uint8:
+                assert (a != b).float().mean().item() < 1e-4, (rep, i)
+            else:
+                assert (a.double() - b.double()).abs().max().item() <= 1e-4 * b.double().abs().max().item(), (rep, i)
+        assert torch.isfinite(other).all()
