@@ -17,7 +17,7 @@ struct Layout {
     int k, r;
     size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_flag, off_c, off_b, zero_bytes;
     size_t off_idx, off_omega, off_linv, off_h1, off_h, off_lam, off_t, off_v0f, off_v0hi, off_v0lo,
-        off_lam3, off_w3, off_t3, total;
+        off_lam3, off_w3, off_t3, off_jscr, total;
 };
 
 Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
@@ -48,6 +48,7 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     L.off_lam3 = take(kk * 8);
     L.off_w3 = take(kk * kk * 8);
     L.off_t3 = take(kk * kk * 8);
+    L.off_jscr = take(jacobi_scratch_doubles((int)r) * 8);
     L.total = o;
     return L;
 }
@@ -201,7 +202,7 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(B, N, 1), op(B, N, 1), r, r, N, split_for(N, tiles_rr),
                                                   epi(G2, r));
     METIS_LAUNCH_CHECK();
-    if ((st = launch_jacobi_eig(s, G2, r, k, lam, nullptr, T, nullptr)) != METIS_OK) return st;
+    if ((st = launch_jacobi_eig(s, G2, r, k, lam, nullptr, T, nullptr, (double*)(ws + L.off_jscr))) != METIS_OK) return st;
     launch_dgemm<double, double, EPI_STORE_SPLIT_T>(s, op(B, 1, N), op(T, 1, k), N, k, r, 1,
                                                      epi(V0f, k, V0hi, V0lo, N));
     METIS_LAUNCH_CHECK();

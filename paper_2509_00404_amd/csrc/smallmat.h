@@ -7,5 +7,8 @@
 // then orthonormal to ~1e-10); skip_in (optional): nonzero -> Linv = identity without factoring
 int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info, int32_t* wellcond_out = nullptr,
                     const int32_t* skip_in = nullptr);
+// gscr (optional): jacobi_scratch_doubles(n) doubles of device scratch; when given (and the order allows it) the
+// sweeps start from columns preconditioned with approximate eigenvectors
 int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
-                      float* sval);
+                      float* sval, double* gscr = nullptr);
+size_t jacobi_scratch_doubles(int n);

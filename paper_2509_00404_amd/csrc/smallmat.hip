@@ -3,6 +3,7 @@
 // one-sided Jacobi eigensolver for the Gram matrices of the reduced problem.
 #include "smallmat.h"
 #include <cstdlib>
+#include <utility>
 
 // ---------------------------------------------------------------------------------------
 // Blocked Cholesky in LDS, shared by both kernels below.  On entry W holds the lower triangle of a
@@ -17,6 +18,9 @@
 // replaced by 1e-300 and its 1-based index is written to *info (CholeskyQR2's rank check).
 // ---------------------------------------------------------------------------------------
 typedef double double4_t __attribute__((ext_vector_type(4)));
+#ifdef JAC_PROF
+__device__ long long g_prof[40];
+#endif
 
 __device__ __forceinline__ double chol_rsqrt(double x) {
     double y = __builtin_amdgcn_rsq(x);
@@ -121,9 +125,6 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
         CH_MARK(cc)
     }
     __syncthreads();                                     // the last block's rows are visible to the caller
-#ifdef JAC_PROF
-    if (tid == 0) printf("chol n=%d: phase1 %lld trailing %lld\n", n, ca, cc);
-#endif
 }
 
 // ---------------------------------------------------------------------------------------
@@ -252,6 +253,484 @@ __host__ __device__ static inline int jacobi_ld(int n, int l) {
     return rows % (2 * l) == l ? rows : rows + l;
 }
 
+// ---------------------------------------------------------------------------------------
+// Eigenvector preconditioner for the one-sided Jacobi below.
+//
+// The cyclic rotations need ~log n sweeps before their quadratic convergence sets in.  If the columns
+// of the factor are first multiplied by an orthogonal P that is close to the eigenvector matrix of
+// L^T L, the very first sweep already finds (nearly) orthogonal columns and the sweeps only confirm and
+// refine: W0 = L P has W0 W0^T = L L^T = G for ANY orthogonal P, so the accuracy of P only affects the
+// number of sweeps, never the result (a P orthogonal to 1e-10 perturbs G multiplicatively, i.e. every
+// eigenvalue by 1e-10 relative).  P comes from the classical dense symmetric path, all inside this
+// workgroup:
+//   1  A = L^T L                                       (fp64 matrix cores)
+//   2  Householder tridiagonalisation  Q^T A Q = T     (one row per 8 lanes, rows in registers)
+//   3  eigenvalues of T by multisection on Sturm counts (8 probes per eigenvalue and round)
+//   4  eigenvectors of T by twisted factorisation       (one thread per eigenvector)
+//   5  back-transformation  P = Q Z                     (one column per 8 lanes, no barriers)
+//   6  Newton-Schulz polish  P <- P (I - (P^T P - I) / 2)  until orthogonal to 1e-10; if the computed
+//      vectors are far from orthogonal (coincident or tiny eigenvalues) the preconditioner is dropped
+//   7  W0 = L P                                         (fp64 matrix cores)
+// R1 holds L on entry (column-major, stride ld, (ne+1) columns); the result is left in R2 in the same
+// layout.  gscr: (ne+1)*ld doubles of global scratch for L.  sa: 10*n + 40 doubles of LDS, 16-byte aligned.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_max(double x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmax(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+__device__ __forceinline__ double readlane64(double x, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l), __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+// x is the same in the 8 lanes of every group: the sum over the wave's 8 groups, in every lane
+__device__ __forceinline__ double wave_sum_of_groups8(double x) {
+    x += dpp_mov64<0x140>(x);     // row_mirror: the other group of this row of 16 lanes
+    return (readlane64(x, 0) + readlane64(x, 16)) + (readlane64(x, 32) + readlane64(x, 48));
+}
+__device__ __forceinline__ double rcp_nr2(double x) {          // 1/x to ~1e-15 relative
+    double y = __builtin_amdgcn_rcp(x);
+    y = y * (2.0 - x * y);
+    return y * (2.0 - x * y);
+}
+
+// 9^12 = 2.8e11 sections of the scaled spectrum: eigenvalues to ~1e-11 ||T||, eigenvectors orthogonal to
+// ~1e-5 before the polish, which one Newton-Schulz step brings to ~1e-10
+#define PRE_ROUNDS 12
+#define PRE_MAX_ROUNDS 20
+
+template <class F, int... I>
+__device__ __forceinline__ void for_each_block_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
+template <int N, class F>
+__device__ __forceinline__ void for_each_block(F&& f) {
+    for_each_block_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// One 16x16 tile of sum_k a(i, k) b(k, j) on the fp64 matrix cores; lane supplies row/column (lane & 15) and the
+// k offset lane >> 4.  fa / fb read in-bounds elements; out-of-range rows, columns and k contribute zero.
+template <class FA, class FB>
+__device__ __forceinline__ double4_t tile_mma(int n, int ia, int jb, int kq, FA fa, FB fb) {
+    const int ic = min(ia, n - 1), jc = min(jb, n - 1);
+    const bool iok = ia < n, jok = jb < n;
+    double4_t acc = {0.0, 0.0, 0.0, 0.0};
+    for (int k0 = 0; k0 < n; k0 += 4) {
+        const int k = k0 + kq, kc = min(k, n - 1);
+        const double a = fa(ic, kc), b = fb(kc, jc);
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64((iok && k < n) ? a : 0.0, (jok && k < n) ? b : 0.0, acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// Reflectors j with (j+1)/8 == E0, highest first, applied to the column piece zr (rows q + 8 e); then the lower blocks.
+template <int NR, int E0>
+__device__ __forceinline__ void back_blocks(double (&zr)[NR], const double* __restrict__ V, int lda, int n, int q,
+                                            const double* __restrict__ tauv) {
+    const int jhi = min(8 * E0 + 6, n - 3), jlo = max(8 * E0 - 1, 0);
+    for (int j = jhi; j >= jlo; --j) {
+        const double tau = tauv[j];
+        double v[NR], dot = 0.0;
+#pragma unroll
+        for (int e = E0; e < NR; ++e) {
+            const int i = q + 8 * e;
+            v[e] = i < n ? V[(size_t)i * lda + j] : 0.0;
+            dot += v[e] * zr[e];
+        }
+        dot = tau * group8_sum(dot);
+#pragma unroll
+        for (int e = E0; e < NR; ++e) zr[e] -= dot * v[e];
+    }
+    if constexpr (E0 > 0) back_blocks<NR, E0 - 1>(zr, V, lda, n, q, tauv);
+}
+
+template <int NE>
+__device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R2, int ld, int n, int ne,
+                                 double* __restrict__ gscr, double* __restrict__ sa) {
+    constexpr int NR = 2 * NE;                    // entries of a row (or column) per lane of an 8-lane group
+    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
+    const int T16 = (n + 15) / 16, ntiles = T16 * T16;
+    const int lda = n | 1;                        // odd stride: rows and columns both walk all banks
+    const size_t rsize = (size_t)(ne + 1) * ld;
+    const int n8 = (n + 7) & ~7;
+    double* dd = sa;            // [n] diagonal of T
+    double* ee = dd + n;        // [n] ee[j] couples j and j+1
+    double* de = ee + n;        // [2 n8] scaled T for the Sturm counts: d_k at [k], e_{k-1}^2 at [n8 + k]; padded with (4, 0): no sign change
+    double* tauv = de + 2 * n8; // [n] Householder tau
+    double* scl = tauv + n;     // [n] v_i = A[i][j] * scl[j] for i > j+1, v_{j+1} = 1
+    double* lamv = scl + n;     // [n] eigenvalues of T, ascending
+    double* xx = lamv + n;      // [n8] current column below the diagonal
+    double* pp = xx + n8;       // [n8] A v, zero up to the current row
+    double* vv = pp + n8;       // [n8] Householder vector of the current step
+    __shared__ double part_k[16], part_s[2][16], tau_s;  // per-wave partial sums: v^T A v, and sigma by step parity
+    __shared__ unsigned long long err_s;
+    __shared__ int fail_s;
+
+#ifdef JAC_PROF
+    long long pc0 = clock64(), pcs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define PRE_MARK(i) { long long c1 = clock64(); pcs[i] += c1 - pc0; pc0 = c1; }
+#else
+#define PRE_MARK(i)
+#endif
+    // ---- 0: L to global scratch (R1 is reused for the eigenvectors) ----
+    for (size_t e = tid; e < rsize; e += nthr) gscr[e] = R1[e];
+    if (tid == 0) fail_s = 0;
+
+    // Gram of the columns of a column-major matrix M (stride ldm, nc columns of nr rows) into R2 (row-major, lda)
+    auto gram_to_R2 = [&](const double* M, int ldm) {
+        for (int t0 = 0; t0 < ntiles; t0 += nwaves) {
+            const int tile = min(t0 + wave, ntiles - 1);
+            const int ti = tile / T16, tj = tile - ti * T16;
+            const int ci = 16 * ti + (lane & 15), cj = 16 * tj + (lane & 15), kq = lane >> 4;
+            const double4_t acc = tile_mma(n, ci, cj, kq, [&](int i, int k) { return M[(size_t)i * ldm + k]; },
+                                           [&](int k, int c) { return M[(size_t)c * ldm + k]; });
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * ti + 4 * v + kq;
+                if (t0 + wave < ntiles && i < n && cj < n) R2[(size_t)i * lda + cj] = acc[v];
+            }
+        }
+    };
+
+    // ---- 1: A = L^T L ----
+    gram_to_R2(R1, ld);
+    __syncthreads();
+
+    PRE_MARK(1)
+    // ---- 2: tridiagonalisation (lower), row r on lanes q = 0..7, columns q, q+8, ... in registers.
+    //         Step j: wave 0 forms the reflector v (zero up to row j) | every row's p_r = A[r][:] v and the wave's
+    //         share of v^T A v | rank-2 update, and column j+1 with its squared norm for the next step.  pp and vv
+    //         are kept zero up to row j (and from n up), so dead rows and columns update by exactly zero without
+    //         any test; waves whose rows are all dead only keep the barriers. ----
+    {
+        const int r = tid >> 3, q = tid & 7;
+        const bool row_ok = r < n;
+        const int nw_rows = (n + 7) >> 3;         // waves that hold rows
+        double areg[NR];
+#pragma unroll
+        for (int e = 0; e < NR; ++e) {
+            const int c = q + 8 * e;
+            areg[e] = (row_ok && c < n) ? R2[(size_t)r * lda + c] : 0.0;
+        }
+        for (int c = tid; c < n8; c += nthr) { vv[c] = 0.0; pp[c] = 0.0; xx[c] = 0.0; }
+        __syncthreads();
+        {
+            if (row_ok && q == 0) xx[r] = areg[0];
+            const double y = (row_ok && r >= 2 && q == 0) ? areg[0] * areg[0] : 0.0;
+            const double t = wave_sum_of_groups8(group8_sum(y));
+            if (lane == 0 && wave < 16) { part_s[0][wave] = t; part_s[1][wave] = 0.0; part_k[wave] = 0.0; }
+        }
+        auto step = [&](int j, auto ES) {
+            constexpr int es = decltype(ES)::value;            // (j + 1) / 8: the register block of column j + 1
+            __syncthreads();                      // column j (xx) and the partial sums of its sigma are complete
+            if (wave == 0) {
+                const double sg = group_sum<16>((lane & 15) < nw_rows ? part_s[j & 1][lane & 15] : 0.0);
+                const double alpha = xx[j + 1];
+                double tau = 0.0, scale = 0.0, beta = alpha;
+                if (sg > 0.0) {
+                    const double h = alpha * alpha + sg;
+                    double ri = __builtin_amdgcn_rsq(h);          // 1/sqrt(h), two Newton steps
+                    ri = ri * (1.5 - 0.5 * h * ri * ri);
+                    ri = ri * (1.5 - 0.5 * h * ri * ri);
+                    const double nr = h * ri;
+                    beta = alpha >= 0.0 ? -nr : nr;
+                    tau = (beta - alpha) * (alpha >= 0.0 ? -ri : ri);
+                    scale = rcp_nr2(alpha - beta);
+                }
+                for (int c = lane; c < n; c += 64) vv[c] = c == j + 1 ? 1.0 : (c > j + 1 ? xx[c] * scale : 0.0);
+                if (lane == 0) {
+                    tau_s = tau;
+                    pp[j] = 0.0;
+                    ee[j] = beta; tauv[j] = tau; scl[j] = scale;
+                }
+            }
+            __syncthreads();
+            const bool live = wave < nw_rows && 8 * wave + 7 > j;       // some row of this wave is below row j
+            double vreg[NR], vr = 0.0;
+            if (live) {                           // p_r = sum_c A[r][c] v_c
+                double p0 = 0.0, p1 = 0.0;
+#pragma unroll
+                for (int e = 0; e < NR; ++e) vreg[e] = vv[q + 8 * e];
+                vr = vv[r];
+#pragma unroll
+                for (int e = 0; e < NR; e += 2) {
+                    p0 += areg[e] * vreg[e];
+                    if (e + 1 < NR) p1 += areg[e + 1] * vreg[e + 1];
+                }
+                const double p = group8_sum(p0 + p1);
+                const double t = wave_sum_of_groups8(p * vr);
+                if (q == 0 && r > j && row_ok) pp[r] = p;
+                if (lane == 0) part_k[wave] = t;
+            } else if (lane == 0 && wave < nw_rows) {
+                part_k[wave] = 0.0;
+                part_s[(j + 1) & 1][wave] = 0.0;
+            }
+            __syncthreads();
+            if (live) {
+                const double ks = group_sum<16>((lane & 15) < nw_rows ? part_k[lane & 15] : 0.0);
+                const double tau = tau_s;
+                const double K = 0.5 * tau * tau * ks;
+                const double wr = tau * pp[r] - K * vr;
+#pragma unroll
+                for (int e = 0; e < NR; ++e) {
+                    const double wc = tau * pp[q + 8 * e] - K * vreg[e];
+                    areg[e] -= vr * wc + wr * vreg[e];
+                }
+                // column j+1 below its diagonal for the next step, and the partial sums of its sigma
+                const double xn = areg[es];
+                const bool own = q == ((j + 1) & 7);
+                if (own && r >= j + 2 && row_ok) xx[r] = xn;
+                const double y = (own && r >= j + 3 && row_ok) ? xn * xn : 0.0;
+                const double t = wave_sum_of_groups8(group8_sum(y));
+                if (lane == 0) part_s[(j + 1) & 1][wave] = t;
+            }
+        };
+        for_each_block<NR>([&](auto ES) {
+            constexpr int es = decltype(ES)::value;
+            const int jlo = es == 0 ? 0 : 8 * es - 1, jhi = min(8 * es + 6, n - 3);
+            for (int j = jlo; j <= jhi; ++j) step(j, ES);
+        });
+        __syncthreads();
+        // the reflectors, normalised, stay in the strict lower triangle: v^(j)_i = R2[i][j] for every i (zeros down
+        // to the diagonal, 1 below it); the diagonal and the subdiagonal move to dd, ee first
+#pragma unroll
+        for (int e = 0; e < NR; ++e) {
+            const int c = q + 8 * e;
+            if (row_ok && c < n) {
+                if (c == r) dd[r] = areg[e];
+                if (c == r - 1 && r == n - 1) ee[n - 2] = areg[e];
+                double v = 0.0;
+                if (c + 2 < n) v = r == c + 1 ? 1.0 : (r > c + 1 ? areg[e] * scl[c] : 0.0);
+                R2[(size_t)r * lda + c] = v;
+            }
+        }
+        if (tid == 0) { tauv[n - 2] = 0.0; tauv[n - 1] = 0.0; ee[n - 1] = 0.0; }
+        __syncthreads();
+    }
+
+    PRE_MARK(2)
+    // ---- 3: eigenvalues of T.  Scale T by a power of two so that |d| + 2|e| <= 1, then multisection ----
+    {
+        if (wave == 0) {
+            double g = 0.0;
+            for (int i = lane; i < n; i += 64)
+                g = fmax(g, fabs(dd[i]) + fabs(ee[i]) + (i ? fabs(ee[i - 1]) : 0.0));
+            g = wave_max(g);
+            const double s = g > 0.0 ? ldexp(1.0, -ilogb(g) - 1) : 1.0;
+            for (int i = lane; i < n8; i += 64) {
+                const double d = i < n ? dd[i] * s : 4.0, e = i < n ? ee[i] * s : 0.0;
+                if (i < n) { dd[i] = d; ee[i] = e; }
+                de[i] = d;
+                if (i + 1 < n8) de[n8 + i + 1] = e * e;
+                if (i == 0) de[n8] = 0.0;
+            }
+        }
+        __syncthreads();
+        const int i = tid >> 3, q = tid & 7;
+        if (i < n) {
+            double lo = -1.0 - 1e-9, hi = 1.0 + 1e-9;       // Gershgorin after scaling
+            for (int round = 0; round < PRE_MAX_ROUNDS; ++round) {
+                // enough once the interval is below 1e-11 of the spectrum's scale and 1e-6 of the eigenvalue itself
+                // (small eigenvalues of a graded matrix keep going); the lanes of a wave leave together
+                const bool done = round >= PRE_ROUNDS && (hi - lo) <= 1e-6 * fmax(fabs(lo), fabs(hi));
+                if (__ballot(!done) == 0ull) break;
+                const double w = (hi - lo) * (1.0 / 9.0);
+                const double mu = lo + w * (double)(q + 1);
+                // Sturm count: sign changes in the sequence of leading principal minors of T - mu,
+                // p_k = (d_k - mu) p_{k-1} - e_{k-1}^2 p_{k-2}; the pair is renormalised every 8 steps
+                double p2 = 0.0, p1 = 1.0;
+                int cnt = 0, hprev = 0;
+                for (int k0 = 0; k0 < n8; k0 += 8) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double p = (de[k0 + u] - mu) * p1 - de[n8 + k0 + u] * p2;
+                        const int h = __double2hiint(p);
+                        cnt += (unsigned)(h ^ hprev) >> 31;
+                        hprev = h;
+                        p2 = p1; p1 = p;
+                    }
+                    const int ex = max((__double2hiint(p1) >> 20) & 0x7ff, (__double2hiint(p2) >> 20) & 0x7ff);
+                    p1 = ldexp(p1, 1023 - ex);
+                    p2 = ldexp(p2, 1023 - ex);
+                }
+                // probes at or below lambda_i have cnt <= i; they form a prefix of the group's 8 lanes
+                const unsigned long long b = __ballot(cnt <= i);
+                const int k0 = __popc((unsigned)((b >> (lane & 56)) & 0xFFull));
+                const double nlo = k0 > 0 ? lo + w * (double)k0 : lo;
+                const double nhi = k0 < 8 ? lo + w * (double)(k0 + 1) : hi;
+                lo = nlo; hi = nhi;
+            }
+            if (q == 0) lamv[i] = 0.5 * (lo + hi);
+        }
+        __syncthreads();
+        // eigenvalues closer than the accuracy of the vectors that follow (repeated eigenvalues, rank deficiency):
+        // those vectors would not come out orthogonal, so the remaining phases are skipped
+        if (tid + 1 < n && lamv[tid + 1] - lamv[tid] < 1e-9) atomicOr(&fail_s, 1);
+        __syncthreads();
+    }
+
+    PRE_MARK(3)
+    // ---- 4: eigenvectors of T by twisted factorisation, thread i -> column i of Z (R1, column-major, lda) ----
+    const bool early_fail = fail_s != 0;          // uniform: read after a barrier
+    if (tid < n && !early_fail) {
+        double* z = R1 + (size_t)tid * lda;
+        const double lam = lamv[tid], pm = 1e-100;
+        auto e2_ = [&](int k) { return de[n8 + k + 1]; };    // e_k^2, k = 0 .. n-2
+        auto piv = [&](double D) { return fabs(D) < pm ? -pm : D; };
+        // forward pivots D+ into z
+        double D = dd[0] - lam;
+        z[0] = D;
+        for (int k = 1; k < n; ++k) {
+            D = (dd[k] - lam) - e2_(k - 1) * rcp_nr2(piv(D));
+            z[k] = D;
+        }
+        // backward pivots D- over z, remembering where |gamma_k| = |D+_k + D-_k - (d_k - lam)| is smallest
+        double Dm = dd[n - 1] - lam;
+        double best = fabs(z[n - 1]);                        // gamma_{n-1} = D+_{n-1}
+        int rr = n - 1;
+        z[n - 1] = Dm;
+        for (int k = n - 2; k >= 0; --k) {
+            const double a = dd[k] - lam;
+            Dm = a - e2_(k) * rcp_nr2(piv(Dm));
+            const double gam = fabs(z[k] + Dm - a);
+            if (gam < best) { best = gam; rr = k; }
+            z[k] = Dm;
+        }
+        // forward pivots again for the rows above the twist
+        D = dd[0] - lam;
+        if (rr > 0) z[0] = D;
+        for (int k = 1; k < rr; ++k) {
+            D = (dd[k] - lam) - e2_(k - 1) * rcp_nr2(piv(D));
+            z[k] = D;
+        }
+        // z_rr = 1; upwards z_k = -e_k z_{k+1} / D+_k; downwards z_{k+1} = -e_k z_k / D-_{k+1}
+        double zz = 1.0, nrm2 = 1.0;
+        for (int k = rr - 1; k >= 0; --k) {
+            zz = -ee[k] * zz * rcp_nr2(piv(z[k]));
+            z[k] = zz;
+            nrm2 += zz * zz;
+        }
+        zz = 1.0;
+        for (int k = rr; k + 1 < n; ++k) {
+            zz = -ee[k] * zz * rcp_nr2(piv(z[k + 1]));
+            z[k + 1] = zz;
+            nrm2 += zz * zz;
+        }
+        z[rr] = 1.0;
+        if (!(nrm2 < 1e300)) atomicOr(&fail_s, 1);
+        const double rn = rsqrt_nr(nrm2);
+        for (int k = 0; k < n; ++k) z[k] *= rn;
+    }
+    __syncthreads();
+
+    PRE_MARK(4)
+    // ---- 5: P = H_0 H_1 ... H_{n-3} Z, column c on lanes q = 0..7.  Reflector j is zero in rows 0 .. j, so the
+    //         register blocks e < (j+1)/8 are skipped (one instantiation of the inner loop per first block) ----
+    {
+        const int c = tid >> 3, q = tid & 7;
+        if (c < n && !early_fail) {
+            double* z = R1 + (size_t)c * lda;
+            double zr[NR];
+#pragma unroll
+            for (int e = 0; e < NR; ++e) zr[e] = (q + 8 * e < n) ? z[q + 8 * e] : 0.0;
+            back_blocks<NR, NR - 1>(zr, R2, lda, n, q, tauv);
+#pragma unroll
+            for (int e = 0; e < NR; ++e)
+                if (q + 8 * e < n) z[q + 8 * e] = zr[e];
+        }
+    }
+    __syncthreads();
+
+    PRE_MARK(5)
+    // ---- 6: orthogonality check and Newton-Schulz polish ----
+    bool ok = fail_s == 0;
+    double err_first = -1.0;
+    int polish_its = 0;
+    for (int it = 0; it < 4 && ok; ++it) {
+        if (tid == 0) err_s = 0ull;
+        gram_to_R2(R1, lda);                      // E + I = P^T P
+        __syncthreads();
+        double m = 0.0;
+        for (int e = tid; e < n * n; e += nthr) {
+            const int i = e / n, j = e - i * n;
+            m = fmax(m, fabs(R2[(size_t)i * lda + j] - (i == j ? 1.0 : 0.0)));
+        }
+        m = wave_max(m);
+        if (lane == 0) atomicMax(&err_s, (unsigned long long)__double_as_longlong(m));
+        __syncthreads();
+        const double err = __longlong_as_double((long long)err_s);
+        __syncthreads();
+        if (it == 0) err_first = err;
+        polish_its = it + 1;
+        if (!(err < 0.03)) { ok = false; break; }
+        if (err < 1e-10) break;
+        if (it == 3) { ok = false; break; }
+        const bool last = err < 1e-4;             // one step squares the error (to < 1e-8): no need to look again
+        // P <- P - P E / 2: every wave first forms its output tiles, then all store
+        double4_t acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int tile = min(wave + t * nwaves, ntiles - 1);
+            const int ti = tile / T16, tj = tile - ti * T16;
+            const int ia = 16 * ti + (lane & 15), jb = 16 * tj + (lane & 15), kq = lane >> 4;
+            acc[t] = tile_mma(n, ia, jb, kq, [&](int i, int k) { return R1[(size_t)k * lda + i]; },
+                              [&](int k, int c) { return R2[(size_t)k * lda + c] - (k == c ? 1.0 : 0.0); });
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int tile = wave + t * nwaves;
+            if (tile < ntiles) {
+                const int ti = tile / T16, tj = tile - ti * T16;
+                const int jb = 16 * tj + (lane & 15), kq = lane >> 4;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int i = 16 * ti + 4 * v + kq;
+                    if (i < n && jb < n) R1[(size_t)jb * lda + i] -= 0.5 * acc[t][v];
+                }
+            }
+        }
+        __syncthreads();
+        if (last) break;
+    }
+
+    PRE_MARK(6)
+    // ---- 7: W0 = L P into R2 (or L itself when the preconditioner was dropped) ----
+    __syncthreads();
+    for (size_t e = tid; e < rsize; e += nthr) R2[e] = ok ? 0.0 : gscr[e];
+    __syncthreads();
+    if (ok) {
+        for (int t0 = 0; t0 < ntiles; t0 += nwaves) {
+            const int tile = min(t0 + wave, ntiles - 1);
+            const int ti = tile / T16, tj = tile - ti * T16;
+            const int ia = 16 * ti + (lane & 15), jb = 16 * tj + (lane & 15), kq = lane >> 4;
+            const double4_t a4 = tile_mma(n, ia, jb, kq, [&](int i, int k) { return gscr[(size_t)k * ld + i]; },   // L[i][k]
+                                          [&](int k, int c) { return R1[(size_t)c * lda + k]; });       // P[k][c]
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * ti + 4 * v + kq;
+                if (t0 + wave < ntiles && i < n && jb < n) R2[(size_t)jb * ld + i] = a4[v];
+            }
+        }
+    }
+    __syncthreads();
+    PRE_MARK(7)
+    (void)err_first; (void)polish_its;
+#ifdef JAC_PROF
+    if (tid == 0) {
+        for (int i2 = 0; i2 < 8; ++i2) g_prof[i2] = pcs[i2];
+        g_prof[8] = ok; g_prof[9] = polish_its; g_prof[10] = (long long)(err_first * 1e15);
+    }
+#endif
+}
+
 // One-sided Jacobi on the Cholesky factor of G.  JGL lanes share a pair of columns, NE = ceil(n / JGL)
 // elements of each column per lane; the two columns of a group live in registers for a whole sweep.
 //
@@ -267,17 +746,21 @@ __host__ __device__ static inline int jacobi_ld(int n, int l) {
 template <int NE, int JGL>
 __global__ void __launch_bounds__(1024)
 k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ lam, double* __restrict__ vec,
-             double* __restrict__ tmat, float* __restrict__ sval) {
+             double* __restrict__ tmat, float* __restrict__ sval, double* __restrict__ gscr) {
     extern __shared__ double sm[];
     const int ne = n + (n & 1);             // even number of columns (a zero column pads odd n)
     // Column stride = 8 (mod 16) doubles spreads the columns that one LDS instruction touches over the banks.
     const int ld = jacobi_ld(n, JGL);
+    const size_t rsize = (size_t)(ne + 1) * ld;
+    // gscr != nullptr: the eigenvector preconditioner runs and needs a second matrix-sized region
     double* W = sm;                              // column-major: W[p*ld + i] = element i of column p; column ne is a spare zero column
-    double* mailn = W + (size_t)(ne + 1) * ld;   // [ne/2] squared norm of the column in transit to even slot 2j
+    double* mailn = sm + (gscr ? 2 : 1) * rsize; // [ne/2] squared norm of the column in transit to even slot 2j
     double* nrm = mailn + ne / 2;                // [ne + 1]
     int* order = (int*)(nrm + ne + 1);           // [ne]
     int* colmap = order + ne;                    // [ne + 1] slot -> column of the columns still rotating
     int* rotf = colmap + ne + 1;                 // [ne + 1] column took part in a rotation this sweep
+    // [10 n + 40] the preconditioner's vectors, past the int arrays, on an even double index (16-byte loads)
+    double* pre_sa = sm + (((gscr ? 2 : 1) * rsize + ne / 2 + ne + 1 + (3 * ne + 4) / 2 + 2) & ~(size_t)1);
     __shared__ int nact_sh, wcnt[2];
     __shared__ double amax_sh;
     const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JGL, gl = tid % JGL;
@@ -311,7 +794,7 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
 #endif
         chol_blocked<true>(W, ld, n, rinv_sh, piv_floor, nullptr);
 #ifdef JAC_PROF
-        if (tid == 0) printf("jacobi n=%d: load %lld chol %lld\n", n, pt1 - pt0, (long long)(clock64() - pt1));
+        if (tid == 0) { g_prof[12] = pt1 - pt0; g_prof[13] = clock64() - pt1; }
 #endif
         // the rotations work on whole columns: clear the part above the diagonal
         for (int e = tid; e < n * n; e += nthr) {
@@ -319,6 +802,16 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             if (i < c) W[(size_t)c * ld + i] = 0.0;
         }
         __syncthreads();
+    }
+    if (gscr) {
+#ifdef JAC_PROF
+        const long long pq0 = clock64();
+#endif
+        eig_precondition<NE>(sm, sm + rsize, ld, n, ne, gscr, pre_sa);
+        W = sm + rsize;
+#ifdef JAC_PROF
+        if (tid == 0) g_prof[11] = clock64() - pq0;
+#endif
     }
 
     // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-7: the
@@ -470,6 +963,9 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             nact_sh = total + (total & 1);
         }
         __syncthreads();
+#ifdef JAC_PROF
+        if (tid == 0 && sweep < 8) { g_prof[16 + 2 * sweep] = m; g_prof[17 + 2 * sweep] = total; }
+#endif
         if (total == 0) break;
     }
     // column norms = singular values of L = square roots of the eigenvalues
@@ -513,13 +1009,18 @@ int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t
 }
 
 int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
-                      float* sval) {
+                      float* sval, double* gscr) {
     if (n < 1 || n > 128) return METIS_UNSUPPORTED;
-    int jgl = jacobi_lanes(n);
-    if (const char* e = getenv("METIS_JACOBI_LANES")) jgl = atoi(e);
+    const int jgl = jacobi_lanes(n);
     const int ne = n + (n & 1), ld = jacobi_ld(n, jgl);
-    const size_t lds = ((size_t)(ne + 1) * ld + ne / 2 + ne + 1) * sizeof(double) +
-                       (size_t)(3 * ne + 2 + ne / 2) * sizeof(int);
+    const size_t rsize = (size_t)(ne + 1) * ld;
+    const size_t small = ((size_t)ne / 2 + ne + 1) * sizeof(double) + (size_t)(3 * ne + 4) * sizeof(int) + 16;
+    // the preconditioner needs two matrix-sized regions and 10 n + 40 doubles; it pays from n ~ 72 on (about 250 us
+    // against 7 of 9 sweeps of 46 us at n = 80; at n = 64 the plain sweeps win), and its second region fits in
+    // the 160 KB of LDS up to n = 88
+    size_t lds = rsize * sizeof(double) + small;
+    const size_t lds_pre = 2 * rsize * sizeof(double) + small + (10 * (size_t)n + 44) * sizeof(double);
+    if (gscr && n >= 72 && lds_pre <= 160 * 1024) lds = lds_pre; else gscr = nullptr;
     // one group of jgl lanes per column pair; the Cholesky pre-pass and the bookkeeping use all 512 threads
     const int threads = ne / 2 * jgl > 512 ? 1024 : 512;
     if (ne / 2 * jgl > threads) return METIS_UNSUPPORTED;
@@ -528,45 +1029,24 @@ int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam
         if (hipFuncSetAttribute((const void*)k_jacobi_eig<NE, JGL>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                      \
             return METIS_HIP_ERROR;                                                                           \
-        hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval); \
+        hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval, gscr); \
     }
-    if (jgl == 4) {
-        switch ((n + 15) / 16) {
-            case 1: JACOBI_CASE(4, 4) break;
-            case 2: JACOBI_CASE(8, 4) break;
-            case 3: JACOBI_CASE(12, 4) break;
-            case 4: JACOBI_CASE(16, 4) break;
-            case 5: JACOBI_CASE(20, 4) break;
-            case 6: JACOBI_CASE(24, 4) break;
-            case 7: JACOBI_CASE(28, 4) break;
-            default: JACOBI_CASE(32, 4) break;
-        }
-    } else if (jgl == 8) {
-        switch ((n + 15) / 16) {
-            case 1: JACOBI_CASE(2, 8) break;
-            case 2: JACOBI_CASE(4, 8) break;
-            case 3: JACOBI_CASE(6, 8) break;
-            case 4: JACOBI_CASE(8, 8) break;
-            case 5: JACOBI_CASE(10, 8) break;
-            case 6: JACOBI_CASE(12, 8) break;
-            case 7: JACOBI_CASE(14, 8) break;
-            default: JACOBI_CASE(16, 8) break;
-        }
-    } else if (jgl == 16) {
-        switch ((n + 15) / 16) {
-            case 1: JACOBI_CASE(1, 16) break;
-            case 2: JACOBI_CASE(2, 16) break;
-            case 3: JACOBI_CASE(3, 16) break;
-            case 4: JACOBI_CASE(4, 16) break;
-            case 5: JACOBI_CASE(5, 16) break;
-            case 6: JACOBI_CASE(6, 16) break;
-            case 7: JACOBI_CASE(7, 16) break;
-            default: JACOBI_CASE(8, 16) break;
-        }
-    } else {
-        return METIS_UNSUPPORTED;
+    switch ((n + 15) / 16) {
+        case 1: JACOBI_CASE(1, 16) break;
+        case 2: JACOBI_CASE(2, 16) break;
+        case 3: JACOBI_CASE(3, 16) break;
+        case 4: JACOBI_CASE(4, 16) break;
+        case 5: JACOBI_CASE(5, 16) break;
+        case 6: JACOBI_CASE(6, 16) break;
+        case 7: JACOBI_CASE(7, 16) break;
+        default: JACOBI_CASE(8, 16) break;
     }
 #undef JACOBI_CASE
     METIS_LAUNCH_CHECK();
     return METIS_OK;
+}
+
+size_t jacobi_scratch_doubles(int n) {
+    const int ne = n + (n & 1);
+    return (size_t)(ne + 1) * jacobi_ld(n, jacobi_lanes(n));
 }
