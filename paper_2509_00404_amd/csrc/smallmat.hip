@@ -366,10 +366,10 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     double* tauv = de + 2 * n8; // [n] Householder tau
     double* scl = tauv + n;     // [n] v_i = A[i][j] * scl[j] for i > j+1, v_{j+1} = 1
     double* lamv = scl + n;     // [n] eigenvalues of T, ascending
-    double* xx = lamv + n;      // [n8] current column below the diagonal
-    double* pp = xx + n8;       // [n8] A v, zero up to the current row
-    double* vv = pp + n8;       // [n8] Householder vector of the current step
-    __shared__ double part_k[16], part_s[2][16], tau_s;  // per-wave partial sums: v^T A v, and sigma by step parity
+    const int n16 = (n + 15) & ~15;
+    double* xx = lamv + n;      // [n16] current column below the diagonal, zero up to the current row and from n up
+    double* pp = xx + n16;      // [n16] A v, zero up to the current row and from n up
+    __shared__ double part_k[16], part_s[2][16];  // per-wave partial sums: v^T A v, and sigma by step parity
     __shared__ unsigned long long err_s;
     __shared__ int fail_s;
 
@@ -405,10 +405,11 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
 
     PRE_MARK(1)
     // ---- 2: tridiagonalisation (lower), row r on lanes q = 0..7, columns q, q+8, ... in registers.
-    //         Step j: wave 0 forms the reflector v (zero up to row j) | every row's p_r = A[r][:] v and the wave's
-    //         share of v^T A v | rank-2 update, and column j+1 with its squared norm for the next step.  pp and vv
-    //         are kept zero up to row j (and from n up), so dead rows and columns update by exactly zero without
-    //         any test; waves whose rows are all dead only keep the barriers. ----
+    //         Step j, two barriers: every live wave forms the reflector's scalars and its own pieces of v from
+    //         column j (xx) | p_r = A[r][:] v and the wave's share of v^T A v || rank-2 update, then column j+1
+    //         with its squared norm for the next step.  xx and pp are kept zero up to row j (and from n up), so
+    //         dead rows and columns update by exactly zero without any test; waves whose rows are all dead only
+    //         keep the barriers. ----
     {
         const int r = tid >> 3, q = tid & 7;
         const bool row_ok = r < n;
@@ -419,10 +420,10 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
             const int c = q + 8 * e;
             areg[e] = (row_ok && c < n) ? R2[(size_t)r * lda + c] : 0.0;
         }
-        for (int c = tid; c < n8; c += nthr) { vv[c] = 0.0; pp[c] = 0.0; xx[c] = 0.0; }
+        for (int c = tid; c < n16; c += nthr) { pp[c] = 0.0; xx[c] = 0.0; }
         __syncthreads();
         {
-            if (row_ok && q == 0) xx[r] = areg[0];
+            if (row_ok && q == 0 && r >= 1) xx[r] = areg[0];
             const double y = (row_ok && r >= 2 && q == 0) ? areg[0] * areg[0] : 0.0;
             const double t = wave_sum_of_groups8(group8_sum(y));
             if (lane == 0 && wave < 16) { part_s[0][wave] = t; part_s[1][wave] = 0.0; part_k[wave] = 0.0; }
@@ -430,10 +431,13 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         auto step = [&](int j, auto ES) {
             constexpr int es = decltype(ES)::value;            // (j + 1) / 8: the register block of column j + 1
             __syncthreads();                      // column j (xx) and the partial sums of its sigma are complete
-            if (wave == 0) {
+            const bool live = wave < nw_rows && 8 * wave + 7 > j;       // some row of this wave is below row j
+            double vreg[NR], vr = 0.0, tau = 0.0;
+            if (live || wave == 0) {
+                // every live wave works out the reflector's scalars for itself: cheaper than a third barrier
                 const double sg = group_sum<16>((lane & 15) < nw_rows ? part_s[j & 1][lane & 15] : 0.0);
                 const double alpha = xx[j + 1];
-                double tau = 0.0, scale = 0.0, beta = alpha;
+                double scale = 0.0, beta = alpha;
                 if (sg > 0.0) {
                     const double h = alpha * alpha + sg;
                     double ri = __builtin_amdgcn_rsq(h);          // 1/sqrt(h), two Newton steps
@@ -444,21 +448,16 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
                     tau = (beta - alpha) * (alpha >= 0.0 ? -ri : ri);
                     scale = rcp_nr2(alpha - beta);
                 }
-                for (int c = lane; c < n; c += 64) vv[c] = c == j + 1 ? 1.0 : (c > j + 1 ? xx[c] * scale : 0.0);
-                if (lane == 0) {
-                    tau_s = tau;
-                    pp[j] = 0.0;
-                    ee[j] = beta; tauv[j] = tau; scl[j] = scale;
-                }
+                if (tid == 0) { pp[j] = 0.0; ee[j] = beta; tauv[j] = tau; scl[j] = scale; }
+                // v_c = x_c * scale below row j+1 (xx is zero up to row j), 1 at row j+1
+                const int qj = (j + 1) & 7;
+#pragma unroll
+                for (int e = 0; e < NR; ++e) vreg[e] = xx[q + 8 * e] * scale;
+                if (q == qj) vreg[es] = 1.0;
+                vr = r == j + 1 ? 1.0 : xx[r] * scale;
             }
-            __syncthreads();
-            const bool live = wave < nw_rows && 8 * wave + 7 > j;       // some row of this wave is below row j
-            double vreg[NR], vr = 0.0;
             if (live) {                           // p_r = sum_c A[r][c] v_c
                 double p0 = 0.0, p1 = 0.0;
-#pragma unroll
-                for (int e = 0; e < NR; ++e) vreg[e] = vv[q + 8 * e];
-                vr = vv[r];
 #pragma unroll
                 for (int e = 0; e < NR; e += 2) {
                     p0 += areg[e] * vreg[e];
@@ -473,9 +472,9 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
                 part_s[(j + 1) & 1][wave] = 0.0;
             }
             __syncthreads();
+            if (tid == 0) xx[j + 1] = 0.0;        // the column's head is spent: rows up to j+1 read as zero from now on
             if (live) {
                 const double ks = group_sum<16>((lane & 15) < nw_rows ? part_k[lane & 15] : 0.0);
-                const double tau = tau_s;
                 const double K = 0.5 * tau * tau * ks;
                 const double wr = tau * pp[r] - K * vr;
 #pragma unroll
@@ -572,7 +571,10 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         __syncthreads();
         // eigenvalues closer than the accuracy of the vectors that follow (repeated eigenvalues, rank deficiency):
         // those vectors would not come out orthogonal, so the remaining phases are skipped
-        if (tid + 1 < n && lamv[tid + 1] - lamv[tid] < 1e-9) atomicOr(&fail_s, 1);
+        if (tid + 1 < n) {
+            const double a = lamv[tid], b = lamv[tid + 1], m = fmax(fabs(a), fabs(b));
+            if (b - a < 1e-9 * m || m < 1e-14) atomicOr(&fail_s, 1);    // relative: a graded spectrum is fine
+        }
         __syncthreads();
     }
 
