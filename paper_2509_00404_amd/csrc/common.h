@@ -48,6 +48,19 @@ __device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// Raising a kernel's dynamic LDS limit is a driver call of tens of microseconds: remember, per device, the largest
+// value already set for that kernel (one zero-initialised cache per call site).  Races only repeat the call.
+struct LdsLimitCache { int bytes[16]; };
+static inline bool ensure_dyn_lds(const void* fn, size_t bytes, LdsLimitCache& c) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const bool slot = dev >= 0 && dev < 16;
+    if (slot && c.bytes[dev] >= (int)bytes) return true;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+    if (slot) c.bytes[dev] = (int)bytes;
+    return true;
+}
+
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -287,9 +287,8 @@ static inline int launch_project(hipStream_t s, const double* H, const double* H
 #define PROJECT_CASE(NT)                                                                                         \
     {                                                                                                            \
         const size_t lds = ProjectCfg<NT>::LDS;                                                                  \
-        if (hipFuncSetAttribute((const void*)k_project<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != \
-            hipSuccess)                                                                                          \
-            return METIS_HIP_ERROR;                                                                              \
+        static LdsLimitCache lds_set;                                                                            \
+        if (!ensure_dyn_lds((const void*)k_project<NT>, lds, lds_set)) return METIS_HIP_ERROR;                   \
         hipLaunchKernelGGL(k_project<NT>, grid, dim3(256), lds, s, H, H_alt, use_alt, r, A, lda, rowmap, Ms, N, kchunk, B);      \
     }
     switch ((r + 15) / 16) {

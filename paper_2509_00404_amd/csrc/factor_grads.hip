@@ -6,6 +6,7 @@
 // dense dW with the dequantized factors on the fp64 matrix cores, contraction split over workgroups.
 #include "common.h"
 #include "dgemm.h"
+#include "dgemm_skinny.h"
 #include "../../include/metis.h"
 
 namespace {
@@ -24,6 +25,33 @@ __global__ void k_dequant_factor(const uint8_t* __restrict__ codes, const uint8_
     out[t] = rowscale ? v * rowscale[j] : v;
 }
 
+// The same values laid out for the skinny kernels: bf16 [cols][k] (exact: a code times an E4M3 scale times a power
+// of two has at most 5 significant bits), or fp64 [cols][k] times rowscale[j]
+template <typename TO>
+__global__ void k_dequant_factor_t(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int k, int64_t cols,
+                                   float g, const float* __restrict__ rowscale, TO* __restrict__ out) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)k * cols) return;
+    const int64_t c = t / k;
+    const int j = (int)(t - c * k);
+    const uint32_t byte = codes[j * (cols / 2) + c / 2];
+    const uint32_t nib = (c & 1) ? (byte >> 4) : (byte & 15u);
+    const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    float v = grid[nib & 7u] * e4m3_decode(scales[j * (cols / 16) + c / 16]) * g;
+    if (nib & 8u) v = -v;
+    if constexpr (sizeof(TO) == 2) out[t] = f32_to_bf16_rne(v);
+    else out[t] = (double)v * (double)rowscale[j];
+}
+
+// out[c][j] = (float) in[j][c]
+__global__ void k_f64_to_f32_t(const double* __restrict__ in, int k, int64_t cols, float* __restrict__ out) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)k * cols) return;
+    const int64_t c = t / k;
+    const int j = (int)(t - c * k);
+    out[t] = (float)in[(int64_t)j * cols + c];
+}
+
 __global__ void k_zero_f64(double* __restrict__ p, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t st = (size_t)gridDim.x * blockDim.x;
@@ -40,7 +68,7 @@ __global__ void k_f64_to_f32_cols(const double* __restrict__ in, int64_t rows, i
 }
 
 struct FgLayout {
-    size_t off_t, off_dv, off_ds, zero_bytes, off_vd, off_ud, off_uds, total;
+    size_t off_t, off_dv, off_ds, zero_bytes, off_vd, off_ud, off_uds, off_vbf, off_h64, total;
 };
 
 FgLayout fg_layout(int64_t N, int64_t K, int k) {
@@ -54,6 +82,8 @@ FgLayout fg_layout(int64_t N, int64_t K, int k) {
     L.off_vd = take((size_t)k * K * 4);
     L.off_ud = take((size_t)k * N * 4);
     L.off_uds = take((size_t)k * N * 4);
+    L.off_vbf = take((size_t)K * k * 2);
+    L.off_h64 = take((size_t)N * k * 8);
     L.total = o;
     return L;
 }
@@ -98,20 +128,42 @@ int run(hipStream_t s, const TW* dW, int64_t ld, int64_t N, int64_t K, int k, co
                        W->Ut.scales, k, N, W->Ut.tscale, W->S, UdS);
     METIS_LAUNCH_CHECK();
     const int64_t tk = ceil_div64(k, 32);
-    // T = dW Vbar                      [N,k], contraction over K
-    launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, ld, 1), opnd(Vd, K, 1), N, k, K,
-                                            splits_for(K, ceil_div64(N, 32) * tk), epi64(T, k));
-    // dV = dW^T (Ubar S)               [K,k], contraction over N
-    launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, 1, ld), opnd(UdS, N, 1), K, k, N,
-                                            splits_for(N, ceil_div64(K, 32) * tk), epi64(dV64, k));
+    // A bf16 dW of aligned rows takes the decomposition's skinny kernels (same shapes as its sketch and projection)
+    bool fast = false;
+    if constexpr (sizeof(TW) == 2) fast = skinny_ok((const bf16_t*)dW, ld, K, k) && N % 8 == 0;
+    if (fast) {
+        bf16_t* Vbf = (bf16_t*)(ws + L.off_vbf);
+        double* H64 = (double*)(ws + L.off_h64);
+        hipLaunchKernelGGL(k_dequant_factor_t<bf16_t>, dim3((unsigned)ceil_div64((int64_t)k * K, 256)), dim3(256), 0, s,
+                           W->Vt.codes, W->Vt.scales, k, K, W->Vt.tscale, (const float*)nullptr, Vbf);
+        hipLaunchKernelGGL(k_dequant_factor_t<double>, dim3((unsigned)ceil_div64((int64_t)k * N, 256)), dim3(256), 0, s,
+                           W->Ut.codes, W->Ut.scales, k, N, W->Ut.tscale, W->S, H64);
+        METIS_LAUNCH_CHECK();
+        int st;
+        // T = dW Vbar                  [N,k], contraction over K
+        if ((st = launch_sketch(s, (const bf16_t*)dW, ld, nullptr, N, K, Vbf, k, T)) != METIS_OK) return st;
+        // dV^T = (Ubar S)^T dW         [k,K], contraction over N
+        if ((st = launch_project(s, H64, nullptr, nullptr, k, (const bf16_t*)dW, ld, nullptr, N, K, dV64)) != METIS_OK)
+            return st;
+    } else {
+        // T = dW Vbar                  [N,k], contraction over K
+        launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, ld, 1), opnd(Vd, K, 1), N, k, K,
+                                                splits_for(K, ceil_div64(N, 32) * tk), epi64(T, k));
+        // dV = dW^T (Ubar S)           [K,k], contraction over N
+        launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, 1, ld), opnd(UdS, N, 1), K, k, N,
+                                                splits_for(N, ceil_div64(K, 32) * tk), epi64(dV64, k));
+    }
     METIS_LAUNCH_CHECK();
     // dS = Ubar^T T                    [k,k], contraction over N
     launch_dgemm<float, double, EPI_ATOMIC_F64>(s, opnd(Ud, N, 1), opnd(T, 1, k), k, k, N, splits_for(N, tk * tk),
                                                 epi64(dS64, k));
     METIS_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(N * k, 256)), dim3(256), 0, s, T, N, k, W->S, dU);
-    hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(K * k, 256)), dim3(256), 0, s, dV64, K, k,
-                       (const float*)nullptr, dV);
+    if (fast)
+        hipLaunchKernelGGL(k_f64_to_f32_t, dim3((unsigned)ceil_div64(K * k, 256)), dim3(256), 0, s, dV64, k, K, dV);
+    else
+        hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(K * k, 256)), dim3(256), 0, s, dV64, K, k,
+                           (const float*)nullptr, dV);
     hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64((int64_t)k * k, 256)), dim3(256), 0, s, dS64,
                        (int64_t)k, k, (const float*)nullptr, dS);
     METIS_LAUNCH_CHECK();

@@ -562,8 +562,8 @@ int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
     constexpr size_t lds = gemm_lds_bytes<256, 256>();
     dim3 grid((unsigned)(tm * tn));
     auto kern = k_fp4_gemm_nt_pipe<OUT>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return METIS_HIP_ERROR;
+    static LdsLimitCache lds_set;
+    if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn));
     METIS_LAUNCH_CHECK();
     return METIS_OK;
@@ -583,13 +583,13 @@ int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
     dim3 grid((unsigned)(tm * tn), (unsigned)ceil_div64(niter, ips));
     if (vec) {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, true, OUT>;
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return METIS_HIP_ERROR;
+        static LdsLimitCache lds_set;
+        if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
         hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
     } else {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, false, OUT>;
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return METIS_HIP_ERROR;
+        static LdsLimitCache lds_set;
+        if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
         hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
     }
     METIS_LAUNCH_CHECK();
@@ -775,9 +775,8 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
             return st;
         const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
         const size_t ax_lds = ((size_t)AX_ROWS * ((ka > kb ? ka : kb) + 1) + (size_t)ka * kb) * sizeof(float);
-        if (ax_lds > 48 * 1024 &&
-            hipFuncSetAttribute((const void*)k_assemble_ext, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ax_lds) != hipSuccess)
-            return METIS_HIP_ERROR;
+        static LdsLimitCache ax_set;
+        if (ax_lds > 48 * 1024 && !ensure_dyn_lds((const void*)k_assemble_ext, ax_lds, ax_set)) return METIS_HIP_ERROR;
         hipLaunchKernelGGL(k_assemble_ext, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
                            T1, Mk, E2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
                            b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);

@@ -1003,8 +1003,8 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
 int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info, int32_t* wellcond_out,
                     const int32_t* skip_in) {
     size_t lds = 2 * (size_t)n * (n + 1) * sizeof(double);
-    if (hipFuncSetAttribute((const void*)k_chol_inv, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return METIS_HIP_ERROR;
+    static LdsLimitCache lds_set;
+    if (!ensure_dyn_lds((const void*)k_chol_inv, lds, lds_set)) return METIS_HIP_ERROR;
     hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), lds, s, G, n, Linv, info, wellcond_out, skip_in);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
@@ -1028,9 +1028,8 @@ int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam
     if (ne / 2 * jgl > threads) return METIS_UNSUPPORTED;
 #define JACOBI_CASE(NE, JGL)                                                                                  \
     {                                                                                                         \
-        if (hipFuncSetAttribute((const void*)k_jacobi_eig<NE, JGL>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)lds) != hipSuccess)                                                      \
-            return METIS_HIP_ERROR;                                                                           \
+        static LdsLimitCache lds_set;                                                                         \
+        if (!ensure_dyn_lds((const void*)k_jacobi_eig<NE, JGL>, lds, lds_set)) return METIS_HIP_ERROR;        \
         hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval, gscr); \
     }
     switch ((n + 15) / 16) {
