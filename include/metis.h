@@ -228,6 +228,36 @@ int metis_fp4_factor_grads(void* stream, const metis_mat* dW, const metis_split*
                            float* dU, float* dS, float* dV,
                            void* workspace, size_t workspace_bytes);
 
+/* ---- MXFP4 variant (the microscaling block format named in Sec. 2.3 beside NVFP4) ------------ */
+
+/*
+ * MXFP4-quantized device matrix (OCP Microscaling Formats v1.0):
+ *   codes  [rows, cols/2]   two E2M1 codes per byte, same nibble layout as metis_fp4
+ *   scales [rows, cols/32]  one E8M0 byte per block of 32 consecutive columns, value 2^(byte - 127)
+ * element value = grid[code] * 2^(scale - 127).  Blocks run along `cols`.
+ */
+typedef struct {
+    uint8_t* codes;
+    uint8_t* scales;
+    int64_t  rows, cols;
+} metis_mxfp4;
+
+/*
+ * Quantize A (device, bf16 or fp32, [rows, cols], cols % 32 == 0, rows 16-byte aligned) to MXFP4:
+ * per block X = 2^(floor(log2 amax) - 2) (the specification's conversion rule), elements round to the
+ * nearest E2M1 value of e / X, ties to the even code, magnitudes above 6 saturate; an all-zero block
+ * stores scale byte 0.  out's buffers are caller-owned and overwritten.  Asynchronous on `stream`.
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE (shape mismatch or misaligned rows).
+ */
+int metis_quantize_mx(void* stream, const metis_mat* A, metis_mxfp4* out);
+
+/*
+ * C[M,N] = A[M,K] B[N,K]^T on the block-scaled FP4 matrix instruction (the scales are applied by
+ * the hardware, fp32 accumulation).  K % 128 == 0; C device, bf16 or fp32, row stride ld >= N.
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (K not a multiple of 128).
+ */
+int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const metis_mxfp4* B, metis_mat* C);
+
 /* ---- measurement aid ---------------------------------------------------------------------- */
 
 /*

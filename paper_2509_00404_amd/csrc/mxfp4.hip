@@ -1,0 +1,291 @@
+// MXFP4 variant of the block-FP4 GEMM: the microscaling format that Sec. 2.3 names next to NVFP4
+// (OCP MX v1.0: blocks of 32, one power-of-two E8M0 scale per block, E2M1 elements).  Its scales are
+// exactly what gfx950's block-scaled matrix instruction applies in hardware, so the codes go from
+// LDS straight into v_mfma_scale_f32_32x32x64_f8f6f4 with no expansion in the vector ALUs: this is
+// the chip's FP4 rate, against which the NVFP4 path (E4M3 scales per 16, expanded to fp16) can be read.
+#include <type_traits>
+#include "common.h"
+#include "gemm_tile.h"
+#include "../../include/metis.h"
+
+typedef int int8v_t __attribute__((ext_vector_type(8)));
+
+namespace {
+
+// ---- quantizer: one lane per block of 32 consecutive elements of a row ----
+// X = 2^(floor(log2 amax) - 2); elements round to the nearest E2M1 value of e / X, ties to the even code,
+// magnitudes above 6 saturate (the packed converter does the rounding, saturation and nibble packing).
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_quantize_mx(const T* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* cols / 32 */, uint8_t* __restrict__ codes,
+              uint8_t* __restrict__ scales) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= M * nblk) return;
+    const int64_t row = t / nblk, bc = t - row * nblk;
+    float v[32];
+    if constexpr (sizeof(T) == 2) {
+        const uint4* src = reinterpret_cast<const uint4*>(A + row * ld + bc * 32);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 a = src[i];
+            const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[8 * i + 2 * j] = bf16lo_to_f32(w[j]);
+                v[8 * i + 2 * j + 1] = bf16hi_to_f32(w[j]);
+            }
+        }
+    } else {
+        const float4* src = reinterpret_cast<const float4*>(A + row * ld + bc * 32);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float4 a = src[i];
+            v[4 * i] = a.x; v[4 * i + 1] = a.y; v[4 * i + 2] = a.z; v[4 * i + 3] = a.w;
+        }
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(v[i]));
+    int sh = -127;
+    if (amax > 0.0f) {
+        sh = ilogbf(amax) - 2;
+        sh = sh < -127 ? -127 : (sh > 127 ? 127 : sh);
+    }
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float y0 = ldexpf(v[8 * i + 2 * j], -sh), y1 = ldexpf(v[8 * i + 2 * j + 1], -sh);   // exact
+            switch (j) {
+                case 0: w[i] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w[i], y0, y1, 1.0f, 0); break;
+                case 1: w[i] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w[i], y0, y1, 1.0f, 1); break;
+                case 2: w[i] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w[i], y0, y1, 1.0f, 2); break;
+                default: w[i] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w[i], y0, y1, 1.0f, 3); break;
+            }
+        }
+    }
+    *reinterpret_cast<uint4*>(codes + t * 16) = make_uint4(w[0], w[1], w[2], w[3]);     // [M, cols/2] contiguous
+    scales[t] = (uint8_t)(sh + 127);
+}
+
+// ---- GEMM C[M,N] = A[M,K] B[N,K]^T ----
+// 256 x 256 tile, 4 waves of 128 x 128 (4 x 4 accumulator tiles of 32 x 32, one wave per SIMD), stages of 128
+// contraction elements = two matrix instructions deep.  A lane's operand of one instruction is the 32 codes
+// (16 bytes) of row lane % 32, contraction half lane / 32, and the E8M0 byte of exactly that block of 32.
+#define MX_KI 128
+#define MX_CROW (MX_KI / 2 + 16)      // padded code row in LDS: 80 bytes, 16-byte reads of 8 consecutive rows hit 8 bank groups
+#define MX_SROW 4                     // the row's four scale bytes of a stage
+
+struct MxOperand {
+    const uint8_t* codes;             // [rows, K/2]
+    const uint8_t* scales;            // [rows, K/32]
+    int64_t rows;
+};
+
+template <typename OUT>
+__global__ void __launch_bounds__(256)
+k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int OFF_CB = BM * MX_CROW, OFF_SA = (BM + BN) * MX_CROW, OFF_SB = OFF_SA + BM * MX_SROW,
+                  BUF = OFF_SB + BN * MX_SROW;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int tile_m, tile_n;
+    tile_coords(tmap, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+    const int li = lane & 31, half = lane >> 5;
+
+    float16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int niter = (int)(K / MX_KI);
+    // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/4 + 64 v, 16-byte segment
+    // tid % 4) and the scale words of rows tid (A) and tid (B); rows past the operand's end re-read its last row
+    const uint8_t* pa[4];
+    const uint8_t* pb[4];
+    const int64_t cstride = K / 2, sstride = K / 32;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        int64_t ga = m0 + (tid >> 2) + 64 * v, gb = n0 + (tid >> 2) + 64 * v;
+        if (ga >= A.rows) ga = A.rows - 1;
+        if (gb >= B.rows) gb = B.rows - 1;
+        pa[v] = A.codes + ga * cstride + 16 * (tid & 3);
+        pb[v] = B.codes + gb * cstride + 16 * (tid & 3);
+    }
+    const uint8_t* psa;
+    const uint8_t* psb;
+    {
+        int64_t ga = m0 + tid, gb = n0 + tid;
+        if (ga >= A.rows) ga = A.rows - 1;
+        if (gb >= B.rows) gb = B.rows - 1;
+        psa = A.scales + ga * sstride;
+        psb = B.scales + gb * sstride;
+    }
+    uint4 ra[4], rb[4];
+    uint32_t rsa, rsb;
+    auto load_stage = [&](int st) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            ra[v] = *reinterpret_cast<const uint4*>(pa[v] + (int64_t)st * (MX_KI / 2));
+            rb[v] = *reinterpret_cast<const uint4*>(pb[v] + (int64_t)st * (MX_KI / 2));
+        }
+        rsa = *reinterpret_cast<const uint32_t*>(psa + (int64_t)st * (MX_KI / 32));
+        rsb = *reinterpret_cast<const uint32_t*>(psb + (int64_t)st * (MX_KI / 32));
+    };
+    auto store_stage = [&](uint8_t* buf) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = (tid >> 2) + 64 * v, seg = tid & 3;
+            *reinterpret_cast<uint4*>(buf + row * MX_CROW + 16 * seg) = ra[v];
+            *reinterpret_cast<uint4*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rb[v];
+        }
+        *reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * MX_SROW) = rsa;
+        *reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * MX_SROW) = rsb;
+    };
+
+    // per-lane byte offsets of this wave's fragment rows inside a buffer
+    const int oca = (wm + li) * MX_CROW + 16 * half, ocb = OFF_CB + (wn + li) * MX_CROW + 16 * half;
+    const int osa = OFF_SA + (wm + li) * MX_SROW, osb = OFF_SB + (wn + li) * MX_SROW;
+    uint4 fa[2][TM], fb[2][TN];       // code fragments of the two contraction steps of a stage
+    uint32_t sa[TM], sb[TN];          // the rows' scale words, shifted so that byte 0 / byte 2 are this lane's blocks
+    auto read_codes = [&](const uint8_t* buf, int ks, int slot) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const uint4*>(buf + oca + 32 * i * MX_CROW + 32 * ks);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const uint4*>(buf + ocb + 32 * j * MX_CROW + 32 * ks);
+    };
+    auto read_scales = [&](const uint8_t* buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(buf + osa + 32 * i * MX_SROW) >> (8 * half);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(buf + osb + 32 * j * MX_SROW) >> (8 * half);
+    };
+    auto mma = [&](int slot, auto KS) {
+        constexpr int ks = decltype(KS)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int8v_t a = {(int)fa[slot][i].x, (int)fa[slot][i].y, (int)fa[slot][i].z, (int)fa[slot][i].w, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int8v_t b = {(int)fb[slot][j].x, (int)fb[slot][j].y, (int)fb[slot][j].z, (int)fb[slot][j].w, 0, 0, 0, 0};
+                // formats 4 = FP4 (E2M1) for both operands; the scale byte is byte 2 ks of the shifted word
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 4, 4, 2 * ks, (int)sa[i],
+                                                                             2 * ks, (int)sb[j]);
+            }
+        }
+    };
+
+    load_stage(0);
+    store_stage(lds);
+    __syncthreads();
+    if (niter > 1) load_stage(1);
+    read_codes(lds, 0, 0);
+    read_scales(lds);
+
+#pragma unroll 1
+    for (int it = 0; it < niter; ++it) {
+        const uint8_t* bufc = lds + (it & 1) * BUF;
+        uint8_t* bufn = lds + ((it & 1) ^ 1) * BUF;
+        // second step's codes arrive while the first step multiplies; the next stage goes to the other buffer
+        read_codes(bufc, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(0, std::integral_constant<int, 0>{});
+        if (it + 1 < niter) store_stage(bufn);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();                          // next stage is in LDS; this stage's codes are all in registers
+        uint32_t sa_n[TM], sb_n[TN];
+        if (it + 1 < niter) {
+            read_codes(bufn, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) sa_n[i] = *reinterpret_cast<const uint32_t*>(bufn + osa + 32 * i * MX_SROW) >> (8 * half);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) sb_n[j] = *reinterpret_cast<const uint32_t*>(bufn + osb + 32 * j * MX_SROW) >> (8 * half);
+            if (it + 2 < niter) load_stage(it + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma(1, std::integral_constant<int, 1>{});
+        if (it + 1 < niter) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) sa[i] = sa_n[i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) sb[j] = sb_n[j];
+        }
+    }
+
+    const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t c = n0 + wn + 32 * j + li;
+            const int64_t rbase = m0 + wm + 32 * i + 4 * half;
+            if (interior) {
+                store_tile16<OUT>(C + rbase * ldc + c, ldc, acc[i][j], 1.0f);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, acc[i][j][v]);
+                }
+            }
+        }
+}
+
+constexpr size_t MX_LDS = 2 * (size_t)(256 + 256) * (MX_CROW + MX_SROW);
+
+template <typename OUT>
+int launch_mx_gemm(hipStream_t s, const MxOperand& a, const MxOperand& b, int64_t K, OUT* C, int64_t ldc) {
+    const int64_t tm = ceil_div64(a.rows, 256), tn = ceil_div64(b.rows, 256);
+    if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+    auto kern = k_mxfp4_gemm_nt<OUT>;
+    static LdsLimitCache lds_set;
+    if (!ensure_dyn_lds((const void*)kern, MX_LDS, lds_set)) return METIS_HIP_ERROR;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(256), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+bool mx_ok(const metis_mxfp4* t) { return t && t->codes && t->scales && t->rows >= 1 && t->cols >= 32 && t->cols % 32 == 0; }
+
+}  // namespace
+
+extern "C" int metis_quantize_mx(void* stream, const metis_mat* A, metis_mxfp4* out) {
+    if (!A || !A->ptr || !mx_ok(out)) return METIS_INVALID_ARG;
+    if (A->dtype != METIS_BF16 && A->dtype != METIS_F32) return METIS_INVALID_ARG;
+    if (A->rows != out->rows || A->cols != out->cols || A->ld < A->cols) return METIS_BAD_SHAPE;
+    const int64_t esz = A->dtype == METIS_BF16 ? 2 : 4;
+    if ((A->ld * esz) % 16 || reinterpret_cast<uintptr_t>(A->ptr) % 16 || reinterpret_cast<uintptr_t>(out->codes) % 16)
+        return METIS_BAD_SHAPE;                                       // 16-byte row loads and code stores
+    const int64_t nblk = A->cols / 32, total = A->rows * nblk;
+    hipStream_t s = (hipStream_t)stream;
+    if (A->dtype == METIS_BF16)
+        hipLaunchKernelGGL(k_quantize_mx<bf16_t>, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, s,
+                           (const bf16_t*)A->ptr, A->ld, A->rows, nblk, out->codes, out->scales);
+    else
+        hipLaunchKernelGGL(k_quantize_mx<float>, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, s,
+                           (const float*)A->ptr, A->ld, A->rows, nblk, out->codes, out->scales);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+extern "C" int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const metis_mxfp4* B, metis_mat* C) {
+    if (!mx_ok(A) || !mx_ok(B) || !C || !C->ptr) return METIS_INVALID_ARG;
+    if (C->dtype != METIS_BF16 && C->dtype != METIS_F32) return METIS_INVALID_ARG;
+    if (A->cols != B->cols || C->rows != A->rows || C->cols != B->rows || C->ld < C->cols) return METIS_BAD_SHAPE;
+    const int64_t K = A->cols;
+    if (K % MX_KI) return METIS_UNSUPPORTED;                          // whole stages of 128
+    if (reinterpret_cast<uintptr_t>(A->codes) % 16 || reinterpret_cast<uintptr_t>(B->codes) % 16 ||
+        reinterpret_cast<uintptr_t>(A->scales) % 4 || reinterpret_cast<uintptr_t>(B->scales) % 4)
+        return METIS_BAD_SHAPE;
+    const MxOperand a = {A->codes, A->scales, A->rows}, b = {B->codes, B->scales, B->rows};
+    hipStream_t s = (hipStream_t)stream;
+    if (C->dtype == METIS_F32) return launch_mx_gemm<float>(s, a, b, K, (float*)C->ptr, C->ld);
+    return launch_mx_gemm<bf16_t>(s, a, b, K, (bf16_t*)C->ptr, C->ld);
+}

@@ -29,6 +29,10 @@ class Split(C.Structure):
     _fields_ = [("Ut", Fp4), ("Vt", Fp4), ("R", Fp4), ("Rt", Fp4), ("S", C.c_void_p), ("k", C.c_int)]
 
 
+class MxFp4(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scales", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64)]
+
+
 class MetisError(RuntimeError):
     pass
 
@@ -64,6 +68,8 @@ _SIGNATURES = {
                                          C.c_void_p, C.c_size_t]),
     "metis_fp4_linear_wgrad": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                          C.c_void_p, C.c_size_t]),
+    "metis_quantize_mx": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(MxFp4)]),
+    "metis_mxfp4_gemm_nt": (C.c_int, [C.c_void_p, C.POINTER(MxFp4), C.POINTER(MxFp4), C.POINTER(Mat)]),
     "metis_factor_grads_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_factor_grads": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Split), C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_size_t]),
@@ -117,6 +123,18 @@ class Fp4Tensor:
 
 def _null_fp4():
     return Fp4(None, None, 1.0, 0, 0)
+
+
+class MxTensor:
+    """Device MXFP4 matrix: codes [rows, cols/2] u8, scales [rows, cols/32] u8 (E8M0)."""
+
+    def __init__(self, rows, cols, device="cuda"):
+        self.rows, self.cols = rows, cols
+        self.codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=device)
+        self.scales = torch.empty((rows, cols // 32), dtype=torch.uint8, device=device)
+
+    def c(self):
+        return MxFp4(self.codes.data_ptr(), self.scales.data_ptr(), self.rows, self.cols)
 
 
 class SplitTensor:
@@ -235,6 +253,19 @@ def split_from_parts(W_R, U, S, V, out, seed=None):
     else:
         _check(lib().metis_split_from_parts_sr(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
                                                out.k, int(seed), C.byref(s)))
+
+
+def quantize_mx(A, out):
+    a, o = _mat(A), out.c()
+    _check(lib().metis_quantize_mx(_stream(), C.byref(a), C.byref(o)))
+    return out
+
+
+def mxfp4_gemm_nt(A, B, Cmat):
+    """Cmat[M,N] = A[M,K] B[N,K]^T of two MxTensors."""
+    a, b, c = A.c(), B.c(), _mat(Cmat)
+    _check(lib().metis_mxfp4_gemm_nt(_stream(), C.byref(a), C.byref(b), C.byref(c)))
+    return Cmat
 
 
 def linear_workspace_bytes(L, N, K, k):
