@@ -9,6 +9,7 @@
 #include "../../include/metis.h"
 
 typedef int int8v_t __attribute__((ext_vector_type(8)));
+typedef uint32_t uvec4_t __attribute__((ext_vector_type(4)));   // a native vector: copies stay in registers
 
 namespace {
 
@@ -107,67 +108,71 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
 
     const int niter = (int)(K / MX_KI);
     // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/4 + 64 v, 16-byte segment
-    // tid % 4) and the scale words of rows tid (A) and tid (B); rows past the operand's end re-read its last row
-    const uint8_t* pa[4];
-    const uint8_t* pb[4];
-    const int64_t cstride = K / 2, sstride = K / 32;
+    // tid % 4) and the scale words of rows tid (A) and tid (B); rows past the operand's end re-read its last row.
+    // Byte offsets fit 32 bits (checked by the host); the stage offset is uniform.
+    uint32_t oa[4], ob[4], osga, osgb;
+    const uint32_t cstride = (uint32_t)(K / 2), sstride = (uint32_t)(K / 32);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         int64_t ga = m0 + (tid >> 2) + 64 * v, gb = n0 + (tid >> 2) + 64 * v;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
-        pa[v] = A.codes + ga * cstride + 16 * (tid & 3);
-        pb[v] = B.codes + gb * cstride + 16 * (tid & 3);
+        oa[v] = (uint32_t)ga * cstride + 16u * (tid & 3);
+        ob[v] = (uint32_t)gb * cstride + 16u * (tid & 3);
     }
-    const uint8_t* psa;
-    const uint8_t* psb;
     {
         int64_t ga = m0 + tid, gb = n0 + tid;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
-        psa = A.scales + ga * sstride;
-        psb = B.scales + gb * sstride;
+        osga = (uint32_t)ga * sstride;
+        osgb = (uint32_t)gb * sstride;
     }
-    uint4 ra[4], rb[4];
-    uint32_t rsa, rsb;
-    auto load_stage = [&](int st) {
+    // Two register sets of staged stages: a stage's loads are issued two stages before its data is written
+    // to LDS (a stage is only ~0.5 us of matrix work, far less than a trip to L2 or HBM under load).
+    // Two register sets: "near" holds the stage that goes to LDS next, "far" the one after.  The stage body is
+    // branch-free (stage indices are clamped, the last stages load and store data nobody uses).
+    uvec4_t ran[4], rbn[4], raf[4], rbf[4];
+    uint32_t rsan, rsbn, rsaf, rsbf;
+    auto load_far = [&](int st) __attribute__((always_inline)) {
+        const uint8_t* ca = A.codes + (size_t)st * (MX_KI / 2);
+        const uint8_t* cb = B.codes + (size_t)st * (MX_KI / 2);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            ra[v] = *reinterpret_cast<const uint4*>(pa[v] + (int64_t)st * (MX_KI / 2));
-            rb[v] = *reinterpret_cast<const uint4*>(pb[v] + (int64_t)st * (MX_KI / 2));
+            raf[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
+            rbf[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
         }
-        rsa = *reinterpret_cast<const uint32_t*>(psa + (int64_t)st * (MX_KI / 32));
-        rsb = *reinterpret_cast<const uint32_t*>(psb + (int64_t)st * (MX_KI / 32));
+        rsaf = *reinterpret_cast<const uint32_t*>(A.scales + (size_t)st * (MX_KI / 32) + osga);
+        rsbf = *reinterpret_cast<const uint32_t*>(B.scales + (size_t)st * (MX_KI / 32) + osgb);
     };
-    auto store_stage = [&](uint8_t* buf) {
+    auto far_to_near = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { ran[v] = raf[v]; rbn[v] = rbf[v]; }
+        rsan = rsaf; rsbn = rsbf;
+    };
+    auto store_near = [&](uint8_t* buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = (tid >> 2) + 64 * v, seg = tid & 3;
-            *reinterpret_cast<uint4*>(buf + row * MX_CROW + 16 * seg) = ra[v];
-            *reinterpret_cast<uint4*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rb[v];
+            *reinterpret_cast<uvec4_t*>(buf + row * MX_CROW + 16 * seg) = ran[v];
+            *reinterpret_cast<uvec4_t*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rbn[v];
         }
-        *reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * MX_SROW) = rsa;
-        *reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * MX_SROW) = rsb;
+        *reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * MX_SROW) = rsan;
+        *reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * MX_SROW) = rsbn;
     };
+    auto clampst = [&](int st) { return st < niter ? st : niter - 1; };
 
     // per-lane byte offsets of this wave's fragment rows inside a buffer
     const int oca = (wm + li) * MX_CROW + 16 * half, ocb = OFF_CB + (wn + li) * MX_CROW + 16 * half;
     const int osa = OFF_SA + (wm + li) * MX_SROW, osb = OFF_SB + (wn + li) * MX_SROW;
-    uint4 fa[2][TM], fb[2][TN];       // code fragments of the two contraction steps of a stage
+    uvec4_t fa[2][TM], fb[2][TN];       // code fragments of the two contraction steps of a stage
     uint32_t sa[TM], sb[TN];          // the rows' scale words, shifted so that byte 0 / byte 2 are this lane's blocks
-    auto read_codes = [&](const uint8_t* buf, int ks, int slot) {
+    auto read_codes = [&](const uint8_t* buf, int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const uint4*>(buf + oca + 32 * i * MX_CROW + 32 * ks);
+        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const uvec4_t*>(buf + oca + 32 * i * MX_CROW + 32 * ks);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const uint4*>(buf + ocb + 32 * j * MX_CROW + 32 * ks);
+        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const uvec4_t*>(buf + ocb + 32 * j * MX_CROW + 32 * ks);
     };
-    auto read_scales = [&](const uint8_t* buf) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(buf + osa + 32 * i * MX_SROW) >> (8 * half);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(buf + osb + 32 * j * MX_SROW) >> (8 * half);
-    };
-    auto mma = [&](int slot, auto KS) {
+    auto mma = [&](int slot, auto KS) __attribute__((always_inline)) {
         constexpr int ks = decltype(KS)::value;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -182,41 +187,40 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
         }
     };
 
-    load_stage(0);
-    store_stage(lds);
+    load_far(0);
+    far_to_near();
+    store_near(lds);
     __syncthreads();
-    if (niter > 1) load_stage(1);
+    load_far(clampst(1));
+    far_to_near();
+    load_far(clampst(2));
     read_codes(lds, 0, 0);
-    read_scales(lds);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(lds + osa + 32 * i * MX_SROW) >> (8 * half);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(lds + osb + 32 * j * MX_SROW) >> (8 * half);
 
 #pragma unroll 1
     for (int it = 0; it < niter; ++it) {
         const uint8_t* bufc = lds + (it & 1) * BUF;
         uint8_t* bufn = lds + ((it & 1) ^ 1) * BUF;
-        // second step's codes arrive while the first step multiplies; the next stage goes to the other buffer
+        // second step's codes arrive while the first step multiplies; stage it + 1 goes to the other buffer
         read_codes(bufc, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
         mma(0, std::integral_constant<int, 0>{});
-        if (it + 1 < niter) store_stage(bufn);
+        store_near(bufn);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();                          // next stage is in LDS; this stage's codes are all in registers
-        uint32_t sa_n[TM], sb_n[TN];
-        if (it + 1 < niter) {
-            read_codes(bufn, 0, 0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) sa_n[i] = *reinterpret_cast<const uint32_t*>(bufn + osa + 32 * i * MX_SROW) >> (8 * half);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) sb_n[j] = *reinterpret_cast<const uint32_t*>(bufn + osb + 32 * j * MX_SROW) >> (8 * half);
-            if (it + 2 < niter) load_stage(it + 2);
-        }
+        read_codes(bufn, 0, 0);
+        far_to_near();                            // stage it + 2 moves up, its registers take stage it + 3
+        load_far(clampst(it + 3));
         __builtin_amdgcn_sched_barrier(0);
         mma(1, std::integral_constant<int, 1>{});
-        if (it + 1 < niter) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) sa[i] = sa_n[i];
+        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(bufn + osa + 32 * i * MX_SROW) >> (8 * half);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) sb[j] = sb_n[j];
-        }
+        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(bufn + osb + 32 * j * MX_SROW) >> (8 * half);
     }
 
     const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
@@ -281,6 +285,7 @@ extern "C" int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const met
     if (A->cols != B->cols || C->rows != A->rows || C->cols != B->rows || C->ld < C->cols) return METIS_BAD_SHAPE;
     const int64_t K = A->cols;
     if (K % MX_KI) return METIS_UNSUPPORTED;                          // whole stages of 128
+    if (A->rows * (K / 2) > 0xFFFFFFFFll || B->rows * (K / 2) > 0xFFFFFFFFll) return METIS_UNSUPPORTED;   // 32-bit byte offsets
     if (reinterpret_cast<uintptr_t>(A->codes) % 16 || reinterpret_cast<uintptr_t>(B->codes) % 16 ||
         reinterpret_cast<uintptr_t>(A->scales) % 4 || reinterpret_cast<uintptr_t>(B->scales) % 4)
         return METIS_BAD_SHAPE;
