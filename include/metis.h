@@ -253,8 +253,8 @@ int metis_quantize_mx(void* stream, const metis_mat* A, metis_mxfp4* out);
 
 /*
  * C[M,N] = A[M,K] B[N,K]^T on the block-scaled FP4 matrix instruction (the scales are applied by
- * the hardware, fp32 accumulation).  K % 128 == 0; C device, bf16 or fp32, row stride ld >= N.
- * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (K not a multiple of 128).
+ * the hardware, fp32 accumulation).  K % 256 == 0; C device, bf16 or fp32, row stride ld >= N.
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (K not a multiple of 256).
  */
 int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const metis_mxfp4* B, metis_mat* C);
 

@@ -10,6 +10,7 @@
 
 typedef int int8v_t __attribute__((ext_vector_type(8)));
 typedef uint32_t uvec4_t __attribute__((ext_vector_type(4)));   // a native vector: copies stay in registers
+typedef uint32_t uvec2_t __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -71,12 +72,17 @@ k_quantize_mx(const T* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* co
 }
 
 // ---- GEMM C[M,N] = A[M,K] B[N,K]^T ----
-// 256 x 256 tile, 4 waves of 128 x 128 (4 x 4 accumulator tiles of 32 x 32, one wave per SIMD), stages of 128
-// contraction elements = two matrix instructions deep.  A lane's operand of one instruction is the 32 codes
-// (16 bytes) of row lane % 32, contraction half lane / 32, and the E8M0 byte of exactly that block of 32.
-#define MX_KI 128
-#define MX_CROW (MX_KI / 2 + 16)      // padded code row in LDS: 80 bytes, 16-byte reads of 8 consecutive rows hit 8 bank groups
-#define MX_SROW 4                     // the row's four scale bytes of a stage
+// 256 x 256 tile, 4 waves of 128 x 128 (4 x 4 accumulator tiles of 32 x 32, one wave per SIMD).  A lane's operand of
+// one matrix instruction is the 32 codes (16 bytes) of row lane % 32, contraction half lane / 32, and the E8M0 byte
+// of exactly that block of 32.  With no expansion work the kernel lives on operand delivery:
+//  * a stage is 256 contraction elements = 128 bytes of every row = whole cache lines (with 64-byte stages every
+//    line crossed L2 -> L1 twice, which was the limit), four matrix instructions deep;
+//  * the next stage's global data sits in registers for one stage before it is written to the other LDS buffer;
+//  * fragments are double-buffered in registers: step s+1 is read from LDS while step s multiplies.
+// The stage body is branch-free (stage indices are clamped; the last stage loads and stores data nobody uses).
+#define MX_KI 256
+#define MX_CROW (MX_KI / 2 + 16)      // padded code row in LDS: 144 bytes, 16-byte reads of 8 consecutive rows hit 8 bank groups
+#define MX_SROW 8                     // the row's eight scale bytes of a stage
 
 struct MxOperand {
     const uint8_t* codes;             // [rows, K/2]
@@ -87,7 +93,7 @@ struct MxOperand {
 template <typename OUT>
 __global__ void __launch_bounds__(256)
 k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
-    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256;
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, KS = MX_KI / 64;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int OFF_CB = BM * MX_CROW, OFF_SA = (BM + BN) * MX_CROW, OFF_SB = OFF_SA + BM * MX_SROW,
                   BUF = OFF_SB + BN * MX_SROW;
@@ -107,18 +113,18 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const int niter = (int)(K / MX_KI);
-    // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/4 + 64 v, 16-byte segment
-    // tid % 4) and the scale words of rows tid (A) and tid (B); rows past the operand's end re-read its last row.
-    // Byte offsets fit 32 bits (checked by the host); the stage offset is uniform.
-    uint32_t oa[4], ob[4], osga, osgb;
+    // this thread's share of a stage: code vectors v = 0..7 of each operand (row tid/8 + 32 v, 16-byte segment
+    // tid % 8: a row's 128 bytes are read by 8 consecutive lanes) and the 8 scale bytes of rows tid (A) and tid (B);
+    // rows past the operand's end re-read its last row.  Byte offsets fit 32 bits (checked by the host).
+    uint32_t oa[8], ob[8], osga, osgb;
     const uint32_t cstride = (uint32_t)(K / 2), sstride = (uint32_t)(K / 32);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        int64_t ga = m0 + (tid >> 2) + 64 * v, gb = n0 + (tid >> 2) + 64 * v;
+    for (int v = 0; v < 8; ++v) {
+        int64_t ga = m0 + (tid >> 3) + 32 * v, gb = n0 + (tid >> 3) + 32 * v;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
-        oa[v] = (uint32_t)ga * cstride + 16u * (tid & 3);
-        ob[v] = (uint32_t)gb * cstride + 16u * (tid & 3);
+        oa[v] = (uint32_t)ga * cstride + 16u * (tid & 7);
+        ob[v] = (uint32_t)gb * cstride + 16u * (tid & 7);
     }
     {
         int64_t ga = m0 + tid, gb = n0 + tid;
@@ -127,100 +133,102 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
         osga = (uint32_t)ga * sstride;
         osgb = (uint32_t)gb * sstride;
     }
-    // Two register sets of staged stages: a stage's loads are issued two stages before its data is written
-    // to LDS (a stage is only ~0.5 us of matrix work, far less than a trip to L2 or HBM under load).
-    // Two register sets: "near" holds the stage that goes to LDS next, "far" the one after.  The stage body is
-    // branch-free (stage indices are clamped, the last stages load and store data nobody uses).
-    uvec4_t ran[4], rbn[4], raf[4], rbf[4];
-    uint32_t rsan, rsbn, rsaf, rsbf;
-    auto load_far = [&](int st) __attribute__((always_inline)) {
+    uvec4_t ra[8], rb[8];
+    uvec2_t rsa, rsb;
+    auto clampst = [&](int st) { return st < niter ? st : niter - 1; };
+    auto load_stage = [&](int st) __attribute__((always_inline)) {
         const uint8_t* ca = A.codes + (size_t)st * (MX_KI / 2);
         const uint8_t* cb = B.codes + (size_t)st * (MX_KI / 2);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            raf[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
-            rbf[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
+        for (int v = 0; v < 8; ++v) {
+            ra[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
+            rb[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
         }
-        rsaf = *reinterpret_cast<const uint32_t*>(A.scales + (size_t)st * (MX_KI / 32) + osga);
-        rsbf = *reinterpret_cast<const uint32_t*>(B.scales + (size_t)st * (MX_KI / 32) + osgb);
+        rsa = *reinterpret_cast<const uvec2_t*>(A.scales + (size_t)st * (MX_KI / 32) + osga);
+        rsb = *reinterpret_cast<const uvec2_t*>(B.scales + (size_t)st * (MX_KI / 32) + osgb);
     };
-    auto far_to_near = [&]() __attribute__((always_inline)) {
+    auto store_stage = [&](uint8_t* buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { ran[v] = raf[v]; rbn[v] = rbf[v]; }
-        rsan = rsaf; rsbn = rsbf;
-    };
-    auto store_near = [&](uint8_t* buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int row = (tid >> 2) + 64 * v, seg = tid & 3;
-            *reinterpret_cast<uvec4_t*>(buf + row * MX_CROW + 16 * seg) = ran[v];
-            *reinterpret_cast<uvec4_t*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rbn[v];
+        for (int v = 0; v < 8; ++v) {
+            const int row = (tid >> 3) + 32 * v, seg = tid & 7;
+            *reinterpret_cast<uvec4_t*>(buf + row * MX_CROW + 16 * seg) = ra[v];
+            *reinterpret_cast<uvec4_t*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rb[v];
         }
-        *reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * MX_SROW) = rsan;
-        *reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * MX_SROW) = rsbn;
+        *reinterpret_cast<uvec2_t*>(buf + OFF_SA + tid * MX_SROW) = rsa;
+        *reinterpret_cast<uvec2_t*>(buf + OFF_SB + tid * MX_SROW) = rsb;
     };
-    auto clampst = [&](int st) { return st < niter ? st : niter - 1; };
 
     // per-lane byte offsets of this wave's fragment rows inside a buffer
     const int oca = (wm + li) * MX_CROW + 16 * half, ocb = OFF_CB + (wn + li) * MX_CROW + 16 * half;
     const int osa = OFF_SA + (wm + li) * MX_SROW, osb = OFF_SB + (wn + li) * MX_SROW;
-    uvec4_t fa[2][TM], fb[2][TN];       // code fragments of the two contraction steps of a stage
-    uint32_t sa[TM], sb[TN];          // the rows' scale words, shifted so that byte 0 / byte 2 are this lane's blocks
+    uvec4_t fa[2][TM], fb[2][TN];     // code fragments, two slots
+    uint32_t sa[2][TM], sb[2][TN];    // the rows' two scale words of the stage, shifted so that byte 0 / byte 2 are this lane's blocks
     auto read_codes = [&](const uint8_t* buf, int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const uvec4_t*>(buf + oca + 32 * i * MX_CROW + 32 * ks);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const uvec4_t*>(buf + ocb + 32 * j * MX_CROW + 32 * ks);
     };
-    auto mma = [&](int slot, auto KS) __attribute__((always_inline)) {
-        constexpr int ks = decltype(KS)::value;
+    auto read_scales = [&](const uint8_t* buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const uvec2_t w = *reinterpret_cast<const uvec2_t*>(buf + osa + 32 * i * MX_SROW);
+            sa[0][i] = w.x >> (8 * half);
+            sa[1][i] = w.y >> (8 * half);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const uvec2_t w = *reinterpret_cast<const uvec2_t*>(buf + osb + 32 * j * MX_SROW);
+            sb[0][j] = w.x >> (8 * half);
+            sb[1][j] = w.y >> (8 * half);
+        }
+    };
+    auto mma = [&](auto KSC) __attribute__((always_inline)) {
+        constexpr int ks = decltype(KSC)::value, slot = ks & 1, word = ks >> 1, sel = 2 * (ks & 1);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int8v_t a = {(int)fa[slot][i].x, (int)fa[slot][i].y, (int)fa[slot][i].z, (int)fa[slot][i].w, 0, 0, 0, 0};
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int8v_t b = {(int)fb[slot][j].x, (int)fb[slot][j].y, (int)fb[slot][j].z, (int)fb[slot][j].w, 0, 0, 0, 0};
-                // formats 4 = FP4 (E2M1) for both operands; the scale byte is byte 2 ks of the shifted word
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 4, 4, 2 * ks, (int)sa[i],
-                                                                             2 * ks, (int)sb[j]);
+                // formats 4 = FP4 (E2M1) for both operands; the scale byte is byte `sel` of the shifted word
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 4, 4, sel, (int)sa[word][i],
+                                                                             sel, (int)sb[word][j]);
             }
         }
     };
 
-    load_far(0);
-    far_to_near();
-    store_near(lds);
+    load_stage(0);
+    store_stage(lds);
     __syncthreads();
-    load_far(clampst(1));
-    far_to_near();
-    load_far(clampst(2));
+    load_stage(clampst(1));
     read_codes(lds, 0, 0);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(lds + osa + 32 * i * MX_SROW) >> (8 * half);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(lds + osb + 32 * j * MX_SROW) >> (8 * half);
+    read_scales(lds);
 
 #pragma unroll 1
     for (int it = 0; it < niter; ++it) {
         const uint8_t* bufc = lds + (it & 1) * BUF;
         uint8_t* bufn = lds + ((it & 1) ^ 1) * BUF;
-        // second step's codes arrive while the first step multiplies; stage it + 1 goes to the other buffer
         read_codes(bufc, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(0, std::integral_constant<int, 0>{});
-        store_near(bufn);
+        mma(std::integral_constant<int, 0>{});
+        store_stage(bufn);                        // stage it + 1 (loaded one stage ago) to the other buffer ...
+        load_stage(clampst(it + 2));              // ... and its registers take stage it + 2
+        __builtin_amdgcn_sched_barrier(0);
+        read_codes(bufc, 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(std::integral_constant<int, 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        read_codes(bufc, 3, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(std::integral_constant<int, 2>{});
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();                          // next stage is in LDS; this stage's codes are all in registers
         read_codes(bufn, 0, 0);
-        far_to_near();                            // stage it + 2 moves up, its registers take stage it + 3
-        load_far(clampst(it + 3));
         __builtin_amdgcn_sched_barrier(0);
-        mma(1, std::integral_constant<int, 1>{});
+        mma(std::integral_constant<int, 3>{});
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) sa[i] = *reinterpret_cast<const uint32_t*>(bufn + osa + 32 * i * MX_SROW) >> (8 * half);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) sb[j] = *reinterpret_cast<const uint32_t*>(bufn + osb + 32 * j * MX_SROW) >> (8 * half);
+        read_scales(bufn);
     }
 
     const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
@@ -284,10 +292,10 @@ extern "C" int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const met
     if (C->dtype != METIS_BF16 && C->dtype != METIS_F32) return METIS_INVALID_ARG;
     if (A->cols != B->cols || C->rows != A->rows || C->cols != B->rows || C->ld < C->cols) return METIS_BAD_SHAPE;
     const int64_t K = A->cols;
-    if (K % MX_KI) return METIS_UNSUPPORTED;                          // whole stages of 128
+    if (K % MX_KI) return METIS_UNSUPPORTED;                          // whole stages of 256
     if (A->rows * (K / 2) > 0xFFFFFFFFll || B->rows * (K / 2) > 0xFFFFFFFFll) return METIS_UNSUPPORTED;   // 32-bit byte offsets
     if (reinterpret_cast<uintptr_t>(A->codes) % 16 || reinterpret_cast<uintptr_t>(B->codes) % 16 ||
-        reinterpret_cast<uintptr_t>(A->scales) % 4 || reinterpret_cast<uintptr_t>(B->scales) % 4)
+        reinterpret_cast<uintptr_t>(A->scales) % 8 || reinterpret_cast<uintptr_t>(B->scales) % 8)
         return METIS_BAD_SHAPE;
     const MxOperand a = {A->codes, A->scales, A->rows}, b = {B->codes, B->scales, B->rows};
     hipStream_t s = (hipStream_t)stream;
