@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_TFLOPS = 2500.0     # MI355X dense fp16/bf16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+PEAK_FP4_TFLOPS = 10100.0     # MI355X dense fp4/fp6 matrix peak
 
 
 def parse():
@@ -214,6 +215,22 @@ def main():
         phases["linear_wgrad_ms"] = timed(lambda: metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin))
     roofline["traffic"] = traffic_from_profile(args.workload)
 
+    # The same product in the MXFP4 variant (block 32, power-of-two scales that the matrix instruction applies itself):
+    # what the chip's FP4 rate gives when no expansion work is needed.  Outside the timed step and outside `value`.
+    mx = None
+    if K % 256 == 0:
+        try:
+            qx, qw = metis.MxTensor(L, K), metis.MxTensor(N, K)
+            Ymx = torch.empty((L, N), dtype=torch.bfloat16, device="cuda")
+            mx_q_ms = timed(lambda: (metis.quantize_mx(X.A, qx), metis.quantize_mx(W.A, qw)))
+            mx_ms = timed(lambda: metis.mxfp4_gemm_nt(qx, qw, Ymx))
+            mx_tf = 2.0 * L * K * N / (mx_ms * 1e-3) / 1e12
+            mx = {"kernel": "k_mxfp4_gemm_nt", "quantize_both_ms": mx_q_ms, "gemm_ms": mx_ms, "achieved": round(mx_tf, 1),
+                  "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": round(mx_tf / PEAK_FP4_TFLOPS, 4)}
+            del qx, qw, Ymx
+        except Exception as e:                                     # an extra figure must never cost the main line
+            mx = {"error": repr(e)[:200]}
+
     # Throughput with several independent steps in flight (different layers or micro-batches of a training
     # job): each slot has its own stream and its own outputs and workspaces, the inputs are shared.  A step's
     # decomposition is a chain of small single-workgroup kernels that leaves the chip idle; steps in other slots
@@ -261,6 +278,7 @@ def main():
                    "L": L, "K": K, "N": N, "k": k, "p": p, "gemms_per_step": n_gemm, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "pipelined": pipelined,
+        "mxfp4_variant": mx,
         "passes": passes,
         "phases": phases,
     }
