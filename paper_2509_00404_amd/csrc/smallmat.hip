@@ -317,10 +317,23 @@ __device__ __forceinline__ void for_each_block(F&& f) {
 // One 16x16 tile of sum_k a(i, k) b(k, j) on the fp64 matrix cores; lane supplies row/column (lane & 15) and the
 // k offset lane >> 4.  fa / fb read in-bounds elements; out-of-range rows, columns and k contribute zero.
 template <class FA, class FB>
-__device__ __forceinline__ double4_t tile_mma(int n, int ia, int jb, int kq, FA fa, FB fb) {
+__device__ __forceinline__ double4_t tile_mma(int n, int ia, int jb, int kq, FA fa, FB fb, bool batch = true) {
     const int ic = min(ia, n - 1), jc = min(jb, n - 1);
     const bool iok = ia < n, jok = jb < n;
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
+    if ((n & 15) == 0 && batch) {                 // whole tiles: no guards, operands of four steps loaded ahead
+        for (int k0 = 0; k0 < n; k0 += 16) {
+            double a[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a[u] = fa(ia, k0 + 4 * u + kq);
+                b[u] = fb(k0 + 4 * u + kq, jb);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[u], acc, 0, 0, 0);
+        }
+        return acc;
+    }
     for (int k0 = 0; k0 < n; k0 += 4) {
         const int k = k0 + kq, kc = min(k, n - 1);
         const double a = fa(ic, kc), b = fb(kc, jc);
@@ -384,13 +397,13 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     if (tid == 0) fail_s = 0;
 
     // Gram of the columns of a column-major matrix M (stride ldm, nc columns of nr rows) into R2 (row-major, lda)
-    auto gram_to_R2 = [&](const double* M, int ldm) {
+    auto gram_to_R2 = [&](const double* M, int ldm, bool batch) {
         for (int t0 = 0; t0 < ntiles; t0 += nwaves) {
             const int tile = min(t0 + wave, ntiles - 1);
             const int ti = tile / T16, tj = tile - ti * T16;
             const int ci = 16 * ti + (lane & 15), cj = 16 * tj + (lane & 15), kq = lane >> 4;
             const double4_t acc = tile_mma(n, ci, cj, kq, [&](int i, int k) { return M[(size_t)i * ldm + k]; },
-                                           [&](int k, int c) { return M[(size_t)c * ldm + k]; });
+                                           [&](int k, int c) { return M[(size_t)c * ldm + k]; }, batch);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * ti + 4 * v + kq;
@@ -400,7 +413,7 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     };
 
     // ---- 1: A = L^T L ----
-    gram_to_R2(R1, ld);
+    gram_to_R2(R1, ld, false);                    // the factor's column stride suits the sweeps, not these reads: no batching
     __syncthreads();
 
     PRE_MARK(1)
@@ -657,7 +670,7 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     int polish_its = 0;
     for (int it = 0; it < 4 && ok; ++it) {
         if (tid == 0) err_s = 0ull;
-        gram_to_R2(R1, lda);                      // E + I = P^T P
+        gram_to_R2(R1, lda, true);                // E + I = P^T P
         __syncthreads();
         double m = 0.0;
         for (int e = tid; e < n * n; e += nthr) {
@@ -1023,8 +1036,11 @@ int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam
     size_t lds = rsize * sizeof(double) + small;
     const size_t lds_pre = 2 * rsize * sizeof(double) + small + (10 * (size_t)n + 44) * sizeof(double);
     if (gscr && n >= 72 && lds_pre <= 160 * 1024) lds = lds_pre; else gscr = nullptr;
-    // one group of jgl lanes per column pair; the Cholesky pre-pass and the bookkeeping use all 512 threads
-    const int threads = ne / 2 * jgl > 512 ? 1024 : 512;
+    // one group of jgl lanes per column pair, in whole waves and at least 512 threads (the Cholesky pre-pass, the
+    // bookkeeping and the preconditioner's 8 lanes per row use them); no idle waves beyond that: every wave of
+    // the workgroup takes part in every barrier
+    const int need = (ne / 2 * jgl + 63) / 64 * 64;
+    const int threads = need > 512 ? need : 512;
     if (ne / 2 * jgl > threads) return METIS_UNSUPPORTED;
 #define JACOBI_CASE(NE, JGL)                                                                                  \
     {                                                                                                         \
