@@ -9,6 +9,7 @@
 #include "dgemm.h"
 #include "dgemm_skinny.h"
 #include "smallmat.h"
+#include "rng_dev.h"
 
 namespace {
 
@@ -53,10 +54,29 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     return L;
 }
 
-__global__ void k_zero_words(uint32_t* __restrict__ p, size_t nwords) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t st = (size_t)gridDim.x * blockDim.x;
-    for (; i < nwords; i += st) p[i] = 0u;
+// Everything the chain needs before its first product, in one launch: blocks [0, zero_blocks) clear the
+// accumulators (a fill kernel, not a memset node, so the call can be graph-captured) and the two optional
+// output words, the next idx_blocks blocks draw the row sample, the rest draw Omega (a null idx / omega means
+// the caller supplied it).
+__global__ void __launch_bounds__(256)
+k_decomp_setup(uint32_t* __restrict__ zero, size_t nwords, uint32_t* __restrict__ amax_out, int32_t* __restrict__ info,
+               int zero_blocks, int idx_blocks, uint64_t seed, int64_t M, int64_t Ms, uint32_t* __restrict__ idx,
+               int64_t omega_count, bf16_t* __restrict__ omega) {
+    const int b = blockIdx.x;
+    if (b < zero_blocks) {
+        size_t i = (size_t)b * 256 + threadIdx.x;
+        const size_t st = (size_t)zero_blocks * 256;
+        for (; i < nwords; i += st) zero[i] = 0u;
+        if (b == 0 && threadIdx.x == 0) {
+            if (amax_out) *amax_out = 0u;
+            if (info) *info = 0;
+        }
+    } else if (b < zero_blocks + idx_blocks) {
+        const int64_t j = (int64_t)(b - zero_blocks) * 256 + threadIdx.x;
+        if (j < Ms) idx[j] = sample_row(seed, M, Ms, j);
+    } else {
+        gaussian_pair(seed, (int64_t)(b - zero_blocks - idx_blocks) * 256 + threadIdx.x, omega_count, omega);
+    }
 }
 
 DOperand op(const void* p, int64_t s_outer, int64_t s_k, const uint32_t* map_outer = nullptr,
@@ -148,22 +168,18 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
     const bf16_t* Ap = (const bf16_t*)A->ptr;
     int st;
 
-    // accumulators start at zero (a fill kernel, not a memset node, so the call can be graph-captured)
-    hipLaunchKernelGGL(k_zero_words, dim3(512), dim3(256), 0, s, (uint32_t*)ws, L.zero_bytes / 4);
-    if (amax_out) hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, (uint32_t*)amax_out, (size_t)1);
-    if (info) hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, (uint32_t*)info, (size_t)1);
-    METIS_LAUNCH_CHECK();
-
-    // draws
-    const uint32_t* idx_use = idx_in;
-    if (!idx_in) {
-        if ((st = metis_sample_rows(stream, seed, M, Ms, idx)) != METIS_OK) return st;
-        idx_use = idx;
-    }
-    const bf16_t* om_use = omega_in;
-    if (!omega_in) {
-        if ((st = metis_gaussian_omega(stream, seed, N, r, omega)) != METIS_OK) return st;
-        om_use = omega;
+    // accumulators start at zero; the draws the caller did not supply
+    const uint32_t* idx_use = idx_in ? idx_in : idx;
+    const bf16_t* om_use = omega_in ? omega_in : omega;
+    {
+        const int zero_blocks = 512, idx_blocks = idx_in ? 0 : (int)ceil_div64(Ms, 256);
+        const int64_t omega_count = N * (int64_t)r;
+        const int64_t omega_blocks = omega_in ? 0 : ceil_div64(ceil_div64(omega_count, 2), 256);
+        if (zero_blocks + idx_blocks + omega_blocks > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+        hipLaunchKernelGGL(k_decomp_setup, dim3((unsigned)(zero_blocks + idx_blocks + omega_blocks)), dim3(256), 0, s,
+                           (uint32_t*)ws, L.zero_bytes / 4, (uint32_t*)amax_out, info, zero_blocks, idx_blocks, seed, M, Ms,
+                           idx_in ? nullptr : idx, omega_count, omega_in ? nullptr : omega);
+        METIS_LAUNCH_CHECK();
     }
 
     const int64_t tiles_zr = ceil_div64(Ms, 32) * ceil_div64(r, 32);
