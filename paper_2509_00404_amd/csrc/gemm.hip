@@ -691,7 +691,7 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         // skinny products: few output tiles, long contraction -> split it over workgroups
         auto splits = [&](int64_t rows, int64_t cols) {
             int64_t tiles = ceil_div64(rows, 128) * ceil_div64(cols, 64), iters = ceil_div64(Kc, G_KI);
-            int64_t want = ceil_div64(512, tiles), maxs = iters / 2 > 0 ? iters / 2 : 1;
+            int64_t want = ceil_div64(256, tiles), maxs = iters / 2 > 0 ? iters / 2 : 1;
             return (int)(want < maxs ? want : maxs);
         };
         const int s1 = kb > 0 ? splits(Ma, kb) : 1, s2 = ka > 0 ? splits(Nb, ka) : 1;
