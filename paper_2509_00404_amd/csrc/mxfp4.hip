@@ -72,13 +72,16 @@ k_quantize_mx(const T* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* co
 }
 
 // ---- GEMM C[M,N] = A[M,K] B[N,K]^T ----
-// 256 x 256 tile, 4 waves of 128 x 128 (4 x 4 accumulator tiles of 32 x 32, one wave per SIMD).  A lane's operand of
+// 256 x 256 tile, 8 waves of 128 x 64 (4 x 2 accumulator tiles of 32 x 32, two waves per SIMD).  A lane's operand of
 // one matrix instruction is the 32 codes (16 bytes) of row lane % 32, contraction half lane / 32, and the E8M0 byte
 // of exactly that block of 32.  With no expansion work the kernel lives on operand delivery:
 //  * a stage is 256 contraction elements = 128 bytes of every row = whole cache lines (with 64-byte stages every
 //    line crossed L2 -> L1 twice, which was the limit), four matrix instructions deep;
 //  * the next stage's global data sits in registers for one stage before it is written to the other LDS buffer;
-//  * fragments are double-buffered in registers: step s+1 is read from LDS while step s multiplies.
+//  * fragments are double-buffered in registers: step s+1 is read from LDS while step s multiplies;
+//  * a wave issues in order and a matrix instruction holds its pipe for 32 cycles, so memory instructions of one
+//    wave leave the pipe idle while they issue: the second wave on the SIMD fills those gaps (four waves of
+//    128 x 128 need fewer LDS bytes per flop but reach 10 % less).
 // The stage body is branch-free (stage indices are clamped; the last stage loads and stores data nobody uses).
 #define MX_KI 256
 #define MX_CROW (MX_KI / 2 + 16)      // padded code row in LDS: 144 bytes, 16-byte reads of 8 consecutive rows hit 8 bank groups
@@ -91,9 +94,9 @@ struct MxOperand {
 };
 
 template <typename OUT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
-    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, KS = MX_KI / 64;
+    constexpr int TM = 4, TN = 2, BM = 256, BN = 256, KS = MX_KI / 64, NV = 4;   // NV: 16-byte code vectors per thread, operand and stage
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int OFF_CB = BM * MX_CROW, OFF_SA = (BM + BN) * MX_CROW, OFF_SB = OFF_SA + BM * MX_SROW,
                   BUF = OFF_SB + BN * MX_SROW;
@@ -101,7 +104,7 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
     int tile_m, tile_n;
     tile_coords(tmap, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+    const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
     const int li = lane & 31, half = lane >> 5;
 
     float16_t acc[TM][TN];
@@ -113,49 +116,48 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const int niter = (int)(K / MX_KI);
-    // this thread's share of a stage: code vectors v = 0..7 of each operand (row tid/8 + 32 v, 16-byte segment
+    // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/8 + 64 v, 16-byte segment
     // tid % 8: a row's 128 bytes are read by 8 consecutive lanes) and the 8 scale bytes of rows tid (A) and tid (B);
     // rows past the operand's end re-read its last row.  Byte offsets fit 32 bits (checked by the host).
-    uint32_t oa[8], ob[8], osga, osgb;
+    uint32_t oa[NV], ob[NV], osga, osgb;
     const uint32_t cstride = (uint32_t)(K / 2), sstride = (uint32_t)(K / 32);
 #pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        int64_t ga = m0 + (tid >> 3) + 32 * v, gb = n0 + (tid >> 3) + 32 * v;
+    for (int v = 0; v < NV; ++v) {
+        int64_t ga = m0 + (tid >> 3) + 64 * v, gb = n0 + (tid >> 3) + 64 * v;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
         oa[v] = (uint32_t)ga * cstride + 16u * (tid & 7);
         ob[v] = (uint32_t)gb * cstride + 16u * (tid & 7);
     }
     {
-        int64_t ga = m0 + tid, gb = n0 + tid;
+        // threads 0..255 carry A's scale rows, threads 256..511 B's
+        int64_t ga = m0 + (tid & 255), gb = n0 + (tid & 255);
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
         osga = (uint32_t)ga * sstride;
         osgb = (uint32_t)gb * sstride;
     }
-    uvec4_t ra[8], rb[8];
-    uvec2_t rsa, rsb;
+    uvec4_t ra[NV], rb[NV];
+    uvec2_t rs;
     auto clampst = [&](int st) { return st < niter ? st : niter - 1; };
     auto load_stage = [&](int st) __attribute__((always_inline)) {
         const uint8_t* ca = A.codes + (size_t)st * (MX_KI / 2);
         const uint8_t* cb = B.codes + (size_t)st * (MX_KI / 2);
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
+        for (int v = 0; v < NV; ++v) {
             ra[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
             rb[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
         }
-        rsa = *reinterpret_cast<const uvec2_t*>(A.scales + (size_t)st * (MX_KI / 32) + osga);
-        rsb = *reinterpret_cast<const uvec2_t*>(B.scales + (size_t)st * (MX_KI / 32) + osgb);
+        rs = *reinterpret_cast<const uvec2_t*>((tid < 256 ? A.scales + osga : B.scales + osgb) + (size_t)st * (MX_KI / 32));
     };
     auto store_stage = [&](uint8_t* buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const int row = (tid >> 3) + 32 * v, seg = tid & 7;
+        for (int v = 0; v < NV; ++v) {
+            const int row = (tid >> 3) + 64 * v, seg = tid & 7;
             *reinterpret_cast<uvec4_t*>(buf + row * MX_CROW + 16 * seg) = ra[v];
             *reinterpret_cast<uvec4_t*>(buf + OFF_CB + row * MX_CROW + 16 * seg) = rb[v];
         }
-        *reinterpret_cast<uvec2_t*>(buf + OFF_SA + tid * MX_SROW) = rsa;
-        *reinterpret_cast<uvec2_t*>(buf + OFF_SB + tid * MX_SROW) = rsb;
+        *reinterpret_cast<uvec2_t*>(buf + OFF_SA + tid * MX_SROW) = rs;          // B's scale rows follow A's
     };
 
     // per-lane byte offsets of this wave's fragment rows inside a buffer
@@ -259,7 +261,7 @@ int launch_mx_gemm(hipStream_t s, const MxOperand& a, const MxOperand& b, int64_
     auto kern = k_mxfp4_gemm_nt<OUT>;
     static LdsLimitCache lds_set;
     if (!ensure_dyn_lds((const void*)kern, MX_LDS, lds_set)) return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(256), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(512), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
