@@ -164,28 +164,90 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
         X[i * ld + j] = 0.0;
     }
     __syncthreads();
+#ifdef JAC_PROF
+    const long long ci0 = clock64();
+#endif
     chol_blocked<false>(L, ld, n, dinv, 0.0, info);
+#ifdef JAC_PROF
+    const long long ci1 = clock64();
+#endif
     if (wellcond_out && tid == 0) {
         double lo = dinv[0], hi = dinv[0];
         for (int j = 1; j < n; ++j) { lo = fmin(lo, dinv[j]); hi = fmax(hi, dinv[j]); }
         *wellcond_out = (hi <= 1e3 * lo) ? 1 : 0;        // a replaced pivot has dinv = 1e150 and fails this
     }
-    // forward substitution: column c of L^-1 by a group of 8 lanes (same wave, so the group's own
-    // LDS writes are visible to it without a workgroup barrier); X[t][c] keeps groups conflict-free
+#ifdef JAC_PROF
+    if (tid == 0) g_prof[38] = clock64() - ci1;
+#endif
+    // L^-1 by 16 x 16 blocks.  The diagonal blocks are inverted by substitution (one thread per column, 16 steps in
+    // registers); then, one block sub-diagonal after the other, X_ij = -X_ii (sum_k L_ik X_kj) on the fp64 matrix
+    // cores, one wave per block.  The inner sum leaves the matrix instruction in exactly the register layout that
+    // the second product wants for its right operand (accumulator element v = contraction chunk v), so it never
+    // touches memory.  Rows and columns past n act as an identity.
     {
-        const int c = tid >> 3, gl = tid & 7;
-        if (c < n) {
-            for (int i = c; i < n; ++i) {
-                double s = 0.0;
-                for (int t = c + gl; t < i; t += 8) s -= L[t * ld + i] * X[t * ld + c];
-                s = chol_group8_sum(s);
-                if (gl == 0) X[i * ld + c] = ((i == c ? 1.0 : 0.0) + s) * dinv[i];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = 1024 >> 6;
+        const int T = (n + 15) / 16;
+        const bool whole = (n & 15) == 0;             // no padding: the accessors need no tests
+        auto Lat = [&](int i, int c2) { return (whole || (i < n && c2 < n)) ? L[min(c2, n - 1) * ld + min(i, n - 1)] : (i == c2 ? 1.0 : 0.0); };
+        auto Xat = [&](int t, int c2) { return (whole || (t < n && c2 < n)) ? X[min(t, n - 1) * ld + min(c2, n - 1)] : (t == c2 ? 1.0 : 0.0); };
+        if (tid < 16 * T) {
+            const int b0 = 16 * (tid >> 4), cc = tid & 15, c = b0 + cc;
+            if (c < n) {
+                double x[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int i = b0 + q;
+                    double v = q == cc ? 1.0 : 0.0;
+#pragma unroll
+                    for (int u = 0; u < q; ++u) v -= Lat(i, b0 + u) * x[u];
+                    x[q] = (q >= cc && i < n) ? v * dinv[i] : 0.0;
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (b0 + q < n) X[(b0 + q) * ld + c] = x[q];
             }
+        }
+        __syncthreads();
+#ifdef JAC_PROF
+        if (tid == 0) g_prof[39] = clock64() - ci1;
+#endif
+        const int r16 = lane & 15, kq = lane >> 4;
+        for (int d = 1; d < T; ++d) {
+            for (int blk0 = 0; blk0 < T - d; blk0 += nwaves) {
+                // block (ib, jb); surplus waves sit the round out (`wave` is a scalar: a uniform branch, and waves that
+                // repeated a block would queue on the same matrix pipes)
+                if (blk0 + wave >= T - d) continue;
+                const int jb = blk0 + wave, ib = jb + d;
+                double4_t P = {0.0, 0.0, 0.0, 0.0};
+                double xa[4];                     // X_ii for the second product, loaded ahead
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc) xa[kc] = Xat(16 * ib + r16, 16 * ib + 4 * kc + kq);
+                for (int k = jb; k < ib; ++k) {
+                    double a[4], b[4];            // the operands of a whole block product before its four instructions
+#pragma unroll
+                    for (int kc = 0; kc < 4; ++kc) {
+                        a[kc] = Lat(16 * ib + r16, 16 * k + 4 * kc + kq);
+                        b[kc] = Xat(16 * k + 4 * kc + kq, 16 * jb + r16);
+                    }
+#pragma unroll
+                    for (int kc = 0; kc < 4; ++kc) P = __builtin_amdgcn_mfma_f64_16x16x4f64(a[kc], b[kc], P, 0, 0, 0);
+                }
+                double4_t R = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc) R = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[kc], P[kc], R, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int i = 16 * ib + 4 * v + kq, c2 = 16 * jb + r16;
+                    if (i < n && c2 < n) X[i * ld + c2] = -R[v];
+                }
+            }
+            __syncthreads();
         }
     }
     __syncthreads();
+#ifdef JAC_PROF
+    if (tid == 0) { g_prof[36] = ci1 - ci0; g_prof[37] = clock64() - ci1; }
+#endif
     for (int e = tid; e < n * n; e += 1024) {
         int i = e / n, j = e - i * n;
         Linv[e] = X[i * ld + j];
@@ -399,7 +461,8 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     // Gram of the columns of a column-major matrix M (stride ldm, nc columns of nr rows) into R2 (row-major, lda)
     auto gram_to_R2 = [&](const double* M, int ldm, bool batch) {
         for (int t0 = 0; t0 < ntiles; t0 += nwaves) {
-            const int tile = min(t0 + wave, ntiles - 1);
+            if (t0 + wave >= ntiles) continue;    // `wave` is a scalar: a uniform branch; a repeated tile would queue on the same matrix pipe
+            const int tile = t0 + wave;
             const int ti = tile / T16, tj = tile - ti * T16;
             const int ci = 16 * ti + (lane & 15), cj = 16 * tj + (lane & 15), kq = lane >> 4;
             const double4_t acc = tile_mma(n, ci, cj, kq, [&](int i, int k) { return M[(size_t)i * ldm + k]; },
@@ -407,7 +470,7 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * ti + 4 * v + kq;
-                if (t0 + wave < ntiles && i < n && cj < n) R2[(size_t)i * lda + cj] = acc[v];
+                if (i < n && cj < n) R2[(size_t)i * lda + cj] = acc[v];
             }
         }
     };
@@ -692,7 +755,8 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         double4_t acc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int tile = min(wave + t * nwaves, ntiles - 1);
+            const int tile = wave + t * nwaves;
+            if (tile >= ntiles) continue;
             const int ti = tile / T16, tj = tile - ti * T16;
             const int ia = 16 * ti + (lane & 15), jb = 16 * tj + (lane & 15), kq = lane >> 4;
             acc[t] = tile_mma(n, ia, jb, kq, [&](int i, int k) { return R1[(size_t)k * lda + i]; },
@@ -723,7 +787,8 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     __syncthreads();
     if (ok) {
         for (int t0 = 0; t0 < ntiles; t0 += nwaves) {
-            const int tile = min(t0 + wave, ntiles - 1);
+            if (t0 + wave >= ntiles) continue;
+            const int tile = t0 + wave;
             const int ti = tile / T16, tj = tile - ti * T16;
             const int ia = 16 * ti + (lane & 15), jb = 16 * tj + (lane & 15), kq = lane >> 4;
             const double4_t a4 = tile_mma(n, ia, jb, kq, [&](int i, int k) { return gscr[(size_t)k * ld + i]; },   // L[i][k]
@@ -731,7 +796,7 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * ti + 4 * v + kq;
-                if (t0 + wave < ntiles && i < n && jb < n) R2[(size_t)jb * ld + i] = a4[v];
+                if (i < n && jb < n) R2[(size_t)jb * ld + i] = a4[v];
             }
         }
     }
