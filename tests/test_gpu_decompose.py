@@ -80,7 +80,9 @@ def test_config1_tiny_planted(metis, explicit):
 @pytest.mark.parametrize("M,N,k,p,rho", [(200, 96, 12, 4, 0.5), (333, 264, 5, 3, 0.1), (1000, 520, 33, 7, 0.25),
                                          (96, 1024, 16, 16, 1.0),
                                          (256, 136, 10, 3, 0.5),        # k+p not a multiple of 8: generic fp64 GEMM path
-                                         (640, 256, 24, 8, 1.0)])
+                                         (640, 256, 24, 8, 1.0),
+                                         # reduced orders 72..79 take the preconditioned eigensolver with ragged tiles
+                                         (512, 384, 60, 15, 0.5), (768, 320, 64, 8, 1.0), (600, 296, 66, 11, 0.5)])
 def test_ragged_shapes(metis, M, N, k, p, rho):
     q = min(M, N)
     s = 50.0 * np.arange(1, q + 1) ** -1.3 + 0.02
