@@ -8,12 +8,13 @@
 // ---------------------------------------------------------------------------------------
 // Blocked Cholesky in LDS, shared by both kernels below.  On entry W holds the lower triangle of a
 // symmetric matrix column-major (element (i, c), i >= c, at W[c*ld + i]); on exit the same places
-// hold L, and rinv[c] = 1 / L[c][c].  Blocks of 4 columns, two workgroup barriers per block:
-//   1  one thread per row at or below the block reads the 4x4 diagonal block (LDS broadcast), factors
+// hold L, and rinv[c] = 1 / L[c][c].  Blocks of CB = 4 columns, two workgroup barriers per block:
+//   1  one thread per row at or below the block reads the CB x CB diagonal block (LDS broadcast), factors
 //      it on its own (every thread repeats the same ~30 operations: cheaper than a barrier and a round
-//      trip through LDS) and solves its row's four entries against it,
-//   2  the trailing matrix takes the rank-4 update on the fp64 matrix cores: one
-//      v_mfma_f64_16x16x4_f64 per 16x16 tile, the block width being exactly the instruction's depth.
+//      trip through LDS) and solves its row's CB entries against it (the chain of dependent pivots is what a
+//      block costs, and it grows faster than the block: CB = 8 measured slower than 4),
+//   2  the trailing matrix takes the rank-CB update on the fp64 matrix cores: CB / 4
+//      v_mfma_f64_16x16x4_f64 per 16x16 tile.
 // BAD_PIVOT_ZEROES: a pivot <= floor zeroes its column (semi-definite input, eigensolver); otherwise it is
 // replaced by 1e-300 and its 1-based index is written to *info (CholeskyQR2's rank check).
 // ---------------------------------------------------------------------------------------
@@ -29,7 +30,7 @@ __device__ __forceinline__ double chol_rsqrt(double x) {
     return y;
 }
 
-template <bool BAD_PIVOT_ZEROES>
+template <bool BAD_PIVOT_ZEROES, int CB = 4>
 __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __restrict__ rinv, double floor_,
                              int32_t* __restrict__ info) {
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63;
@@ -40,19 +41,20 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
 #else
 #define CH_MARK(acc)
 #endif
-    for (int k0 = 0; k0 < n; k0 += 4) {
+    static_assert(CB % 4 == 0, "the trailing update takes the block in chunks of the matrix instruction's depth");
+    for (int k0 = 0; k0 < n; k0 += CB) {
         // ---- 1: diagonal block (entries past n act as an identity block) and the rows below ----
-        double d[4][4];                                  // lower triangle of the diagonal block
-        double r[4];
+        double d[CB][CB];                                // lower triangle of the diagonal block
+        double r[CB];
         if (tid < n - k0) {
             const int i = k0 + tid;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < CB; ++q)
 #pragma unroll
                 for (int c = 0; c <= q; ++c)
                     d[q][c] = (k0 + q < n) ? W[(size_t)(k0 + c) * ld + k0 + q] : (q == c ? 1.0 : 0.0);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
+            for (int c = 0; c < CB; ++c) {
                 double piv = d[c][c];
 #pragma unroll
                 for (int t = 0; t < c; ++t) piv -= d[c][t] * d[c][t];
@@ -67,32 +69,32 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
                 }
                 d[c][c] = piv * r[c];                    // sqrt(pivot), or 0 for a zeroed column
 #pragma unroll
-                for (int q = c + 1; q < 4; ++q) {
+                for (int q = c + 1; q < CB; ++q) {
                     double v = d[q][c];
 #pragma unroll
                     for (int t = 0; t < c; ++t) v -= d[q][t] * d[c][t];
                     d[q][c] = v * r[c];
                 }
             }
-            if (tid >= 4) {
-                double x[4];
+            if (tid >= CB) {
+                double x[CB];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
+                for (int c = 0; c < CB; ++c) {
                     double v = W[(size_t)(k0 + c) * ld + i];
 #pragma unroll
                     for (int t = 0; t < c; ++t) v -= x[t] * d[c][t];
                     x[c] = v * r[c];
                 }
 #pragma unroll
-                for (int c = 0; c < 4; ++c) W[(size_t)(k0 + c) * ld + i] = x[c];
+                for (int c = 0; c < CB; ++c) W[(size_t)(k0 + c) * ld + i] = x[c];
             }
         }
         __syncthreads();
         // the block's own rows are written once every thread has read the unfactored block; nothing
         // reads them again before the next barrier
-        if (tid < 4 && tid < n - k0) {
+        if (tid < CB && tid < n - k0) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < CB; ++q)
                 if (tid == q) {
                     rinv[k0 + q] = r[q];
 #pragma unroll
@@ -100,31 +102,39 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
                 }
         }
         CH_MARK(ca)
-        if (n - k0 <= 4) break;
-        // ---- 2: trailing update A22 -= L21 L21^T over the 16-aligned lower tiles that reach past k0 + 4 ----
-        const int t0 = (k0 + 4) & ~15;
+        if (n - k0 <= CB) break;
+        // ---- 2: trailing update A22 -= L21 L21^T over the 16-aligned lower tiles that reach past k0 + CB ----
+        const int t0 = (k0 + CB) & ~15;
         const int T = (n - t0 + 15) / 16, ntiles = T * (T + 1) / 2;
         for (int tile = wave; tile < ntiles; tile += nwaves) {
             int ti = 0, rem = tile;
             while (rem > ti) { rem -= ti + 1; ++ti; }       // tile -> (ti, tc), tc <= ti
             const int i0 = t0 + 16 * ti, c0 = t0 + 16 * rem;
             const int ia = i0 + (lane & 15), cb = c0 + (lane & 15);
-            const size_t col = (size_t)(k0 + (lane >> 4)) * ld;
-            const double av = (ia < n && ia >= k0 + 4) ? W[col + ia] : 0.0;
-            const double bv = (cb < n && cb >= k0 + 4) ? W[col + cb] : 0.0;
+            double av[CB / 4], bv[CB / 4];
+#pragma unroll
+            for (int kc = 0; kc < CB / 4; ++kc) {
+                const size_t col = (size_t)(k0 + 4 * kc + (lane >> 4)) * ld;
+                av[kc] = (ia < n && ia >= k0 + CB) ? W[col + ia] : 0.0;
+                bv[kc] = (cb < n && cb >= k0 + CB) ? W[col + cb] : 0.0;
+            }
             double4_t acc = {0.0, 0.0, 0.0, 0.0};
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+#pragma unroll
+            for (int kc = 0; kc < CB / 4; ++kc) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av[kc], bv[kc], acc, 0, 0, 0);
             // D: lane l, element v -> (row 4 v + l / 16, column l % 16) of the tile
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = i0 + 4 * v + (lane >> 4), c = cb;
-                if (i < n && c < n && c >= k0 + 4 && i >= c) W[(size_t)c * ld + i] -= acc[v];
+                if (i < n && c < n && c >= k0 + CB && i >= c) W[(size_t)c * ld + i] -= acc[v];
             }
         }
         __syncthreads();
         CH_MARK(cc)
     }
     __syncthreads();                                     // the last block's rows are visible to the caller
+#ifdef JAC_PROF
+    if (tid == 0) { g_prof[14] = ca; g_prof[15] = cc; }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------
