@@ -16,10 +16,12 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 #define BC_NC 64                  // contraction elements per stage
 #define BC_LDB (BC_NC + 8)        // padded LDS row (bf16 elements): 144 B keeps b128 accesses conflict-free
 #define BC_KS (BC_NC / 16)        // MFMA steps per stage
-#define BC_DEPTH 3                // stages of A and V0 kept in flight in registers
+
+// native vector (a HIP uint4 is a struct: arrays of it, and selects between two of them, end up in scratch)
+typedef uint32_t uvec4_t __attribute__((ext_vector_type(4)));
 
 union Frag {
-    uint4 u;
+    uvec4_t u;
     bf16x8_t v;
 };
 
@@ -39,7 +41,9 @@ __global__ void __launch_bounds__(64 * BC_WAVES)
 k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, const bf16_t* __restrict__ V0hi,
             const bf16_t* __restrict__ V0lo, int k, float* __restrict__ Cpart, uint32_t* __restrict__ amax_bits) {
     constexpr int NT = 64 * BC_WAVES;
-    constexpr int BVEC = (2 * 32 * KT * (BC_NC / 8) + NT - 1) / NT;          // 16-byte V0 vectors per thread
+    constexpr int BVEC = 2 * 32 * KT * (BC_NC / 8) / NT;                     // 16-byte V0 vectors per thread
+    static_assert(BVEC * NT == 2 * 32 * KT * (BC_NC / 8), "a V0 stage is a whole number of vectors per thread");
+    constexpr int BC_DEPTH = KT <= 2 ? 3 : 2;                                // stages of A and V0 kept in flight in registers
     __shared__ __attribute__((aligned(16))) bf16_t Bs[2][2][32 * KT][BC_LDB];  // [buffer][hi/lo][column][n]
     __shared__ __attribute__((aligned(16))) bf16_t As[BC_WAVES][32][BC_LDB];   // per-wave slice of A
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -66,12 +70,21 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
         aok[q] = r < M;
         aptr[q] = A + (aok[q] ? r : M - 1) * lda + 8 * piece;
     }
-    auto load_a = [&](int64_t n0, uint4 (&a)[4]) {
+    const int64_t nst = nbeg < N ? (N - nbeg + nstride - 1) / nstride : 0;     // stages of this workgroup
+    // Every load is unconditional, so that the compiler can count the loads in flight and wait for
+    // exactly the stage it needs: a lane with nothing to read (row or column past the end, stage past
+    // the last) loads the first 16 bytes of the array instead, and its value becomes zero on the way
+    // into LDS.
+    const uvec4_t zero4 = {0u, 0u, 0u, 0u};
+    auto a_valid = [&](int64_t i) { return i < nst && nbeg + i * nstride + 8 * piece < N; };
+    auto load_a = [&](int64_t i, uvec4_t (&a)[4]) {
+        const bool in = a_valid(i);
+        const int64_t n0 = nbeg + i * nstride;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            a[q] = (aok[q] && n0 + 8 * piece < N) ? *reinterpret_cast<const uint4*>(aptr[q] + n0) : make_uint4(0, 0, 0, 0);
+        for (int q = 0; q < 4; ++q) a[q] = *reinterpret_cast<const uvec4_t*>((in && aok[q]) ? aptr[q] + n0 : A);
     };
-    auto load_b = [&](int64_t n0, uint4 (&b)[BVEC]) {
+    auto load_b = [&](int64_t i, uvec4_t (&b)[BVEC]) {
+        const int64_t n0 = nbeg + i * nstride;
 #pragma unroll
         for (int v = 0; v < BVEC; ++v) {
             int e = tid + NT * v;
@@ -79,73 +92,89 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
             int r = e % (32 * KT * (BC_NC / 8));
             int c = r / (BC_NC / 8), seg = r % (BC_NC / 8);
             int64_t n = n0 + seg * 8;
-            b[v] = make_uint4(0, 0, 0, 0);
-            if (part < 2 && c < k && n < N)
-                b[v] = *reinterpret_cast<const uint4*>((part ? V0lo : V0hi) + (int64_t)c * N + n);
+            const bool ok = c < k && i < nst && n < N;
+            b[v] = *reinterpret_cast<const uvec4_t*>(ok ? (part ? V0lo : V0hi) + (int64_t)c * N + n : V0hi);
         }
     };
-    auto store_b = [&](int buf, const uint4 (&b)[BVEC]) {
+    auto store_b = [&](int buf, const uvec4_t (&b)[BVEC], int64_t i) {
+        const int64_t n0 = nbeg + i * nstride;
 #pragma unroll
         for (int v = 0; v < BVEC; ++v) {
             int e = tid + NT * v;
             int part = e / (32 * KT * (BC_NC / 8));
             int r = e % (32 * KT * (BC_NC / 8));
             int c = r / (BC_NC / 8), seg = r % (BC_NC / 8);
-            if (part < 2) *reinterpret_cast<uint4*>(&Bs[buf][part][c][seg * 8]) = b[v];
+            const bool ok = c < k && i < nst && n0 + seg * 8 < N;
+            *reinterpret_cast<uvec4_t*>(&Bs[buf][part][c][seg * 8]) = ok ? b[v] : zero4;
         }
     };
-    auto store_a = [&](const uint4 (&a)[4]) {
+    auto store_a = [&](const uvec4_t (&a)[4], int64_t i) {
+        const bool in = a_valid(i);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            *reinterpret_cast<uint4*>(&As[wave][8 * q + lrow][8 * piece]) = a[q];
+            const uvec4_t x = (in && aok[q]) ? a[q] : zero4;
+            *reinterpret_cast<uvec4_t*>(&As[wave][8 * q + lrow][8 * piece]) = x;
             // |x| as 15-bit patterns, compared as unsigned 16-bit integers
-            amax2 = pk_umax16(amax2, pk_umax16(a[q].x & 0x7FFF7FFFu, a[q].y & 0x7FFF7FFFu));
-            amax2 = pk_umax16(amax2, pk_umax16(a[q].z & 0x7FFF7FFFu, a[q].w & 0x7FFF7FFFu));
+            amax2 = pk_umax16(amax2, pk_umax16(x.x & 0x7FFF7FFFu, x.y & 0x7FFF7FFFu));
+            amax2 = pk_umax16(amax2, pk_umax16(x.z & 0x7FFF7FFFu, x.w & 0x7FFF7FFFu));
         }
+    };
+    int buf = 0;
+    // one stage: multiply what is in LDS, then move the next stage from its registers into LDS
+    auto multiply = [&]() {
+#pragma unroll
+        for (int s = 0; s < BC_KS; ++s) {
+            Frag a;
+            a.u = *reinterpret_cast<const uvec4_t*>(&As[wave][li][16 * s + 8 * half]);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                Frag bh, bl;
+                bh.u = *reinterpret_cast<const uvec4_t*>(&Bs[buf][0][32 * t + li][16 * s + 8 * half]);
+                bl.u = *reinterpret_cast<const uvec4_t*>(&Bs[buf][1][32 * t + li][16 * s + 8 * half]);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bh.v, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bl.v, acc[t], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     };
 
     // Register ring: the loads of stages i+1 .. i+BC_DEPTH are in flight while stage i is multiplied.
-    uint4 ra[BC_DEPTH][4], rb[BC_DEPTH][BVEC];
-    const int64_t nst = nbeg < N ? (N - nbeg + nstride - 1) / nstride : 0;     // stages of this workgroup
+    uvec4_t ra[BC_DEPTH][4], rb[BC_DEPTH][BVEC];
 #pragma unroll
     for (int j = 0; j < BC_DEPTH; ++j) {
-        load_a(nbeg + j * nstride, ra[j]);       // out-of-range stages load zeros
-        load_b(nbeg + j * nstride, rb[j]);
+        load_a(j, ra[j]);
+        load_b(j, rb[j]);
     }
-    store_a(ra[0]);
-    store_b(0, rb[0]);
+    store_a(ra[0], 0);
+    store_b(0, rb[0], 0);
     __syncthreads();
-    int buf = 0;
-    for (int64_t base = 0; base < nst; base += BC_DEPTH) {
+    // whole groups of BC_DEPTH stages, branch-free (a stage past the last is stored as zeros and never used)
+    int64_t base = 0;
+    for (; base + BC_DEPTH <= nst; base += BC_DEPTH) {
 #pragma unroll
         for (int j = 0; j < BC_DEPTH; ++j) {
             const int64_t i = base + j;
-            if (i < nst) {
-                // slot j held stage i (now in LDS): refill it with stage i + BC_DEPTH
-                load_a(nbeg + (i + BC_DEPTH) * nstride, ra[j]);
-                load_b(nbeg + (i + BC_DEPTH) * nstride, rb[j]);
+            // slot j held stage i (now in LDS): refill it with stage i + BC_DEPTH
+            load_a(i + BC_DEPTH, ra[j]);
+            load_b(i + BC_DEPTH, rb[j]);
+            multiply();
+            store_a(ra[(j + 1) % BC_DEPTH], i + 1);
+            store_b(buf ^ 1, rb[(j + 1) % BC_DEPTH], i + 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    // the last nst % BC_DEPTH stages: everything they need is already in registers or in LDS
 #pragma unroll
-                for (int s = 0; s < BC_KS; ++s) {
-                    Frag a;
-                    a.u = *reinterpret_cast<const uint4*>(&As[wave][li][16 * s + 8 * half]);
-#pragma unroll
-                    for (int t = 0; t < KT; ++t) {
-                        Frag bh, bl;
-                        bh.u = *reinterpret_cast<const uint4*>(&Bs[buf][0][32 * t + li][16 * s + 8 * half]);
-                        bl.u = *reinterpret_cast<const uint4*>(&Bs[buf][1][32 * t + li][16 * s + 8 * half]);
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bh.v, acc[t], 0, 0, 0);
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bl.v, acc[t], 0, 0, 0);
-                    }
-                }
-                if (i + 1 < nst) {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    store_a(ra[(j + 1) % BC_DEPTH]);
-                    store_b(buf ^ 1, rb[(j + 1) % BC_DEPTH]);
-                }
-                __syncthreads();
-                buf ^= 1;
-            }
+    for (int j = 0; j < BC_DEPTH - 1; ++j) {
+        const int64_t i = base + j;
+        if (i < nst) {
+            multiply();
+            store_a(ra[j + 1], i + 1);
+            store_b(buf ^ 1, rb[j + 1], i + 1);
+            __syncthreads();
+            buf ^= 1;
         }
     }
     // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32.
@@ -160,14 +189,24 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
             if (r < M && c < k) P[r * k + c] = acc[t][v];
         }
     }
-    if (amax_bits) {
+    if (amax_bits) {                          // kernel argument: the branch is uniform
         uint32_t m = (amax2 & 0xFFFFu) > (amax2 >> 16) ? (amax2 & 0xFFFFu) : (amax2 >> 16);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             uint32_t other = __shfl_xor(m, o);
             m = other > m ? other : m;
         }
-        if (lane == 0) atomicMax(amax_bits, m << 16);     // fp32 bit pattern of the bf16 magnitude
+        // One atomic per workgroup at most, and none when the stored maximum already covers it: thousands
+        // of atomics on one address at the end of the kernel take longer than the whole pass over A.
+        __shared__ uint32_t wmax[BC_WAVES];
+        if (lane == 0) wmax[wave] = m;
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 1; w < BC_WAVES; ++w) m = wmax[w] > m ? wmax[w] : m;
+            const uint32_t bits = m << 16;        // fp32 bit pattern of the bf16 magnitude
+            if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, bits);
+        }
     }
 }
 

@@ -43,6 +43,22 @@ __global__ void k_split_factors(const float* __restrict__ U, const float* __rest
     *lo = f32_to_bf16_rne(x - bf16_to_f32(h));
 }
 
+// 16 bytes of codes (two neighbouring blocks) to an 8-byte aligned address in one store
+typedef uint32_t uvec4_a8 __attribute__((ext_vector_type(4), aligned(8)));
+__device__ __forceinline__ void store_codes16(uint8_t* p, uint2 c0, uint2 c1) {
+    uvec4_a8 v = {c0.x, c0.y, c1.x, c1.y};
+    *reinterpret_cast<uvec4_a8*>(p) = v;
+}
+// the scale bytes of two neighbouring blocks: one 16-bit store where the address allows it
+__device__ __forceinline__ void store_scale_pair(uint8_t* p, uint32_t s0, uint32_t s1) {
+    if ((reinterpret_cast<uintptr_t>(p) & 1) == 0) {
+        *reinterpret_cast<uint16_t*>(p) = (uint16_t)((s0 & 0xFFu) | ((s1 & 0xFFu) << 8));
+    } else {
+        p[0] = (uint8_t)s0;
+        p[1] = (uint8_t)s1;
+    }
+}
+
 #define RQ_ROWS 128              // rows per workgroup (4 waves x 32)
 #define RQ_COLS 64               // columns per step
 #define RQ_LDR 68                // padded fp32 row of the per-wave residual tile (16-byte aligned rows)
@@ -182,6 +198,8 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         __builtin_amdgcn_wave_barrier();
         {
             const int64_t m = wr0 + li;
+            uint2 cc[2] = {make_uint2(0, 0), make_uint2(0, 0)};
+            uint32_t ss[2] = {0, 0};
 #pragma unroll
             for (int bb = 0; bb < 2; ++bb) {
                 const int blk = 2 * half + bb;
@@ -195,12 +213,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 }
                 if (m < M && n < cend) {
                     if (codes) {
-                        uint2 c;
                         // stochastic rounding draws: stream 3, word = row-major position in R
-                        uint32_t sc = SR ? quantize_block16_sr(x, qp, c, seed, 3u, (uint64_t)(m * N + n))
-                                         : quantize_block16(x, qp, c);
-                        *reinterpret_cast<uint2*>(codes + m * (N / 2) + n / 2) = c;
-                        scales[m * (N / 16) + n / 16] = (uint8_t)sc;
+                        ss[bb] = SR ? quantize_block16_sr(x, qp, cc[bb], seed, 3u, (uint64_t)(m * N + n))
+                                    : quantize_block16(x, qp, cc[bb]);
                     }
                     if (R_debug) {
                         float4* dst = reinterpret_cast<float4*>(R_debug + m * N + n);
@@ -209,9 +224,25 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                     }
                 }
             }
+            // the lane's two blocks are neighbours in the row: one 16-byte and one 2-byte store (scattered
+            // narrow stores, not the bytes, are what this kernel's output costs)
+            const int64_t na = n0 + 32 * half;
+            if (codes && m < M && na < cend) {
+                uint8_t* cp = codes + m * (N / 2) + na / 2;
+                uint8_t* sp = scales + m * (N / 16) + na / 16;
+                if (na + 16 < cend) {
+                    store_codes16(cp, cc[0], cc[1]);
+                    store_scale_pair(sp, ss[0], ss[1]);
+                } else {
+                    *reinterpret_cast<uint2*>(cp) = cc[0];
+                    sp[0] = (uint8_t)ss[0];
+                }
+            }
         }
         // ---- blocks along the rows (transposed output): half-wave swap, then in-lane ----
         if (codes_t) {
+            uint2 ct[2] = {make_uint2(0, 0), make_uint2(0, 0)};
+            uint32_t st[2] = {0, 0};
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 float x[16];
@@ -225,12 +256,26 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 }
                 const int64_t n = n0 + 32 * t + li, m = wr0 + 16 * half;
                 if (n < cend && m < M) {
-                    uint2 c;
                     // transposed copy: stream 4, word = row-major position in R^T
-                    uint32_t sc = SR ? quantize_block16_sr(x, qp, c, seed, 4u, (uint64_t)(n * M + m))
-                                     : quantize_block16(x, qp, c);
-                    *reinterpret_cast<uint2*>(codes_t + n * (M / 2) + m / 2) = c;
-                    scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
+                    st[t] = SR ? quantize_block16_sr(x, qp, ct[t], seed, 4u, (uint64_t)(n * M + m))
+                               : quantize_block16(x, qp, ct[t]);
+                }
+            }
+            // second swap: the lower lanes end up with both 16-row blocks of column li of tile 0, the upper
+            // lanes with those of tile 1 (element 0 = rows 0-15, element 1 = rows 16-31), 16 bytes in a row
+            auto sx = __builtin_amdgcn_permlane32_swap(ct[0].x, ct[1].x, false, false);
+            auto sy = __builtin_amdgcn_permlane32_swap(ct[0].y, ct[1].y, false, false);
+            auto sq = __builtin_amdgcn_permlane32_swap(st[0], st[1], false, false);
+            const int64_t n = n0 + 32 * half + li;
+            if (n < cend && wr0 < M) {
+                uint8_t* cp = codes_t + n * (M / 2) + wr0 / 2;
+                uint8_t* sp = scales_t + n * (M / 16) + wr0 / 16;
+                if (wr0 + 16 < M) {
+                    store_codes16(cp, make_uint2(sx[0], sy[0]), make_uint2(sx[1], sy[1]));
+                    store_scale_pair(sp, sq[0], sq[1]);
+                } else {
+                    *reinterpret_cast<uint2*>(cp) = make_uint2(sx[0], sy[0]);
+                    sp[0] = (uint8_t)sq[0];
                 }
             }
         }
