@@ -45,12 +45,14 @@ __device__ __forceinline__ float recip_rn(float step) {
 
 // y = fl32(x / step), correctly rounded, from r = fl32(1/step): one product, the exact remainder by
 // fma, one correction (Markstein: correct unless the divisor's significand is all ones; a step has
-// at most 4 significant bits).  Keeps the sign of x for zeros and for r = 0.
+// at most 4 significant bits).  Keeps the sign of x for zeros and for r = 0 without a separate sign
+// copy: the remainder is taken as d = q step - x, which is +0 whenever it vanishes (round to nearest
+// gives +0 for every exact cancellation, and for x = -+0 the two terms are zeros of opposite sign),
+// so the correction term d (-r) is -0 there and q - 0 keeps the sign q took from x.
 __device__ __forceinline__ float quot_rn(float x, float step, float r) {
     float q = x * r;
-    float e = __builtin_fmaf(-q, step, x);
-    // (+0) + (-0) rounds to +0: restore the sign of x, which the IEEE quotient carries
-    return __builtin_copysignf(__builtin_fmaf(e, r, q), x);
+    float d = __builtin_fmaf(q, step, -x);
+    return __builtin_fmaf(d, -r, q);
 }
 
 // Quantize 16 values; returns the scale byte, writes 8 code bytes (low nibble = even element).

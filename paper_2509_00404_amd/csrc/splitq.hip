@@ -5,6 +5,7 @@
 // parts (hi*hi + hi*lo + lo*hi, ~2^-16 relative), fp32 accumulation; A is streamed once and
 // the fp32 residual tile is quantized along both axes before it leaves the workgroup.
 #include "quant_dev.h"
+#include <type_traits>
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -63,24 +64,33 @@ __device__ __forceinline__ void store_scale_pair(uint8_t* p, uint32_t s0, uint32
 #define RQ_COLS 64               // columns per step
 #define RQ_LDR 68                // padded fp32 row of the per-wave residual tile (16-byte aligned rows)
 
+typedef uint32_t uvec4_t __attribute__((ext_vector_type(4)));   // native vector: selects and arrays stay in registers
+
 // Residual + quantize.  One workgroup = 4 waves = 128 rows x a run of 64-column steps.
 // Per step and wave: R[32 x 64] = A + (-U S) V^T entirely on the matrix cores (A enters through an
 // identity operand, so the bf16 values are added exactly into the fp32 accumulators); the
 // -U S fragments of the wave's rows stay in registers for the whole run, V is staged through
-// double-buffered LDS, A for the next step is in flight while the current one is processed.
-// Blocks along the rows of A (transposed output) are quantized straight from the accumulators
+// LDS, A and V for the next step are in flight while the current one is processed.
+// Blocks along the rows of A (transposed output, WT) are quantized straight from the accumulators
 // after a half-wave swap; blocks along the columns go through a per-wave LDS tile.
+// Every global load is unconditional (a lane with nothing to read loads the first 16 bytes of the
+// array and its value is replaced by zero on the way into LDS).  A workgroup whose rows and steps
+// are all whole runs a step body without any branch around its loads and stores: the compiler can
+// then count them and wait for the loads of the next step only, not for this step's stores, whose
+// round trip would otherwise stall every step.
 // grid: (ceil(M/128), csplit); block 256.  KS = kp / 16.
-template <int KS, bool SR>
-__global__ void __launch_bounds__(256)
+template <int KS, bool SR, bool WT>
+__global__ void __launch_bounds__(256, KS <= 4 ? 2 : 1)
 k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, int64_t cchunk,
                  const bf16_t* __restrict__ us_hi, const bf16_t* __restrict__ us_lo,
                  const bf16_t* __restrict__ v_hi, const bf16_t* __restrict__ v_lo, QuantParams qp,
                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint8_t* __restrict__ codes_t,
                  uint8_t* __restrict__ scales_t, float* __restrict__ R_debug, uint64_t seed) {
     constexpr int KP = 16 * KS, LDV = KP + 8;
-    constexpr int VVEC = (2 * RQ_COLS * (KP / 8) + 255) / 256;                  // 16-byte V vectors per thread
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][2][RQ_COLS][LDV];      // [buffer][hi/lo][column][k]
+    constexpr int VVEC = 2 * RQ_COLS * (KP / 8) / 256;                          // 16-byte V vectors per thread
+    static_assert(VVEC * 256 == 2 * RQ_COLS * (KP / 8), "a V stage is a whole number of vectors per thread");
+    // one V stage (hi and lo): a second buffer saves a barrier per step but measured slower
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][RQ_COLS][LDV];         // [hi/lo][column][k]
     __shared__ __attribute__((aligned(16))) float Rt[4][32][RQ_LDR];           // per-wave residual tile
     // per-wave bf16 slice of A, overlaid on the wave's residual tile: it is consumed (operand reads)
     // before the tile is written and refilled after the tile has been read
@@ -120,67 +130,72 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         int64_t r = wr0 + 8 * q + lrow;
         aptr[q] = A + (r < M ? r : M - 1) * lda + 8 * piece;
     }
-    auto load_a = [&](int64_t n0, uint4 (&a)[4]) {
+    const uvec4_t zero4 = {0u, 0u, 0u, 0u};
+    ASlice& aslice = *reinterpret_cast<ASlice*>(&Rt[wave][0][0]);
+    // `live` = the step exists; columns at or past cend read nothing
+    auto load_a = [&](int64_t n0, bool live, uvec4_t (&a)[4]) {
+        const bool in = live && n0 + 8 * piece < cend;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            a[q] = n0 + 8 * piece < cend ? *reinterpret_cast<const uint4*>(aptr[q] + n0) : make_uint4(0, 0, 0, 0);
+        for (int q = 0; q < 4; ++q) a[q] = *reinterpret_cast<const uvec4_t*>(in ? aptr[q] + n0 : A);
     };
-    auto store_a = [&](const uint4 (&a)[4]) {
+    auto store_a = [&](const uvec4_t (&a)[4], int64_t n0, bool live, bool whole) {
+        const bool in = whole || (live && n0 + 8 * piece < cend);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[8 * q + lrow][8 * piece]) = a[q];
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<uvec4_t*>(&aslice[8 * q + lrow][8 * piece]) = in ? a[q] : zero4;
     };
-    auto load_v = [&](int64_t n0, uint4 (&b)[VVEC]) {
+    auto load_v = [&](int64_t n0, bool live, uvec4_t (&b)[VVEC]) {
 #pragma unroll
         for (int v = 0; v < VVEC; ++v) {
             int e = tid + 256 * v;
             int part = e / (RQ_COLS * (KP / 8));
             int r = e % (RQ_COLS * (KP / 8));
             int c = r / (KP / 8), seg = r % (KP / 8);
-            b[v] = make_uint4(0, 0, 0, 0);
-            if (part < 2 && n0 + c < cend)
-                b[v] = *reinterpret_cast<const uint4*>((part ? v_lo : v_hi) + (n0 + c) * KP + seg * 8);
+            const bool in = live && n0 + c < cend;
+            b[v] = *reinterpret_cast<const uvec4_t*>(in ? (part ? v_lo : v_hi) + (n0 + c) * KP + seg * 8 : v_hi);
         }
     };
-    auto store_v = [&](int buf, const uint4 (&b)[VVEC]) {
+    auto store_v = [&](const uvec4_t (&b)[VVEC], int64_t n0, bool live, bool whole) {
 #pragma unroll
         for (int v = 0; v < VVEC; ++v) {
             int e = tid + 256 * v;
             int part = e / (RQ_COLS * (KP / 8));
             int r = e % (RQ_COLS * (KP / 8));
             int c = r / (KP / 8), seg = r % (KP / 8);
-            if (part < 2) *reinterpret_cast<uint4*>(&Vs[buf][part][c][seg * 8]) = b[v];
+            const bool in = whole || (live && n0 + c < cend);
+            *reinterpret_cast<uvec4_t*>(&Vs[part][c][seg * 8]) = in ? b[v] : zero4;
         }
     };
 
-    uint4 a_nxt[4];
-    uint4 v_nxt[VVEC];
-    load_a(cbeg, a_nxt);
-    load_v(cbeg, v_nxt);
-    store_a(a_nxt);
-    store_v(0, v_nxt);
+    uvec4_t a_nxt[4];
+    uvec4_t v_nxt[VVEC];
+    load_a(cbeg, true, a_nxt);
+    load_v(cbeg, true, v_nxt);
+    store_a(a_nxt, cbeg, true, false);
+    store_v(v_nxt, cbeg, true, false);
     __syncthreads();
-    int buf = 0;
-    for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) {
+
+    // one 64-column step; WHOLE = every row, column and step of this workgroup exists and the scale rows
+    // start on even addresses (no bounds checks, no branches around loads and stores)
+    auto step = [&](auto WHOLE_C, int64_t n0) {
+        constexpr bool WHOLE = decltype(WHOLE_C)::value;
         const bool more = n0 + RQ_COLS < cend;
-        if (more) {
-            load_a(n0 + RQ_COLS, a_nxt);
-            load_v(n0 + RQ_COLS, v_nxt);
-        }
+        load_a(n0 + RQ_COLS, more, a_nxt);
+        load_v(n0 + RQ_COLS, more, v_nxt);
         float16_t acc[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
             Frag a0, a1;
-            a0.u = *reinterpret_cast<const uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[li][32 * t + 8 * half]);
-            a1.u = *reinterpret_cast<const uint4*>(&(*reinterpret_cast<ASlice*>(&Rt[wave][0][0]))[li][32 * t + 16 + 8 * half]);
+            a0.u = *reinterpret_cast<const uint4*>(&aslice[li][32 * t + 8 * half]);
+            a1.u = *reinterpret_cast<const uint4*>(&aslice[li][32 * t + 16 + 8 * half]);
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, idf[0].v, acc[t], 0, 0, 0);
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, idf[1].v, acc[t], 0, 0, 0);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 Frag bh, bl;
-                bh.u = *reinterpret_cast<const uint4*>(&Vs[buf][0][32 * t + li][16 * ks + 8 * half]);
-                bl.u = *reinterpret_cast<const uint4*>(&Vs[buf][1][32 * t + li][16 * ks + 8 * half]);
+                bh.u = *reinterpret_cast<const uint4*>(&Vs[0][32 * t + li][16 * ks + 8 * half]);
+                bl.u = *reinterpret_cast<const uint4*>(&Vs[1][32 * t + li][16 * ks + 8 * half]);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ush[ks].v, bh.v, acc[t], 0, 0, 0);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ush[ks].v, bl.v, acc[t], 0, 0, 0);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(usl[ks].v, bh.v, acc[t], 0, 0, 0);
@@ -211,13 +226,11 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                     float4 f = src[q4];
                     x[4 * q4] = f.x; x[4 * q4 + 1] = f.y; x[4 * q4 + 2] = f.z; x[4 * q4 + 3] = f.w;
                 }
-                if (m < M && n < cend) {
-                    if (codes) {
-                        // stochastic rounding draws: stream 3, word = row-major position in R
-                        ss[bb] = SR ? quantize_block16_sr(x, qp, cc[bb], seed, 3u, (uint64_t)(m * N + n))
-                                    : quantize_block16(x, qp, cc[bb]);
-                    }
-                    if (R_debug) {
+                if (WHOLE || (m < M && n < cend)) {
+                    // stochastic rounding draws: stream 3, word = row-major position in R
+                    ss[bb] = SR ? quantize_block16_sr(x, qp, cc[bb], seed, 3u, (uint64_t)(m * N + n))
+                                : quantize_block16(x, qp, cc[bb]);
+                    if (!WHOLE && R_debug) {
                         float4* dst = reinterpret_cast<float4*>(R_debug + m * N + n);
 #pragma unroll
                         for (int q4 = 0; q4 < 4; ++q4) dst[q4] = make_float4(x[4 * q4], x[4 * q4 + 1], x[4 * q4 + 2], x[4 * q4 + 3]);
@@ -227,9 +240,12 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             // the lane's two blocks are neighbours in the row: one 16-byte and one 2-byte store (scattered
             // narrow stores, not the bytes, are what this kernel's output costs)
             const int64_t na = n0 + 32 * half;
-            if (codes && m < M && na < cend) {
-                uint8_t* cp = codes + m * (N / 2) + na / 2;
-                uint8_t* sp = scales + m * (N / 16) + na / 16;
+            uint8_t* cp = codes + m * (N / 2) + na / 2;
+            uint8_t* sp = scales + m * (N / 16) + na / 16;
+            if (WHOLE) {
+                store_codes16(cp, cc[0], cc[1]);
+                *reinterpret_cast<uint16_t*>(sp) = (uint16_t)((ss[0] & 0xFFu) | ((ss[1] & 0xFFu) << 8));
+            } else if (m < M && na < cend) {
                 if (na + 16 < cend) {
                     store_codes16(cp, cc[0], cc[1]);
                     store_scale_pair(sp, ss[0], ss[1]);
@@ -240,7 +256,7 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             }
         }
         // ---- blocks along the rows (transposed output): half-wave swap, then in-lane ----
-        if (codes_t) {
+        if (WT) {
             uint2 ct[2] = {make_uint2(0, 0), make_uint2(0, 0)};
             uint32_t st[2] = {0, 0};
 #pragma unroll
@@ -255,7 +271,7 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                     x[(i & 3) + 8 * (i >> 2) + 4] = __uint_as_float(sw[1]);
                 }
                 const int64_t n = n0 + 32 * t + li, m = wr0 + 16 * half;
-                if (n < cend && m < M) {
+                if (WHOLE || (n < cend && m < M)) {
                     // transposed copy: stream 4, word = row-major position in R^T
                     st[t] = SR ? quantize_block16_sr(x, qp, ct[t], seed, 4u, (uint64_t)(n * M + m))
                                : quantize_block16(x, qp, ct[t]);
@@ -267,9 +283,12 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             auto sy = __builtin_amdgcn_permlane32_swap(ct[0].y, ct[1].y, false, false);
             auto sq = __builtin_amdgcn_permlane32_swap(st[0], st[1], false, false);
             const int64_t n = n0 + 32 * half + li;
-            if (n < cend && wr0 < M) {
-                uint8_t* cp = codes_t + n * (M / 2) + wr0 / 2;
-                uint8_t* sp = scales_t + n * (M / 16) + wr0 / 16;
+            uint8_t* cp = codes_t + n * (M / 2) + wr0 / 2;
+            uint8_t* sp = scales_t + n * (M / 16) + wr0 / 16;
+            if (WHOLE) {
+                store_codes16(cp, make_uint2(sx[0], sy[0]), make_uint2(sx[1], sy[1]));
+                *reinterpret_cast<uint16_t*>(sp) = (uint16_t)((sq[0] & 0xFFu) | ((sq[1] & 0xFFu) << 8));
+            } else if (n < cend && wr0 < M) {
                 if (wr0 + 16 < M) {
                     store_codes16(cp, make_uint2(sx[0], sy[0]), make_uint2(sx[1], sy[1]));
                     store_scale_pair(sp, sq[0], sq[1]);
@@ -279,14 +298,21 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 }
             }
         }
-        if (more) {
-            store_v(buf ^ 1, v_nxt);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            store_a(a_nxt);
-        }
+        __syncthreads();                      // everybody has finished reading the V stage
+        store_v(v_nxt, n0 + RQ_COLS, more, WHOLE);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        store_a(a_nxt, n0 + RQ_COLS, more, WHOLE);
         __syncthreads();
-        buf ^= 1;
+    };
+
+    const bool whole = !R_debug && (int64_t)blockIdx.x * RQ_ROWS + RQ_ROWS <= M && (cend - cbeg) % RQ_COLS == 0 &&
+                       N % 32 == 0 && (reinterpret_cast<uintptr_t>(scales) & 1) == 0 &&
+                       (!WT || (M % 32 == 0 && (reinterpret_cast<uintptr_t>(scales_t) & 1) == 0));
+    if (whole) {
+        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) step(std::true_type{}, n0);
+    } else {
+        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) step(std::false_type{}, n0);
     }
 }
 
@@ -358,12 +384,16 @@ static int split_quantize_impl(void* stream, const metis_mat* A, const float* U,
     uint8_t* st_ = want_t ? out->Rt.scales : nullptr;
     const bf16_t* Ap = (const bf16_t*)A->ptr;
     const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
+#define RQ_LAUNCH(KS_, WT_)                                                                                         \
+    hipLaunchKernelGGL((k_residual_quant<KS_, SR, WT_>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, \
+                       v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed)
     switch (kp / 16) {
-        case 1: hipLaunchKernelGGL((k_residual_quant<1, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
-        case 2: hipLaunchKernelGGL((k_residual_quant<2, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
-        case 4: hipLaunchKernelGGL((k_residual_quant<4, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
-        default: hipLaunchKernelGGL((k_residual_quant<8, SR>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed); break;
+        case 1: if (want_t) RQ_LAUNCH(1, true); else RQ_LAUNCH(1, false); break;
+        case 2: if (want_t) RQ_LAUNCH(2, true); else RQ_LAUNCH(2, false); break;
+        case 4: if (want_t) RQ_LAUNCH(4, true); else RQ_LAUNCH(4, false); break;
+        default: if (want_t) RQ_LAUNCH(8, true); else RQ_LAUNCH(8, false); break;
     }
+#undef RQ_LAUNCH
     metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
     METIS_LAUNCH_CHECK();
     // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
