@@ -96,6 +96,14 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
     // before the tile is written and refilled after the tile has been read
     typedef bf16_t ASlice[32][RQ_COLS + 8];
     static_assert(sizeof(ASlice) <= sizeof(float) * 32 * RQ_LDR, "A slice must fit in the residual tile");
+    // Output staging of the whole-workgroup path.  Scattered 16-byte and 2-byte stores make the memory
+    // system request-bound, so the codes leave as whole lines: a wave collects four steps of its 32 rows
+    // (128 bytes of codes and 16 bytes of scales per row), the workgroup collects one step of the
+    // transposed copy (64 bytes of codes and 8 bytes of scales per column of A).
+    __shared__ __attribute__((aligned(16))) uvec4_t Cst[4][32][9];              // [wave][row][16-byte piece], padded
+    __shared__ __attribute__((aligned(4))) uint16_t Sst[4][32][8];              // [wave][row][2 * step + half]
+    __shared__ __attribute__((aligned(16))) uvec4_t Tst[WT ? RQ_COLS : 1][5];   // [column][wave], padded
+    __shared__ __attribute__((aligned(2))) uint16_t Tsc[WT ? RQ_COLS : 1][4];   // [column][wave]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, half = lane >> 5;
     const int64_t wr0 = (int64_t)blockIdx.x * RQ_ROWS + 32 * wave;
@@ -176,9 +184,32 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
 
     // one 64-column step; WHOLE = every row, column and step of this workgroup exists and the scale rows
     // start on even addresses (no bounds checks, no branches around loads and stores)
-    auto step = [&](auto WHOLE_C, int64_t n0) {
+    // the four finished steps of this wave's rows (cnt < 4: the last, shorter group) as whole lines
+    auto flush_rows = [&](int64_t gn0, int cnt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row = 8 * q + lrow;
+            if (piece < 2 * cnt)
+                *reinterpret_cast<uvec4_t*>(codes + (wr0 + row) * (N / 2) + gn0 / 2 + 16 * piece) = Cst[wave][row][piece];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int w = 2 * half + j;       // the scale bytes of step w of the group: one dword per row
+            if (w < cnt)
+                *reinterpret_cast<uint32_t*>(scales + (wr0 + li) * (N / 16) + gn0 / 16 + 4 * w) =
+                    *reinterpret_cast<const uint32_t*>(&Sst[wave][li][2 * w]);
+        }
+    };
+    const int64_t brow0 = (int64_t)blockIdx.x * RQ_ROWS;
+
+    auto step = [&](auto WHOLE_C, int64_t n0, int g) {
         constexpr bool WHOLE = decltype(WHOLE_C)::value;
         const bool more = n0 + RQ_COLS < cend;
+        // a finished group leaves before the next loads are issued: the wait for those loads then never
+        // includes these stores
+        if (WHOLE && g == 0 && n0 > cbeg) flush_rows(n0 - 4 * RQ_COLS, 4);
         load_a(n0 + RQ_COLS, more, a_nxt);
         load_v(n0 + RQ_COLS, more, v_nxt);
         float16_t acc[2];
@@ -243,8 +274,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             uint8_t* cp = codes + m * (N / 2) + na / 2;
             uint8_t* sp = scales + m * (N / 16) + na / 16;
             if (WHOLE) {
-                store_codes16(cp, cc[0], cc[1]);
-                *reinterpret_cast<uint16_t*>(sp) = (uint16_t)((ss[0] & 0xFFu) | ((ss[1] & 0xFFu) << 8));
+                const uvec4_t cv = {cc[0].x, cc[0].y, cc[1].x, cc[1].y};
+                Cst[wave][li][2 * g + half] = cv;
+                Sst[wave][li][2 * g + half] = (uint16_t)((ss[0] & 0xFFu) | ((ss[1] & 0xFFu) << 8));
             } else if (m < M && na < cend) {
                 if (na + 16 < cend) {
                     store_codes16(cp, cc[0], cc[1]);
@@ -286,8 +318,9 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             uint8_t* cp = codes_t + n * (M / 2) + wr0 / 2;
             uint8_t* sp = scales_t + n * (M / 16) + wr0 / 16;
             if (WHOLE) {
-                store_codes16(cp, make_uint2(sx[0], sy[0]), make_uint2(sx[1], sy[1]));
-                *reinterpret_cast<uint16_t*>(sp) = (uint16_t)((sq[0] & 0xFFu) | ((sq[1] & 0xFFu) << 8));
+                const uvec4_t cv = {sx[0], sy[0], sx[1], sy[1]};
+                Tst[32 * half + li][wave] = cv;
+                Tsc[32 * half + li][wave] = (uint16_t)((sq[0] & 0xFFu) | ((sq[1] & 0xFFu) << 8));
             } else if (n < cend && wr0 < M) {
                 if (wr0 + 16 < M) {
                     store_codes16(cp, make_uint2(sx[0], sy[0]), make_uint2(sx[1], sy[1]));
@@ -299,6 +332,12 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             }
         }
         __syncthreads();                      // everybody has finished reading the V stage
+        if (WHOLE && WT) {
+            // four lanes cover the 64 bytes one column of A gets from this workgroup's 128 rows
+            const int nl = tid >> 2, w = tid & 3;
+            *reinterpret_cast<uvec4_t*>(codes_t + (n0 + nl) * (M / 2) + brow0 / 2 + 16 * w) = Tst[nl][w];
+            *reinterpret_cast<uint16_t*>(scales_t + (n0 + nl) * (M / 16) + brow0 / 16 + 2 * w) = Tsc[nl][w];
+        }
         store_v(v_nxt, n0 + RQ_COLS, more, WHOLE);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -306,13 +345,19 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         __syncthreads();
     };
 
-    const bool whole = !R_debug && (int64_t)blockIdx.x * RQ_ROWS + RQ_ROWS <= M && (cend - cbeg) % RQ_COLS == 0 &&
-                       N % 32 == 0 && (reinterpret_cast<uintptr_t>(scales) & 1) == 0 &&
-                       (!WT || (M % 32 == 0 && (reinterpret_cast<uintptr_t>(scales_t) & 1) == 0));
+    // whole: all 128 rows and every step exist, and rows of the outputs start where 16-byte code stores and
+    // 4-byte (transposed copy: 2-byte) scale stores are aligned
+    const bool whole = !R_debug && brow0 + RQ_ROWS <= M && (cend - cbeg) % RQ_COLS == 0 && N % 64 == 0 &&
+                       reinterpret_cast<uintptr_t>(codes) % 16 == 0 && reinterpret_cast<uintptr_t>(scales) % 4 == 0 &&
+                       (!WT || (M % 32 == 0 && reinterpret_cast<uintptr_t>(codes_t) % 16 == 0 &&
+                                reinterpret_cast<uintptr_t>(scales_t) % 2 == 0));
     if (whole) {
-        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) step(std::true_type{}, n0);
+        int g = 0;
+        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS, g = (g + 1) & 3) step(std::true_type{}, n0, g);
+        const int cnt = g == 0 ? 4 : g;       // steps in the last group
+        flush_rows(cend - (int64_t)cnt * RQ_COLS, cnt);
     } else {
-        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) step(std::false_type{}, n0);
+        for (int64_t n0 = cbeg; n0 < cend; n0 += RQ_COLS) step(std::false_type{}, n0, 0);
     }
 }
 

@@ -117,3 +117,46 @@ def test_split_quantize_sr(metis, M, N, k, p, rho, want_t):
     torch.cuda.synchronize()
     assert np.array_equal(sp0.R.scales.cpu().numpy(), sp.R.scales.cpu().numpy())
     assert not np.array_equal(sp0.R.codes.cpu().numpy(), sp.R.codes.cpu().numpy())
+
+
+@pytest.mark.parametrize("M,N,k,want_t", [(8192, 2432, 64, True), (384, 832, 16, True), (2048, 1024, 64, False),
+                                          (256, 320, 16, True), (4096, 2368, 32, False)])
+def test_whole_workgroup_path(metis, M, N, k, want_t):
+    """Without the debug output, workgroups whose 128 rows and 64-column steps all exist take the kernel's
+    branch-free path, which stages codes and scales in LDS and writes whole lines (groups of four steps per
+    wave; a shorter last group when the column run is not a multiple of 256).  Its codes and scales must be
+    the oracle's for the residual the checked path dumps from the same inputs."""
+    gen = torch.Generator().manual_seed(M * 7 + N)
+    A = (torch.randn((M, N), generator=gen) * 0.05).to(torch.bfloat16)
+    U = torch.randn((M, k), generator=gen).mul_(M ** -0.5).cuda().contiguous()
+    V = torch.randn((N, k), generator=gen).mul_(N ** -0.5).cuda().contiguous()
+    S = (torch.rand((k,), generator=gen) * 3.0 + 0.5).cuda().contiguous()
+    Ad = A.cuda()
+    g = oq.tensor_scale_for(float(A.abs().max()))
+    sp_dbg = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+    Rd = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    metis.split_quantize(Ad, U, S, V, sp_dbg, R_debug=Rd)
+    sp = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+    metis.split_quantize(Ad, U, S, V, sp)
+    torch.cuda.synchronize()
+    R = Rd.double().cpu().numpy()
+    Rref = odec.residual(A.double().numpy(), U.double().cpu().numpy(), S.double().cpu().numpy(), V.double().cpu().numpy())
+    assert np.linalg.norm(R - Rref) <= 1e-4 * np.linalg.norm(A.double().numpy())
+    c, s = oq.quantize(R, g)
+    assert np.array_equal(sp.R.scales.cpu().numpy(), s)
+    assert np.array_equal(sp.R.codes.cpu().numpy(), c)
+    assert np.array_equal(sp_dbg.R.codes.cpu().numpy(), c)
+    if want_t:
+        c, s = oq.quantize(np.ascontiguousarray(R.T), g)
+        assert np.array_equal(sp.Rt.scales.cpu().numpy(), s)
+        assert np.array_equal(sp.Rt.codes.cpu().numpy(), c)
+    if k == 16:
+        # the stochastically rounded variant shares the step body: its whole-workgroup path must reproduce the
+        # checked path (test_split_quantize_sr pins that one to the oracle) bit for bit
+        a = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+        b = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, want_t)
+        metis.split_quantize_sr(Ad, U, S, V, 77, a, R_debug=Rd)
+        metis.split_quantize_sr(Ad, U, S, V, 77, b)
+        torch.cuda.synchronize()
+        for x, y in ((a.R, b.R), (a.Rt, b.Rt)):
+            assert torch.equal(x.codes, y.codes) and torch.equal(x.scales, y.scales)
