@@ -120,7 +120,8 @@ def test_split_quantize_sr(metis, M, N, k, p, rho, want_t):
 
 
 @pytest.mark.parametrize("M,N,k,want_t", [(8192, 2432, 64, True), (384, 832, 16, True), (2048, 1024, 64, False),
-                                          (256, 320, 16, True), (4096, 2368, 32, False)])
+                                          (256, 320, 16, True), (4096, 2368, 32, False),
+                                          (512, 576, 96, True), (208, 272, 80, True)])
 def test_whole_workgroup_path(metis, M, N, k, want_t):
     """Without the debug output, workgroups whose 128 rows and 64-column steps all exist take the kernel's
     branch-free path, which stages codes and scales in LDS and writes whole lines (groups of four steps per
