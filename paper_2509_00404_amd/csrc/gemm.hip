@@ -564,10 +564,11 @@ __device__ __forceinline__ float fp4_elem_nog(const uint8_t* codes, const uint8_
 //   Aext[m, kb:kb+ka] = Ua[m,:] without its tensor scale (exact in bf16)
 //   Bext[n, 0:kb]     = Ub[n,:] without its tensor scale (exact in bf16)
 //   Bext[n, kb:kb+ka] = E2[n,:] * Sa * gUa / (gRa gRb)
-// Blocks [0, ceil(Ma/64)) build 64 rows of Aext each: the dequantized factor rows U_a S_a and the small
+// Blocks [0, ceil(Ma/16)) build 16 rows of Aext each: the dequantized factor rows U_a S_a and the small
 // matrix Mk sit in LDS, so the k_a-term sum of the first kb columns reads global memory once.  The
-// remaining blocks build 64 rows of Bext each the same way.
-#define AX_ROWS 64
+// remaining blocks build 16 rows of Bext each the same way.  (16 rows: several workgroups per CU; with 64
+// the 8192 + 4096 rows of a layer gave fewer workgroups than CUs and the kernel took three times as long.)
+#define AX_ROWS 16
 __global__ void __launch_bounds__(256)
 k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1,
                const float* __restrict__ Mk, const float* __restrict__ E2,
@@ -605,7 +606,7 @@ k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __r
         }
         return;
     }
-    // Bext: 64 rows per block; the stored factor rows of U_b are decoded along their contiguous axis into LDS
+    // Bext: 16 rows per block; the stored factor rows of U_b are decoded along their contiguous axis into LDS
     float* ub = ax_sm;                              // [AX_ROWS][kb + 1]
     const int64_t r0 = ((int64_t)blockIdx.x - nblk_a) * AX_ROWS;
     for (int e = tid; e < AX_ROWS * kb; e += 256) {
