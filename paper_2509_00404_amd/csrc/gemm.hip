@@ -695,8 +695,11 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
             int64_t want = ceil_div64(256, tiles), maxs = iters / 2 > 0 ? iters / 2 : 1;
             return (int)(want < maxs ? want : maxs);
         };
+        // (the k_a x k_b product Mk is a single output tile: without a split one workgroup would walk the whole
+        // contraction alone, ~100 us at 14336 columns)
         const int s1 = kb > 0 ? splits(Ma, kb) : 1, s2 = ka > 0 ? splits(Nb, ka) : 1;
-        if (s1 > 1 || s2 > 1) {     // T1, Mk, E2 are contiguous at the start of the workspace
+        const int s3 = ka > 0 && kb > 0 ? splits(ka, kb) : 1;
+        if (s1 > 1 || s2 > 1 || s3 > 1) {     // T1, Mk, E2 are contiguous at the start of the workspace
             hipLaunchKernelGGL(k_zero_f32, dim3(256), dim3(256), 0, s, (float*)ws, w.off_aext / 4);
             METIS_LAUNCH_CHECK();
         }
@@ -705,7 +708,7 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         if (ka > 0 && (st = launch_gemm<float>(s, b.R, a.Vt, nullptr, nullptr, 0, b.R.tscale * a.Vt.tscale, E2, ka, s2)))
             return st;
         if (ka > 0 && kb > 0 &&
-            (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb)))
+            (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb, s3)))
             return st;
         const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
         const size_t ax_lds = ((size_t)AX_ROWS * ((ka > kb ? ka : kb) + 1) + (size_t)ka * kb) * sizeof(float);
