@@ -265,6 +265,15 @@ def main():
                                  "frac_hbm": round(qb / sr_ms / 1e6 / PEAK_HBM_GBS, 4)}
         metis.quantize(X.A, X.q.R, None)
 
+    # The same HBM passes at the FFN activation shape (8192 x 14336, the largest matrix of a LLaMA-3-8B layer), one
+    # operand at a time: on the 4096 x 4096 weight of the default workload a pass is a few microseconds of traffic
+    # and mostly launch ramp, and on the three-operand workloads the figures above include the operands' contention.
+    passes_ffn = None
+    try:
+        passes_ffn = ffn_shape_passes(torch, metis, oq, k, p, prm["rho_x"])
+    except Exception as e:                                         # an extra figure must never cost the main line
+        passes_ffn = {"error": repr(e)[:200]}
+
     out = {
         "metric": "split-FP4 linear TFLOP/s + decompose/quantize GB/s (frac of roofline), 1 GPU",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -280,12 +289,46 @@ def main():
         "pipelined": pipelined,
         "mxfp4_variant": mx,
         "passes": passes,
+        "passes_ffn_shape": passes_ffn,
         "phases": phases,
     }
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, torch, T, c, prm, oq)
     print(json.dumps(out))
+
+
+def ffn_shape_passes(torch, metis, oq, k, p, rho, reps=5):
+    """Event-bracketed broadcast and residual + quantize kernels on one seeded 8192 x 14336 bf16 operand."""
+    Mf, Nf = 8192, 14336
+    gen = torch.Generator(device="cuda").manual_seed(20250904)
+    Af = (torch.randn((Mf, Nf), generator=gen, device="cuda") * 0.05).to(torch.bfloat16)
+    mn = Mf * Nf
+    res = {"shape": [Mf, Nf], "k": k, "sample_rate": rho, "data": "seeded N(0, 0.05^2), timing only"}
+    for want_t in (False, True):
+        o = Operand(metis, torch, Af, k, p, rho, 11, want_t, oq)
+        o.prepare()
+        tb = metis.KernelTimer(metis.PROF_BROADCAST, reps)
+        tr = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, reps)
+        tb.__enter__()
+        tr.__enter__()
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            o.prepare()
+        torch.cuda.synchronize()
+        tb.__exit__()
+        tr.__exit__()
+        bc, rq = tb.durations_ms(reps), tr.durations_ms(reps)
+        bc_ms, rq_ms = sum(bc) / len(bc), sum(rq) / len(rq)
+        if not want_t:
+            res["broadcast"] = {"avg_ms": round(bc_ms, 4), "GB/s": round(2 * mn / bc_ms / 1e6, 1),
+                                "frac_hbm": round(2 * mn / bc_ms / 1e6 / PEAK_HBM_GBS, 4)}
+        rq_bytes = (2 + 0.5625 * (2 if want_t else 1)) * mn
+        res["residual_quant_%d_orientation%s" % ((2, "s") if want_t else (1, ""))] = {
+            "avg_ms": round(rq_ms, 4), "GB/s": round(rq_bytes / rq_ms / 1e6, 1),
+            "frac_hbm": round(rq_bytes / rq_ms / 1e6 / PEAK_HBM_GBS, 4)}
+        del o
+    return res
 
 
 def pipelined_throughput(args, torch, metis, oq, T, W, X, Y, ws_lin, p, full, depth, useful_flops):
