@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ffn-passes", action="store_true",
+                    help="skip the extra figure on an 8192 x 14336 operand (keeps a profile to the workload's own shapes)")
     ap.add_argument("--pipeline-depth", type=int, default=3,
                     help="extra measurement: independent steps in flight at once, one stream and one set of "
                          "buffers each (0 or 1 = skip); never enters `value`")
@@ -269,10 +271,11 @@ def main():
     # operand at a time: on the 4096 x 4096 weight of the default workload a pass is a few microseconds of traffic
     # and mostly launch ramp, and on the three-operand workloads the figures above include the operands' contention.
     passes_ffn = None
-    try:
-        passes_ffn = ffn_shape_passes(torch, metis, oq, k, p, prm["rho_x"])
-    except Exception as e:                                         # an extra figure must never cost the main line
-        passes_ffn = {"error": repr(e)[:200]}
+    if not args.no_ffn_passes:
+        try:
+            passes_ffn = ffn_shape_passes(torch, metis, oq, k, p, prm["rho_x"])
+        except Exception as e:                                     # an extra figure must never cost the main line
+            passes_ffn = {"error": repr(e)[:200]}
 
     out = {
         "metric": "split-FP4 linear TFLOP/s + decompose/quantize GB/s (frac of roofline), 1 GPU",
