@@ -134,10 +134,11 @@ __device__ __forceinline__ void stage_store_one(const uint4& v, uint8_t* __restr
 __device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t spair, bool hi) {
     const half2_t sp = __builtin_bit_cast(half2_t, spair);
     const half2_t s2 = hi ? (half2_t){sp[1], sp[1]} : (half2_t){sp[0], sp[0]};
-    half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0) * s2;
-    half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1) * s2;
-    half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2) * s2;
-    half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 3) * s2;
+    const half2_t c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0);
+    const half2_t c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1);
+    const half2_t c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2);
+    const half2_t c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 3);
+    half2_t p0 = c0 * s2, p1 = c1 * s2, p2 = c2 * s2, p3 = c3 * s2;
     half8_t r = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
     return r;
 }
