@@ -291,8 +291,15 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
                    const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
     constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
-                  BUF = OFF_SB + BN * G_SROW;
+    // LDS layout of a stage, chosen so that ONE 16-byte read per lane fetches the raw words of all four row
+    // tiles of a wave (the wave issues an instruction only every ~9 clocks, so instructions, not bytes, count):
+    // codes of an operand: planes (g = row / 128, step s, half) of 32 lanes x 4 tiles dwords,
+    //   dword (g, s, half, l, i) = the 8 codes of row 128 g + 32 i + l at contraction 16 s + 8 half;
+    // scales: planes (g, pair q of steps) of 32 x 4 dwords, dword (g, q, l, i) = the fp16 scales of blocks 2q, 2q+1.
+    // A plane is 512 bytes, padded to 528 (planes of neighbouring 16-byte code segments then start in different banks).
+    constexpr int PL = 528, CODES_OP = 2 * KS * 2 * PL, SC_OP = 2 * (KS / 2) * PL;
+    constexpr int OFF_CB = CODES_OP, OFF_SA = 2 * CODES_OP, OFF_SB = OFF_SA + SC_OP, BUF = OFF_SB + SC_OP;
+    static_assert(2 * BUF <= (int)gemm_lds_bytes<256, 256>(), "two stages fit the allocation");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int tile_m, tile_n;
     tile_coords(tmap, tile_m, tile_n);
@@ -347,21 +354,33 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         for (int v = 0; v < 4; ++v) load_codes(st, v);
         load_scales(st);
     };
+    // a 16-byte code vector = two steps (2 seg, 2 seg + 1) x two halves of one row: four dwords to four planes
     auto store_codes = [&](uint8_t* buf, int v) {
-        stage_store_one(ra[v], buf, tid + NT * v);
-        stage_store_one(rb[v], buf + OFF_CB, tid + NT * v);
+        const int e = tid + NT * v, row = e >> 2, seg = e & 3;
+        const int off = (((row >> 7) * KS + 2 * seg) * 2) * PL + (row & 31) * 16 + ((row >> 5) & 3) * 4;
+        uint8_t* da = buf + off;
+        uint8_t* db = buf + OFF_CB + off;
+        *reinterpret_cast<uint32_t*>(da) = ra[v].x;
+        *reinterpret_cast<uint32_t*>(da + PL) = ra[v].y;
+        *reinterpret_cast<uint32_t*>(da + 2 * PL) = ra[v].z;
+        *reinterpret_cast<uint32_t*>(da + 3 * PL) = ra[v].w;
+        *reinterpret_cast<uint32_t*>(db) = rb[v].x;
+        *reinterpret_cast<uint32_t*>(db + PL) = rb[v].y;
+        *reinterpret_cast<uint32_t*>(db + 2 * PL) = rb[v].z;
+        *reinterpret_cast<uint32_t*>(db + 3 * PL) = rb[v].w;
     };
     auto store_scales = [&](uint8_t* buf) {
-        uint32_t* da = reinterpret_cast<uint32_t*>(buf + OFF_SA + tid * G_SROW);
-        uint32_t* db = reinterpret_cast<uint32_t*>(buf + OFF_SB + tid * G_SROW);
-        da[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, false));
-        da[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, true));
-        da[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, false));
-        da[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, true));
-        db[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, false));
-        db[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, true));
-        db[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, false));
-        db[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, true));
+        const int off = ((tid >> 7) * (KS / 2)) * PL + (tid & 31) * 16 + ((tid >> 5) & 3) * 4;
+        uint8_t* da = buf + OFF_SA + off;
+        uint8_t* db = buf + OFF_SB + off;
+        *reinterpret_cast<uint32_t*>(da) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, false));
+        *reinterpret_cast<uint32_t*>(da + PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.x, 1.0f, true));
+        *reinterpret_cast<uint32_t*>(da + 2 * PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, false));
+        *reinterpret_cast<uint32_t*>(da + 3 * PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsa.y, 1.0f, true));
+        *reinterpret_cast<uint32_t*>(db) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, false));
+        *reinterpret_cast<uint32_t*>(db + PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.x, 1.0f, true));
+        *reinterpret_cast<uint32_t*>(db + 2 * PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, false));
+        *reinterpret_cast<uint32_t*>(db + 3 * PL) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rsb.y, 1.0f, true));
     };
     load_stage(0);
 #pragma unroll
@@ -370,21 +389,26 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     __syncthreads();
     load_stage(niter > 1 ? 1 : 0);
 
-    // per-lane byte offsets of this wave's fragment rows inside a buffer
-    const int oca = (wm + li) * G_CROW + 4 * half, ocb = OFF_CB + (wn + li) * G_CROW + 4 * half;
-    const int osa = OFF_SA + (wm + li) * G_SROW, osb = OFF_SB + (wn + li) * G_SROW;
+    // per-lane byte offsets of this wave's planes inside a buffer (step 0 / pair 0)
+    typedef uint32_t rawvec_t __attribute__((ext_vector_type(4)));
+    const int oca = (((wave >> 1) * KS) * 2 + half) * PL + li * 16, ocb = OFF_CB + (((wave & 1) * KS) * 2 + half) * PL + li * 16;
+    const int osa = OFF_SA + ((wave >> 1) * (KS / 2)) * PL + li * 16, osb = OFF_SB + ((wave & 1) * (KS / 2)) * PL + li * 16;
     uint32_t rawc[2][TM + TN], raws[2][TM + TN];
     half8_t frag[2][TM + TN];
     auto read_raw = [&](const uint8_t* buf, int s, int slot) {
+        const rawvec_t ca = *reinterpret_cast<const rawvec_t*>(buf + oca + 2 * s * PL);
+        const rawvec_t cb = *reinterpret_cast<const rawvec_t*>(buf + ocb + 2 * s * PL);
+        const rawvec_t sa = *reinterpret_cast<const rawvec_t*>(buf + osa + (s >> 1) * PL);
+        const rawvec_t sb = *reinterpret_cast<const rawvec_t*>(buf + osb + (s >> 1) * PL);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            rawc[slot][i] = *reinterpret_cast<const uint32_t*>(buf + oca + 32 * i * G_CROW + 8 * s);
-            raws[slot][i] = *reinterpret_cast<const uint32_t*>(buf + osa + 32 * i * G_SROW + 4 * (s >> 1));
+            rawc[slot][i] = ca[i];
+            raws[slot][i] = sa[i];
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            rawc[slot][TM + j] = *reinterpret_cast<const uint32_t*>(buf + ocb + 32 * j * G_CROW + 8 * s);
-            raws[slot][TM + j] = *reinterpret_cast<const uint32_t*>(buf + osb + 32 * j * G_SROW + 4 * (s >> 1));
+            rawc[slot][TM + j] = cb[j];
+            raws[slot][TM + j] = sb[j];
         }
     };
     read_raw(lds, 0, 0);
