@@ -122,13 +122,6 @@ __device__ __forceinline__ void stage_store(const StageRegs<ROWS * 4 / NT>& rg, 
     }
 }
 
-// one 16-byte code vector (element e of the stage: row e/4, 16-byte segment e%4) into the padded LDS rows
-__device__ __forceinline__ void stage_store_one(const uint4& v, uint8_t* __restrict__ lc, int e) {
-    const int row = e >> 2, seg = e & 3;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(lc + row * G_CROW + 16 * seg);
-    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-}
-
 // 8 codes (one dword) times one block scale -> 8 fp16.  `spair` holds the fp16 scales of two
 // consecutive blocks; `hi` picks the second (the splat folds into the packed multiply's operand select).
 __device__ __forceinline__ half8_t dequant8(uint32_t cw, uint32_t spair, bool hi) {
