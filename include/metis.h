@@ -79,6 +79,16 @@ typedef struct {
 const char* metis_status_string(int status);
 int metis_version(void);
 
+/*
+ * Per-tensor scale of a metis_fp4 for data whose largest magnitude is `amax` (host-only helper, no
+ * GPU work): the smallest power of two g with 6 * 448 * g >= amax, so that the largest block scale
+ * still fits FP8-E4M3.  The paper's text has no such scale (g = 1); this build's reading adds it so
+ * that small-magnitude tensors (singular vectors, gradients) do not fall into E4M3's subnormals,
+ * and keeps it a power of two so that every quantizer comparison stays exact.  amax <= 0 or not
+ * finite returns 1.  Callers typically take amax from a previous step (metis_decompose's amax_out).
+ */
+float metis_tensor_scale(float amax);
+
 /* ---- random draws of the decomposition (Sec. 3.1) ------------------------------------- */
 
 /* Number of sampled rows l_k = min(M, max(k+p, ceil(rho*M))). Host-only helper. */

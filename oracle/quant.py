@@ -10,11 +10,11 @@ round(e / (s*g)) * (s*g) on the grid +-{0, .5, 1, 1.5, 2, 3, 4, 6}.
 
 Readings of this build where the paper is silent:
   * g is a per-tensor power-of-two scale (g = 1 is the paper's text verbatim);
-  * the quotient e/s is the IEEE fp32 quotient y = fl32(e / (s*g)) (the precision of the
-    kernels; the paper's own emulation evaluates it in floating point as well); inputs are
-    taken as fp32 values.  y is exact whenever it is representable, so a value that sits
-    exactly on a rounding midpoint stays there;
-  * round() is round-to-nearest of y, ties to the even E2M1 code;
+  * round(e / (s*g)) is taken in real arithmetic: |e| is compared with midpoint * s * g for
+    the seven midpoints between neighbouring grid values (Sec. 2.3).  No division is done:
+    midpoint * s * g has at most 7 significant bits and e is a float, so every comparison is
+    exact in fp64;
+  * round() is round-to-nearest, ties to the even E2M1 code;
   * a block whose amax exceeds 6*448*g saturates (scale 448, elements clamp to 6);
   * an all-zero block gets scale byte 0 and codes that keep only the sign bit.
 
@@ -54,18 +54,17 @@ def quantize(x, g=1.0):
     cover = 6.0 * E4M3_POS * g
     sidx = np.searchsorted(cover, amax, side="left")
     sidx = np.minimum(sidx, 126)                    # saturate at 448
-    step = (E4M3_POS[sidx] * g).astype(np.float32)  # s*g: at most 4 significant bits, exact in fp32
-    # e/s as the IEEE fp32 quotient; an all-zero block (step 0) maps to +-0
-    safe = np.where(step > 0, step, np.float32(1.0)).astype(np.float32)
-    y = (xb.astype(np.float32) / safe[:, :, None]).astype(np.float32).astype(np.float64)
-    a = np.abs(y)
+    step = (E4M3_POS[sidx] * g)[:, :, None]         # s*g: at most 4 significant bits
+    a = np.abs(xb)
     mag = np.zeros(xb.shape, dtype=np.int64)
     for j, mid in enumerate(E2M1_MID):
+        bound = mid * step                          # exact: at most 7 significant bits
         # a tie goes to the even code: boundary j separates codes j and j+1
         if (j + 1) % 2 == 0:
-            mag += (a >= mid)
+            mag += (a >= bound)
         else:
-            mag += (a > mid)
+            mag += (a > bound)
+    mag = np.where(step == 0, 0, mag)               # all-zero block: only the signs remain
     sign = np.signbit(xb).astype(np.int64)
     nib = (sign << 3) | mag
     nib = nib.reshape(rows, cols)
@@ -82,14 +81,14 @@ def quantize_sr(x, g, seed, stream=STREAM_SR, words=None):
 
     The paper names the rounding mode and nothing else; readings of this build:
       * block scale exactly as in quantize(): chosen from the block's amax, rounded up;
-      * y = fl32(x / (s*g)) as in quantize(), a = min(|y|, 6);
-      * with lo <= a <= hi the two neighbouring E2M1 magnitudes, the element goes to hi with
+      * a = min(|x| / (s*g), 6) in real arithmetic, as in quantize();
+      * with lo <= a < hi the two neighbouring E2M1 magnitudes, the element goes to hi with
         probability t = (a - lo) / (hi - lo) and to lo otherwise (so its expectation is a);
         a value on the grid stays where it is;
       * the draw: u = (w >> 8) * 2^-24 with w the Philox4x32-10 word whose index is the
         element's row-major position in x, stream 3 (4 for a transposed copy); go up iff u < t.
-        t is exact in fp32 (a - lo is exact and hi - lo is a power of two), so the comparison
-        is the same on every machine.
+        Evaluated without a division as (lo + u (hi - lo)) * s * g < |x|: the left side has at
+        most 31 significant bits, so the comparison is exact in fp64 and the same everywhere.
     words (optional, uint32 of x's shape) replaces the Philox draws -- for tests.
     Returns (codes, scales) in the storage layout of quantize().
     """
@@ -101,19 +100,20 @@ def quantize_sr(x, g, seed, stream=STREAM_SR, words=None):
     amax = np.abs(xb).max(axis=2)
     cover = 6.0 * E4M3_POS * g
     sidx = np.minimum(np.searchsorted(cover, amax, side="left"), 126)
-    step = (E4M3_POS[sidx] * g).astype(np.float32)
-    safe = np.where(step > 0, step, np.float32(1.0)).astype(np.float32)
-    y = (xb.astype(np.float32) / safe[:, :, None]).astype(np.float32).astype(np.float64)
-    a = np.minimum(np.abs(y), 6.0).reshape(rows, cols)
+    step = np.repeat(E4M3_POS[sidx] * g, BLOCK, axis=1)             # s*g per element, [rows, cols]
+    a = np.abs(x)
     if words is None:
         words = rng.philox_words(seed, stream, 0, rows * cols).reshape(rows, cols)
     u = (np.asarray(words, dtype=np.uint64) >> np.uint64(8)).astype(np.float64) * 2.0 ** -24
-    lo_i = np.searchsorted(E2M1_GRID, a, side="right") - 1          # largest grid value <= a
+    # lo = largest grid magnitude with lo * s * g <= |x| (products exact: at most 6 significant bits)
+    lo_i = np.zeros(x.shape, dtype=np.int64)
+    for j in range(1, 8):
+        lo_i += (a >= E2M1_GRID[j] * step)
     hi_i = np.minimum(lo_i + 1, 7)
     lo, hi = E2M1_GRID[lo_i], E2M1_GRID[hi_i]
-    width = np.where(hi > lo, hi - lo, 1.0)
-    t = (a - lo) / width
-    mag = np.where(u < t, hi_i, lo_i).astype(np.int64)
+    up = (lo + u * (hi - lo)) * step < a                             # exact; never true at lo = hi = 6
+    mag = np.where(up, hi_i, lo_i).astype(np.int64)
+    mag = np.where(step == 0, 0, mag)
     sign = np.signbit(x).astype(np.int64)
     nib = (sign << 3) | mag
     codes = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)

@@ -1,5 +1,6 @@
 // Status strings and version of the C ABI.
 #include "common.h"
+#include <math.h>
 
 extern "C" const char* metis_status_string(int status) {
     switch (status) {
@@ -13,7 +14,16 @@ extern "C" const char* metis_status_string(int status) {
     }
 }
 
-extern "C" int metis_version(void) { return 1; }
+extern "C" int metis_version(void) { return 2; }
+
+// Smallest power of two g with 6 * 448 * g >= amax (host arithmetic only).  frexp gives amax = m 2^e with
+// 0.5 <= m < 1; 2688 = 0.65625 * 2^12, so g = 2^(e - 12) covers amax when m <= 0.65625 and 2^(e - 11) otherwise.
+extern "C" float metis_tensor_scale(float amax) {
+    if (!(amax > 0.0f) || amax > 3.0e38f) return 1.0f;
+    int e = 0;
+    const float m = frexpf(amax, &e);
+    return ldexpf(1.0f, m <= 0.65625f ? e - 12 : e - 11);
+}
 
 MetisProfSlot g_metis_prof[METIS_PROF_COUNT] = {};
 

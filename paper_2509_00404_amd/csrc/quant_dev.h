@@ -1,7 +1,13 @@
 // NVFP4 block quantizer (Sec. 2.3; value set App. C.1), device side.
 // One block = 16 values held by one lane.  The scale choice compares exactly (6*s needs at
-// most 6 significand bits and the tensor scale g is a power of two); the quotient e/s of the
-// element rule is the IEEE fp32 quotient.
+// most 6 significand bits and the tensor scale g is a power of two).  The element rule is
+// round(e / (s g)) in real arithmetic, ties to the even code.  It is met through the correctly
+// rounded fp32 quotient y = fl32(e / step), step = s g: rounding is monotone and the seven
+// midpoints m are fp32 values, so y can only mislead by landing ON a midpoint while e != m step.
+// That needs |e - m step| / (m step) <= 2^-24 / significand(m), whereas two distinct fp32 values
+// near T = m step differ by at least 2^-23 / significand(T) of T (2^-24 just below a power of
+// two): impossible unless T is a power of two with significand(m) = 1, i.e. m = 0.25 and step a
+// power of two, where the division is exact anyway.  So no input changes a decision.
 #pragma once
 #include "common.h"
 
@@ -56,8 +62,9 @@ __device__ __forceinline__ float quot_rn(float x, float step, float r) {
 }
 
 // Quantize 16 values; returns the scale byte, writes 8 code bytes (low nibble = even element).
-// Element rule: y = fl32(x / (e4m3(scale) * g)) (IEEE fp32 quotient), code = nearest E2M1 value
-// of y, ties to the even code, magnitudes above 6 saturate, sign bit of x kept (also for zeros).
+// Element rule: code = nearest E2M1 value of x / (e4m3(scale) * g), ties to the even code, magnitudes
+// above 6 saturate, sign bit of x kept (also for zeros); taken on the correctly rounded fp32 quotient,
+// which decides exactly as real arithmetic does (see the head of this file).
 // The packed converter of gfx950 does the rounding, saturation and nibble packing for two values.
 __device__ __forceinline__ uint32_t quantize_block16(const float (&v)[16], QuantParams qp, uint2& codes) {
     float amax = 0.0f;
@@ -84,22 +91,28 @@ __device__ __forceinline__ uint32_t quantize_block16(const float (&v)[16], Quant
     return sc;
 }
 
-// Stochastically rounded variant (Sec. 4, FP4 Training).  Same block scale and the same fp32 quotient y
-// as above; a = min(|y|, 6) lies between two neighbouring E2M1 magnitudes lo <= a <= hi and goes up
-// with probability t = (a - lo) / (hi - lo): up iff u < t, u = (word >> 8) * 2^-24, word = Philox word
-// `first_word + i` of `stream` for element i.  The E2M1 spacing around a is w = 2^(max(exponent(a), 0) - 1)
-// (0.5 below 2, then 1, then 2), so with q = a / w (exact) lo = floor(q) w, t = q - floor(q) (exact), and the
-// chosen neighbour (floor(q) + up) w is a grid value, which the packed converter then encodes exactly.
-__device__ __forceinline__ float sr_pick(float y, uint32_t word) {
+// Stochastically rounded variant (Sec. 4, FP4 Training).  Same block scale; a = min(|x| / step, 6) in real
+// arithmetic lies between two neighbouring E2M1 magnitudes lo <= a < hi and goes up with probability
+// t = (a - lo) / (hi - lo): up iff u < t, u = (word >> 8) * 2^-24, word = Philox word `first_word + i` of
+// `stream` for element i.  Evaluated without rounding error: the correctly rounded quotient y locates lo
+// (the E2M1 spacing around y is w = 2^(max(exponent(y), 0) - 1): 0.5 below 2, then 1, then 2, and
+// lo = floor(y / w) w); rem = |x| - lo step is exact in fp32 (lo step has at most 6 significant bits and
+// |x| < 2 lo step) and never negative: by the argument at the head of this file y reaches a grid point only
+// when the true quotient is that grid point.  Then u < t  <=>  u w step < rem, decided by the sign of one
+// fused multiply-add, which is exact.  The chosen neighbour is a grid value, which the packed converter
+// encodes exactly.
+__device__ __forceinline__ float sr_pick(float x, float y, float step, uint32_t word) {
+    const float ax = fabsf(x);
     const float a = fminf(fabsf(y), 6.0f);
-    int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;      // floor(log2 a) for normal a; a < 1 -> e = 0
+    int e = (int)((__float_as_uint(a) >> 23) & 0xFFu) - 127;                   // floor(log2 a) for normal a; a < 1 -> e = 0
     e = e < 0 ? 0 : e;
     const float w = __uint_as_float((uint32_t)(126 + e) << 23);  // 2^(e-1)
     const float winv = __uint_as_float((uint32_t)(128 - e) << 23);   // 2^(1-e)
-    const float q = a * winv;
-    const float fl = floorf(q);
+    const float lo = floorf(a * winv) * w;
+    const float rem = __builtin_fmaf(-lo, step, ax);
     const float u = (float)(word >> 8) * 5.9604644775390625e-08f;    // 2^-24, exact
-    const float v = (fl + (u < q - fl ? 1.0f : 0.0f)) * w;
+    const bool up = __builtin_fmaf(-(u * w), step, rem) > 0.0f;
+    const float v = fminf(lo + (up ? w : 0.0f), 6.0f);           // at lo = 6 there is nowhere to go
     return __builtin_copysignf(v, y);
 }
 
@@ -115,10 +128,10 @@ __device__ __forceinline__ uint32_t quantize_block16_sr(const float (&v)[16], Qu
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const u32x4 rw = philox_block(seed, stream, (first_word >> 2) + b);
-        y[4 * b + 0] = sr_pick(quot_rn(v[4 * b + 0], step, r), rw.x);
-        y[4 * b + 1] = sr_pick(quot_rn(v[4 * b + 1], step, r), rw.y);
-        y[4 * b + 2] = sr_pick(quot_rn(v[4 * b + 2], step, r), rw.z);
-        y[4 * b + 3] = sr_pick(quot_rn(v[4 * b + 3], step, r), rw.w);
+        y[4 * b + 0] = sr_pick(v[4 * b + 0], quot_rn(v[4 * b + 0], step, r), step, rw.x);
+        y[4 * b + 1] = sr_pick(v[4 * b + 1], quot_rn(v[4 * b + 1], step, r), step, rw.y);
+        y[4 * b + 2] = sr_pick(v[4 * b + 2], quot_rn(v[4 * b + 2], step, r), step, rw.z);
+        y[4 * b + 3] = sr_pick(v[4 * b + 3], quot_rn(v[4 * b + 3], step, r), step, rw.w);
     }
     uint32_t w0 = 0u, w1 = 0u;
     w0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w0, y[0], y[1], 1.0f, 0);

@@ -42,6 +42,7 @@ _lib = None
 _SIGNATURES = {
     "metis_status_string": (C.c_char_p, [C.c_int]),
     "metis_version": (C.c_int, []),
+    "metis_tensor_scale": (C.c_float, [C.c_float]),
     "metis_sample_count": (C.c_int64, [C.c_int64, C.c_int, C.c_int, C.c_double]),
     "metis_sample_rows": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int64, C.c_void_p]),
     "metis_gaussian_omega": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int, C.c_void_p]),
@@ -151,6 +152,11 @@ class SplitTensor:
     def c(self):
         return Split(self.Ut.c() if self.Ut else _null_fp4(), self.Vt.c() if self.Vt else _null_fp4(),
                      self.R.c(), self.Rt.c() if self.Rt else _null_fp4(), self.S.data_ptr(), self.k)
+
+
+def tensor_scale(amax):
+    """Smallest power of two g with 6 * 448 * g >= amax (host helper of the library)."""
+    return float(lib().metis_tensor_scale(float(amax)))
 
 
 def sample_count(M, k, p, rho):

@@ -45,3 +45,19 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.metis_gaussian_omega(None, 1, 0, 4, None) == -1
     assert L.metis_quantize(None, None, None, None) == -1
     assert L.metis_quantize_sr(None, None, 0, None, None) == -1
+
+
+def test_tensor_scale_helper_is_the_smallest_covering_power_of_two():
+    from paper_2509_00404_amd import metis
+    if not os.path.exists(metis.LIB_PATH):
+        pytest.skip("library not built")
+    import numpy as np
+    ts = metis.tensor_scale
+    assert ts(6 * 448.0) == 1.0 and ts(6 * 448.0 + 1) == 2.0 and ts(1.0) == 2.0 ** -11
+    assert ts(0.0) == 1.0 and ts(-3.0) == 1.0 and ts(float("inf")) == 1.0 and ts(float("nan")) == 1.0
+    rs = np.random.default_rng(0)
+    for a in np.exp(rs.uniform(-40, 40, 2000)).astype(np.float32):
+        g = ts(float(a))
+        m, e = np.frexp(g)
+        assert m == 0.5                                            # a power of two
+        assert 2688.0 * g >= float(a) and 2688.0 * (g / 2) < float(a)

@@ -70,6 +70,30 @@ def test_every_scale_and_every_tie(metis):
     _check(metis, x * 2.0 ** -11, 2.0 ** -11)
 
 
+def test_fp32_inputs_within_a_few_ulp_of_every_threshold(metis):
+    # real-arithmetic round(e / (s g)): fp32 inputs k ulp (k = -3..3) from midpoint * s * g for every scale, with
+    # and without mantissa bits; the kernel's fp32 quotient must decide every one of them as exact arithmetic does
+    mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    for g in (1.0, 2.0 ** -11):
+        rows = []
+        for sidx in range(1, 127):
+            step = oq.E4M3_POS[sidx] * g
+            t = (mids * step).astype(np.float32)
+            for k in range(-3, 4):
+                v = (t.view(np.int32) + k).view(np.float32)
+                sign = -1.0 if (k + sidx) % 2 else 1.0
+                rows.append(np.concatenate([[6 * step], v * sign, -v * sign, [step]]).astype(np.float32))
+        x = torch.from_numpy(np.array(rows))
+        _check(metis, x, g)
+
+
+def test_fp32_random_mantissas_large(metis):
+    # two million fp32 values with full 24-bit significands spread over many block scales
+    rs = np.random.default_rng(99)
+    x = (rs.standard_normal((1024, 2048)) * np.exp(rs.uniform(-3, 3, (1024, 128)).repeat(16, axis=1))).astype(np.float32)
+    _check(metis, torch.from_numpy(x), oq.tensor_scale_for(float(np.abs(x).max())))
+
+
 def test_all_bf16_magnitudes(metis):
     # every finite non-negative bf16 pattern, shuffled into blocks
     bits = np.arange(0, 0x7F80, dtype=np.uint32)

@@ -55,6 +55,25 @@ def test_transposed_and_both(metis, M, N, dtype):
     _check(metis, x, g, seed=78, both=True)
 
 
+def test_draws_at_the_threshold_and_inputs_next_to_grid_points(metis):
+    # probability t = (|x|/(s g) - lo)/(hi - lo) in real arithmetic: fp32 inputs with full significands (t is not
+    # an fp32-rounded value) and inputs a few ulp around every grid point * s, many seeds' worth of draws
+    rs = np.random.default_rng(5)
+    rows = []
+    for sidx in range(9, 120, 3):
+        step = oq.E4M3_POS[sidx]
+        gridp = (oq.E2M1_GRID[1:] * step).astype(np.float32)
+        for k in (-2, -1, 0, 1, 2):
+            v = np.minimum((gridp.view(np.int32) + k).view(np.float32), np.float32(6 * step))
+            fill = (rs.uniform(0.0, 6.0, 8) * step).astype(np.float32)
+            rows.append(np.concatenate([[6 * step], v, -fill]).astype(np.float32))
+    x = torch.from_numpy(np.array(rows).repeat(16, axis=0))     # the same row under 16 different word offsets
+    for seed in (1, 2, 3):
+        _check(metis, x, 1.0, seed)
+    big = (rs.uniform(-6, 6, (2048, 1024)) * np.exp(rs.uniform(-2, 2, (2048, 64)).repeat(16, axis=1))).astype(np.float32)
+    _check(metis, torch.from_numpy(big), oq.tensor_scale_for(float(np.abs(big).max())), seed=123456789, both=True)
+
+
 def test_degenerate_blocks(metis):
     # all-zero blocks, signed zeros, grid points, saturated blocks (amax above 6*448*g)
     x = torch.zeros(16, 64)

@@ -73,14 +73,7 @@ def test_against_exact_rational_rounding_random():
                 blk = x[i, 16 * b:16 * b + 16]
                 sidx, mags = _exact_quantize_block(blk, g)
                 assert scales[i, b] == sidx
-                got = list(nib[i, 16 * b:16 * b + 16] & 7)
-                # the quotient is taken in fp32: it can only disagree with exact arithmetic when the
-                # exact quotient lies within an fp32 ulp of a rounding midpoint
-                step = quant.E4M3_POS[sidx] * g
-                for v, c_got, c_ref in zip(blk, got, mags):
-                    if c_got != c_ref:
-                        t = abs(v) / step
-                        assert min(abs(t - m) / m for m in quant.E2M1_MID) < 2.0 ** -22
+                assert list(nib[i, 16 * b:16 * b + 16] & 7) == mags
         assert np.array_equal(nib >> 3, np.signbit(x).astype(np.int64))
 
 
@@ -199,17 +192,60 @@ def test_ties_to_even_with_every_scale_mantissa():
         assert list(d[:8]) == [6.0, 0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0]
 
 
-def test_quotient_is_ieee_fp32_division():
-    # decision on y = fl32(x / step): place x one fp32 ulp around midpoint * step for a scale with mantissa
-    s = np.float32(quant.E4M3_POS[0x3B])             # 1.375
-    mid = np.float32(2.5) * s
-    for x in (np.nextafter(mid, np.float32(0)), mid, np.nextafter(mid, np.float32(10))):
-        blk = np.zeros(16, dtype=np.float32)
-        blk[0], blk[1] = np.float32(6) * s, x
-        codes, _ = quant.quantize(blk[None, :].astype(np.float64))
-        y = np.float32(x) / s
-        want = 4 if y <= np.float32(2.5) else 5          # 2.5 itself ties to the even code 4
-        assert (int(codes[0, 0]) >> 4) == want
+def test_one_ulp_either_side_of_every_midpoint_every_scale():
+    # round(e/s) in real arithmetic: an fp32 input one ulp below / on / one ulp above midpoint * s * g decides by its
+    # true side, for every E4M3 scale (with and without mantissa bits) -- checked against exact rationals
+    mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    below = [0, 1, 2, 3, 4, 5, 6]            # code just below each midpoint
+    even = [0, 2, 2, 4, 4, 6, 6]             # where a tie goes
+    for g in (1.0, 2.0 ** -11, 2.0 ** 5):
+        for sidx in range(1, 127):
+            s = quant.E4M3_POS[sidx] * g
+            t = (mids * s).astype(np.float32)
+            assert np.array_equal(t.astype(np.float64), mids * s)      # thresholds are fp32 values
+            for delta, want in ((-1, below), (0, even), (1, [b + 1 for b in below])):
+                blk = np.zeros(16)
+                blk[0] = 6.0 * s
+                v = t if delta == 0 else np.nextafter(t, np.float32(np.inf if delta > 0 else 0))
+                blk[1:8] = v.astype(np.float64)
+                blk[8:15] = -blk[1:8]
+                codes, scales = quant.quantize(blk[None, :], g)
+                assert scales[0, 0] == sidx
+                nib = _nibbles(codes)[0]
+                assert list(nib[1:8]) == want and list(nib[8:15] & 7) == want and np.all(nib[8:15] >> 3 == 1)
+                ref_s, ref_c = _exact_quantize_block(blk, g)
+                assert ref_s == sidx and list(nib & 7) == ref_c
+
+
+def test_correctly_rounded_fp32_quotient_never_changes_a_decision():
+    # Property the GPU quantizer relies on: for fp32 inputs, rounding the IEEE fp32 quotient x / (s g) to the E2M1 grid
+    # (ties to even) takes the same decisions as the exact rule.  fl32(x/step) can equal a midpoint m with x != m step
+    # only if two fp32 neighbours of m step are closer than m's own half-ulp relative spacing, which would need
+    # significand(m step) >= 2 significand(m).  Checked here on the fp32 neighbours of every threshold and at random.
+    rs = np.random.default_rng(7)
+    mids32 = quant.E2M1_MID.astype(np.float32)
+
+    def by_quotient(x32, step32):
+        y = np.abs(x32 / step32).astype(np.float32)
+        mag = np.zeros(y.shape, dtype=np.int64)
+        for j, m in enumerate(mids32):
+            mag += (y >= m) if (j + 1) % 2 == 0 else (y > m)
+        return mag
+
+    for g in (1.0, 2.0 ** -11):
+        for sidx in range(1, 127):
+            step = np.float32(quant.E4M3_POS[sidx] * g)
+            t = mids32 * step
+            x = np.concatenate([t, np.nextafter(t, np.float32(0)), np.nextafter(t, np.float32(np.inf)),
+                                (rs.uniform(0, 6, 57) * float(step)).astype(np.float32)])
+            x[0] = np.float32(6) * step
+            got = by_quotient(x, step)
+            for i in range(0, x.size, 16):
+                blk = x[i:i + 16].astype(np.float64).copy()
+                blk[0] = 6.0 * float(step)
+                ref_s, ref_c = _exact_quantize_block(blk, g)
+                assert ref_s == sidx
+                assert list(got[i + 1:i + 16]) == ref_c[1:]
 
 
 # ---------------------------------------------------------------------------------------------
@@ -236,10 +272,10 @@ def test_sr_result_is_one_of_the_two_neighbours_and_grid_points_stay():
     g = 2.0 ** -3
     codes, scales = oq.quantize_sr(x, g, seed=3)
     step = np.repeat(oq.e4m3_value(scales) * g, 16, axis=1)
-    y = np.abs((x.astype(np.float32) / step.astype(np.float32)).astype(np.float64))
+    y = np.minimum(np.abs(x) / step, 6.0)            # fp64 quotient: off by 1e-16, far from any grid point here
     q = _deq_mag(codes, scales, g) / step
-    lo = oq.E2M1_GRID[np.searchsorted(oq.E2M1_GRID, np.minimum(y, 6.0), side="right") - 1]
-    hi = oq.E2M1_GRID[np.minimum(np.searchsorted(oq.E2M1_GRID, np.minimum(y, 6.0), side="left"), 7)]
+    lo = oq.E2M1_GRID[np.searchsorted(oq.E2M1_GRID, y, side="right") - 1]
+    hi = oq.E2M1_GRID[np.minimum(np.searchsorted(oq.E2M1_GRID, y, side="left"), 7)]
     assert np.all((q == lo) | (q == hi))
     # values that already sit on the grid never move, whatever the draw
     grid_vals = np.tile(np.concatenate([oq.E2M1_GRID, -oq.E2M1_GRID]), (4, 1))     # amax 6 -> scale 1
@@ -277,7 +313,7 @@ def test_sr_is_unbiased_and_uses_the_pinned_philox_stream():
     # draws are the words of stream 3 at the elements' row-major positions
     w = orng.philox_words(2024, oq.STREAM_SR, 0, x.size).reshape(x.shape)
     u = (w >> 8) * 2.0 ** -24
-    assert np.array_equal(d == 3.0, (u < np.float64(np.float32(val) - 2.0))[:, 1:])
+    assert np.array_equal(d == 3.0, (2.0 + u < val)[:, 1:])
     # another seed or the transposed copy's stream gives other draws
     c2, _ = oq.quantize_sr(x, 1.0, seed=2025)
     c3, _ = oq.quantize_sr(x, 1.0, seed=2024, stream=oq.STREAM_SR_T)
@@ -291,3 +327,61 @@ def test_sr_expected_error_beats_rne_bias_on_a_constant():
     c_sr, s_sr = oq.quantize_sr(x, 1.0, seed=9)
     assert np.all(oq.dequantize(c_rne, s_rne, 1.0)[:, 1:] == 2.0)
     assert abs(oq.dequantize(c_sr, s_sr, 1.0)[:, 1:].mean() - 2.4) < 0.01
+
+
+def _exact_sr_block(block, g, words):
+    """Stochastic rounding with exact rationals: scale as for nearest rounding; a = |e|/(s g) clipped at 6;
+    between grid neighbours lo <= a < hi go up iff u < (a - lo)/(hi - lo), u = (word >> 8) / 2^24."""
+    fr = [Fraction(float(v)) for v in block]
+    sidx, _ = _exact_quantize_block(block, g)
+    step = Fraction(float(quant.E4M3_POS[sidx])) * Fraction(float(g))
+    grid = [Fraction(float(v)) for v in quant.E2M1_GRID]
+    mags = []
+    for v, w in zip(fr, words):
+        if step == 0:
+            mags.append(0)
+            continue
+        a = min(abs(v) / step, Fraction(6))
+        lo_i = max(i for i in range(8) if grid[i] <= a)
+        if lo_i == 7:
+            mags.append(7)
+            continue
+        t = (a - grid[lo_i]) / (grid[lo_i + 1] - grid[lo_i])
+        u = Fraction(int(w) >> 8, 2 ** 24)
+        mags.append(lo_i + 1 if u < t else lo_i)
+    return sidx, mags
+
+
+def test_sr_against_exact_rationals_random_and_at_the_threshold():
+    rs = np.random.default_rng(8)
+    for g in (1.0, 2.0 ** -11):
+        x = (rs.standard_normal((24, 32)) * np.exp(rs.uniform(-6, 6, (24, 1))) * g).astype(np.float32).astype(np.float64)
+        w = rs.integers(0, 2 ** 32, x.shape, dtype=np.uint64).astype(np.uint32)
+        codes, scales = oq.quantize_sr(x, g, seed=0, words=w)
+        nib = _nibbles(codes)
+        for i in range(x.shape[0]):
+            for b in range(2):
+                sl = slice(16 * b, 16 * b + 16)
+                sidx, mags = _exact_sr_block(x[i, sl], g, w[i, sl])
+                assert scales[i, b] == sidx and list(nib[i, sl] & 7) == mags
+    # draws placed on the threshold of each element: floor(t 2^24) is the last u that does not go up ... unless t 2^24
+    # is an integer, in which case u == t does not go up either (strict comparison); one below always goes up
+    for sidx in (0x38, 0x3B, 0x45, 0x1D):
+        s = float(quant.E4M3_POS[sidx])
+        blk = (rs.uniform(0.01, 5.99, 16) * s).astype(np.float32).astype(np.float64)
+        blk[0] = 6.0 * s
+        step = Fraction(s)
+        grid = [Fraction(float(v)) for v in quant.E2M1_GRID]
+        words_hi, words_lo = [], []
+        for v in blk:
+            a = min(Fraction(float(v)) / step, Fraction(6))
+            lo_i = max(i for i in range(8) if grid[i] <= a)
+            t = (a - grid[lo_i]) / (grid[min(lo_i + 1, 7)] - grid[lo_i]) if lo_i < 7 else Fraction(0)
+            n = (t * 2 ** 24).__ceil__()                       # smallest integer n with n / 2^24 >= t
+            words_lo.append((max(n - 1, 0) << 8) & 0xFFFFFFFF)  # u < t (when t > 0): up
+            words_hi.append((min(n, 2 ** 24 - 1) << 8) | 0xFF)  # u >= t: stays (unless clipped at the top draw)
+        for words in (words_lo, words_hi):
+            wa = np.array(words, dtype=np.uint32)[None, :]
+            c, sc = oq.quantize_sr(blk[None, :], 1.0, seed=0, words=wa)
+            ref_s, ref_m = _exact_sr_block(blk, 1.0, wa[0])
+            assert sc[0, 0] == ref_s == sidx and list(_nibbles(c)[0] & 7) == ref_m
