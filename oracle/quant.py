@@ -50,7 +50,7 @@ def quantize(x, g=1.0):
     assert cols % BLOCK == 0
     xb = x.reshape(rows, cols // BLOCK, BLOCK)
     amax = np.abs(xb).max(axis=2)
-    # smallest E4M3 value s with 6*s*g >= amax  ("rounded up ... to ensure coverage")
+    # smallest E4M3 value s with 6*s*g >= amax: the scale rounds upward so the block maximum is covered (Sec. 2.3)
     cover = 6.0 * E4M3_POS * g
     sidx = np.searchsorted(cover, amax, side="left")
     sidx = np.minimum(sidx, 126)                    # saturate at 448

@@ -19,9 +19,6 @@
 // replaced by 1e-300 and its 1-based index is written to *info (CholeskyQR2's rank check).
 // ---------------------------------------------------------------------------------------
 typedef double double4_t __attribute__((ext_vector_type(4)));
-#ifdef JAC_PROF
-__device__ long long g_prof[40];
-#endif
 
 __device__ __forceinline__ double chol_rsqrt(double x) {
     double y = __builtin_amdgcn_rsq(x);
@@ -35,12 +32,6 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
                              int32_t* __restrict__ info) {
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
-#ifdef JAC_PROF
-    long long ca = 0, cc = 0, c0 = clock64();
-#define CH_MARK(acc) { long long c1 = clock64(); acc += c1 - c0; c0 = c1; }
-#else
-#define CH_MARK(acc)
-#endif
     static_assert(CB % 4 == 0, "the trailing update takes the block in chunks of the matrix instruction's depth");
     for (int k0 = 0; k0 < n; k0 += CB) {
         // ---- 1: diagonal block (entries past n act as an identity block) and the rows below ----
@@ -101,7 +92,6 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
                     for (int c = 0; c <= q; ++c) W[(size_t)(k0 + c) * ld + k0 + q] = d[q][c];
                 }
         }
-        CH_MARK(ca)
         if (n - k0 <= CB) break;
         // ---- 2: trailing update A22 -= L21 L21^T over the 16-aligned lower tiles that reach past k0 + CB ----
         const int t0 = (k0 + CB) & ~15;
@@ -129,12 +119,8 @@ __device__ void chol_blocked(double* __restrict__ W, int ld, int n, double* __re
             }
         }
         __syncthreads();
-        CH_MARK(cc)
     }
     __syncthreads();                                     // the last block's rows are visible to the caller
-#ifdef JAC_PROF
-    if (tid == 0) { g_prof[14] = ca; g_prof[15] = cc; }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------
@@ -174,21 +160,12 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
         X[i * ld + j] = 0.0;
     }
     __syncthreads();
-#ifdef JAC_PROF
-    const long long ci0 = clock64();
-#endif
     chol_blocked<false>(L, ld, n, dinv, 0.0, info);
-#ifdef JAC_PROF
-    const long long ci1 = clock64();
-#endif
     if (wellcond_out && tid == 0) {
         double lo = dinv[0], hi = dinv[0];
         for (int j = 1; j < n; ++j) { lo = fmin(lo, dinv[j]); hi = fmax(hi, dinv[j]); }
         *wellcond_out = (hi <= 1e3 * lo) ? 1 : 0;        // a replaced pivot has dinv = 1e150 and fails this
     }
-#ifdef JAC_PROF
-    if (tid == 0) g_prof[38] = clock64() - ci1;
-#endif
     // L^-1 by 16 x 16 blocks.  The diagonal blocks are inverted by substitution (one thread per column, 16 steps in
     // registers); then, one block sub-diagonal after the other, X_ij = -X_ii (sum_k L_ik X_kj) on the fp64 matrix
     // cores, one wave per block.  The inner sum leaves the matrix instruction in exactly the register layout that
@@ -218,9 +195,6 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
             }
         }
         __syncthreads();
-#ifdef JAC_PROF
-        if (tid == 0) g_prof[39] = clock64() - ci1;
-#endif
         const int r16 = lane & 15, kq = lane >> 4;
         for (int d = 1; d < T; ++d) {
             for (int blk0 = 0; blk0 < T - d; blk0 += nwaves) {
@@ -255,9 +229,6 @@ k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32
         }
     }
     __syncthreads();
-#ifdef JAC_PROF
-    if (tid == 0) { g_prof[36] = ci1 - ci0; g_prof[37] = clock64() - ci1; }
-#endif
     for (int e = tid; e < n * n; e += 1024) {
         int i = e / n, j = e - i * n;
         Linv[e] = X[i * ld + j];
@@ -458,12 +429,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     __shared__ unsigned long long err_s;
     __shared__ int fail_s;
 
-#ifdef JAC_PROF
-    long long pc0 = clock64(), pcs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define PRE_MARK(i) { long long c1 = clock64(); pcs[i] += c1 - pc0; pc0 = c1; }
-#else
-#define PRE_MARK(i)
-#endif
     // ---- 0: L to global scratch (R1 is reused for the eigenvectors) ----
     for (size_t e = tid; e < rsize; e += nthr) gscr[e] = R1[e];
     if (tid == 0) fail_s = 0;
@@ -488,8 +453,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
     // ---- 1: A = L^T L ----
     gram_to_R2(R1, ld, false);                    // the factor's column stride suits the sweeps, not these reads: no batching
     __syncthreads();
-
-    PRE_MARK(1)
     // ---- 2: tridiagonalisation (lower), row r on lanes q = 0..7, columns q, q+8, ... in registers.
     //         Step j, two barriers: every live wave forms the reflector's scalars and its own pieces of v from
     //         column j (xx) | p_r = A[r][:] v and the wave's share of v^T A v || rank-2 update, then column j+1
@@ -599,8 +562,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         if (tid == 0) { tauv[n - 2] = 0.0; tauv[n - 1] = 0.0; ee[n - 1] = 0.0; }
         __syncthreads();
     }
-
-    PRE_MARK(2)
     // ---- 3: eigenvalues of T.  Scale T by a power of two so that |d| + 2|e| <= 1, then multisection ----
     {
         if (wave == 0) {
@@ -663,8 +624,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         }
         __syncthreads();
     }
-
-    PRE_MARK(3)
     // ---- 4: eigenvectors of T by twisted factorisation, thread i -> column i of Z (R1, column-major, lda) ----
     const bool early_fail = fail_s != 0;          // uniform: read after a barrier
     if (tid < n && !early_fail) {
@@ -717,8 +676,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         for (int k = 0; k < n; ++k) z[k] *= rn;
     }
     __syncthreads();
-
-    PRE_MARK(4)
     // ---- 5: P = H_0 H_1 ... H_{n-3} Z, column c on lanes q = 0..7.  Reflector j is zero in rows 0 .. j, so the
     //         register blocks e < (j+1)/8 are skipped (one instantiation of the inner loop per first block) ----
     {
@@ -735,12 +692,8 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         }
     }
     __syncthreads();
-
-    PRE_MARK(5)
     // ---- 6: orthogonality check and Newton-Schulz polish ----
     bool ok = fail_s == 0;
-    double err_first = -1.0;
-    int polish_its = 0;
     for (int it = 0; it < 4 && ok; ++it) {
         if (tid == 0) err_s = 0ull;
         gram_to_R2(R1, lda, true);                // E + I = P^T P
@@ -755,8 +708,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         __syncthreads();
         const double err = __longlong_as_double((long long)err_s);
         __syncthreads();
-        if (it == 0) err_first = err;
-        polish_its = it + 1;
         if (!(err < 0.03)) { ok = false; break; }
         if (err < 1e-10) break;
         if (it == 3) { ok = false; break; }
@@ -789,8 +740,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         __syncthreads();
         if (last) break;
     }
-
-    PRE_MARK(6)
     // ---- 7: W0 = L P into R2 (or L itself when the preconditioner was dropped) ----
     __syncthreads();
     for (size_t e = tid; e < rsize; e += nthr) R2[e] = ok ? 0.0 : gscr[e];
@@ -811,14 +760,6 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
         }
     }
     __syncthreads();
-    PRE_MARK(7)
-    (void)err_first; (void)polish_its;
-#ifdef JAC_PROF
-    if (tid == 0) {
-        for (int i2 = 0; i2 < 8; ++i2) g_prof[i2] = pcs[i2];
-        g_prof[8] = ok; g_prof[9] = polish_its; g_prof[10] = (long long)(err_first * 1e15);
-    }
-#endif
 }
 
 // One-sided Jacobi on the Cholesky factor of G.  JGL lanes share a pair of columns, NE = ceil(n / JGL)
@@ -855,9 +796,6 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     __shared__ double amax_sh;
     const int tid = threadIdx.x, nthr = blockDim.x, grp = tid / JGL, gl = tid % JGL;
 
-#ifdef JAC_PROF
-    const long long pt0 = clock64();
-#endif
     for (int e = tid; e < (ne + 1) * ld; e += nthr) {
         int p = e / ld, i = e - p * ld;
         W[e] = (p < n && i < n) ? G[(size_t)i * n + p] : 0.0;
@@ -879,13 +817,7 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             piv_floor = m * 1e-30;
         }
         __syncthreads();
-#ifdef JAC_PROF
-        const long long pt1 = clock64();
-#endif
         chol_blocked<true>(W, ld, n, rinv_sh, piv_floor, nullptr);
-#ifdef JAC_PROF
-        if (tid == 0) { g_prof[12] = pt1 - pt0; g_prof[13] = clock64() - pt1; }
-#endif
         // the rotations work on whole columns: clear the part above the diagonal
         for (int e = tid; e < n * n; e += nthr) {
             const int c = e / n, i = e - c * n;
@@ -894,14 +826,8 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
         __syncthreads();
     }
     if (gscr) {
-#ifdef JAC_PROF
-        const long long pq0 = clock64();
-#endif
         eig_precondition<NE>(sm, sm + rsize, ld, n, ne, gscr, pre_sa);
         W = sm + rsize;
-#ifdef JAC_PROF
-        if (tid == 0) g_prof[11] = clock64() - pq0;
-#endif
     }
 
     // Rotate while gamma^2 > tol^2 alpha beta + (c eps)^2 amax (alpha + beta), tol = 1e-7: the
@@ -1053,9 +979,6 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
             nact_sh = total + (total & 1);
         }
         __syncthreads();
-#ifdef JAC_PROF
-        if (tid == 0 && sweep < 8) { g_prof[16 + 2 * sweep] = m; g_prof[17 + 2 * sweep] = total; }
-#endif
         if (total == 0) break;
     }
     // column norms = singular values of L = square roots of the eigenvalues

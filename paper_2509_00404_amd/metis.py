@@ -325,8 +325,10 @@ class KernelTimer:
         self.hip = C.CDLL("libamdhip64.so")
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
         self.hip.hipEventCreate.restype = C.c_int
         self.hip.hipEventElapsedTime.restype = C.c_int
+        self.hip.hipEventDestroy.restype = C.c_int
         self.start = (C.c_void_p * n)()
         self.stop = (C.c_void_p * n)()
         for arr in (self.start, self.stop):
@@ -342,6 +344,21 @@ class KernelTimer:
 
     def __exit__(self, *exc):
         _check(lib().metis_profile_events(self.kernel_id, None, None, 0))
+
+    def close(self):
+        """Destroy the events (after the last durations_ms call)."""
+        for arr in (self.start, self.stop):
+            for i in range(self.n):
+                if arr[i]:
+                    self.hip.hipEventDestroy(arr[i])
+                    arr[i] = None
+        self.n = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def durations_ms(self, count):
         """Durations of the last `count` (<= n) bracketed launches; call after a device sync."""
