@@ -29,7 +29,8 @@ typedef enum {
     METIS_BAD_SHAPE = -2,        /* quantized axis not a multiple of 16, k+p too large, mismatched operands */
     METIS_WORKSPACE_TOO_SMALL = -3,
     METIS_HIP_ERROR = -4,        /* a launch failed; hipGetLastError() has the reason */
-    METIS_UNSUPPORTED = -5       /* size outside what the kernels are built for (e.g. k+p > 128) */
+    METIS_UNSUPPORTED = -5,      /* size outside what the kernels are built for (e.g. k+p > 128) */
+    METIS_SCRATCH_TOO_SMALL = -6 /* the input needs more than the library's built-in scratch array holds */
 } metis_status;
 
 enum { METIS_BF16 = 0, METIS_F32 = 1 };
@@ -171,6 +172,23 @@ size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k);
 int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S,
                          const float* V, int k, metis_split* out, float* R_debug,
                          void* workspace, size_t workspace_bytes);
+
+/*
+ * metis_split_quantize for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments minus
+ * the workspace, same kernels, same results bit for bit.  The factor staging (-U S and V as bf16 pairs,
+ * metis_split_workspace_bytes(M, N, k) bytes) lives in an array built into the library,
+ * METIS_SPLIT_STATIC_SCRATCH_BYTES per GPU, held until the process ends; an input that needs more
+ * returns METIS_SCRATCH_TOO_SMALL before anything is enqueued ((M + N) * 4 * k' <= 8 MiB with k' = k
+ * rounded up to 16/32/64/128: e.g. 16384 x 14336 at k = 64 fits).  The call itself allocates nothing
+ * and never synchronises.  All calls on one GPU share that GPU's array: calls that may overlap on one
+ * GPU (different streams, concurrent graph branches) race on it and must be serialised by the caller;
+ * calls on one stream are ordered and safe.  Nothing in the array needs clearing between calls (every
+ * byte read is rewritten first by the same call).
+ */
+#define METIS_SPLIT_STATIC_SCRATCH_BYTES (8u << 20)
+int metis_split_quantize_static(void* stream, const metis_mat* A, const float* U, const float* S,
+                                const float* V, int k, metis_split* out, float* R_debug);
 
 /*
  * Stochastically rounded split (Sec. 4, "FP4 Training"): as metis_split_quantize, with every

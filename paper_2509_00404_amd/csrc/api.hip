@@ -10,6 +10,7 @@ extern "C" const char* metis_status_string(int status) {
         case METIS_WORKSPACE_TOO_SMALL: return "workspace too small";
         case METIS_HIP_ERROR: return "HIP launch error";
         case METIS_UNSUPPORTED: return "unsupported size or dtype";
+        case METIS_SCRATCH_TOO_SMALL: return "input exceeds the built-in scratch array";
         default: return "unknown status";
     }
 }

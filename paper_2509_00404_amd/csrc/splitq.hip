@@ -466,6 +466,30 @@ extern "C" int metis_split_quantize_sr(void* stream, const metis_mat* A, const f
     return split_quantize_impl<true>(stream, A, U, S, V, k, seed, out, R_debug, workspace, workspace_bytes);
 }
 
+// ---- variant for callers that cannot allocate ---------------------------------------------------------------
+// Same kernels; the bf16 factor staging lives in a file-scope device array instead of a caller workspace.  Each
+// GPU holds its own copy of the array at its own address: the address is looked up once per device (with that
+// device current) and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[METIS_SPLIT_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[64];          // per device; a race between first calls only repeats the lookup
+
+extern "C" int metis_split_quantize_static(void* stream, const metis_mat* A, const float* U, const float* S,
+                                           const float* V, int k, metis_split* out, float* R_debug) {
+    if (!A || k < 1 || k > 128) return METIS_INVALID_ARG;
+    const size_t need = metis_split_workspace_bytes(A->rows, A->cols, k);
+    if (need == 0) return METIS_BAD_SHAPE;
+    if (need > (size_t)METIS_SPLIT_STATIC_SCRATCH_BYTES) return METIS_SCRATCH_TOO_SMALL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return METIS_HIP_ERROR;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return METIS_HIP_ERROR;
+        g_scratch_ptr[dev] = ptr;
+    }
+    // every byte the kernels read is rewritten by k_split_factors first: nothing has to start at zero
+    return split_quantize_impl<false>(stream, A, U, S, V, k, 0, out, R_debug, g_scratch_ptr[dev], need);
+}
+
 // Split of a weight whose factors and residual are stored variables (Sec. 3.2): nothing is subtracted,
 // the three parts go through the quantizer as they are and S is copied.
 template <bool SR>

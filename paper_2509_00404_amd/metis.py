@@ -55,6 +55,8 @@ _SIGNATURES = {
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
+    "metis_split_quantize_static": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_int, C.POINTER(Split), C.c_void_p]),
     "metis_split_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_int, C.c_uint64, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
     "metis_split_from_parts": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
@@ -232,6 +234,17 @@ def split_quantize(A, U, S, V, out, R_debug=None, workspace=None):
     _check(lib().metis_split_quantize(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
                                       out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None,
                                       workspace.data_ptr(), workspace.numel()))
+
+
+SPLIT_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def split_quantize_static(A, U, S, V, out, R_debug=None):
+    """split_quantize on the library's built-in scratch array (no workspace, no allocation)."""
+    a = _mat(A)
+    s = out.c()
+    _check(lib().metis_split_quantize_static(_stream(), C.byref(a), U.data_ptr(), S.data_ptr(), V.data_ptr(),
+                                             out.k, C.byref(s), R_debug.data_ptr() if R_debug is not None else None))
 
 
 def split_quantize_sr(A, U, S, V, seed, out, R_debug=None, workspace=None):
