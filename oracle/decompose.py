@@ -18,11 +18,13 @@ import numpy as np
 from . import rng
 
 
-def decompose(A, k, p, rho, seed, idx=None, omega=None):
+def decompose(A, k, p, rho, seed, idx=None, omega=None, details=None):
     """A[M,N] fp64 -> U[M,k], S[k], V[N,k].
 
     idx / omega override the seeded draws (used to feed identical draws to two
-    implementations)."""
+    implementations).  details (optional dict) receives by-products for reports:
+    'sigma_reduced' = all k+p singular values of the reduced matrix B, whose gap
+    between positions k and k+1 says how well defined the selected subspace is."""
     A = np.asarray(A, dtype=np.float64)
     M, N = A.shape
     r = k + p
@@ -35,7 +37,9 @@ def decompose(A, k, p, rho, seed, idx=None, omega=None):
     Z = As @ omega                        # sketch Z = X Omega
     H, _ = np.linalg.qr(Z)                # thin QR, Z = H R
     B = H.T @ As                          # reduced matrix  (r x N)
-    _, _, Vt = np.linalg.svd(B, full_matrices=False)
+    _, sB, Vt = np.linalg.svd(B, full_matrices=False)
+    if details is not None:
+        details["sigma_reduced"] = sB
     V0 = Vt[:k, :].T                      # top-k subspace in the reduced space
     C = A @ V0                            # broadcast to the full batch
     U, S, Wt = np.linalg.svd(C, full_matrices=False)

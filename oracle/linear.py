@@ -106,20 +106,26 @@ def assemble(sq, transposed_residual=False):
     return (Ub * sq.S) @ Vb.T + Rb
 
 
-def linear_fwd(xq, wq):
-    """Y = Xbar Wbar^T; contraction over K: X_R and W_R blocked along K."""
-    return assemble(xq) @ assemble(wq).T
+def _take(M, rows):
+    return M if rows is None else M[np.asarray(rows)]
 
 
-def linear_dgrad(gq, wq):
+def linear_fwd(xq, wq, rows=None):
+    """Y = Xbar Wbar^T; contraction over K: X_R and W_R blocked along K.
+    rows (optional): only these rows of Y (the same product, fewer output rows)."""
+    return _take(assemble(xq), rows) @ assemble(wq).T
+
+
+def linear_dgrad(gq, wq, rows=None):
     """dX = Gbar Wbar; contraction over N: G_R blocked along N (its columns),
-    W_R blocked along N (its rows -> Rt)."""
-    return assemble(gq) @ assemble(wq, transposed_residual=True)
+    W_R blocked along N (its rows -> Rt).  rows: only these rows of dX."""
+    return _take(assemble(gq), rows) @ assemble(wq, transposed_residual=True)
 
 
-def linear_wgrad(gq, xq):
-    """dW = Gbar^T Xbar; contraction over L: both residuals blocked along rows."""
-    return assemble(gq, transposed_residual=True).T @ assemble(xq, transposed_residual=True)
+def linear_wgrad(gq, xq, rows=None):
+    """dW = Gbar^T Xbar; contraction over L: both residuals blocked along rows.
+    rows: only these rows of dW."""
+    return _take(assemble(gq, transposed_residual=True).T, rows) @ assemble(xq, transposed_residual=True)
 
 
 def factor_grads(dW, wq):

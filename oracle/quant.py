@@ -120,16 +120,18 @@ def quantize_sr(x, g, seed, stream=STREAM_SR, words=None):
     return codes, sidx.astype(np.uint8)
 
 
+# value of each nibble (sign << 3 | magnitude code), and of both nibbles of each code byte (low nibble first)
+_NIBBLE_VALUE = E2M1_GRID[np.arange(16) & 7] * np.where(np.arange(16) & 8, -1.0, 1.0)
+_BYTE_VALUES = np.stack([_NIBBLE_VALUE[np.arange(256) & 15], _NIBBLE_VALUE[np.arange(256) >> 4]], axis=1)
+
+
 def dequantize(codes, scales, g=1.0):
     """Inverse map: fp64 matrix [rows, cols] of grid * s * g."""
-    codes = np.asarray(codes, dtype=np.int64)
+    codes = np.asarray(codes).astype(np.uint8, copy=False)
     rows, half = codes.shape
-    nib = np.empty((rows, half * 2), dtype=np.int64)
-    nib[:, 0::2] = codes & 15
-    nib[:, 1::2] = codes >> 4
-    val = E2M1_GRID[nib & 7] * np.where(nib & 8, -1.0, 1.0)
+    val = _BYTE_VALUES[codes].reshape(rows, half * 2 // BLOCK, BLOCK)    # element 2j = low nibble of byte j
     s = e4m3_value(scales) * g
-    return val * np.repeat(s, BLOCK, axis=1)
+    return (val * s[:, :, None]).reshape(rows, half * 2)
 
 
 def tensor_scale_for(amax, headroom=1.0):

@@ -110,10 +110,26 @@ def config(c):
     if c == 4:
         return dict(W=weight(4096, 14336, seed_for(4, 0)), X=activation(8192, 14336, seed_for(4, 1)),
                     G=gradient(8192, 4096, seed_for(4, 2)))
-    raise ValueError("config must be 1..4 (config 5 is built by layer_linears)")
+    raise ValueError("config must be 1..4 (config 5 is built per linear by layer_linear)")
 
 
-def layer_linears(L=16384):
-    """Config 5: (name, N, K) of one LLaMA-3-8B layer's seven linears."""
-    return [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o", 4096, 4096),
-            ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
+# Config 5: (name, N, K) of one LLaMA-3-8B layer's seven linears (k and v are 1024 wide under GQA)
+LAYER_LINEARS = [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o", 4096, 4096),
+                 ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
+LAYER_TOKENS = 16384
+
+
+def layer_linear(name, L=LAYER_TOKENS):
+    """One linear of config 5 as an independent (X, W, G) triple with its own seeds:
+    W[N,K] (alpha = 1.0), X[L,K] (alpha = 1.2, outlier channels), G[L,N] (alpha = 2.0, top-4 x100).
+    Tensor ids 10 i + {0: W, 1: X, 2: G} for the i-th linear, so seed_for(5, id) + 7 is its library seed."""
+    i = [n for n, _, _ in LAYER_LINEARS].index(name)
+    _, N, K = LAYER_LINEARS[i]
+    return dict(W=weight(N, K, seed_for(5, 10 * i)), X=activation(L, K, seed_for(5, 10 * i + 1)),
+                G=gradient(L, N, seed_for(5, 10 * i + 2)))
+
+
+def layer_seed(name, tensor):
+    """Library seed of tensor 'W' / 'X' / 'G' of config 5's linear `name`."""
+    i = [n for n, _, _ in LAYER_LINEARS].index(name)
+    return seed_for(5, 10 * i + "WXG".index(tensor)) + 7

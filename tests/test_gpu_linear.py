@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from oracle import linear as olin
-from gpu_helpers import make_split, rel_fro, split_to_oracle
+from gpu_helpers import elementwise_bound, make_split, operand_parts, rel_fro, split_to_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -37,9 +37,16 @@ def _three(metis, X, W, G, kx, kw, kg, p, rho, out_dtype=torch.bfloat16):
     metis.fp4_linear_wgrad(gs, xs, dW, wsb)
     torch.cuda.synchronize()
     xo, wo, go = split_to_oracle(xs), split_to_oracle(ws), split_to_oracle(gs)
-    e = (rel_fro(Y.double().cpu().numpy(), olin.linear_fwd(xo, wo)),
-         rel_fro(dX.double().cpu().numpy(), olin.linear_dgrad(go, wo)),
-         rel_fro(dW.double().cpu().numpy(), olin.linear_wgrad(go, xo)))
+    refs = (olin.linear_fwd(xo, wo), olin.linear_dgrad(go, wo), olin.linear_wgrad(go, xo))
+    gots = tuple(t.double().cpu().numpy() for t in (Y, dX, dW))
+    e = tuple(rel_fro(g, r) for g, r in zip(gots, refs))
+    # element by element as well, so that a wrong row or tile cannot hide in the norm
+    operands = ((operand_parts(xo), operand_parts(wo)),
+                (operand_parts(go), operand_parts(wo, transposed=True)),
+                (operand_parts(go, transposed=True), operand_parts(xo, transposed=True)))
+    for name, g, r, (a, b) in zip(("fwd", "dgrad", "wgrad"), gots, refs, operands):
+        worst = float((np.abs(g - r) / elementwise_bound(a, b, r, out_dtype)).max())
+        assert worst <= 1.0, (name, worst)
     return e, (Y, dX, dW), (xo, wo, go)
 
 
@@ -53,8 +60,11 @@ def test_config1_forward(metis):
     Y = torch.empty((128, 256), dtype=torch.bfloat16, device="cuda")
     metis.fp4_linear_fwd(xs, ws, Y, wsb)
     torch.cuda.synchronize()
-    ref = olin.linear_fwd(split_to_oracle(xs), split_to_oracle(ws))
-    assert rel_fro(Y.double().cpu().numpy(), ref) < GEMM_RTOL
+    xo, wo = split_to_oracle(xs), split_to_oracle(ws)
+    ref = olin.linear_fwd(xo, wo)
+    got = Y.double().cpu().numpy()
+    assert rel_fro(got, ref) < GEMM_RTOL
+    assert (np.abs(got - ref) <= elementwise_bound(operand_parts(xo), operand_parts(wo), ref, torch.bfloat16)).all()
     # and the quantized product is a faithful approximation of the bf16 one (FP4: ~10 %)
     exact = X.double().numpy() @ W.double().numpy().T
     assert rel_fro(ref, exact) < 0.2

@@ -137,3 +137,19 @@ def test_fix_signs():
     U2, V2 = dec.fix_signs(U, V)
     assert np.all(V2[np.abs(V2).argmax(axis=0), np.arange(3)] > 0)
     assert np.allclose(U2 @ V2.T, U @ V.T)
+
+
+def test_reduced_spectrum_report():
+    # rho = 1 and k + p = min(M, N): the reduced matrix has the singular values of A itself
+    rs = np.random.default_rng(21)
+    A = _planted(rs, 40, 24, np.linspace(5.0, 0.1, 24))
+    d = {}
+    dec.decompose(A, 16, 8, 1.0, seed=3, details=d)
+    assert np.allclose(d["sigma_reduced"], np.linalg.svd(A, compute_uv=False), rtol=1e-10)
+    # in general they are r values, descending, bounded by the singular values of the sampled rows (interlacing)
+    d = {}
+    idx = np.arange(0, 40, 2)
+    dec.decompose(A, 6, 4, 0.5, seed=4, idx=idx, details=d)
+    sB = d["sigma_reduced"]
+    sv = np.linalg.svd(A[idx], compute_uv=False)
+    assert sB.shape == (10,) and np.all(np.diff(sB) <= 0) and np.all(sB <= sv[:10] * (1 + 1e-12))

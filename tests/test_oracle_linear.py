@@ -227,3 +227,15 @@ def test_split_from_parts_stores_the_parts_it_is_given():
     d = lin.split_from_parts(WR2, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, g, seed=5)
     e = lin.split_quantize_sr(WR2 + (Uo * So) @ Vo.T, Uo, So, Vo, 2.0 ** -11, 2.0 ** -11, g, 5)
     assert np.array_equal(d.Ut[0], e.Ut[0]) and np.array_equal(d.Vt[0], e.Vt[0])   # same keys as the recomputed split
+
+
+def test_row_subsets_are_rows_of_the_full_products():
+    rs = np.random.default_rng(11)
+    _, xq = _split(rs, 48, 64, 4)
+    _, wq = _split(rs, 32, 64, 4)
+    _, gq = _split(rs, 48, 32, 4)
+    rows = np.array([0, 5, 17, 31])
+    # (a library matmul may sum in another order for another shape: compare to rounding)
+    assert np.allclose(lin.linear_fwd(xq, wq, rows), lin.linear_fwd(xq, wq)[rows], rtol=1e-13, atol=1e-13)
+    assert np.allclose(lin.linear_dgrad(gq, wq, rows), lin.linear_dgrad(gq, wq)[rows], rtol=1e-13, atol=1e-13)
+    assert np.allclose(lin.linear_wgrad(gq, xq, rows), lin.linear_wgrad(gq, xq)[rows], rtol=1e-13, atol=1e-13)
