@@ -1,21 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the Metis split-FP4 linear hot path on one MI355X.
 
-A step is one pass of the whole hot path over one batch of seeded synthetic input
-already resident in HBM.  Default workload "c2": the LLaMA-3-8B attention projection
-(W 4096x4096 decomposed with k=64, p=16 and split-quantized; X 8192x4096 quantized;
-forward X W^T on the FP4 operands).  "c4" is the full W4A4G4 step of the FFN down
-projection (three decompositions, three split-quantizations with both block
-orientations, fprop + dgrad + wgrad).
+A step is one pass of the whole hot path over one batch of seeded synthetic input already
+resident in HBM: every operand of every linear of the workload is decomposed
+(metis_decompose) and split-quantized (metis_split_quantize), then the FP4 GEMMs run.
+Default workload "c5": one LLaMA-3-8B layer's seven linears at 16384 tokens, each an
+independent (X, W, G) triple: 21 decompositions + splits (both block orientations) and
+21 GEMMs (fprop, dgrad, wgrad), 21.44 TFLOP of useful GEMM work per step.  "c1".."c4" are
+the smaller configurations (c4 = the FFN down projection alone, full W4A4G4 step).
 
-Prints ONE JSON line: whole-step throughput (useful GEMM flops / step time), the
-roofline of the dominant kernel (the FP4 GEMM, measured with HIP events around each of
-its launches inside the timed region), per-pass HBM rates, and the fp64 oracle timed on
-the host cores on a bounded sample of the same workload.
+Prints ONE JSON line: whole-step throughput (useful GEMM flops / step time), the roofline
+of the dominant kernel (the FP4 GEMM, HIP events around each of its launches inside the
+timed region), the steady-state step in which weights are stored as parts (no weight
+decomposition), per-pass HBM rates warm and cold, end-to-end effective bandwidth of
+decompose + split against the algorithmic minimum, measured copy / read / matrix-loop
+ceilings of the box, and the fp64 oracle timed on the host cores on a bounded sample.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -27,32 +31,41 @@ PEAK_MFMA_TFLOPS = 2500.0     # MI355X dense fp16/bf16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 PEAK_FP4_TFLOPS = 10100.0     # MI355X dense fp4/fp6 matrix peak
 
+WORKLOAD_TEXT = {
+    "c1": "config 1: tiny planted W 256x512 (k=8, p=8, rho=0.25) x X 128x512, decompose+split_quantize(W), quantize(X), fwd",
+    "c2": "config 2: LLaMA-3-8B attention projection W 4096x4096 (k=64, p=16) x X 8192x4096, "
+          "decompose+split_quantize(W), quantize(X), fwd",
+    "c3": "config 3: FFN up W 14336x4096, X 8192x4096, both decomposed and split, fwd",
+    "c4": "config 4: FFN down W 4096x14336, X 8192x14336, G 8192x4096, all decomposed and split both ways, "
+          "fwd + dgrad + wgrad",
+    "c5": "config 5: one LLaMA-3-8B layer at 16384 tokens, seven linears (q, o 4096x4096; k, v 1024x4096; gate, up "
+          "14336x4096; down 4096x14336), each an independent (X, W, G) triple: 21 decompose + split_quantize (both "
+          "orientations), 21 GEMMs (fwd + dgrad + wgrad)",
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-ffn-passes", action="store_true",
-                    help="skip the extra figure on an 8192 x 14336 operand (keeps a profile to the workload's own shapes)")
-    ap.add_argument("--pipeline-depth", type=int, default=3,
-                    help="extra measurement: independent steps in flight at once, one stream and one set of "
-                         "buffers each (0 or 1 = skip); never enters `value`")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed step and its roofline (keeps a profile to the step's own kernels)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
 
 
 class Operand:
-    """One matrix of the layer with everything its decomposition and split need, preallocated."""
+    """One matrix of a linear with everything its decomposition and split need, preallocated."""
 
-    def __init__(self, metis, torch, A, k, p, rho, seed, want_t, oq, share=None):
-        self.A = share.A if share is not None else A.cuda()       # a pipeline slot reads the same input
+    def __init__(self, metis, torch, A, k, p, rho, seed, want_t):
+        self.A = A.cuda()
         self.M, self.N = A.shape
-        self.k, self.p, self.rho, self.seed = k, p, rho, seed
-        g_r = oq.tensor_scale_for(float(A.abs().max()))         # delayed scaling: amax known from setup
+        self.k, self.p, self.rho, self.seed, self.want_t = k, p, rho, seed, want_t
+        g_r = metis.tensor_scale(float(A.abs().max()))           # delayed scaling: amax known from setup
         dev = "cuda"
         if k:
             self.U = torch.empty((self.M, k), dtype=torch.float32, device=dev)
@@ -62,18 +75,90 @@ class Operand:
                                       dtype=torch.uint8, device=dev)
             self.ws_split = torch.empty((metis.split_workspace_bytes(self.M, self.N, k),), dtype=torch.uint8, device=dev)
         self.q = metis.SplitTensor(self.M, self.N, k, 2.0 ** -11, 2.0 ** -11, g_r, want_t)
-        self.metis = metis
+        self.metis, self.torch = metis, torch
+        self.parts = None
+
+    def decompose(self, rho=None):
+        self.metis.decompose(self.A, self.k, self.p, self.rho if rho is None else rho, self.seed,
+                             workspace=self.ws_dec, out=(self.U, self.S, self.V))
+
+    def split(self):
+        self.metis.split_quantize(self.A, self.U, self.S, self.V, self.q, workspace=self.ws_split)
 
     def prepare(self):
-        m = self.metis
         if self.k:
-            m.decompose(self.A, self.k, self.p, self.rho, self.seed, workspace=self.ws_dec, out=(self.U, self.S, self.V))
-            m.split_quantize(self.A, self.U, self.S, self.V, self.q, workspace=self.ws_split)
+            self.decompose()
+            self.split()
         else:
-            m.quantize(self.A, self.q.R, self.q.Rt)
+            self.metis.quantize(self.A, self.q.R, self.q.Rt)
 
-    def bytes_read_once(self):
-        return 2 * self.M * self.N
+    def store_parts(self):
+        """Residual of the current factors as a stored bf16 variable (Sec. 3.2: a weight's factors and residual
+        are separate parameters); set-up only."""
+        t = self.torch
+        self.parts = (self.A.float() - (self.U * self.S) @ self.V.T).to(t.bfloat16)
+
+    def prepare_from_parts(self):
+        self.metis.split_from_parts(self.parts, self.U, self.S, self.V, self.q)
+
+    def orientations(self):
+        return 2 if self.want_t else 1
+
+    def min_bytes(self):
+        """Algorithmic minimum of decompose + split: A read once, codes and scales written once per orientation."""
+        return (2.0 + 0.5625 * self.orientations()) * self.M * self.N
+
+
+class Linear:
+    def __init__(self, name, W, X, G, metis, torch):
+        self.name, self.W, self.X, self.G = name, W, X, G
+        self.L, self.K, self.N = X.M, X.N, W.M
+        kmax = max(W.k, X.k, G.k if G else 0)
+        self.ws = torch.empty((max(metis.linear_workspace_bytes(self.L, self.N, self.K, kmax), 256),),
+                              dtype=torch.uint8, device="cuda")
+        self.Y = torch.empty((self.L, self.N), dtype=torch.bfloat16, device="cuda")
+        self.dX = torch.empty((self.L, self.K), dtype=torch.bfloat16, device="cuda") if G else None
+        self.dW = torch.empty((self.N, self.K), dtype=torch.bfloat16, device="cuda") if G else None
+        self.metis = metis
+
+    def ops(self):
+        return [o for o in (self.W, self.X, self.G) if o is not None]
+
+    def n_gemms(self):
+        return 3 if self.G else 1
+
+    def flops(self):
+        return 2.0 * self.L * self.K * self.N * self.n_gemms()
+
+    def gemms(self):
+        m = self.metis
+        m.fp4_linear_fwd(self.X.q, self.W.q, self.Y, self.ws)
+        if self.G:
+            m.fp4_linear_dgrad(self.G.q, self.W.q, self.dX, self.ws)
+            m.fp4_linear_wgrad(self.G.q, self.X.q, self.dW, self.ws)
+
+
+def build_workload(name, metis, torch, workloads):
+    c = int(name[1])
+    prm = workloads.PARAMS[c]
+    k, p = prm["k"], prm["p"]
+    if c <= 4:
+        T = workloads.config(c)
+        full = c == 4
+        W = Operand(metis, torch, T["W"], k, p, prm["rho_w"], workloads.seed_for(c, 0) + 7, full)
+        X = Operand(metis, torch, T["X"], k if c >= 3 else 0, p, prm["rho_x"], workloads.seed_for(c, 1) + 7, full)
+        G = Operand(metis, torch, T["G"], k, p, prm["rho_x"], workloads.seed_for(c, 2) + 7, True) if full else None
+        return [Linear({1: "tiny", 2: "attn", 3: "ffn_up", 4: "ffn_down"}[c], W, X, G, metis, torch)], {"c": T}
+    lin, host = [], {}
+    for nm, _, _ in workloads.LAYER_LINEARS:
+        T = workloads.layer_linear(nm)
+        W = Operand(metis, torch, T["W"], k, p, prm["rho_w"], workloads.layer_seed(nm, "W"), True)
+        X = Operand(metis, torch, T["X"], k, p, prm["rho_x"], workloads.layer_seed(nm, "X"), True)
+        G = Operand(metis, torch, T["G"], k, p, prm["rho_x"], workloads.layer_seed(nm, "G"), True)
+        lin.append(Linear(nm, W, X, G, metis, torch))
+        if nm == "k":
+            host["k"] = T                                           # the CPU baseline's sample
+    return lin, host
 
 
 def main():
@@ -84,59 +169,44 @@ def main():
     import numpy as np
     import torch
     from paper_2509_00404_amd import metis, workloads
-    from oracle import quant as oq                    # only tensor_scale_for (setup) and the cpu_baseline leg
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     metis.lib()
 
-    c = int(args.workload[1])
-    prm = workloads.PARAMS[c]
     t0 = time.time()
-    T = workloads.config(c)
-    k, p = prm["k"], prm["p"]
-    split_x = c >= 3
-    full = c == 4
-    W = Operand(metis, torch, T["W"], k, p, prm["rho_w"], workloads.seed_for(c, 0) + 7, full, oq)
-    X = Operand(metis, torch, T["X"], k if split_x else 0, p, prm["rho_x"], workloads.seed_for(c, 1) + 7, full, oq)
-    G = Operand(metis, torch, T["G"], k, p, prm["rho_x"], workloads.seed_for(c, 2) + 7, True, oq) if full else None
-    L, K = X.M, X.N
-    N = W.M
-    ws_lin = torch.empty((max(metis.linear_workspace_bytes(L, N, K, k), 256),), dtype=torch.uint8, device="cuda")
-    Y = torch.empty((L, N), dtype=torch.bfloat16, device="cuda")
-    dX = torch.empty((L, K), dtype=torch.bfloat16, device="cuda") if full else None
-    dW = torch.empty((N, K), dtype=torch.bfloat16, device="cuda") if full else None
+    linears, host = build_workload(args.workload, metis, torch, workloads)
     setup_s = time.time() - t0
-    ops = [W, X] + ([G] if full else [])
-    n_gemm = 3 if full else 1
+    all_ops = [o for l in linears for o in l.ops()]
+    n_gemm = sum(l.n_gemms() for l in linears)
+    n_split = sum(1 for o in all_ops if o.k)
+    useful_flops = sum(l.flops() for l in linears)
 
-    # The operands' preparations (decompose + split_quantize, or quantize) are independent of each other, and
-    # the decomposition's small-matrix kernels occupy one CU each: one stream per operand lets them overlap.
-    # Every entry point only enqueues on the caller's current stream, so this is plain caller-side concurrency.
-    main_stream = torch.cuda.current_stream()
-    side = [torch.cuda.Stream() for _ in ops]                 # default priority
-    ev_fork = torch.cuda.Event()
-    ev_join = [torch.cuda.Event() for _ in ops]
+    # One step on one stream: every decomposition of the step in one batched call (the single-workgroup
+    # factorizations of all operands then run side by side), the splits, then the GEMMs.
+    split_ops = [o for o in all_ops if o.k]
+    multi = n_split >= 2
 
-    multi = sum(1 for o in ops if o.k) >= 2                   # worth a fork/join only with two or more decompositions
+    def batch_of(ops):
+        return metis.DecomposeBatch([dict(A=o.A, k=o.k, p=o.p, rho=o.rho, seed=o.seed, U=o.U, S=o.S, V=o.V,
+                                          workspace=o.ws_dec) for o in ops]) if ops else None
 
-    def step():
-        if not multi:
-            for o in ops:
-                o.prepare()
-            metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin)
-            return
-        ev_fork.record(main_stream)
-        for o, st, ev in zip(ops, side, ev_join):
-            st.wait_event(ev_fork)
-            with torch.cuda.stream(st):
-                o.prepare()
-                ev.record(st)
-        for ev in ev_join:
-            main_stream.wait_event(ev)
-        metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin)
-        if full:
-            metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin)
-            metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin)
+    batch_all = batch_of(split_ops)
+    batch_xg = batch_of([o for l in linears for o in (l.X, l.G) if o is not None and o.k])
+
+    def step(weights_from_parts=False):
+        b = batch_xg if weights_from_parts else batch_all
+        if b is not None:
+            b.run()
+        for l in linears:
+            for o in l.ops():
+                if not o.k:
+                    o.prepare()
+                elif weights_from_parts and o is l.W:
+                    o.prepare_from_parts()
+                else:
+                    o.split()
+        for l in linears:
+            l.gemms()
 
     for _ in range(args.warmup):
         step()
@@ -148,12 +218,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    n_split = sum(1 for o in ops if o.k)
     timers = {
         "gemm": metis.KernelTimer(metis.PROF_GEMM, args.steps * n_gemm),
         "broadcast": metis.KernelTimer(metis.PROF_BROADCAST, max(1, args.steps * n_split)),
         "residual_quant": metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, max(1, args.steps * n_split)),
-        "quantize": metis.KernelTimer(metis.PROF_QUANTIZE, max(1, args.steps)),
+        "quantize": metis.KernelTimer(metis.PROF_QUANTIZE, max(1, args.steps * 4)),
     }
     for t in timers.values():
         t.__enter__()
@@ -166,224 +235,220 @@ def main():
     for t in timers.values():
         t.__exit__()
     ms_per_step = elapsed * 1e3 / args.steps
-
-    useful_flops = 2.0 * L * K * N * n_gemm
     value = useful_flops / (ms_per_step * 1e-3) / 1e12
 
-    def avg(name, count):
-        d = timers[name].durations_ms(count)
-        return sum(d) / len(d) if d else None
-
-    gemm_ms = avg("gemm", args.steps * n_gemm)
-    gemm_tflops = 2.0 * L * K * N / (gemm_ms * 1e-3) / 1e12
+    # dominant kernel: the FP4 GEMM.  achieved = algorithmic flops of the bracketed launches / their summed durations
+    gd = timers["gemm"].durations_ms(args.steps * n_gemm)
+    gemm_ms = sum(gd) / len(gd)
+    gemm_tflops = useful_flops * args.steps / (sum(gd) * 1e-3) / 1e12
     roofline = {"kernel": "k_fp4_gemm_nt_pipe", "bound": "mfma", "achieved": round(gemm_tflops, 2),
                 "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_TFLOPS, 4),
-                "traffic": None, "avg_launch_ms": round(gemm_ms, 4)}
+                "traffic": traffic_from_profile(args.workload), "avg_launch_ms": round(gemm_ms, 4),
+                "launches_per_step": n_gemm, "flop_per_launch": useful_flops / n_gemm,
+                "frac_of_fp8_peak": round(gemm_tflops / 5000.0, 4), "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
+                "timing": "HIP events on the launch stream around every launch of the timed steps"}
 
-    # per-call wall time of each entry point, measured after the timed region (5 repetitions)
-    def timed(fn):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn()                                      # kernels that no step has launched yet load on first use
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(5):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return round(e0.elapsed_time(e1) / 5, 4)
-
-    phases = {}
-    for name, o in (("W", W), ("X", X), ("G", G)):
-        if o is None:
-            continue
-        if o.k:
-            phases[f"decompose_{name}_ms"] = timed(lambda: metis.decompose(o.A, o.k, o.p, o.rho, o.seed, workspace=o.ws_dec,
-                                                                        out=(o.U, o.S, o.V)))
-            phases[f"split_quantize_{name}_ms"] = timed(lambda: metis.split_quantize(o.A, o.U, o.S, o.V, o.q,
-                                                                                  workspace=o.ws_split))
-        else:
-            phases[f"quantize_{name}_ms"] = timed(lambda: metis.quantize(o.A, o.q.R, o.q.Rt))
-    phases["linear_fwd_ms"] = timed(lambda: metis.fp4_linear_fwd(X.q, W.q, Y, ws_lin))
-    if W.k:
-        # gradients of W's factors from a dense dW (outside the timed step: an extra output of the backward pass)
-        dWf = dW if full else torch.randn((N, K), dtype=torch.bfloat16, device="cuda")
-        gU = torch.empty((N, W.k), dtype=torch.float32, device="cuda")
-        gS = torch.empty((W.k, W.k), dtype=torch.float32, device="cuda")
-        gV = torch.empty((K, W.k), dtype=torch.float32, device="cuda")
-        ws_fg = torch.empty((metis.factor_grads_workspace_bytes(N, K, W.k),), dtype=torch.uint8, device="cuda")
-        phases["factor_grads_W_ms"] = timed(lambda: metis.fp4_factor_grads(dWf, W.q, gU, gS, gV, ws_fg))
-    if full:
-        phases["linear_dgrad_ms"] = timed(lambda: metis.fp4_linear_dgrad(G.q, W.q, dX, ws_lin))
-        phases["linear_wgrad_ms"] = timed(lambda: metis.fp4_linear_wgrad(G.q, X.q, dW, ws_lin))
-    roofline["traffic"] = traffic_from_profile(args.workload)
-
-    # The same product in the MXFP4 variant (block 32, power-of-two scales that the matrix instruction applies itself):
-    # what the chip's FP4 rate gives when no expansion work is needed.  Outside the timed step and outside `value`.
-    mx = None
-    if K % 256 == 0:
-        try:
-            qx, qw = metis.MxTensor(L, K), metis.MxTensor(N, K)
-            Ymx = torch.empty((L, N), dtype=torch.bfloat16, device="cuda")
-            mx_q_ms = timed(lambda: (metis.quantize_mx(X.A, qx), metis.quantize_mx(W.A, qw)))
-            mx_ms = timed(lambda: metis.mxfp4_gemm_nt(qx, qw, Ymx))
-            mx_tf = 2.0 * L * K * N / (mx_ms * 1e-3) / 1e12
-            mx = {"kernel": "k_mxfp4_gemm_nt", "quantize_both_ms": mx_q_ms, "gemm_ms": mx_ms, "achieved": round(mx_tf, 1),
-                  "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s", "frac": round(mx_tf / PEAK_FP4_TFLOPS, 4)}
-            del qx, qw, Ymx
-        except Exception as e:                                     # an extra figure must never cost the main line
-            mx = {"error": repr(e)[:200]}
-
-    # Throughput with several independent steps in flight (different layers or micro-batches of a training
-    # job): each slot has its own stream and its own outputs and workspaces, the inputs are shared.  A step's
-    # decomposition is a chain of small single-workgroup kernels that leaves the chip idle; steps in other slots
-    # fill it.  Reported beside `value`, which stays the one-step-at-a-time figure.
-    pipelined = None
-    depth = args.pipeline_depth
-    if depth > 1 and not multi:
-        try:
-            pipelined = pipelined_throughput(args, torch, metis, oq, T, W, X, Y, ws_lin, p, full, depth, useful_flops)
-        except Exception as e:                                     # an extra figure must never cost the main line
-            pipelined = {"depth": depth, "error": repr(e)[:200]}
-
-    passes = {}
+    passes = {"note": "inside the timed step; per-shape figures, warm and cold, under passes_standalone"}
     if n_split:
-        bc_ms = avg("broadcast", args.steps * n_split)
-        rq_ms = avg("residual_quant", args.steps * n_split)
-        mn = sum(o.M * o.N for o in ops if o.k) / n_split
-        orient = 2 if full else 1
-        passes["broadcast"] = {"avg_ms": round(bc_ms, 4), "GB/s": round(2 * mn / bc_ms / 1e6, 1),
-                               "frac_hbm": round(2 * mn / bc_ms / 1e6 / PEAK_HBM_GBS, 4)}
-        rq_bytes = (2 + 0.5625 * orient) * mn
-        passes["residual_quant"] = {"avg_ms": round(rq_ms, 4), "GB/s": round(rq_bytes / rq_ms / 1e6, 1),
-                                    "frac_hbm": round(rq_bytes / rq_ms / 1e6 / PEAK_HBM_GBS, 4)}
-    if not split_x:
-        q_ms = avg("quantize", args.steps)
-        qb = 2.5625 * L * K
-        passes["quantize"] = {"avg_ms": round(q_ms, 4), "GB/s": round(qb / q_ms / 1e6, 1),
-                              "frac_hbm": round(qb / q_ms / 1e6 / PEAK_HBM_GBS, 4)}
-        # the stochastically rounded variant of the same pass (outside the timed step: the graded path rounds to nearest)
-        sr_ms = timed(lambda: metis.quantize_sr(X.A, 1, X.q.R, None))
-        passes["quantize_sr"] = {"avg_ms": round(sr_ms, 4), "GB/s": round(qb / sr_ms / 1e6, 1),
-                                 "frac_hbm": round(qb / sr_ms / 1e6 / PEAK_HBM_GBS, 4)}
-        metis.quantize(X.A, X.q.R, None)
-
-    # The same HBM passes at the FFN activation shape (8192 x 14336, the largest matrix of a LLaMA-3-8B layer), one
-    # operand at a time: on the 4096 x 4096 weight of the default workload a pass is a few microseconds of traffic
-    # and mostly launch ramp, and on the three-operand workloads the figures above include the operands' contention.
-    passes_ffn = None
-    if not args.no_ffn_passes:
-        try:
-            passes_ffn = ffn_shape_passes(torch, metis, oq, k, p, prm["rho_x"])
-        except Exception as e:                                     # an extra figure must never cost the main line
-            passes_ffn = {"error": repr(e)[:200]}
+        bd = timers["broadcast"].durations_ms(args.steps * n_split)
+        rd = timers["residual_quant"].durations_ms(args.steps * n_split)
+        bc_bytes = sum(2.0 * o.M * o.N for o in all_ops if o.k) * args.steps
+        rq_bytes = sum(o.min_bytes() for o in all_ops if o.k) * args.steps
+        passes["broadcast"] = rate(bc_bytes, sum(bd))
+        passes["residual_quant"] = rate(rq_bytes, sum(rd))
+    plain = [o for o in all_ops if not o.k]
+    if plain:
+        qd = timers["quantize"].durations_ms(args.steps * len(plain))
+        passes["quantize"] = rate(sum(2.5625 * o.M * o.N for o in plain) * args.steps, sum(qd))
+    for t in timers.values():
+        t.close()
 
     out = {
         "metric": "split-FP4 linear TFLOP/s + decompose/quantize GB/s (frac of roofline), 1 GPU",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp4(e2m1)+e4m3 block scales, fp16 MFMA, fp32 accumulate", "data": "synthetic",
-        "config": {"workload": {"c1": "config 1: tiny planted 256x512, X 128x512, k=8",
-                                "c2": "config 2: LLaMA-3-8B attention projection W 4096x4096 (k=64,p=16) x X 8192x4096, "
-                                      "decompose+split_quantize(W), quantize(X), fwd",
-                                "c3": "config 3: FFN up W 14336x4096, X 8192x4096 both split, fwd",
-                                "c4": "config 4: FFN down W 4096x14336, X 8192x14336, G 8192x4096, full W4A4G4 step"}[args.workload],
-                   "L": L, "K": K, "N": N, "k": k, "p": p, "gemms_per_step": n_gemm, "setup_s": round(setup_s, 1)},
+        "config": {"workload": WORKLOAD_TEXT[args.workload],
+                   "linears": [{"name": l.name, "L": l.L, "K": l.K, "N": l.N} for l in linears],
+                   "k": all_ops[0].k or linears[0].W.k, "p": linears[0].W.p, "gemms_per_step": n_gemm,
+                   "decompositions_per_step": n_split, "useful_tflop_per_step": round(useful_flops / 1e12, 3),
+                   "setup_s": round(setup_s, 1)},
         "roofline": roofline,
-        "pipelined": pipelined,
-        "mxfp4_variant": mx,
         "passes": passes,
-        "passes_ffn_shape": passes_ffn,
-        "phases": phases,
     }
 
+    if not args.no_extras:
+        extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(np, torch, T, c, prm, oq)
+        out["cpu_baseline"] = cpu_baseline(np, torch, workloads, host, args.workload)
     print(json.dumps(out))
 
 
-def ffn_shape_passes(torch, metis, oq, k, p, rho, reps=5):
-    """Event-bracketed broadcast and residual + quantize kernels on one seeded 8192 x 14336 bf16 operand."""
-    Mf, Nf = 8192, 14336
-    gen = torch.Generator(device="cuda").manual_seed(20250904)
-    Af = (torch.randn((Mf, Nf), generator=gen, device="cuda") * 0.05).to(torch.bfloat16)
-    mn = Mf * Nf
-    res = {"shape": [Mf, Nf], "k": k, "sample_rate": rho, "data": "seeded N(0, 0.05^2), timing only"}
-    for want_t in (False, True):
-        o = Operand(metis, torch, Af, k, p, rho, 11, want_t, oq)
-        o.prepare()
-        tb = metis.KernelTimer(metis.PROF_BROADCAST, reps)
-        tr = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, reps)
-        tb.__enter__()
-        tr.__enter__()
+def rate(nbytes, ms):
+    gbs = nbytes / ms / 1e6
+    return {"total_ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+
+
+def timed(torch, fn, reps=5, between=None):
+    """Wall time per call on the current stream, HIP events; `between` runs untimed before every call."""
+    fn()                                          # kernels that no step has launched yet load on first use
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        if between:
+            between()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
         torch.cuda.synchronize()
-        for _ in range(reps):
+        ts.append(e0.elapsed_time(e1))
+    return {"median_ms": round(statistics.median(ts), 4), "min_ms": round(min(ts), 4)}
+
+
+def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops):
+    """Figures beside the timed step; none of them enters `value`."""
+    # steady state (Sec. 3.2): the weights' factors and residuals are stored variables, so a training step
+    # quantizes them as they are (metis_split_from_parts); activations and gradients are decomposed every step
+    if multi:
+        for l in linears:
+            l.W.store_parts()
+        for _ in range(2):
+            step(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(True)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["steady_state"] = {"what": "weights quantized from stored parts (no weight decomposition); X and G decomposed",
+                               "ms_per_step": round(ms, 4), "value": round(useful_flops / (ms * 1e-3) / 1e12, 3),
+                               "unit": "TFLOP/s"}
+        for l in linears:
+            l.W.parts = None
+        step()                                     # back to the decomposed weights' codes
+        torch.cuda.synchronize()
+
+    # measured ceilings of this box (library kernels metis_ceiling_*)
+    buf_a = torch.empty((1 << 29,), dtype=torch.uint8, device="cuda")
+    buf_b = torch.empty((1 << 29,), dtype=torch.uint8, device="cuda")
+    buf_a.fill_(1)
+    sink = torch.zeros((512 * 256,), dtype=torch.float32, device="cuda")
+    tc = timed(torch, lambda: metis.ceiling_copy(buf_a, buf_b))
+    tr = timed(torch, lambda: metis.ceiling_read(buf_a, sink.view(torch.int32)))
+    fl = metis.ceiling_mfma(2000, sink)
+    tm = timed(torch, lambda: metis.ceiling_mfma(2000, sink))
+    out["ceilings"] = {
+        "copy_GB/s": round(2 * buf_a.numel() / tc["median_ms"] / 1e6, 1),
+        "read_GB/s": round(buf_a.numel() / tr["median_ms"] / 1e6, 1),
+        "mfma_fp16_loop_TFLOP/s": round(fl / (tm["median_ms"] * 1e-3) / 1e12, 1),
+        "what": "512 MiB streaming copy and read (beyond the 256 MB last-level cache), register-resident 32x32x16 fp16 "
+                "matrix-instruction loop on all CUs (2 waves per SIMD, ~%.0f ms)" % tm["median_ms"]}
+
+    def sweep():                                   # evicts the last-level cache: 1 GiB of other traffic
+        metis.ceiling_copy(buf_a, buf_b)
+
+    # stand-alone passes, one operand at a time, per distinct operand shape: warm (back to back) and cold (cache swept)
+    seen, alone = set(), []
+    for o in sorted((o for o in all_ops if o.k), key=lambda o: -o.M * o.N):
+        key = (o.M, o.N, o.orientations(), o.rho)
+        if key in seen or len(alone) >= 6:
+            continue
+        seen.add(key)
+        row = {"shape": [o.M, o.N], "orientations": o.orientations(), "sample_rate": round(o.rho, 4)}
+        for label, between in (("warm", None), ("cold", sweep)):
+            tb = metis.KernelTimer(metis.PROF_BROADCAST, 7)
+            tq = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, 7)
+            tot = []
             o.prepare()
-        torch.cuda.synchronize()
-        tb.__exit__()
-        tr.__exit__()
-        bc, rq = tb.durations_ms(reps), tr.durations_ms(reps)
-        bc_ms, rq_ms = sum(bc) / len(bc), sum(rq) / len(rq)
-        if not want_t:
-            res["broadcast"] = {"avg_ms": round(bc_ms, 4), "GB/s": round(2 * mn / bc_ms / 1e6, 1),
-                                "frac_hbm": round(2 * mn / bc_ms / 1e6 / PEAK_HBM_GBS, 4)}
-        rq_bytes = (2 + 0.5625 * (2 if want_t else 1)) * mn
-        res["residual_quant_%d_orientation%s" % ((2, "s") if want_t else (1, ""))] = {
-            "avg_ms": round(rq_ms, 4), "GB/s": round(rq_bytes / rq_ms / 1e6, 1),
-            "frac_hbm": round(rq_bytes / rq_ms / 1e6 / PEAK_HBM_GBS, 4)}
-        del o
-    return res
+            torch.cuda.synchronize()
+            with tb, tq:
+                for _ in range(7):
+                    if between:
+                        between()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    o.prepare()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    tot.append(e0.elapsed_time(e1))
+            bd, rd = tb.durations_ms(7), tq.durations_ms(7)
+            tb.close()
+            tq.close()
+            mn = o.M * o.N
+            row[label] = {
+                "broadcast": dict(median_us=round(statistics.median(bd) * 1e3, 1), min_us=round(min(bd) * 1e3, 1),
+                                  frac_hbm=round(2.0 * mn / statistics.median(bd) / 1e6 / PEAK_HBM_GBS, 4)),
+                "residual_quant": dict(median_us=round(statistics.median(rd) * 1e3, 1), min_us=round(min(rd) * 1e3, 1),
+                                       frac_hbm=round(o.min_bytes() / statistics.median(rd) / 1e6 / PEAK_HBM_GBS, 4)),
+                "decompose_plus_split": dict(median_ms=round(statistics.median(tot), 4), min_ms=round(min(tot), 4),
+                                             effective_GBps_vs_minimum=round(o.min_bytes() / statistics.median(tot) / 1e6, 1))}
+        alone.append(row)
+    out["passes_standalone"] = {
+        "rows": alone,
+        "bytes": "broadcast 2 M N; residual_quant (2 + 0.5625 orientations) M N; decompose_plus_split is the whole "
+                 "two-call chain against the algorithmic minimum 2 M N + 0.5625 M N orientations",
+        "timing": "HIP event pairs (about 3 us of bracket overhead per kernel); cold = a 1 GiB copy between repetitions"}
 
+    # per-call wall time of each entry point on the first linear (and the last, if different)
+    phases = {}
+    for l in ([linears[0]] if len(linears) == 1 else [linears[0], linears[-1]]):
+        for nm, o in (("W", l.W), ("X", l.X), ("G", l.G)):
+            if o is None:
+                continue
+            tag = f"{l.name}.{nm}[{o.M}x{o.N}]"
+            if o.k:
+                phases[f"decompose {tag}"] = timed(torch, o.decompose)
+                phases[f"split_quantize {tag}"] = timed(torch, o.split)
+            else:
+                phases[f"quantize {tag}"] = timed(torch, o.prepare)
+        phases[f"linear_fwd {l.name}"] = timed(torch, lambda: metis.fp4_linear_fwd(l.X.q, l.W.q, l.Y, l.ws))
+        if l.G:
+            phases[f"linear_dgrad {l.name}"] = timed(torch, lambda: metis.fp4_linear_dgrad(l.G.q, l.W.q, l.dX, l.ws))
+            phases[f"linear_wgrad {l.name}"] = timed(torch, lambda: metis.fp4_linear_wgrad(l.G.q, l.X.q, l.dW, l.ws))
+    # the paper's sampling rate ("less than 1 % of the rows"): one data point
+    big = max((o for o in all_ops if o.k and o.rho < 1.0), key=lambda o: o.M * o.N, default=None)
+    if big is not None:
+        try:
+            phases[f"decompose [{big.M}x{big.N}] at sample_rate 0.01"] = timed(torch, lambda: big.decompose(0.01))
+            big.decompose()
+        except metis.MetisError as e:
+            phases["decompose at sample_rate 0.01"] = {"error": str(e)[:120]}
+    l0 = linears[0]
+    if l0.W.k and l0.G:
+        gU = torch.empty((l0.N, l0.W.k), dtype=torch.float32, device="cuda")
+        gS = torch.empty((l0.W.k, l0.W.k), dtype=torch.float32, device="cuda")
+        gV = torch.empty((l0.K, l0.W.k), dtype=torch.float32, device="cuda")
+        ws_fg = torch.empty((metis.factor_grads_workspace_bytes(l0.N, l0.K, l0.W.k),), dtype=torch.uint8, device="cuda")
+        phases[f"factor_grads {l0.name}.W"] = timed(torch, lambda: metis.fp4_factor_grads(l0.dW, l0.W.q, gU, gS, gV, ws_fg))
+    out["phases"] = phases
 
-def pipelined_throughput(args, torch, metis, oq, T, W, X, Y, ws_lin, p, full, depth, useful_flops):
-    """Steps per second with `depth` independent steps in flight, each slot a HIP graph on its own stream."""
-    slots = []
-    for d in range(depth):
-        Wd = Operand(metis, torch, T["W"], W.k, p, W.rho, W.seed, full, oq, share=W)
-        Xd = Operand(metis, torch, T["X"], X.k, p, X.rho, X.seed, full, oq, share=X)
-        slots.append((Wd, Xd, torch.empty_like(Y), torch.empty_like(ws_lin), torch.cuda.Stream()))
-
-    def slot_step(sl):
-        Wd, Xd, Yd, wsd, st = sl
-        with torch.cuda.stream(st):
-            Wd.prepare()
-            Xd.prepare()
-            metis.fp4_linear_fwd(Xd.q, Wd.q, Yd, wsd)
-
-    for i in range(max(args.warmup, depth)):
-        slot_step(slots[i % depth])
-    torch.cuda.synchronize()
-    # one HIP graph per slot: a step is ~35 launches, and with several steps in flight the host would
-    # otherwise be the limit.  The library records kernels only (its buffers are cleared by fill kernels).
-    graphs = []
-    for sl in slots:
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=sl[4]):
-            sl[0].prepare()
-            sl[1].prepare()
-            metis.fp4_linear_fwd(sl[1].q, sl[0].q, sl[2], sl[3])
-        graphs.append(g)
-    torch.cuda.synchronize()
-
-    def replay(i):
-        with torch.cuda.stream(slots[i % depth][4]):
-            graphs[i % depth].replay()
-
-    for i in range(depth):
-        slots[i][2].zero_()
-        replay(i)
-    torch.cuda.synchronize()
-    t_p = time.perf_counter()
-    for i in range(args.steps):
-        replay(i)
-    torch.cuda.synchronize()
-    ms_p = (time.perf_counter() - t_p) * 1e3 / args.steps
-    ref = Y.float()                                            # every slot reproduces the serial step's output
-    same = all(((sl[2].float() - ref).abs().max() <= 1e-3 * ref.abs().max()).item() for sl in slots)
-    pipelined = {"depth": depth, "ms_per_step": round(ms_p, 4),
-                 "value": round(useful_flops / (ms_p * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
-                 "outputs_match_serial": bool(same)}
-    del graphs, slots
-    return pipelined
+    # the same product in the MXFP4 variant (block 32, power-of-two scales that the matrix instruction applies itself)
+    l = linears[-1]
+    if l.K % 32 == 0:
+        try:
+            qx, qw = metis.MxTensor(l.L, l.K), metis.MxTensor(l.N, l.K)
+            Ymx = torch.empty((l.L, l.N), dtype=torch.bfloat16, device="cuda")
+            mx_q = timed(torch, lambda: (metis.quantize_mx(l.X.A, qx), metis.quantize_mx(l.W.A, qw)))
+            mx_g = timed(torch, lambda: metis.mxfp4_gemm_nt(qx, qw, Ymx))
+            tf = 2.0 * l.L * l.K * l.N / (mx_g["median_ms"] * 1e-3) / 1e12
+            out["mxfp4_variant"] = {"kernel": "k_mxfp4_gemm_nt", "linear": l.name, "quantize_both_ms": mx_q["median_ms"],
+                                    "gemm_ms": mx_g["median_ms"], "achieved": round(tf, 1), "peak": PEAK_FP4_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": round(tf / PEAK_FP4_TFLOPS, 4)}
+        except Exception as e:                                     # an extra figure must never cost the main line
+            out["mxfp4_variant"] = {"error": repr(e)[:200]}
+    # stochastic rounding of the largest activation (the paper's training default; the timed step rounds to nearest)
+    try:
+        x = max((o for o in all_ops), key=lambda o: o.M * o.N)
+        sr = timed(torch, lambda: metis.quantize_sr(x.A, 1, x.q.R, None))
+        rn = timed(torch, lambda: metis.quantize(x.A, x.q.R, None))
+        qb = 2.5625 * x.M * x.N
+        out["quantize_plain"] = {"shape": [x.M, x.N],
+                                 "nearest": dict(rn, frac_hbm=round(qb / rn["median_ms"] / 1e6 / PEAK_HBM_GBS, 4)),
+                                 "stochastic": dict(sr, frac_hbm=round(qb / sr["median_ms"] / 1e6 / PEAK_HBM_GBS, 4))}
+        x.prepare()
+    except Exception as e:
+        out["quantize_plain"] = {"error": repr(e)[:200]}
 
 
 def traffic_from_profile(workload):
@@ -400,33 +465,51 @@ def traffic_from_profile(workload):
     return None
 
 
-def cpu_baseline(np, torch, T, c, prm, oq):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(np, torch, workloads, host, workload):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload (test infrastructure, timed only)."""
     from oracle import decompose as odec
     from oracle import linear as olin
+    from oracle import quant as oq
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
+    c = int(workload[1])
+    prm = workloads.PARAMS[c]
     k, p = prm["k"], prm["p"]
+    T = host["k"] if c == 5 else host["c"]
+    cap = 2048                                                     # tokens of the sample
     Wn = T["W"].double().numpy()
-    Xn = T["X"].double().numpy()
-    rows = Xn.shape[0]
-    # whole steps of the same workload, repeated until about ten seconds of oracle time have passed
+    Xn = T["X"][:cap].double().numpy()
+    Gn = T["G"][:cap].double().numpy() if "G" in T else None
+    split_x = c >= 3
+    both = Gn is not None
+
+    def sq(A, kk, rho, seed):
+        g = oq.tensor_scale_for(np.abs(A).max())
+        if kk:
+            U, S, V = odec.decompose(A, kk, p, rho, seed)
+            return olin.split_quantize(A, U, S, V, 2.0 ** -11, 2.0 ** -11, g, want_t=both)
+        return olin.split_quantize(A, None, None, None, 1.0, 1.0, g, want_t=both)
+
     passes, t0, dt = 0, time.perf_counter(), 0.0
     while dt < 10.0 and passes < 64:
-        U, S, V = odec.decompose(Wn, k, p, prm["rho_w"], 1)
-        wq = olin.split_quantize(Wn, U, S, V, 2.0 ** -11, 2.0 ** -11, oq.tensor_scale_for(np.abs(Wn).max()), want_t=False)
-        xq = olin.split_quantize(Xn, None, None, None, 1.0, 1.0, oq.tensor_scale_for(np.abs(Xn).max()), want_t=False)
-        Yo = olin.linear_fwd(xq, wq)
+        wq = sq(Wn, k, prm["rho_w"], 1)
+        xq = sq(Xn, k if split_x else 0, max(prm["rho_x"], (k + p) / Xn.shape[0]), 2)
+        olin.linear_fwd(xq, wq)
+        if both:
+            gq = sq(Gn, k, max(prm["rho_x"], (k + p) / Gn.shape[0]), 3)
+            olin.linear_dgrad(gq, wq)
+            olin.linear_wgrad(gq, xq)
         passes += 1
         dt = time.perf_counter() - t0
-    flops = 2.0 * rows * Wn.shape[0] * Wn.shape[1] * passes
+    flops = 2.0 * Xn.shape[0] * Wn.shape[0] * Wn.shape[1] * (3 if both else 1) * passes
+    what = "the k projection of the layer (W 1024x4096)" if c == 5 else f"the workload's linear (W {Wn.shape[0]}x{Wn.shape[1]})"
     return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": round(dt, 2),
-            "sample": f"{passes} whole steps of the workload (decompose + split_quantize of W {Wn.shape[0]}x{Wn.shape[1]}, "
-                      f"quantize + fwd of all {rows} rows of X); useful flops / oracle seconds"}
+            "sample": f"{passes} whole steps of {what} on the first {Xn.shape[0]} tokens: decompose + split_quantize of every "
+                      f"split operand, {'fwd + dgrad + wgrad' if both else 'fwd'}; useful GEMM flops / oracle seconds"}
 
 
 if __name__ == "__main__":

@@ -135,6 +135,34 @@ int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, dou
                     void* workspace, size_t workspace_bytes,
                     const uint32_t* idx, int64_t n_idx, const uint16_t* omega, int32_t* info);
 
+/*
+ * Several decompositions in one call (Sec. 3.2: activations and output gradients are re-decomposed at every
+ * step, so one training step decomposes many matrices; they are independent of each other).  Each job has
+ * the arguments of metis_decompose; results are what n_jobs separate calls would give.  The stages that
+ * run on a single workgroup (Cholesky factorizations, the two eigen-decompositions) are launched once for
+ * all jobs of the same k + oversample (resp. k), so they cost one problem's latency instead of n_jobs
+ * times it; the stages that stream the matrices are enqueued job after job.  Jobs may differ in every
+ * argument; their workspaces and outputs must not overlap.  The array is host memory, read before return.
+ * Errors: those of metis_decompose, for the first offending job, before anything is enqueued.
+ */
+typedef struct {
+    const metis_mat* A;
+    int      k, oversample;
+    double   sample_rate;
+    uint64_t seed;
+    float*   U;
+    float*   S;
+    float*   V;
+    float*   amax_out;          /* optional */
+    void*    workspace;
+    size_t   workspace_bytes;
+    const uint32_t* idx;        /* optional explicit draws, as for metis_decompose */
+    int64_t  n_idx;
+    const uint16_t* omega;
+    int32_t* info;              /* optional */
+} metis_decompose_job;
+int metis_decompose_batch(void* stream, int n_jobs, const metis_decompose_job* jobs);
+
 /* ---- quantization (Sec. 2.3) and split (Sec. 3.2) -------------------------------------- */
 
 /*
@@ -297,6 +325,21 @@ int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const metis_mxfp4* B
  * Host-side state, not thread-safe; for benchmarks only.
  */
 int metis_profile_events(int kernel_id, void** start, void** stop, int n);
+
+/*
+ * Measured ceilings of the GPU the library runs on, for quoting roofline fractions against what the chip
+ * sustains as well as against its datasheet peaks.  Asynchronous on `stream`; the caller times them.
+ *   metis_ceiling_copy   dst[0..bytes) = src[0..bytes) (device, 16-byte aligned, bytes % 16 == 0): a plain
+ *                        streaming copy, 2 * bytes of traffic.
+ *   metis_ceiling_read   streams src once; sink: device uint32[2048], normally left untouched.
+ *   metis_ceiling_mfma   512 workgroups x 4 waves issue iters x 8 independent 32x32x16 fp16 matrix instructions
+ *                        from registers; *flops_out (host, optional) = floating-point operations of the launch;
+ *                        sink: device float[512 * 256], normally left untouched.
+ * Errors: METIS_INVALID_ARG.
+ */
+int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes);
+int metis_ceiling_read(void* stream, const void* src, size_t bytes, uint32_t* sink);
+int metis_ceiling_mfma(void* stream, int iters, float* sink, double* flops_out);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,86 @@
+// Measurement aids: what this GPU sustains for a plain streaming read, a plain copy, and a register-resident
+// fp16 matrix-instruction loop, so that roofline fractions can be quoted against measured ceilings as well
+// as against the datasheet peaks.  Not part of the hot path.
+#include "common.h"
+
+namespace {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+// grid-stride copy in 16-byte pieces, four in flight per lane
+__global__ void __launch_bounds__(256) k_ceiling_copy(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4_t a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// grid-stride read; the xor of everything read goes to one word per workgroup so the loads cannot be dropped
+__global__ void __launch_bounds__(256) k_ceiling_read(const u32x4_t* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4_t a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= src[i];
+    const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (x == 0x9E3779B9u) sink[blockIdx.x] = x;            // practically never taken; keeps the loads alive
+}
+
+// every wave issues `iters` rounds of eight independent 32x32x16 fp16 matrix instructions on registers
+__global__ void __launch_bounds__(256) k_ceiling_mfma(int iters, float* __restrict__ sink) {
+    half8_t a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * (float)(threadIdx.x & 7) + (float)i); b[i] = (_Float16)(0.5f * (float)i); }
+    float16_t c[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[t][i] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) c[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c[t], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += c[t][i];
+    if (s == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace
+
+extern "C" int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes) {
+    if (!src || !dst || bytes < 16 || bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 ||
+        reinterpret_cast<uintptr_t>(dst) % 16)
+        return METIS_INVALID_ARG;
+    hipLaunchKernelGGL(k_ceiling_copy, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const u32x4_t*)src,
+                       (u32x4_t*)dst, bytes / 16);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+extern "C" int metis_ceiling_read(void* stream, const void* src, size_t bytes, uint32_t* sink) {
+    if (!src || !sink || bytes < 16 || bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16) return METIS_INVALID_ARG;
+    hipLaunchKernelGGL(k_ceiling_read, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const u32x4_t*)src, bytes / 16,
+                       sink);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+extern "C" int metis_ceiling_mfma(void* stream, int iters, float* sink, double* flops_out) {
+    if (iters < 1 || !sink) return METIS_INVALID_ARG;
+    const int blocks = 256 * 2;                           // two workgroups of four waves per CU: two waves per SIMD
+    hipLaunchKernelGGL(k_ceiling_mfma, dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
+    METIS_LAUNCH_CHECK();
+    if (flops_out) *flops_out = (double)blocks * 4.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return METIS_OK;
+}

@@ -10,6 +10,7 @@
 #include "dgemm_skinny.h"
 #include "smallmat.h"
 #include "rng_dev.h"
+#include <vector>
 
 namespace {
 
@@ -124,128 +125,258 @@ extern "C" size_t metis_decompose_workspace_bytes(int64_t M, int64_t N, int k, i
     return make_layout(M, N, k, p, Ms).total;
 }
 
+namespace {
+
+// One decomposition in flight: the caller's arguments plus the carved-up workspace.
+struct Job {
+    const bf16_t* A;
+    int64_t M, N, lda, Ms;
+    int k, r;
+    uint64_t seed;
+    float *U, *S, *V, *amax_out;
+    const uint32_t *idx_in, *idx_use;
+    const bf16_t *omega_in, *om_use;
+    int32_t *info, *wellcond;
+    bool fast, gram_fast;
+    int cparts;
+    char* ws;
+    Layout L;
+    double *Zacc, *G1, *G1b, *G2, *G3, *Linv, *H1, *H, *B, *lam, *T, *lam3, *W3, *T3, *jscr;
+    float *C, *V0f;
+    uint32_t* idx;
+    bf16_t *omega, *V0hi, *V0lo;
+};
+
+int make_job(const metis_decompose_job& a, Job& j) {
+    if (!a.A || !a.A->ptr || !a.U || !a.S || !a.V || !a.workspace) return METIS_INVALID_ARG;
+    if (a.k < 1 || a.oversample < 0 || !(a.sample_rate > 0.0) || a.sample_rate > 1.0) return METIS_INVALID_ARG;
+    if (a.A->dtype != METIS_BF16) return METIS_UNSUPPORTED;
+    j.M = a.A->rows; j.N = a.A->cols; j.lda = a.A->ld;
+    if (j.M < 1 || j.N < 1 || j.lda < j.N) return METIS_BAD_SHAPE;
+    if (j.N % 8 || j.lda % 8 || reinterpret_cast<uintptr_t>(a.A->ptr) % 16) return METIS_BAD_SHAPE;  // 16-byte row loads
+    j.k = a.k;
+    j.r = a.k + a.oversample;
+    j.Ms = a.idx ? a.n_idx : metis_sample_count(j.M, a.k, a.oversample, a.sample_rate);
+    if (j.Ms < 1 || j.Ms > j.M) return METIS_BAD_SHAPE;
+    if (j.r > j.Ms || j.r > j.N) return METIS_BAD_SHAPE;
+    if (j.r > SM_MAX_CHOL || j.k > 128) return METIS_UNSUPPORTED;
+    j.L = make_layout(j.M, j.N, a.k, a.oversample, j.Ms);
+    if (a.workspace_bytes < j.L.total) return METIS_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(a.workspace) % 16) return METIS_INVALID_ARG;
+    const Layout& L = j.L;
+    char* ws = (char*)a.workspace;
+    j.ws = ws;
+    j.A = (const bf16_t*)a.A->ptr;
+    j.seed = a.seed;
+    j.U = a.U; j.S = a.S; j.V = a.V; j.amax_out = a.amax_out; j.info = a.info;
+    j.Zacc = (double*)(ws + L.off_zacc);
+    j.G1 = (double*)(ws + L.off_g1);
+    j.G1b = (double*)(ws + L.off_g1b);
+    j.G2 = (double*)(ws + L.off_g2);
+    j.G3 = (double*)(ws + L.off_g3);
+    j.C = (float*)(ws + L.off_c);
+    j.idx = (uint32_t*)(ws + L.off_idx);
+    j.omega = (bf16_t*)(ws + L.off_omega);
+    j.Linv = (double*)(ws + L.off_linv);
+    j.H1 = (double*)(ws + L.off_h1);
+    j.H = (double*)(ws + L.off_h);
+    j.B = (double*)(ws + L.off_b);
+    j.lam = (double*)(ws + L.off_lam);
+    j.T = (double*)(ws + L.off_t);
+    j.V0f = (float*)(ws + L.off_v0f);
+    j.V0hi = (bf16_t*)(ws + L.off_v0hi);
+    j.V0lo = (bf16_t*)(ws + L.off_v0lo);
+    j.lam3 = (double*)(ws + L.off_lam3);
+    j.W3 = (double*)(ws + L.off_w3);
+    j.T3 = (double*)(ws + L.off_t3);
+    j.jscr = (double*)(ws + L.off_jscr);
+    j.idx_in = a.idx;
+    j.omega_in = (const bf16_t*)a.omega;
+    j.idx_use = a.idx ? a.idx : j.idx;
+    j.om_use = a.omega ? (const bf16_t*)a.omega : j.omega;
+    j.fast = skinny_ok(j.A, j.lda, j.N, j.r) && reinterpret_cast<uintptr_t>(j.om_use) % 16 == 0;
+    // The second CholeskyQR pass only repairs the orthogonality the first one lost to cond(Z)^2 eps.  When the
+    // first factor's diagonal shows a well-conditioned sketch the first pass's H1 is orthonormal to ~1e-10
+    // already: a device flag then turns the second pass's kernels into no-ops and the projection reads H1.
+    j.wellcond = j.fast ? (int32_t*)(ws + L.off_flag) : nullptr;
+    j.gram_fast = a.k % 4 == 0;
+    j.cparts = broadcast_splits(j.M, j.N);
+    return METIS_OK;
+}
+
+// The single-workgroup factorizations of all jobs in one launch per distinct order (they are latency-bound on
+// one CU each, so a batch costs what one problem costs).
+template <class P, class F>
+int launch_grouped(const std::vector<Job>& jobs, F order_of, int (*launch)(hipStream_t, const P*, int, int, int),
+                   hipStream_t s, const std::vector<P>& probs, const std::vector<int>& kks) {
+    std::vector<char> done(jobs.size(), 0);
+    for (size_t i = 0; i < jobs.size(); ++i) {
+        if (done[i]) continue;
+        std::vector<P> grp;
+        for (size_t t = i; t < jobs.size(); ++t)
+            if (!done[t] && order_of(jobs[t]) == order_of(jobs[i]) && kks[t] == kks[i]) {
+                grp.push_back(probs[t]);
+                done[t] = 1;
+            }
+        const int st = launch(s, grp.data(), (int)grp.size(), order_of(jobs[i]), kks[i]);
+        if (st != METIS_OK) return st;
+    }
+    return METIS_OK;
+}
+
+int chol_launch(hipStream_t s, const CholProblem* p, int count, int n, int) { return launch_chol_inv_batch(s, p, count, n); }
+
+}  // namespace
+
+extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decompose_job* args) {
+    if (n_jobs < 0 || (n_jobs > 0 && !args)) return METIS_INVALID_ARG;
+    if (n_jobs == 0) return METIS_OK;
+    std::vector<Job> jobs((size_t)n_jobs);
+    int st;
+    // every argument error is found before anything is enqueued
+    for (int i = 0; i < n_jobs; ++i)
+        if ((st = make_job(args[i], jobs[(size_t)i])) != METIS_OK) return st;
+    for (const Job& j : jobs) {
+        const int64_t omega_blocks = j.omega_in ? 0 : ceil_div64(ceil_div64(j.N * (int64_t)j.r, 2), 256);
+        if (512 + ceil_div64(j.Ms, 256) + omega_blocks > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const std::vector<int> zeros(jobs.size(), 0);
+
+    // ---- accumulators to zero, the draws the caller did not supply, sketch Z = A_s Omega, Gram of Z ----
+    for (const Job& j : jobs) {
+        const int zero_blocks = 512, idx_blocks = j.idx_in ? 0 : (int)ceil_div64(j.Ms, 256);
+        const int64_t omega_count = j.N * (int64_t)j.r;
+        const int64_t omega_blocks = j.omega_in ? 0 : ceil_div64(ceil_div64(omega_count, 2), 256);
+        hipLaunchKernelGGL(k_decomp_setup, dim3((unsigned)(zero_blocks + idx_blocks + omega_blocks)), dim3(256), 0, s,
+                           (uint32_t*)j.ws, j.L.zero_bytes / 4, (uint32_t*)j.amax_out, j.info, zero_blocks, idx_blocks, j.seed,
+                           j.M, j.Ms, j.idx_in ? nullptr : j.idx, omega_count, j.omega_in ? nullptr : j.omega);
+        METIS_LAUNCH_CHECK();
+    }
+    // products of the same kind and step of all jobs go out together (DgemmList): the small ones are latency-bound
+    DgemmList<double, double, EPI_ATOMIC_F64> gram;
+    DgemmList<double, double, EPI_STORE_F64> mul;
+    DgemmList<double, double, EPI_STORE_SPLIT_T> v0mul;
+    DgemmList<float, double, EPI_STORE_F32> outmul;
+    for (const Job& j : jobs) {
+        const int r = j.r;
+        const int64_t tiles_zr = ceil_div64(j.Ms, 32) * ceil_div64(r, 32), tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
+        if (j.fast) {
+            if ((st = launch_sketch(s, j.A, j.lda, j.idx_use, j.Ms, j.N, j.om_use, r, j.Zacc)) != METIS_OK) return st;
+        } else {
+            launch_dgemm<bf16_t, bf16_t, EPI_ATOMIC_F64>(s, op(j.A, j.lda, 1, j.idx_use), op(j.om_use, 1, r), j.Ms, r, j.N,
+                                                          split_for(j.N, tiles_zr), epi(j.Zacc, r));
+        }
+        gram.add(op(j.Zacc, 1, r), op(j.Zacc, 1, r), r, r, j.Ms, split_for(j.Ms, tiles_rr), epi(j.G1, r));
+        METIS_LAUNCH_CHECK();
+    }
+    gram.launch(s);
+    METIS_LAUNCH_CHECK();
+    // ---- CholeskyQR2: Z = H R ----
+    {
+        std::vector<CholProblem> pr;
+        for (const Job& j : jobs) pr.push_back({j.G1, j.Linv, j.info, j.wellcond, nullptr});
+        if ((st = launch_grouped<CholProblem>(jobs, [](const Job& j) { return j.r; }, chol_launch, s, pr, zeros)) != METIS_OK)
+            return st;
+    }
+    for (const Job& j : jobs) {
+        const int r = j.r;
+        const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
+        mul.add(op(j.Zacc, r, 1), op(j.Linv, r, 1), j.Ms, r, r, 1, epi(j.H1, r));
+        gram.add(op(j.H1, 1, r), op(j.H1, 1, r), r, r, j.Ms, split_for(j.Ms, tiles_rr), epi_skip(j.G1b, r, j.wellcond));
+    }
+    mul.launch(s);
+    gram.launch(s);
+    METIS_LAUNCH_CHECK();
+    {
+        std::vector<CholProblem> pr;
+        for (const Job& j : jobs) pr.push_back({j.G1b, j.Linv, j.info, nullptr, j.wellcond});
+        if ((st = launch_grouped<CholProblem>(jobs, [](const Job& j) { return j.r; }, chol_launch, s, pr, zeros)) != METIS_OK)
+            return st;
+    }
+    // ---- reduced matrix B = H^T A_s (r x N) and its Gram matrix ----
+    for (const Job& j : jobs) mul.add(op(j.H1, j.r, 1), op(j.Linv, j.r, 1), j.Ms, j.r, j.r, 1, epi_skip(j.H, j.r, j.wellcond));
+    mul.launch(s);
+    METIS_LAUNCH_CHECK();
+    for (const Job& j : jobs) {
+        const int r = j.r;
+        const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
+        if (j.fast) {
+            if ((st = launch_project(s, j.H, j.H1, j.wellcond, r, j.A, j.lda, j.idx_use, j.Ms, j.N, j.B)) != METIS_OK) return st;
+        } else {
+            launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(j.H, 1, r), op(j.A, 1, j.lda, nullptr, j.idx_use), r, j.N, j.Ms,
+                                                          split_for(j.Ms, ceil_div64(r, 32) * ceil_div64(j.N, 32)), epi(j.B, j.N));
+        }
+        gram.add(op(j.B, j.N, 1), op(j.B, j.N, 1), r, r, j.N, split_for(j.N, tiles_rr), epi(j.G2, r));
+        METIS_LAUNCH_CHECK();
+    }
+    gram.launch(s);
+    METIS_LAUNCH_CHECK();
+    // ---- top-k right singular vectors of B from the eigen-decomposition of B B^T ----
+    {
+        std::vector<JacobiProblem> pr;
+        std::vector<int> kks;
+        for (const Job& j : jobs) {
+            pr.push_back({j.G2, j.lam, nullptr, j.T, nullptr, j.jscr});
+            kks.push_back(j.k);
+        }
+        if ((st = launch_grouped<JacobiProblem>(jobs, [](const Job& j) { return j.r; }, launch_jacobi_eig_batch, s, pr, kks)) !=
+            METIS_OK)
+            return st;
+    }
+    // ---- broadcast to the full batch: C = A V0, and its Gram matrix ----
+    for (const Job& j : jobs)
+        v0mul.add(op(j.B, 1, j.N), op(j.T, 1, j.k), j.N, j.k, j.r, 1, epi(j.V0f, j.k, j.V0hi, j.V0lo, j.N));
+    v0mul.launch(s);
+    METIS_LAUNCH_CHECK();
+    for (const Job& j : jobs) {
+        const int k = j.k;
+        const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
+        st = launch_broadcast(s, j.A, j.lda, j.M, j.N, j.V0hi, j.V0lo, k, j.C, (uint32_t*)j.amax_out);
+        metis_prof_end(METIS_PROF_BROADCAST, pi, s);
+        if (st != METIS_OK) return st;
+        const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
+        const int64_t cstride = j.M * (int64_t)k;
+        if (j.gram_fast) {
+            // sums the broadcast's partial products into C (part 0) on the way
+            if ((st = launch_gram_parts(s, j.C, k, j.M, j.cparts, cstride, j.C, j.G3)) != METIS_OK) return st;
+        } else {
+            launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(j.C, 1, k, j.cparts, cstride), op_parts(j.C, 1, k, j.cparts, cstride),
+                                                        k, k, j.M, split_for(j.M, tiles_kk), epi(j.G3, k));
+        }
+        METIS_LAUNCH_CHECK();
+    }
+    // ---- singular-value form: C = U S W^T, V = V0 W ----
+    {
+        std::vector<JacobiProblem> pr;
+        std::vector<int> kks;
+        for (const Job& j : jobs) {
+            pr.push_back({j.G3, j.lam3, j.W3, j.T3, j.S, nullptr});
+            kks.push_back(j.k);
+        }
+        if ((st = launch_grouped<JacobiProblem>(jobs, [](const Job& j) { return j.k; }, launch_jacobi_eig_batch, s, pr, kks)) !=
+            METIS_OK)
+            return st;
+    }
+    for (const Job& j : jobs) {
+        const int k = j.k;
+        const int64_t cstride = j.M * (int64_t)k;
+        if (j.gram_fast)
+            outmul.add(op(j.C, k, 1), op(j.T3, 1, k), j.M, k, k, 1, epi(j.U, k));
+        else
+            outmul.add(op_parts(j.C, k, 1, j.cparts, cstride), op(j.T3, 1, k), j.M, k, k, 1, epi(j.U, k));
+        outmul.add(op(j.V0f, k, 1), op(j.W3, 1, k), j.N, k, k, 1, epi(j.V, k));
+    }
+    outmul.launch(s);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
 extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
                                uint64_t seed, float* U, float* S, float* V, float* amax_out, void* workspace,
                                size_t workspace_bytes, const uint32_t* idx_in, int64_t n_idx,
                                const uint16_t* omega_in, int32_t* info) {
-    if (!A || !A->ptr || !U || !S || !V || !workspace) return METIS_INVALID_ARG;
-    if (k < 1 || oversample < 0 || !(sample_rate > 0.0) || sample_rate > 1.0) return METIS_INVALID_ARG;
-    if (A->dtype != METIS_BF16) return METIS_UNSUPPORTED;
-    const int64_t M = A->rows, N = A->cols, lda = A->ld;
-    if (M < 1 || N < 1 || lda < N) return METIS_BAD_SHAPE;
-    if (N % 8 || lda % 8 || reinterpret_cast<uintptr_t>(A->ptr) % 16) return METIS_BAD_SHAPE;  // 16-byte row loads
-    const int r = k + oversample;
-    int64_t Ms = idx_in ? n_idx : metis_sample_count(M, k, oversample, sample_rate);
-    if (Ms < 1 || Ms > M) return METIS_BAD_SHAPE;
-    if (r > Ms || r > N) return METIS_BAD_SHAPE;
-    if (r > SM_MAX_CHOL || k > 128) return METIS_UNSUPPORTED;
-    const Layout L = make_layout(M, N, k, oversample, Ms);
-    if (workspace_bytes < L.total) return METIS_WORKSPACE_TOO_SMALL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16) return METIS_INVALID_ARG;
-
-    hipStream_t s = (hipStream_t)stream;
-    char* ws = (char*)workspace;
-    double* Zacc = (double*)(ws + L.off_zacc);
-    double* G1 = (double*)(ws + L.off_g1);
-    double* G1b = (double*)(ws + L.off_g1b);
-    double* G2 = (double*)(ws + L.off_g2);
-    double* G3 = (double*)(ws + L.off_g3);
-    float* C = (float*)(ws + L.off_c);
-    uint32_t* idx = (uint32_t*)(ws + L.off_idx);
-    bf16_t* omega = (bf16_t*)(ws + L.off_omega);
-    double* Linv = (double*)(ws + L.off_linv);
-    double* H1 = (double*)(ws + L.off_h1);
-    double* H = (double*)(ws + L.off_h);
-    double* B = (double*)(ws + L.off_b);
-    double* lam = (double*)(ws + L.off_lam);
-    double* T = (double*)(ws + L.off_t);
-    float* V0f = (float*)(ws + L.off_v0f);
-    bf16_t* V0hi = (bf16_t*)(ws + L.off_v0hi);
-    bf16_t* V0lo = (bf16_t*)(ws + L.off_v0lo);
-    double* lam3 = (double*)(ws + L.off_lam3);
-    double* W3 = (double*)(ws + L.off_w3);
-    double* T3 = (double*)(ws + L.off_t3);
-    const bf16_t* Ap = (const bf16_t*)A->ptr;
-    int st;
-
-    // accumulators start at zero; the draws the caller did not supply
-    const uint32_t* idx_use = idx_in ? idx_in : idx;
-    const bf16_t* om_use = omega_in ? omega_in : omega;
-    {
-        const int zero_blocks = 512, idx_blocks = idx_in ? 0 : (int)ceil_div64(Ms, 256);
-        const int64_t omega_count = N * (int64_t)r;
-        const int64_t omega_blocks = omega_in ? 0 : ceil_div64(ceil_div64(omega_count, 2), 256);
-        if (zero_blocks + idx_blocks + omega_blocks > 0x7FFFFFFF) return METIS_UNSUPPORTED;
-        hipLaunchKernelGGL(k_decomp_setup, dim3((unsigned)(zero_blocks + idx_blocks + omega_blocks)), dim3(256), 0, s,
-                           (uint32_t*)ws, L.zero_bytes / 4, (uint32_t*)amax_out, info, zero_blocks, idx_blocks, seed, M, Ms,
-                           idx_in ? nullptr : idx, omega_count, omega_in ? nullptr : omega);
-        METIS_LAUNCH_CHECK();
-    }
-
-    const int64_t tiles_zr = ceil_div64(Ms, 32) * ceil_div64(r, 32);
-    const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
-    // sketch Z = A_s Omega
-    const bool fast = skinny_ok(Ap, lda, N, r) && reinterpret_cast<uintptr_t>(om_use) % 16 == 0;
-    if (fast) {
-        if ((st = launch_sketch(s, Ap, lda, idx_use, Ms, N, om_use, r, Zacc)) != METIS_OK) return st;
-    } else {
-        launch_dgemm<bf16_t, bf16_t, EPI_ATOMIC_F64>(s, op(Ap, lda, 1, idx_use), op(om_use, 1, r), Ms, r, N,
-                                                      split_for(N, tiles_zr), epi(Zacc, r));
-    }
-    // CholeskyQR2: Z = H R
-    launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(Zacc, 1, r), op(Zacc, 1, r), r, r, Ms,
-                                                  split_for(Ms, tiles_rr), epi(G1, r));
-    METIS_LAUNCH_CHECK();
-    // The second pass only repairs the orthogonality the first one lost to cond(Z)^2 eps.  When the first
-    // factor's diagonal shows a well-conditioned sketch the first pass's H1 is orthonormal to ~1e-10 already:
-    // a device flag then turns the second pass's kernels into no-ops and the projection reads H1.
-    int32_t* wellcond = fast ? (int32_t*)(ws + L.off_flag) : nullptr;
-    if ((st = launch_chol_inv(s, G1, r, Linv, info, wellcond, nullptr)) != METIS_OK) return st;
-    launch_dgemm<double, double, EPI_STORE_F64>(s, op(Zacc, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi(H1, r));
-    launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(H1, 1, r), op(H1, 1, r), r, r, Ms,
-                                                  split_for(Ms, tiles_rr), epi_skip(G1b, r, wellcond));
-    METIS_LAUNCH_CHECK();
-    if ((st = launch_chol_inv(s, G1b, r, Linv, info, nullptr, wellcond)) != METIS_OK) return st;
-    launch_dgemm<double, double, EPI_STORE_F64>(s, op(H1, r, 1), op(Linv, r, 1), Ms, r, r, 1, epi_skip(H, r, wellcond));
-    // reduced matrix B = H^T A_s  (r x N)
-    if (fast) {
-        if ((st = launch_project(s, H, H1, wellcond, r, Ap, lda, idx_use, Ms, N, B)) != METIS_OK) return st;
-    } else {
-        launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(H, 1, r), op(Ap, 1, lda, nullptr, idx_use), r, N, Ms,
-                                                      split_for(Ms, ceil_div64(r, 32) * ceil_div64(N, 32)), epi(B, N));
-    }
-    // top-k right singular vectors of B from the eigen-decomposition of B B^T
-    launch_dgemm<double, double, EPI_ATOMIC_F64>(s, op(B, N, 1), op(B, N, 1), r, r, N, split_for(N, tiles_rr),
-                                                  epi(G2, r));
-    METIS_LAUNCH_CHECK();
-    if ((st = launch_jacobi_eig(s, G2, r, k, lam, nullptr, T, nullptr, (double*)(ws + L.off_jscr))) != METIS_OK) return st;
-    launch_dgemm<double, double, EPI_STORE_SPLIT_T>(s, op(B, 1, N), op(T, 1, k), N, k, r, 1,
-                                                     epi(V0f, k, V0hi, V0lo, N));
-    METIS_LAUNCH_CHECK();
-    // broadcast to the full batch: C = A V0
-    const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
-    st = launch_broadcast(s, Ap, lda, M, N, V0hi, V0lo, k, C, (uint32_t*)amax_out);
-    metis_prof_end(METIS_PROF_BROADCAST, pi, s);
-    if (st != METIS_OK) return st;
-    // singular-value form: C = U S W^T, V = V0 W
-    const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
-    const int cparts = broadcast_splits(M, N);
-    const int64_t cstride = M * (int64_t)k;
-    const bool gram_fast = k % 4 == 0;
-    if (gram_fast) {
-        // sums the broadcast's partial products into C (part 0) on the way
-        if ((st = launch_gram_parts(s, C, k, M, cparts, cstride, C, G3)) != METIS_OK) return st;
-    } else {
-        launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(C, 1, k, cparts, cstride), op_parts(C, 1, k, cparts, cstride),
-                                                    k, k, M, split_for(M, tiles_kk), epi(G3, k));
-    }
-    METIS_LAUNCH_CHECK();
-    if ((st = launch_jacobi_eig(s, G3, k, k, lam3, W3, T3, S)) != METIS_OK) return st;
-    if (gram_fast)
-        launch_dgemm<float, double, EPI_STORE_F32>(s, op(C, k, 1), op(T3, 1, k), M, k, k, 1, epi(U, k));
-    else
-        launch_dgemm<float, double, EPI_STORE_F32>(s, op_parts(C, k, 1, cparts, cstride), op(T3, 1, k), M, k, k, 1, epi(U, k));
-    launch_dgemm<float, double, EPI_STORE_F32>(s, op(V0f, k, 1), op(W3, 1, k), N, k, k, 1, epi(V, k));
-    METIS_LAUNCH_CHECK();
-    return METIS_OK;
+    const metis_decompose_job job = {A, k, oversample, sample_rate, seed, U, S, V, amax_out, workspace, workspace_bytes,
+                                     idx_in, n_idx, omega_in, info};
+    return metis_decompose_batch(stream, 1, &job);
 }

@@ -4,6 +4,7 @@
 // operands of type bf16, fp32 or fp64; several epilogues.
 #pragma once
 #include "common.h"
+#include <vector>
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
@@ -51,16 +52,17 @@ __device__ __forceinline__ double dload_sum(const DOperand& o, int64_t off) {
 #define DG_BK 32
 #define DG_PAD 2
 
-// grid: (ceil(N/32), ceil(M/32), ksplit); block 256 (4 waves, each a 16x16 sub-tile)
+// one 32 x 32 output tile of one contraction chunk: block (bx, by, bz) of a (ceil(N/32), ceil(M/32), ksplit) grid;
+// 256 threads (4 waves, each a 16x16 sub-tile)
 template <typename TA, typename TB, int EPI>
-__global__ void __launch_bounds__(256)
-k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
+__device__ __forceinline__ void dgemm_tile(const DOperand& A, const DOperand& B, int64_t M, int64_t N, int64_t K,
+                                           int64_t kchunk, const DEpilogue& ep, uint32_t bx, uint32_t by, uint32_t bz) {
     __shared__ double As[DG_BK][DG_BM + DG_PAD];
     __shared__ double Bs[DG_BK][DG_BN + DG_PAD];
     if (ep.skip && *ep.skip) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t m0 = (int64_t)blockIdx.y * DG_BM, n0 = (int64_t)blockIdx.x * DG_BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
+    const int64_t m0 = (int64_t)by * DG_BM, n0 = (int64_t)bx * DG_BN;
+    const int64_t kbeg = (int64_t)bz * kchunk;
     const int64_t kend = kbeg + kchunk < K ? kbeg + kchunk : K;
     const int wm = (wave >> 1) * 16, wn = (wave & 1) * 16;
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
@@ -139,6 +141,39 @@ k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk,
             ((float*)ep.c)[m * ep.ldc + n] = bf16_to_f32(hi) + bf16_to_f32(lo);
         }
     }
+}
+
+template <typename TA, typename TB, int EPI>
+__global__ void __launch_bounds__(256)
+k_dgemm(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kchunk, DEpilogue ep) {
+    dgemm_tile<TA, TB, EPI>(A, B, M, N, K, kchunk, ep, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Several independent small products in one launch (the same step of several decompositions): the calls travel
+// by value in the kernel arguments, call c owns the blocks [off[c], off[c+1]) of a one-dimensional grid.
+#define DG_MAX_BATCH 16
+struct DgemmCall {
+    DOperand A, B;
+    int64_t M, N, K, kchunk;
+    DEpilogue ep;
+    uint32_t gx, gy, gz;
+};
+struct DgemmBatch {
+    int n;
+    uint32_t off[DG_MAX_BATCH + 1];
+    DgemmCall c[DG_MAX_BATCH];
+};
+
+template <typename TA, typename TB, int EPI>
+__global__ void __launch_bounds__(256)
+k_dgemm_batch(const DgemmBatch b) {
+    const uint32_t blk = blockIdx.x;
+    int c = 0;
+    while (c + 1 < b.n && blk >= b.off[c + 1]) ++c;
+    const DgemmCall& call = b.c[c];
+    const uint32_t local = blk - b.off[c];
+    const uint32_t bx = local % call.gx, by = (local / call.gx) % call.gy, bz = local / (call.gx * call.gy);
+    dgemm_tile<TA, TB, EPI>(call.A, call.B, call.M, call.N, call.K, call.kchunk, call.ep, bx, by, bz);
 }
 
 // Epilogue shared by both kernels.
@@ -278,3 +313,45 @@ static inline void launch_dgemm(hipStream_t s, DOperand A, DOperand B, int64_t M
     dim3 grid((unsigned)ceil_div64(N, DG_BN), (unsigned)ceil_div64(M, DG_BM), (unsigned)ksplit);
     hipLaunchKernelGGL((k_dgemm<TA, TB, EPI>), grid, dim3(256), 0, s, A, B, M, N, K, kchunk, ep);
 }
+
+
+// A list of products of one kind: the small ones go out in launches of up to DG_MAX_BATCH calls, a large one
+// (see launch_dgemm) on its own.
+template <typename TA, typename TB, int EPI>
+struct DgemmList {
+    struct Item { DOperand A, B; int64_t M, N, K; int ksplit; DEpilogue ep; };
+    std::vector<Item> items;
+    void add(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int ksplit, DEpilogue ep) {
+        items.push_back({A, B, M, N, K, ksplit, ep});
+    }
+    void launch(hipStream_t s) {
+        DgemmBatch b;
+        b.n = 0;
+        b.off[0] = 0;
+        auto flush = [&]() {
+            if (b.n == 0) return;
+            for (int i = b.n; i < DG_MAX_BATCH; ++i) { b.c[i] = b.c[0]; b.off[i + 1] = b.off[b.n]; }
+            hipLaunchKernelGGL((k_dgemm_batch<TA, TB, EPI>), dim3(b.off[b.n]), dim3(256), 0, s, b);
+            b.n = 0;
+        };
+        for (const Item& it : items) {
+            const bool big = it.M * it.N * it.K >= ((int64_t)1 << 26) && it.M >= 48 && it.N >= 48;
+            if (big) {
+                launch_dgemm<TA, TB, EPI>(s, it.A, it.B, it.M, it.N, it.K, it.ksplit, it.ep);
+                continue;
+            }
+            int ksplit = it.ksplit < 1 ? 1 : it.ksplit;
+            const int64_t kchunk = ceil_div64(ceil_div64(it.K, ksplit), DG_BK) * DG_BK;
+            ksplit = (int)ceil_div64(it.K, kchunk);
+            DgemmCall& c = b.c[b.n];
+            c.A = it.A; c.B = it.B; c.M = it.M; c.N = it.N; c.K = it.K; c.kchunk = kchunk; c.ep = it.ep;
+            c.gx = (uint32_t)ceil_div64(it.N, DG_BN);
+            c.gy = (uint32_t)ceil_div64(it.M, DG_BM);
+            c.gz = (uint32_t)ksplit;
+            b.off[b.n + 1] = b.off[b.n] + c.gx * c.gy * c.gz;
+            if (++b.n == DG_MAX_BATCH) flush();
+        }
+        flush();
+        items.clear();
+    }
+};

@@ -557,6 +557,10 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
                      reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
     if (M >= 1024 && N >= 1024) {
+        // an output of at most 128 tiles of 256 x 256 would leave half the CUs without work: 128 x 128 tiles
+        // (four times as many workgroups, each less efficient) finish sooner
+        if (ceil_div64(M, 256) * ceil_div64(N, 256) <= 128 && ksplit <= 1)
+            return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, 1);
         // 256x256 tile, 4 waves of 128x128, software-pipelined (needs whole 128-deep stages and aligned rows)
         if (vec) return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
         // otherwise 8 waves of 128x64 with bounds-checked staging

@@ -142,9 +142,14 @@ __device__ __forceinline__ double chol_group8_sum(double x) {
 }
 
 __global__ void __launch_bounds__(1024)
-k_chol_inv(const double* __restrict__ G, int n, double* __restrict__ Linv, int32_t* __restrict__ info,
-           int32_t* __restrict__ wellcond_out, const int32_t* __restrict__ skip_in) {
+k_chol_inv(const CholBatch batch, int n) {
     extern __shared__ double sm[];
+    const CholProblem& prob = batch.p[blockIdx.x];
+    const double* __restrict__ G = prob.G;
+    double* __restrict__ Linv = prob.Linv;
+    int32_t* __restrict__ info = prob.info;
+    int32_t* __restrict__ wellcond_out = prob.wellcond_out;
+    const int32_t* __restrict__ skip_in = prob.skip_in;
     if (skip_in && *skip_in) {
         for (int e = threadIdx.x; e < n * n; e += 1024) Linv[e] = (e / n == e % n) ? 1.0 : 0.0;
         return;
@@ -776,9 +781,15 @@ __device__ void eig_precondition(double* __restrict__ R1, double* __restrict__ R
 // the later sweeps run over the columns that still move.
 template <int NE, int JGL>
 __global__ void __launch_bounds__(1024)
-k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ lam, double* __restrict__ vec,
-             double* __restrict__ tmat, float* __restrict__ sval, double* __restrict__ gscr) {
+k_jacobi_eig(const JacobiBatch batch, int n, int kk, int use_pre) {
     extern __shared__ double sm[];
+    const JacobiProblem& prob = batch.p[blockIdx.x];
+    const double* __restrict__ G = prob.G;
+    double* __restrict__ lam = prob.lam;
+    double* __restrict__ vec = prob.vec;
+    double* __restrict__ tmat = prob.tmat;
+    float* __restrict__ sval = prob.sval;
+    double* __restrict__ gscr = use_pre ? prob.gscr : nullptr;
     const int ne = n + (n & 1);             // even number of columns (a zero column pads odd n)
     // Column stride = 8 (mod 16) doubles spreads the columns that one LDS instruction touches over the banks.
     const int ld = jacobi_ld(n, JGL);
@@ -1011,53 +1022,65 @@ k_jacobi_eig(const double* __restrict__ G, int n, int kk, double* __restrict__ l
     }
 }
 
-int launch_chol_inv(hipStream_t s, const double* G, int n, double* Linv, int32_t* info, int32_t* wellcond_out,
-                    const int32_t* skip_in) {
+int launch_chol_inv_batch(hipStream_t s, const CholProblem* probs, int count, int n) {
+    if (n < 1 || n > SM_MAX_CHOL || count < 0) return METIS_UNSUPPORTED;
     size_t lds = 2 * (size_t)n * (n + 1) * sizeof(double);
     static LdsLimitCache lds_set;
     if (!ensure_dyn_lds((const void*)k_chol_inv, lds, lds_set)) return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), lds, s, G, n, Linv, info, wellcond_out, skip_in);
-    METIS_LAUNCH_CHECK();
+    for (int b0 = 0; b0 < count; b0 += SM_MAX_BATCH) {
+        const int nb = count - b0 < SM_MAX_BATCH ? count - b0 : SM_MAX_BATCH;
+        CholBatch batch;
+        for (int i = 0; i < SM_MAX_BATCH; ++i) batch.p[i] = probs[b0 + (i < nb ? i : 0)];
+        hipLaunchKernelGGL(k_chol_inv, dim3(nb), dim3(1024), lds, s, batch, n);
+        METIS_LAUNCH_CHECK();
+    }
     return METIS_OK;
 }
 
-int launch_jacobi_eig(hipStream_t s, const double* G, int n, int kk, double* lam, double* vec, double* tmat,
-                      float* sval, double* gscr) {
-    if (n < 1 || n > 128) return METIS_UNSUPPORTED;
+int launch_jacobi_eig_batch(hipStream_t s, const JacobiProblem* probs, int count, int n, int kk) {
+    if (n < 1 || n > 128 || count < 0) return METIS_UNSUPPORTED;
     const int jgl = jacobi_lanes(n);
     const int ne = n + (n & 1), ld = jacobi_ld(n, jgl);
     const size_t rsize = (size_t)(ne + 1) * ld;
     const size_t small = ((size_t)ne / 2 + ne + 1) * sizeof(double) + (size_t)(3 * ne + 4) * sizeof(int) + 16;
     // the preconditioner needs two matrix-sized regions and 10 n + 40 doubles; it pays from n ~ 72 on (about 250 us
     // against 7 of 9 sweeps of 46 us at n = 80; at n = 64 the plain sweeps win), and its second region fits in
-    // the 160 KB of LDS up to n = 88
+    // the 160 KB of LDS up to n = 88.  It runs when every problem of the batch brings scratch.
     size_t lds = rsize * sizeof(double) + small;
     const size_t lds_pre = 2 * rsize * sizeof(double) + small + (10 * (size_t)n + 44) * sizeof(double);
-    if (gscr && n >= 72 && lds_pre <= 160 * 1024) lds = lds_pre; else gscr = nullptr;
+    bool all_scratch = count > 0;
+    for (int i = 0; i < count; ++i) all_scratch = all_scratch && probs[i].gscr != nullptr;
+    const int use_pre = all_scratch && n >= 72 && lds_pre <= 160 * 1024;
+    if (use_pre) lds = lds_pre;
     // one group of jgl lanes per column pair, in whole waves and at least 512 threads (the Cholesky pre-pass, the
     // bookkeeping and the preconditioner's 8 lanes per row use them); no idle waves beyond that: every wave of
     // the workgroup takes part in every barrier
     const int need = (ne / 2 * jgl + 63) / 64 * 64;
     const int threads = need > 512 ? need : 512;
     if (ne / 2 * jgl > threads) return METIS_UNSUPPORTED;
+    for (int b0 = 0; b0 < count; b0 += SM_MAX_BATCH) {
+        const int nb = count - b0 < SM_MAX_BATCH ? count - b0 : SM_MAX_BATCH;
+        JacobiBatch batch;
+        for (int i = 0; i < SM_MAX_BATCH; ++i) batch.p[i] = probs[b0 + (i < nb ? i : 0)];
 #define JACOBI_CASE(NE, JGL)                                                                                  \
     {                                                                                                         \
         static LdsLimitCache lds_set;                                                                         \
         if (!ensure_dyn_lds((const void*)k_jacobi_eig<NE, JGL>, lds, lds_set)) return METIS_HIP_ERROR;        \
-        hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(1), dim3(threads), lds, s, G, n, kk, lam, vec, tmat, sval, gscr); \
+        hipLaunchKernelGGL((k_jacobi_eig<NE, JGL>), dim3(nb), dim3(threads), lds, s, batch, n, kk, use_pre);  \
     }
-    switch ((n + 15) / 16) {
-        case 1: JACOBI_CASE(1, 16) break;
-        case 2: JACOBI_CASE(2, 16) break;
-        case 3: JACOBI_CASE(3, 16) break;
-        case 4: JACOBI_CASE(4, 16) break;
-        case 5: JACOBI_CASE(5, 16) break;
-        case 6: JACOBI_CASE(6, 16) break;
-        case 7: JACOBI_CASE(7, 16) break;
-        default: JACOBI_CASE(8, 16) break;
-    }
+        switch ((n + 15) / 16) {
+            case 1: JACOBI_CASE(1, 16) break;
+            case 2: JACOBI_CASE(2, 16) break;
+            case 3: JACOBI_CASE(3, 16) break;
+            case 4: JACOBI_CASE(4, 16) break;
+            case 5: JACOBI_CASE(5, 16) break;
+            case 6: JACOBI_CASE(6, 16) break;
+            case 7: JACOBI_CASE(7, 16) break;
+            default: JACOBI_CASE(8, 16) break;
+        }
 #undef JACOBI_CASE
-    METIS_LAUNCH_CHECK();
+        METIS_LAUNCH_CHECK();
+    }
     return METIS_OK;
 }
 

@@ -33,6 +33,13 @@ class MxFp4(C.Structure):
     _fields_ = [("codes", C.c_void_p), ("scales", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64)]
 
 
+class DecomposeJob(C.Structure):
+    _fields_ = [("A", C.POINTER(Mat)), ("k", C.c_int), ("oversample", C.c_int), ("sample_rate", C.c_double),
+                ("seed", C.c_uint64), ("U", C.c_void_p), ("S", C.c_void_p), ("V", C.c_void_p), ("amax_out", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("idx", C.c_void_p), ("n_idx", C.c_int64),
+                ("omega", C.c_void_p), ("info", C.c_void_p)]
+
+
 class MetisError(RuntimeError):
     pass
 
@@ -50,6 +57,7 @@ _SIGNATURES = {
     "metis_decompose": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_int, C.c_int, C.c_double, C.c_uint64,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "metis_decompose_batch": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(DecomposeJob)]),
     "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
     "metis_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_uint64, C.POINTER(Fp4), C.POINTER(Fp4)]),
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
@@ -64,6 +72,9 @@ _SIGNATURES = {
     "metis_split_from_parts_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                             C.c_uint64, C.POINTER(Split)]),
     "metis_profile_events": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_int]),
+    "metis_ceiling_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "metis_ceiling_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "metis_ceiling_mfma": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_double)]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                        C.c_void_p, C.c_size_t]),
@@ -204,6 +215,27 @@ def decompose(A, k, oversample, sample_rate, seed, idx=None, omega=None, workspa
     return (U, S, V, amax) if want_amax else (U, S, V)
 
 
+class DecomposeBatch:
+    """Argument block of metis_decompose_batch, built once and reused: jobs = list of dicts with keys
+    A, k, p, rho, seed, U, S, V, workspace and optionally amax, idx, omega, info (all tensors on the GPU)."""
+
+    def __init__(self, jobs):
+        self.keep = jobs                                   # the tensors stay alive with the block
+        self.mats = [_mat(j["A"]) for j in jobs]
+        self.arr = (DecomposeJob * len(jobs))()
+        for a, m, j in zip(self.arr, self.mats, jobs):
+            ptr = lambda key: j[key].data_ptr() if j.get(key) is not None else None
+            a.A = C.pointer(m)
+            a.k, a.oversample, a.sample_rate, a.seed = j["k"], j["p"], j["rho"], j["seed"]
+            a.U, a.S, a.V, a.amax_out = ptr("U"), ptr("S"), ptr("V"), ptr("amax")
+            a.workspace, a.workspace_bytes = ptr("workspace"), j["workspace"].numel()
+            a.idx, a.n_idx = ptr("idx"), (j["idx"].numel() if j.get("idx") is not None else 0)
+            a.omega, a.info = ptr("omega"), ptr("info")
+
+    def run(self):
+        _check(lib().metis_decompose_batch(_stream(), len(self.arr), self.arr))
+
+
 def quantize(A, out=None, out_t=None):
     """Plain NVFP4 quantization into out (blocks along cols) and/or out_t (A^T)."""
     a = _mat(A)
@@ -325,6 +357,21 @@ def fp4_factor_grads(dW, W, dU, dS, dV, workspace=None):
     _check(lib().metis_fp4_factor_grads(_stream(), C.byref(m), C.byref(w), dU.data_ptr(), dS.data_ptr(),
                                         dV.data_ptr(), workspace.data_ptr(), workspace.numel()))
     return dU, dS, dV
+
+
+def ceiling_copy(src, dst):
+    _check(lib().metis_ceiling_copy(_stream(), src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size()))
+
+
+def ceiling_read(src, sink):
+    _check(lib().metis_ceiling_read(_stream(), src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr()))
+
+
+def ceiling_mfma(iters, sink):
+    """Launches the register-resident fp16 matrix-instruction loop; returns the launch's flop count."""
+    fl = C.c_double()
+    _check(lib().metis_ceiling_mfma(_stream(), iters, sink.data_ptr(), C.byref(fl)))
+    return fl.value
 
 
 PROF_GEMM, PROF_BROADCAST, PROF_RESIDUAL_QUANT, PROF_QUANTIZE = 0, 1, 2, 3

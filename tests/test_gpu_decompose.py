@@ -142,3 +142,41 @@ def test_rank_deficient_sketch_sets_info(metis):
     metis.decompose(A, 4, 4, 1.0, 1, info=info)
     torch.cuda.synchronize()
     assert int(info.item()) != 0
+
+
+def test_batch_of_mixed_jobs_matches_single_calls(metis):
+    """metis_decompose_batch: jobs of different shapes, ranks, oversampling and sampling rates in one call (the
+    single-workgroup stages are launched once per distinct order) against one metis_decompose call per job."""
+    from paper_2509_00404_amd import workloads
+    specs = [(768, 512, 64, 16, 1.0, 11), (1024, 256, 64, 16, 0.25, 12), (512, 384, 16, 8, 0.5, 13),
+             (640, 1024, 64, 16, 0.5, 14), (300, 264, 5, 3, 1.0, 15), (512, 512, 16, 8, 1.0, 16)]
+    jobs, singles = [], []
+    for M, N, k, p, rho, seed in specs:
+        s = 20.0 * np.arange(1, min(M, N) + 1) ** -1.2 + 0.01
+        A = workloads.planted(M, N, s, seed).cuda()
+        out = lambda: dict(U=torch.empty((M, k), dtype=torch.float32, device="cuda"),
+                           S=torch.empty((k,), dtype=torch.float32, device="cuda"),
+                           V=torch.empty((N, k), dtype=torch.float32, device="cuda"))
+        ws = torch.empty((metis.decompose_workspace_bytes(M, N, k, p, rho),), dtype=torch.uint8, device="cuda")
+        j = dict(A=A, k=k, p=p, rho=rho, seed=seed, workspace=ws, amax=torch.zeros(1, device="cuda"),
+                 info=torch.full((1,), 7, dtype=torch.int32, device="cuda"), **out())
+        jobs.append(j)
+        singles.append(metis.decompose(A, k, p, rho, seed, want_amax=True))
+    batch = metis.DecomposeBatch(jobs)
+    for rep in range(2):                                 # the argument block is reusable
+        for j in jobs:
+            j["U"].fill_(float("nan"))
+        batch.run()
+        torch.cuda.synchronize()
+        for j, (U1, S1, V1, amax1) in zip(jobs, singles):
+            assert int(j["info"].item()) == 0 and torch.equal(j["amax"], amax1)
+            S, S1n = j["S"].double().cpu().numpy(), S1.double().cpu().numpy()
+            assert np.max(np.abs(S - S1n) / S1n) < 1e-5
+            P = (j["U"].double() * j["S"].double()) @ j["V"].double().T
+            P1 = (U1.double() * S1.double()) @ V1.double().T
+            assert float((P - P1).norm() / P1.norm()) < 1e-5
+    # an error in any job is reported before anything runs
+    bad = dict(jobs[2])
+    bad["k"] = 0
+    with pytest.raises(metis.MetisError):
+        metis.DecomposeBatch([jobs[0], bad]).run()
