@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed step and its roofline (keeps a profile to the step's own kernels)")
+    ap.add_argument("--fused", action="store_true",
+                    help="decompose + split through the fused metis_decompose_split_quantize path (A read once from HBM, "
+                         "band by band) instead of two calls per operand; measured slower on this GPU, hence not the default")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
@@ -71,7 +74,7 @@ class Operand:
             self.U = torch.empty((self.M, k), dtype=torch.float32, device=dev)
             self.S = torch.empty((k,), dtype=torch.float32, device=dev)
             self.V = torch.empty((self.N, k), dtype=torch.float32, device=dev)
-            self.ws_dec = torch.empty((metis.decompose_workspace_bytes(self.M, self.N, k, p, rho),),
+            self.ws_dec = torch.empty((metis.decompose_split_workspace_bytes(self.M, self.N, k, p, rho),),
                                       dtype=torch.uint8, device=dev)
             self.ws_split = torch.empty((metis.split_workspace_bytes(self.M, self.N, k),), dtype=torch.uint8, device=dev)
         self.q = metis.SplitTensor(self.M, self.N, k, 2.0 ** -11, 2.0 ** -11, g_r, want_t)
@@ -85,8 +88,14 @@ class Operand:
     def split(self):
         self.metis.split_quantize(self.A, self.U, self.S, self.V, self.q, workspace=self.ws_split)
 
-    def prepare(self):
-        if self.k:
+    def fused(self):
+        self.metis.decompose_split_quantize(self.A, self.k, self.p, self.rho, self.seed, self.q, workspace=self.ws_dec,
+                                            factors=(self.U, self.S, self.V))
+
+    def prepare(self, two_call=True):
+        if self.k and not two_call:
+            self.fused()
+        elif self.k:
             self.decompose()
             self.split()
         else:
@@ -186,9 +195,11 @@ def main():
     split_ops = [o for o in all_ops if o.k]
     multi = n_split >= 2
 
+    fused = args.fused
+
     def batch_of(ops):
         return metis.DecomposeBatch([dict(A=o.A, k=o.k, p=o.p, rho=o.rho, seed=o.seed, U=o.U, S=o.S, V=o.V,
-                                          workspace=o.ws_dec) for o in ops]) if ops else None
+                                          workspace=o.ws_dec, split=o.q if fused else None) for o in ops]) if ops else None
 
     batch_all = batch_of(split_ops)
     batch_xg = batch_of([o for l in linears for o in (l.X, l.G) if o is not None and o.k])
@@ -203,7 +214,7 @@ def main():
                     o.prepare()
                 elif weights_from_parts and o is l.W:
                     o.prepare_from_parts()
-                else:
+                elif not fused:
                     o.split()
         for l in linears:
             l.gemms()
@@ -272,6 +283,8 @@ def main():
                    "linears": [{"name": l.name, "L": l.L, "K": l.K, "N": l.N} for l in linears],
                    "k": all_ops[0].k or linears[0].W.k, "p": linears[0].W.p, "gemms_per_step": n_gemm,
                    "decompositions_per_step": n_split, "useful_tflop_per_step": round(useful_flops / 1e12, 3),
+                   "split_path": "fused decompose + split (one HBM pass over each operand, metis_decompose_batch)" if fused
+                                 else "two calls per operand (metis_decompose_batch, then metis_split_quantize)",
                    "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "passes": passes,
@@ -356,38 +369,47 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
             continue
         seen.add(key)
         row = {"shape": [o.M, o.N], "orientations": o.orientations(), "sample_rate": round(o.rho, 4)}
-        for label, between in (("warm", None), ("cold", sweep)):
-            tb = metis.KernelTimer(metis.PROF_BROADCAST, 7)
-            tq = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, 7)
-            tot = []
-            o.prepare()
-            torch.cuda.synchronize()
-            with tb, tq:
-                for _ in range(7):
-                    if between:
-                        between()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    o.prepare()
-                    e1.record()
-                    torch.cuda.synchronize()
-                    tot.append(e0.elapsed_time(e1))
-            bd, rd = tb.durations_ms(7), tq.durations_ms(7)
-            tb.close()
-            tq.close()
-            mn = o.M * o.N
-            row[label] = {
-                "broadcast": dict(median_us=round(statistics.median(bd) * 1e3, 1), min_us=round(min(bd) * 1e3, 1),
-                                  frac_hbm=round(2.0 * mn / statistics.median(bd) / 1e6 / PEAK_HBM_GBS, 4)),
-                "residual_quant": dict(median_us=round(statistics.median(rd) * 1e3, 1), min_us=round(min(rd) * 1e3, 1),
-                                       frac_hbm=round(o.min_bytes() / statistics.median(rd) / 1e6 / PEAK_HBM_GBS, 4)),
-                "decompose_plus_split": dict(median_ms=round(statistics.median(tot), 4), min_ms=round(min(tot), 4),
-                                             effective_GBps_vs_minimum=round(o.min_bytes() / statistics.median(tot) / 1e6, 1))}
+        mn = o.M * o.N
+        for mode, two_call in (("two_call", True), ("fused", False)):
+            row[mode] = {}
+            for label, between in (("warm", None), ("cold", sweep)):
+                nb = 7 * 16                                        # the fused path launches one pair of kernels per band
+                tb = metis.KernelTimer(metis.PROF_BROADCAST, nb)
+                tq = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, nb)
+                tot = []
+                o.prepare(two_call)
+                torch.cuda.synchronize()
+                with tb, tq:
+                    for _ in range(7):
+                        if between:
+                            between()
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        o.prepare(two_call)
+                        e1.record()
+                        torch.cuda.synchronize()
+                        tot.append(e0.elapsed_time(e1))
+                bd, rd = tb.durations_ms(nb), tq.durations_ms(nb)
+                tb.close()
+                tq.close()
+                bands = max(1, len(bd) // 7) if not two_call else 1
+                bd = [sum(bd[i * bands:(i + 1) * bands]) for i in range(min(7, len(bd) // bands))]
+                rd = [sum(rd[i * bands:(i + 1) * bands]) for i in range(min(7, len(rd) // bands))]
+                row[mode][label] = {
+                    "broadcast": dict(median_us=round(statistics.median(bd) * 1e3, 1), min_us=round(min(bd) * 1e3, 1),
+                                      frac_hbm=round(2.0 * mn / statistics.median(bd) / 1e6 / PEAK_HBM_GBS, 4)),
+                    "residual_quant": dict(median_us=round(statistics.median(rd) * 1e3, 1), min_us=round(min(rd) * 1e3, 1),
+                                           frac_hbm=round(o.min_bytes() / statistics.median(rd) / 1e6 / PEAK_HBM_GBS, 4)),
+                    "decompose_plus_split": dict(median_ms=round(statistics.median(tot), 4), min_ms=round(min(tot), 4),
+                                                 effective_GBps_vs_minimum=round(o.min_bytes() / statistics.median(tot) / 1e6, 1))}
+                if not two_call:
+                    row[mode][label]["bands"] = bands
         alone.append(row)
     out["passes_standalone"] = {
         "rows": alone,
-        "bytes": "broadcast 2 M N; residual_quant (2 + 0.5625 orientations) M N; decompose_plus_split is the whole "
-                 "two-call chain against the algorithmic minimum 2 M N + 0.5625 M N orientations",
+        "bytes": "broadcast 2 M N; residual_quant (2 + 0.5625 orientations) M N (in the fused path the band's second "
+                 "read comes from the last-level cache; the fraction is still bytes moved / time); decompose_plus_split is "
+                 "the whole chain against the algorithmic minimum 2 M N + 0.5625 M N orientations",
         "timing": "HIP event pairs (about 3 us of bracket overhead per kernel); cold = a 1 GiB copy between repetitions"}
 
     # per-call wall time of each entry point on the first linear (and the last, if different)

@@ -136,6 +136,25 @@ int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, dou
                     const uint32_t* idx, int64_t n_idx, const uint16_t* omega, int32_t* info);
 
 /*
+ * Decomposition and split in one call, with one pass over A in HBM (Sec. 3.2's residual A - U S V^T equals
+ * A - (A V0) V0^T, V0 being the subspace found on the sampled rows, so it does not have to wait for the
+ * singular-value form of the factors).  A is processed in bands of rows small enough to stay in the
+ * last-level cache (64 MiB of A): a band's C = A V0 is formed, then the band is read again -- from cache -- for
+ * the residual and its quantization into out->R (and out->Rt when its codes pointer is non-null).  Afterwards
+ * U, S, V are brought to singular-value form as in metis_decompose and Q(U^T), Q(V^T), S go to out.
+ * Arguments as for metis_decompose and metis_split_quantize (out->R.tscale etc. are read as the tensor
+ * scales); workspace: metis_decompose_split_workspace_bytes.  U, S, V equal those of metis_decompose; the
+ * residual differs from the two-call form only by fp32 rounding (both subtract the same product in different
+ * factorizations), so quantization codes may differ where a value sits within rounding of a decision threshold.
+ * Errors: those of metis_decompose and metis_split_quantize.
+ */
+size_t metis_decompose_split_workspace_bytes(int64_t M, int64_t N, int k, int p, double rho);
+int metis_decompose_split_quantize(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
+                                   uint64_t seed, float* U, float* S, float* V, float* amax_out, metis_split* out,
+                                   float* R_debug, void* workspace, size_t workspace_bytes,
+                                   const uint32_t* idx, int64_t n_idx, const uint16_t* omega, int32_t* info);
+
+/*
  * Several decompositions in one call (Sec. 3.2: activations and output gradients are re-decomposed at every
  * step, so one training step decomposes many matrices; they are independent of each other).  Each job has
  * the arguments of metis_decompose; results are what n_jobs separate calls would give.  The stages that
@@ -160,6 +179,9 @@ typedef struct {
     int64_t  n_idx;
     const uint16_t* omega;
     int32_t* info;              /* optional */
+    metis_split* split;         /* optional: also split-quantize A as metis_decompose_split_quantize does; the
+                                   workspace is then metis_decompose_split_workspace_bytes */
+    float*   R_debug;           /* optional, with split: fp32 [M,N] dump of the quantizer's input */
 } metis_decompose_job;
 int metis_decompose_batch(void* stream, int n_jobs, const metis_decompose_job* jobs);
 

@@ -9,6 +9,7 @@
 #include "dgemm.h"
 #include "dgemm_skinny.h"
 #include "smallmat.h"
+#include "splitq.h"
 #include "rng_dev.h"
 #include <vector>
 
@@ -53,6 +54,33 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     L.off_jscr = take(jacobi_scratch_doubles((int)r) * 8);
     L.total = o;
     return L;
+}
+
+// Extra workspace of the fused decomposition + split (after the decomposition's own layout): the bf16 operands of
+// R = A - C V0^T and the partial products of one band of rows.  A band is as many rows as stay resident in the
+// last-level cache between the pass that forms C = A V0 and the pass that subtracts and quantizes (64 MiB of A).
+struct FusedLayout {
+    size_t off_us_hi, off_us_lo, off_v_hi, off_v_lo, off_band, total;
+    int64_t band_rows;
+    int kp;
+};
+
+FusedLayout make_fused_layout(size_t base, int64_t M, int64_t N, int k) {
+    FusedLayout F;
+    F.kp = padded_rank(k);
+    int64_t rows = (((int64_t)64 << 20) / (2 * N)) / 256 * 256;
+    if (rows < 256) rows = 256;
+    if (rows >= M) rows = M;
+    F.band_rows = rows;
+    size_t o = align_up(base, 256);
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    F.off_us_hi = take((size_t)M * F.kp * 2);
+    F.off_us_lo = take((size_t)M * F.kp * 2);
+    F.off_v_hi = take((size_t)N * F.kp * 2);
+    F.off_v_lo = take((size_t)N * F.kp * 2);
+    F.off_band = take((size_t)16 * (size_t)rows * (size_t)k * 4);
+    F.total = o;
+    return F;
 }
 
 // Everything the chain needs before its first product, in one launch: blocks [0, zero_blocks) clear the
@@ -145,6 +173,10 @@ struct Job {
     float *C, *V0f;
     uint32_t* idx;
     bf16_t *omega, *V0hi, *V0lo;
+    // fused split (split != nullptr): R = A - C V0^T is quantized band by band right after the band's C
+    metis_split* split;
+    float* R_debug;
+    FusedLayout F;
 };
 
 int make_job(const metis_decompose_job& a, Job& j) {
@@ -161,7 +193,16 @@ int make_job(const metis_decompose_job& a, Job& j) {
     if (j.r > j.Ms || j.r > j.N) return METIS_BAD_SHAPE;
     if (j.r > SM_MAX_CHOL || j.k > 128) return METIS_UNSUPPORTED;
     j.L = make_layout(j.M, j.N, a.k, a.oversample, j.Ms);
-    if (a.workspace_bytes < j.L.total) return METIS_WORKSPACE_TOO_SMALL;
+    j.split = a.split;
+    j.R_debug = a.R_debug;
+    size_t need = j.L.total;
+    if (a.split) {
+        const int cs = check_split_out(j.M, j.N, a.k, a.split);
+        if (cs != METIS_OK) return cs;
+        j.F = make_fused_layout(j.L.total, j.M, j.N, a.k);
+        need = j.F.total;
+    }
+    if (a.workspace_bytes < need) return METIS_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(a.workspace) % 16) return METIS_INVALID_ARG;
     const Layout& L = j.L;
     char* ws = (char*)a.workspace;
@@ -200,7 +241,7 @@ int make_job(const metis_decompose_job& a, Job& j) {
     // already: a device flag then turns the second pass's kernels into no-ops and the projection reads H1.
     j.wellcond = j.fast ? (int32_t*)(ws + L.off_flag) : nullptr;
     j.gram_fast = a.k % 4 == 0;
-    j.cparts = broadcast_splits(j.M, j.N);
+    j.cparts = a.split ? 1 : broadcast_splits(j.M, j.N);      // the fused path sums each band's parts at once
     return METIS_OK;
 }
 
@@ -331,10 +372,42 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
     METIS_LAUNCH_CHECK();
     for (const Job& j : jobs) {
         const int k = j.k;
-        const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
-        st = launch_broadcast(s, j.A, j.lda, j.M, j.N, j.V0hi, j.V0lo, k, j.C, (uint32_t*)j.amax_out);
-        metis_prof_end(METIS_PROF_BROADCAST, pi, s);
-        if (st != METIS_OK) return st;
+        if (j.split) {
+            // Fused split (R = A - U S V^T = A - (A V0) V0^T needs only V0): band by band, C = A V0 for the band's
+            // rows, then the band's residual and its quantization while the band is still in the last-level cache.
+            const FusedLayout& F = j.F;
+            bf16_t* us_hi = (bf16_t*)(j.ws + F.off_us_hi);
+            bf16_t* us_lo = (bf16_t*)(j.ws + F.off_us_lo);
+            bf16_t* v_hi = (bf16_t*)(j.ws + F.off_v_hi);
+            bf16_t* v_lo = (bf16_t*)(j.ws + F.off_v_lo);
+            float* band = (float*)(j.ws + F.off_band);
+            metis_split* o = j.split;
+            const bool want_t = o->Rt.codes != nullptr;
+            if ((st = launch_v_factors(s, j.V0f, j.N, k, F.kp, v_hi, v_lo)) != METIS_OK) return st;
+            for (int64_t r0 = 0; r0 < j.M; r0 += F.band_rows) {
+                const int64_t rows = j.M - r0 < F.band_rows ? j.M - r0 : F.band_rows;
+                const int parts = broadcast_splits(rows, j.N);
+                const bf16_t* Ab = j.A + r0 * j.lda;
+                const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
+                st = launch_broadcast(s, Ab, j.lda, rows, j.N, j.V0hi, j.V0lo, k, band, (uint32_t*)j.amax_out);
+                metis_prof_end(METIS_PROF_BROADCAST, pi, s);
+                if (st != METIS_OK) return st;
+                if ((st = launch_band_factors(s, band, parts, rows * (int64_t)k, rows, k, F.kp, j.C + r0 * k,
+                                              us_hi + r0 * F.kp, us_lo + r0 * F.kp)) != METIS_OK)
+                    return st;
+                if ((st = launch_residual_quant(s, Ab, j.lda, rows, j.N, j.M, r0, us_hi + r0 * F.kp, us_lo + r0 * F.kp, v_hi,
+                                                v_lo, F.kp, o->R.tscale, o->R.codes + r0 * (j.N / 2),
+                                                o->R.scales + r0 * (j.N / 16), want_t ? o->Rt.codes + r0 / 2 : nullptr,
+                                                want_t ? o->Rt.scales + r0 / 16 : nullptr,
+                                                j.R_debug ? j.R_debug + r0 * j.N : nullptr, false, 0)) != METIS_OK)
+                    return st;
+            }
+        } else {
+            const int pi = metis_prof_begin(METIS_PROF_BROADCAST, s);
+            st = launch_broadcast(s, j.A, j.lda, j.M, j.N, j.V0hi, j.V0lo, k, j.C, (uint32_t*)j.amax_out);
+            metis_prof_end(METIS_PROF_BROADCAST, pi, s);
+            if (st != METIS_OK) return st;
+        }
         const int64_t tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
         const int64_t cstride = j.M * (int64_t)k;
         if (j.gram_fast) {
@@ -369,7 +442,26 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
     }
     outmul.launch(s);
     METIS_LAUNCH_CHECK();
+    for (const Job& j : jobs)
+        if (j.split && (st = quantize_factors(s, j.U, j.S, j.V, j.M, j.N, j.k, j.split, false, 0)) != METIS_OK) return st;
     return METIS_OK;
+}
+
+extern "C" size_t metis_decompose_split_workspace_bytes(int64_t M, int64_t N, int k, int p, double rho) {
+    const size_t base = metis_decompose_workspace_bytes(M, N, k, p, rho);
+    if (base == 0 || k > 128) return 0;
+    return make_fused_layout(base, M, N, k).total;
+}
+
+extern "C" int metis_decompose_split_quantize(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
+                                              uint64_t seed, float* U, float* S, float* V, float* amax_out,
+                                              metis_split* out, float* R_debug, void* workspace, size_t workspace_bytes,
+                                              const uint32_t* idx_in, int64_t n_idx, const uint16_t* omega_in,
+                                              int32_t* info) {
+    if (!out) return METIS_INVALID_ARG;
+    const metis_decompose_job job = {A, k, oversample, sample_rate, seed, U, S, V, amax_out, workspace, workspace_bytes,
+                                     idx_in, n_idx, omega_in, info, out, R_debug};
+    return metis_decompose_batch(stream, 1, &job);
 }
 
 extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
@@ -377,6 +469,6 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
                                size_t workspace_bytes, const uint32_t* idx_in, int64_t n_idx,
                                const uint16_t* omega_in, int32_t* info) {
     const metis_decompose_job job = {A, k, oversample, sample_rate, seed, U, S, V, amax_out, workspace, workspace_bytes,
-                                     idx_in, n_idx, omega_in, info};
+                                     idx_in, n_idx, omega_in, info, nullptr, nullptr};
     return metis_decompose_batch(stream, 1, &job);
 }

@@ -4,6 +4,7 @@
 // The low-rank product runs on the bf16 matrix cores with both factors split in two bf16
 // parts (hi*hi + hi*lo + lo*hi, ~2^-16 relative), fp32 accumulation; A is streamed once and
 // the fp32 residual tile is quantized along both axes before it leaves the workgroup.
+#include "splitq.h"
 #include "quant_dev.h"
 #include <type_traits>
 
@@ -85,7 +86,10 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                  const bf16_t* __restrict__ us_hi, const bf16_t* __restrict__ us_lo,
                  const bf16_t* __restrict__ v_hi, const bf16_t* __restrict__ v_lo, QuantParams qp,
                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint8_t* __restrict__ codes_t,
-                 uint8_t* __restrict__ scales_t, float* __restrict__ R_debug, uint64_t seed) {
+                 uint8_t* __restrict__ scales_t, float* __restrict__ R_debug, uint64_t seed, int64_t Mt, int64_t row_off) {
+    // A may be a band of rows of a taller matrix: Mt = rows of the whole matrix (row length of the transposed
+    // outputs, whose pointers already point at this band's first row), row_off = the band's first row (only the
+    // stochastic-rounding word index needs it)
     constexpr int KP = 16 * KS, LDV = KP + 8;
     constexpr int VVEC = 2 * RQ_COLS * (KP / 8) / 256;                          // 16-byte V vectors per thread
     static_assert(VVEC * 256 == 2 * RQ_COLS * (KP / 8), "a V stage is a whole number of vectors per thread");
@@ -259,7 +263,7 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 }
                 if (WHOLE || (m < M && n < cend)) {
                     // stochastic rounding draws: stream 3, word = row-major position in R
-                    ss[bb] = SR ? quantize_block16_sr(x, qp, cc[bb], seed, 3u, (uint64_t)(m * N + n))
+                    ss[bb] = SR ? quantize_block16_sr(x, qp, cc[bb], seed, 3u, (uint64_t)((row_off + m) * N + n))
                                 : quantize_block16(x, qp, cc[bb]);
                     if (!WHOLE && R_debug) {
                         float4* dst = reinterpret_cast<float4*>(R_debug + m * N + n);
@@ -305,7 +309,7 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
                 const int64_t n = n0 + 32 * t + li, m = wr0 + 16 * half;
                 if (WHOLE || (n < cend && m < M)) {
                     // transposed copy: stream 4, word = row-major position in R^T
-                    st[t] = SR ? quantize_block16_sr(x, qp, ct[t], seed, 4u, (uint64_t)(n * M + m))
+                    st[t] = SR ? quantize_block16_sr(x, qp, ct[t], seed, 4u, (uint64_t)(n * Mt + row_off + m))
                                : quantize_block16(x, qp, ct[t]);
                 }
             }
@@ -315,8 +319,8 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
             auto sy = __builtin_amdgcn_permlane32_swap(ct[0].y, ct[1].y, false, false);
             auto sq = __builtin_amdgcn_permlane32_swap(st[0], st[1], false, false);
             const int64_t n = n0 + 32 * half + li;
-            uint8_t* cp = codes_t + n * (M / 2) + wr0 / 2;
-            uint8_t* sp = scales_t + n * (M / 16) + wr0 / 16;
+            uint8_t* cp = codes_t + n * (Mt / 2) + wr0 / 2;
+            uint8_t* sp = scales_t + n * (Mt / 16) + wr0 / 16;
             if (WHOLE) {
                 const uvec4_t cv = {sx[0], sy[0], sx[1], sy[1]};
                 Tst[32 * half + li][wave] = cv;
@@ -335,8 +339,8 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
         if (WHOLE && WT) {
             // four lanes cover the 64 bytes one column of A gets from this workgroup's 128 rows
             const int nl = tid >> 2, w = tid & 3;
-            *reinterpret_cast<uvec4_t*>(codes_t + (n0 + nl) * (M / 2) + brow0 / 2 + 16 * w) = Tst[nl][w];
-            *reinterpret_cast<uint16_t*>(scales_t + (n0 + nl) * (M / 16) + brow0 / 16 + 2 * w) = Tsc[nl][w];
+            *reinterpret_cast<uvec4_t*>(codes_t + (n0 + nl) * (Mt / 2) + brow0 / 2 + 16 * w) = Tst[nl][w];
+            *reinterpret_cast<uint16_t*>(scales_t + (n0 + nl) * (Mt / 16) + brow0 / 16 + 2 * w) = Tsc[nl][w];
         }
         store_v(v_nxt, n0 + RQ_COLS, more, WHOLE);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -349,7 +353,7 @@ k_residual_quant(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N
     // 4-byte (transposed copy: 2-byte) scale stores are aligned
     const bool whole = !R_debug && brow0 + RQ_ROWS <= M && (cend - cbeg) % RQ_COLS == 0 && N % 64 == 0 &&
                        reinterpret_cast<uintptr_t>(codes) % 16 == 0 && reinterpret_cast<uintptr_t>(scales) % 4 == 0 &&
-                       (!WT || (M % 32 == 0 && reinterpret_cast<uintptr_t>(codes_t) % 16 == 0 &&
+                       (!WT || (M % 32 == 0 && Mt % 32 == 0 && reinterpret_cast<uintptr_t>(codes_t) % 16 == 0 &&
                                 reinterpret_cast<uintptr_t>(scales_t) % 2 == 0));
     if (whole) {
         int g = 0;
@@ -378,9 +382,90 @@ __global__ void k_copy_f32(const float* __restrict__ src, float* __restrict__ ds
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[i];
 }
+
+// C = sum of the partial products (fp64 sum in part order, rounded once: the same sum the Gram kernel takes of
+// separate parts), -C as bf16 hi / lo with the rank padded to kp
+__global__ void __launch_bounds__(256)
+k_band_factors(const float* __restrict__ parts, int nparts, int64_t part_stride, int64_t rows, int k, int kp,
+               float* __restrict__ C_out, bf16_t* __restrict__ us_hi, bf16_t* __restrict__ us_lo) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * kp) return;
+    const int64_t row = t / kp;
+    const int c = (int)(t - row * kp);
+    float x = 0.0f;
+    if (c < k) {
+        double acc = 0.0;
+        for (int p = 0; p < nparts; ++p) acc += (double)parts[p * part_stride + row * k + c];
+        x = (float)acc;
+        C_out[row * k + c] = x;
+        x = -x;
+    }
+    const bf16_t h = f32_to_bf16_rne(x);
+    us_hi[row * kp + c] = h;
+    us_lo[row * kp + c] = f32_to_bf16_rne(x - bf16_to_f32(h));
+}
 }  // namespace
 
-static int padded_rank(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : k <= 64 ? 64 : 128; }
+int launch_v_factors(hipStream_t s, const float* V, int64_t N, int k, int kp, bf16_t* v_hi, bf16_t* v_lo) {
+    hipLaunchKernelGGL(k_split_factors, dim3((unsigned)ceil_div64(N * kp, 256)), dim3(256), 0, s, (const float*)nullptr,
+                       (const float*)nullptr, V, (int64_t)0, N, k, kp, (bf16_t*)nullptr, (bf16_t*)nullptr, v_hi, v_lo,
+                       (float*)nullptr);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+int launch_band_factors(hipStream_t s, const float* parts, int nparts, int64_t part_stride, int64_t rows, int k, int kp,
+                        float* C_out, bf16_t* us_hi, bf16_t* us_lo) {
+    hipLaunchKernelGGL(k_band_factors, dim3((unsigned)ceil_div64(rows * kp, 256)), dim3(256), 0, s, parts, nparts, part_stride,
+                       rows, k, kp, C_out, us_hi, us_lo);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+int check_split_out(int64_t M, int64_t N, int k, const metis_split* out) {
+    if (!out || k < 1 || out->k != k || !out->S) return METIS_INVALID_ARG;
+    if (k > 128) return METIS_UNSUPPORTED;
+    if (N % 16) return METIS_BAD_SHAPE;
+    const bool want_t = out->Rt.codes != nullptr;
+    if (!fp4_ok(out->R, M, N)) return METIS_BAD_SHAPE;
+    if (want_t && (!fp4_ok(out->Rt, N, M) || out->Rt.tscale != out->R.tscale)) return METIS_BAD_SHAPE;
+    if (!fp4_ok(out->Ut, k, M) || !fp4_ok(out->Vt, k, N)) return METIS_BAD_SHAPE;
+    return METIS_OK;
+}
+
+
+// Launch of the fused residual + quantize kernel on A [M rows, N] (possibly a band of rows of a matrix with Mt
+// rows, starting at row row_off; the transposed outputs then point at the band's first row).
+int launch_residual_quant(hipStream_t s, const bf16_t* Ap, int64_t lda, int64_t M, int64_t N, int64_t Mt, int64_t row_off,
+                          const bf16_t* us_hi, const bf16_t* us_lo, const bf16_t* v_hi, const bf16_t* v_lo, int kp, float g,
+                          uint8_t* codes, uint8_t* scales, uint8_t* ct, uint8_t* st_, float* R_debug, bool sr, uint64_t seed) {
+    // about two workgroups per CU; every workgroup walks at least four 64-column steps
+    const int64_t row_blocks = ceil_div64(M, RQ_ROWS);
+    int64_t want = ceil_div64(512, row_blocks);
+    int64_t cchunk = ceil_div64(ceil_div64(N, want), RQ_COLS) * RQ_COLS;
+    if (cchunk < 4 * RQ_COLS) cchunk = 4 * RQ_COLS;
+    dim3 grid((unsigned)row_blocks, (unsigned)ceil_div64(N, cchunk));
+    const QuantParams qp = make_quant_params(g);
+    const bool want_t = ct != nullptr;
+    const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
+#define RQ_LAUNCH3(KS_, SR_, WT_)                                                                                       \
+    hipLaunchKernelGGL((k_residual_quant<KS_, SR_, WT_>), grid, dim3(256), 0, s, Ap, lda, M, N, cchunk, us_hi, us_lo,   \
+                       v_hi, v_lo, qp, codes, scales, ct, st_, R_debug, seed, Mt, row_off)
+#define RQ_LAUNCH(KS_, WT_) do { if (sr) RQ_LAUNCH3(KS_, true, WT_); else RQ_LAUNCH3(KS_, false, WT_); } while (0)
+    switch (kp / 16) {
+        case 1: if (want_t) RQ_LAUNCH(1, true); else RQ_LAUNCH(1, false); break;
+        case 2: if (want_t) RQ_LAUNCH(2, true); else RQ_LAUNCH(2, false); break;
+        case 4: if (want_t) RQ_LAUNCH(4, true); else RQ_LAUNCH(4, false); break;
+        default: if (want_t) RQ_LAUNCH(8, true); else RQ_LAUNCH(8, false); break;
+    }
+#undef RQ_LAUNCH
+#undef RQ_LAUNCH3
+    metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+int padded_rank(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : k <= 64 ? 64 : 128; }
 
 extern "C" size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k) {
     if (M < 1 || N < 1 || k < 1 || k > 128) return 0;
@@ -389,6 +474,28 @@ extern "C" size_t metis_split_workspace_bytes(int64_t M, int64_t N, int k) {
 }
 
 extern "C" int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t);
+
+extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* out_t);
+
+int quantize_factors(hipStream_t s, const float* U, const float* S, const float* V, int64_t M, int64_t N, int k,
+                     metis_split* out, bool sr, uint64_t seed) {
+    // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
+    metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
+    int st;
+    if (sr) {
+        // the factors draw under their own keys so that no two tensors share draws
+        if ((st = metis_quantize_sr((void*)s, &um, seed + 1, nullptr, &out->Ut)) != METIS_OK) return st;
+        if ((st = metis_quantize_sr((void*)s, &vm, seed + 2, nullptr, &out->Vt)) != METIS_OK) return st;
+    } else {
+        if ((st = metis_quantize((void*)s, &um, nullptr, &out->Ut)) != METIS_OK) return st;
+        if ((st = metis_quantize((void*)s, &vm, nullptr, &out->Vt)) != METIS_OK) return st;
+    }
+    if (S && out->S != S) {
+        hipLaunchKernelGGL(k_copy_f32, dim3(1), dim3(128), 0, s, S, out->S, k);
+        METIS_LAUNCH_CHECK();
+    }
+    return METIS_OK;
+}
 
 template <bool SR>
 static int split_quantize_impl(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,
@@ -418,40 +525,15 @@ static int split_quantize_impl(void* stream, const metis_mat* A, const float* U,
     int64_t tot = (M + N) * kp;
     hipLaunchKernelGGL(k_split_factors, dim3((unsigned)ceil_div64(tot, 256)), dim3(256), 0, s, U, S, V, M, N, k, kp,
                        us_hi, us_lo, v_hi, v_lo, out->S);
-    // about two workgroups per CU; every workgroup walks at least four 64-column steps
-    const int64_t row_blocks = ceil_div64(M, RQ_ROWS);
-    int64_t want = ceil_div64(512, row_blocks);
-    int64_t cchunk = ceil_div64(ceil_div64(N, want), RQ_COLS) * RQ_COLS;
-    if (cchunk < 4 * RQ_COLS) cchunk = 4 * RQ_COLS;
-    dim3 grid((unsigned)row_blocks, (unsigned)ceil_div64(N, cchunk));
-    const QuantParams qp = make_quant_params(out->R.tscale);
+    const bf16_t* Ap = (const bf16_t*)A->ptr;
     uint8_t* ct = want_t ? out->Rt.codes : nullptr;
     uint8_t* st_ = want_t ? out->Rt.scales : nullptr;
-    const bf16_t* Ap = (const bf16_t*)A->ptr;
-    const int pi = metis_prof_begin(METIS_PROF_RESIDUAL_QUANT, s);
-#define RQ_LAUNCH(KS_, WT_)                                                                                         \
-    hipLaunchKernelGGL((k_residual_quant<KS_, SR, WT_>), grid, dim3(256), 0, s, Ap, A->ld, M, N, cchunk, us_hi, us_lo, \
-                       v_hi, v_lo, qp, out->R.codes, out->R.scales, ct, st_, R_debug, seed)
-    switch (kp / 16) {
-        case 1: if (want_t) RQ_LAUNCH(1, true); else RQ_LAUNCH(1, false); break;
-        case 2: if (want_t) RQ_LAUNCH(2, true); else RQ_LAUNCH(2, false); break;
-        case 4: if (want_t) RQ_LAUNCH(4, true); else RQ_LAUNCH(4, false); break;
-        default: if (want_t) RQ_LAUNCH(8, true); else RQ_LAUNCH(8, false); break;
+    {
+        const int rs = launch_residual_quant(s, Ap, A->ld, M, N, M, 0, us_hi, us_lo, v_hi, v_lo, kp, out->R.tscale,
+                                             out->R.codes, out->R.scales, ct, st_, R_debug, SR, seed);
+        if (rs != METIS_OK) return rs;
     }
-#undef RQ_LAUNCH
-    metis_prof_end(METIS_PROF_RESIDUAL_QUANT, pi, s);
-    METIS_LAUNCH_CHECK();
-    // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
-    metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
-    if (SR) {
-        // the factors draw under their own keys so that no two tensors share draws
-        int st = metis_quantize_sr(stream, &um, seed + 1, nullptr, &out->Ut);
-        if (st != METIS_OK) return st;
-        return metis_quantize_sr(stream, &vm, seed + 2, nullptr, &out->Vt);
-    }
-    int st = metis_quantize(stream, &um, nullptr, &out->Ut);
-    if (st != METIS_OK) return st;
-    return metis_quantize(stream, &vm, nullptr, &out->Vt);
+    return quantize_factors(s, U, nullptr, V, M, N, k, out, SR, seed);
 }
 
 extern "C" int metis_split_quantize(void* stream, const metis_mat* A, const float* U, const float* S, const float* V,

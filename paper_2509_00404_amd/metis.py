@@ -37,7 +37,7 @@ class DecomposeJob(C.Structure):
     _fields_ = [("A", C.POINTER(Mat)), ("k", C.c_int), ("oversample", C.c_int), ("sample_rate", C.c_double),
                 ("seed", C.c_uint64), ("U", C.c_void_p), ("S", C.c_void_p), ("V", C.c_void_p), ("amax_out", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("idx", C.c_void_p), ("n_idx", C.c_int64),
-                ("omega", C.c_void_p), ("info", C.c_void_p)]
+                ("omega", C.c_void_p), ("info", C.c_void_p), ("split", C.POINTER(Split)), ("R_debug", C.c_void_p)]
 
 
 class MetisError(RuntimeError):
@@ -57,6 +57,11 @@ _SIGNATURES = {
     "metis_decompose": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_int, C.c_int, C.c_double, C.c_uint64,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "metis_decompose_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double]),
+    "metis_decompose_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_int, C.c_int, C.c_double, C.c_uint64,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Split),
+                                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_int64, C.c_void_p,
+                                                 C.c_void_p]),
     "metis_decompose_batch": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(DecomposeJob)]),
     "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
     "metis_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_uint64, C.POINTER(Fp4), C.POINTER(Fp4)]),
@@ -222,8 +227,12 @@ class DecomposeBatch:
     def __init__(self, jobs):
         self.keep = jobs                                   # the tensors stay alive with the block
         self.mats = [_mat(j["A"]) for j in jobs]
+        self.splits = [j["split"].c() if j.get("split") is not None else None for j in jobs]
         self.arr = (DecomposeJob * len(jobs))()
-        for a, m, j in zip(self.arr, self.mats, jobs):
+        for a, m, sp, j in zip(self.arr, self.mats, self.splits, jobs):
+            if sp is not None:                             # optional keys: split (SplitTensor), R_debug
+                a.split = C.pointer(sp)
+                a.R_debug = j["R_debug"].data_ptr() if j.get("R_debug") is not None else None
             ptr = lambda key: j[key].data_ptr() if j.get(key) is not None else None
             a.A = C.pointer(m)
             a.k, a.oversample, a.sample_rate, a.seed = j["k"], j["p"], j["rho"], j["seed"]
@@ -234,6 +243,32 @@ class DecomposeBatch:
 
     def run(self):
         _check(lib().metis_decompose_batch(_stream(), len(self.arr), self.arr))
+
+
+def decompose_split_workspace_bytes(M, N, k, p, rho):
+    return int(lib().metis_decompose_split_workspace_bytes(M, N, k, p, rho))
+
+
+def decompose_split_quantize(A, k, oversample, sample_rate, seed, out, R_debug=None, workspace=None, factors=None,
+                             idx=None, omega=None, info=None):
+    """Fused decomposition + split of A into `out` (SplitTensor); returns (U, S, V)."""
+    M, N = A.shape
+    if factors is None:
+        U = torch.empty((M, k), dtype=torch.float32, device=A.device)
+        S = torch.empty((k,), dtype=torch.float32, device=A.device)
+        V = torch.empty((N, k), dtype=torch.float32, device=A.device)
+    else:
+        U, S, V = factors
+    if workspace is None:
+        workspace = torch.empty((decompose_split_workspace_bytes(M, N, k, oversample, sample_rate),), dtype=torch.uint8,
+                                device=A.device)
+    a, s = _mat(A), out.c()
+    _check(lib().metis_decompose_split_quantize(
+        _stream(), C.byref(a), k, oversample, sample_rate, seed, U.data_ptr(), S.data_ptr(), V.data_ptr(), None,
+        C.byref(s), R_debug.data_ptr() if R_debug is not None else None, workspace.data_ptr(), workspace.numel(),
+        idx.data_ptr() if idx is not None else None, idx.numel() if idx is not None else 0,
+        omega.data_ptr() if omega is not None else None, info.data_ptr() if info is not None else None))
+    return U, S, V
 
 
 def quantize(A, out=None, out_t=None):
@@ -389,6 +424,7 @@ class KernelTimer:
         self.hip.hipEventCreate.restype = C.c_int
         self.hip.hipEventElapsedTime.restype = C.c_int
         self.hip.hipEventDestroy.restype = C.c_int
+        self.hip.hipGetLastError.restype = C.c_int
         self.start = (C.c_void_p * n)()
         self.stop = (C.c_void_p * n)()
         for arr in (self.start, self.stop):
@@ -421,10 +457,13 @@ class KernelTimer:
             pass
 
     def durations_ms(self, count):
-        """Durations of the last `count` (<= n) bracketed launches; call after a device sync."""
+        """Durations of the first `count` (<= n) bracketed launches since the timer was switched on, stopping at
+        the first pair that was never recorded; call after a device sync."""
         out = []
         for i in range(min(count, self.n)):
             ms = C.c_float()
-            if self.hip.hipEventElapsedTime(C.byref(ms), self.start[i], self.stop[i]) == 0:
-                out.append(ms.value)
+            if self.hip.hipEventElapsedTime(C.byref(ms), self.start[i], self.stop[i]) != 0:
+                self.hip.hipGetLastError()                  # an unrecorded pair: clear the error it left behind
+                break
+            out.append(ms.value)
         return out
