@@ -18,19 +18,20 @@ import numpy as np
 from . import rng
 
 
-def decompose(A, k, p, rho, seed, idx=None, omega=None, details=None):
+def decompose(A, k, p, rho, seed, idx=None, omega=None, details=None, group=1):
     """A[M,N] fp64 -> U[M,k], S[k], V[N,k].
 
     idx / omega override the seeded draws (used to feed identical draws to two
     implementations).  details (optional dict) receives by-products for reports:
     'sigma_reduced' = all k+p singular values of the reduced matrix B, whose gap
-    between positions k and k+1 says how well defined the selected subspace is."""
+    between positions k and k+1 says how well defined the selected subspace is.
+    group > 1: whole sequences of `group` consecutive rows are sampled (Sec. 3.1)."""
     A = np.asarray(A, dtype=np.float64)
     M, N = A.shape
     r = k + p
     if idx is None:
-        Ms = rng.sample_count(M, k, p, rho)
-        idx = rng.sample_rows(seed, M, Ms)
+        Ms = rng.sample_count(M, k, p, rho, group)
+        idx = rng.sample_rows(seed, M, Ms, group)
     if omega is None:
         omega = rng.gaussian_omega(seed, N, r)
     As = A[idx, :]                        # sparse random sampling of rows

@@ -60,20 +60,32 @@ def philox_words(seed, stream, first, count):
     return out[np.arange(count), lane]
 
 
-def sample_count(M, k, p, rho):
-    """Number of sampled rows l_k: ceil(rho*M), at least k+p, at most M."""
+def sample_count(M, k, p, rho, group=1):
+    """Number of sampled rows l_k.  group = 1: ceil(rho*M), at least k+p, at most M.
+    group > 1 (whole sequences of `group` consecutive rows are drawn, Sec. 3.1 samples sequences; M % group == 0):
+    ceil(rho * M/group) sequences, at least ceil((k+p)/group), at most M/group, times group."""
     r = k + p
-    return int(min(M, max(r, int(np.ceil(rho * M - 1e-12)))))
+    if group == 1:
+        return int(min(M, max(r, int(np.ceil(rho * M - 1e-12)))))
+    assert M % group == 0
+    G = M // group
+    return int(min(G, max(-(-r // group), int(np.ceil(rho * G - 1e-12))))) * group
 
 
-def sample_rows(seed, M, Ms):
+def sample_rows(seed, M, Ms, group=1):
     """Random subset of Ms of the M rows (Sec. 3.1, sparse random sampling).
 
     Reading: one row drawn uniformly from each of Ms equal strata, so the rows
     are distinct, ascending, and every row has inclusion probability ~Ms/M.
       lo_j = floor(j*M/Ms), hi_j = floor((j+1)*M/Ms),
       idx_j = lo_j + (u_j mod (hi_j - lo_j)),  u_j = word j of stream 1.
+    group > 1: the same draw over the M/group sequences (Ms/group of them), each chosen
+    sequence contributing its `group` consecutive rows.
     """
+    if group > 1:
+        assert M % group == 0 and Ms % group == 0
+        g = sample_rows(seed, M // group, Ms // group)
+        return (g[:, None] * group + np.arange(group, dtype=np.int64)[None, :]).reshape(-1)
     j = np.arange(Ms, dtype=np.int64)
     lo = (j * M) // Ms
     hi = ((j + 1) * M) // Ms

@@ -106,3 +106,27 @@ def test_omega_entry_definition():
     u2 = (int(w[1]) >> 8) / 2 ** 24
     z = math.sqrt(-2 * math.log(u1)) * math.cos(2 * math.pi * u2)
     assert abs(om[2, 3] - z) <= abs(z) * 2.0 ** -8
+
+
+def test_sequence_granular_sample_closed_form():
+    # whole sequences of `group` consecutive rows: group-aligned runs, distinct, ascending, one sequence per stratum
+    # of sequences, the sequence indices being the (already pinned) row sampler's draw over M/group items
+    for M, group, k, p, rho in ((4096, 64, 8, 8, 1.0 / 16), (8192, 512, 64, 16, 1.0 / 16), (1024, 16, 64, 16, 0.01),
+                                (960, 32, 4, 4, 0.5), (256, 256, 8, 8, 0.1)):
+        Ms = rng.sample_count(M, k, p, rho, group)
+        G = M // group
+        assert Ms % group == 0 and Ms <= M
+        Gs = Ms // group
+        assert Gs == min(G, max(-(-(k + p) // group), int(np.ceil(rho * G - 1e-12))))
+        assert Ms >= min(M, k + p)
+        idx = rng.sample_rows(123, M, Ms, group)
+        assert idx.shape == (Ms,) and np.all(np.diff(idx) > 0) and idx.min() >= 0 and idx.max() < M
+        runs = idx.reshape(Gs, group)
+        assert np.all(runs[:, 0] % group == 0) and np.all(np.diff(runs, axis=1) == 1)
+        g = runs[:, 0] // group
+        j = np.arange(Gs)
+        assert np.all(g >= (j * G) // Gs) and np.all(g < ((j + 1) * G) // Gs)
+        assert np.array_equal(g, rng.sample_rows(123, G, Gs))
+    # group = 1 is the row sampler itself
+    assert rng.sample_count(8192, 64, 16, 1.0 / 16, 1) == rng.sample_count(8192, 64, 16, 1.0 / 16)
+    assert np.array_equal(rng.sample_rows(9, 8192, 512, 1), rng.sample_rows(9, 8192, 512))
