@@ -103,6 +103,18 @@ int64_t metis_sample_count(int64_t M, int k, int p, double rho);
 int metis_sample_rows(void* stream, uint64_t seed, int64_t M, int64_t Ms, uint32_t* idx);
 
 /*
+ * Sequence-granular sample (Sec. 3.1 speaks of sampling sequences, i.e. runs of consecutive token rows): the M
+ * rows are M / group sequences of `group` consecutive rows (M % group == 0); whole sequences are drawn exactly as
+ * metis_sample_rows draws rows -- one sequence per stratum of sequences, offset = word j of Philox stream 1 modulo
+ * the stratum length -- and each contributes its rows in order.  metis_sample_count_sequences gives the number of
+ * sampled ROWS: ceil(rho * M / group) sequences, at least ceil((k+p) / group), at most M / group, times group
+ * (0 on invalid arguments); group = 1 is metis_sample_count / metis_sample_rows.  idx: device uint32 [Ms].
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE (M or Ms not a multiple of group, Ms > M).
+ */
+int64_t metis_sample_count_sequences(int64_t M, int k, int p, double rho, int64_t group);
+int metis_sample_sequences(void* stream, uint64_t seed, int64_t M, int64_t Ms, int64_t group, uint32_t* idx);
+
+/*
  * Gaussian test matrix (Sec. 3.1, random projection): omega[N,r] (device, bf16 bits as
  * uint16, row-major).  Entry e = n*r+c: Box-Muller on words 2e, 2e+1 of Philox stream 2,
  * u1 = ((w0>>9)+0.5)*2^-23, u2 = (w1>>8)*2^-24, z = sqrt(-2 ln u1) cos(2 pi u2), rounded
@@ -182,6 +194,8 @@ typedef struct {
     metis_split* split;         /* optional: also split-quantize A as metis_decompose_split_quantize does; the
                                    workspace is then metis_decompose_split_workspace_bytes */
     float*   R_debug;           /* optional, with split: fp32 [M,N] dump of the quantizer's input */
+    int64_t  sample_group;      /* 0 or 1: rows are sampled; > 1: whole sequences of that many consecutive rows
+                                   (metis_sample_sequences; needs M % sample_group == 0) */
 } metis_decompose_job;
 int metis_decompose_batch(void* stream, int n_jobs, const metis_decompose_job* jobs);
 

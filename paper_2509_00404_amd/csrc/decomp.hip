@@ -89,8 +89,8 @@ FusedLayout make_fused_layout(size_t base, int64_t M, int64_t N, int k) {
 // the caller supplied it).
 __global__ void __launch_bounds__(256)
 k_decomp_setup(uint32_t* __restrict__ zero, size_t nwords, uint32_t* __restrict__ amax_out, int32_t* __restrict__ info,
-               int zero_blocks, int idx_blocks, uint64_t seed, int64_t M, int64_t Ms, uint32_t* __restrict__ idx,
-               int64_t omega_count, bf16_t* __restrict__ omega) {
+               int zero_blocks, int idx_blocks, uint64_t seed, int64_t M, int64_t Ms, int64_t group,
+               uint32_t* __restrict__ idx, int64_t omega_count, bf16_t* __restrict__ omega) {
     const int b = blockIdx.x;
     if (b < zero_blocks) {
         size_t i = (size_t)b * 256 + threadIdx.x;
@@ -102,7 +102,7 @@ k_decomp_setup(uint32_t* __restrict__ zero, size_t nwords, uint32_t* __restrict_
         }
     } else if (b < zero_blocks + idx_blocks) {
         const int64_t j = (int64_t)(b - zero_blocks) * 256 + threadIdx.x;
-        if (j < Ms) idx[j] = sample_row(seed, M, Ms, j);
+        if (j < Ms) idx[j] = sample_row_grouped(seed, M, Ms, group, j);
     } else {
         gaussian_pair(seed, (int64_t)(b - zero_blocks - idx_blocks) * 256 + threadIdx.x, omega_count, omega);
     }
@@ -158,7 +158,7 @@ namespace {
 // One decomposition in flight: the caller's arguments plus the carved-up workspace.
 struct Job {
     const bf16_t* A;
-    int64_t M, N, lda, Ms;
+    int64_t M, N, lda, Ms, group;
     int k, r;
     uint64_t seed;
     float *U, *S, *V, *amax_out;
@@ -188,7 +188,9 @@ int make_job(const metis_decompose_job& a, Job& j) {
     if (j.N % 8 || j.lda % 8 || reinterpret_cast<uintptr_t>(a.A->ptr) % 16) return METIS_BAD_SHAPE;  // 16-byte row loads
     j.k = a.k;
     j.r = a.k + a.oversample;
-    j.Ms = a.idx ? a.n_idx : metis_sample_count(j.M, a.k, a.oversample, a.sample_rate);
+    j.group = a.sample_group > 1 ? a.sample_group : 1;
+    if (j.group > 1 && (j.M % j.group || j.M >= ((int64_t)1 << 32))) return METIS_BAD_SHAPE;
+    j.Ms = a.idx ? a.n_idx : metis_sample_count_sequences(j.M, a.k, a.oversample, a.sample_rate, j.group);
     if (j.Ms < 1 || j.Ms > j.M) return METIS_BAD_SHAPE;
     if (j.r > j.Ms || j.r > j.N) return METIS_BAD_SHAPE;
     if (j.r > SM_MAX_CHOL || j.k > 128) return METIS_UNSUPPORTED;
@@ -291,7 +293,7 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
         const int64_t omega_blocks = j.omega_in ? 0 : ceil_div64(ceil_div64(omega_count, 2), 256);
         hipLaunchKernelGGL(k_decomp_setup, dim3((unsigned)(zero_blocks + idx_blocks + omega_blocks)), dim3(256), 0, s,
                            (uint32_t*)j.ws, j.L.zero_bytes / 4, (uint32_t*)j.amax_out, j.info, zero_blocks, idx_blocks, j.seed,
-                           j.M, j.Ms, j.idx_in ? nullptr : j.idx, omega_count, j.omega_in ? nullptr : j.omega);
+                           j.M, j.Ms, j.group, j.idx_in ? nullptr : j.idx, omega_count, j.omega_in ? nullptr : j.omega);
         METIS_LAUNCH_CHECK();
     }
     // products of the same kind and step of all jobs go out together (DgemmList): the small ones are latency-bound
@@ -460,7 +462,7 @@ extern "C" int metis_decompose_split_quantize(void* stream, const metis_mat* A, 
                                               int32_t* info) {
     if (!out) return METIS_INVALID_ARG;
     const metis_decompose_job job = {A, k, oversample, sample_rate, seed, U, S, V, amax_out, workspace, workspace_bytes,
-                                     idx_in, n_idx, omega_in, info, out, R_debug};
+                                     idx_in, n_idx, omega_in, info, out, R_debug, 1};
     return metis_decompose_batch(stream, 1, &job);
 }
 
@@ -469,6 +471,6 @@ extern "C" int metis_decompose(void* stream, const metis_mat* A, int k, int over
                                size_t workspace_bytes, const uint32_t* idx_in, int64_t n_idx,
                                const uint16_t* omega_in, int32_t* info) {
     const metis_decompose_job job = {A, k, oversample, sample_rate, seed, U, S, V, amax_out, workspace, workspace_bytes,
-                                     idx_in, n_idx, omega_in, info, nullptr, nullptr};
+                                     idx_in, n_idx, omega_in, info, nullptr, nullptr, 1};
     return metis_decompose_batch(stream, 1, &job);
 }

@@ -13,6 +13,14 @@ __device__ __forceinline__ uint32_t sample_row(uint64_t seed, int64_t M, int64_t
     return (uint32_t)(lo + u % (uint32_t)(hi - lo));
 }
 
+// Row j of a sample of whole sequences of `group` consecutive rows: sequence j / group of the sample is drawn like
+// a row above among the M / group sequences, and contributes its rows in order.  group = 1 is sample_row.
+__device__ __forceinline__ uint32_t sample_row_grouped(uint64_t seed, int64_t M, int64_t Ms, int64_t group, int64_t j) {
+    if (group <= 1) return sample_row(seed, M, Ms, j);
+    const int64_t jg = j / group;
+    return sample_row(seed, M / group, Ms / group, jg) * (uint32_t)group + (uint32_t)(j - jg * group);
+}
+
 // Entries 2 b and 2 b + 1 of Omega (one Philox block of stream 2 = 4 words = 2 Box-Muller entries).
 __device__ __forceinline__ void gaussian_pair(uint64_t seed, int64_t b, int64_t count, bf16_t* __restrict__ omega) {
     int64_t e0 = b * 2;

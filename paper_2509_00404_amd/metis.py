@@ -37,7 +37,7 @@ class DecomposeJob(C.Structure):
     _fields_ = [("A", C.POINTER(Mat)), ("k", C.c_int), ("oversample", C.c_int), ("sample_rate", C.c_double),
                 ("seed", C.c_uint64), ("U", C.c_void_p), ("S", C.c_void_p), ("V", C.c_void_p), ("amax_out", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("idx", C.c_void_p), ("n_idx", C.c_int64),
-                ("omega", C.c_void_p), ("info", C.c_void_p), ("split", C.POINTER(Split)), ("R_debug", C.c_void_p)]
+                ("omega", C.c_void_p), ("info", C.c_void_p), ("split", C.POINTER(Split)), ("R_debug", C.c_void_p), ("sample_group", C.c_int64)]
 
 
 class MetisError(RuntimeError):
@@ -52,6 +52,8 @@ _SIGNATURES = {
     "metis_tensor_scale": (C.c_float, [C.c_float]),
     "metis_sample_count": (C.c_int64, [C.c_int64, C.c_int, C.c_int, C.c_double]),
     "metis_sample_rows": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int64, C.c_void_p]),
+    "metis_sample_count_sequences": (C.c_int64, [C.c_int64, C.c_int, C.c_int, C.c_double, C.c_int64]),
+    "metis_sample_sequences": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]),
     "metis_gaussian_omega": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int64, C.c_int, C.c_void_p]),
     "metis_decompose_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double]),
     "metis_decompose": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_int, C.c_int, C.c_double, C.c_uint64,
@@ -177,13 +179,14 @@ def tensor_scale(amax):
     return float(lib().metis_tensor_scale(float(amax)))
 
 
-def sample_count(M, k, p, rho):
-    return int(lib().metis_sample_count(M, k, p, rho))
+def sample_count(M, k, p, rho, group=1):
+    return int(lib().metis_sample_count_sequences(M, k, p, rho, group))
 
 
-def sample_rows(seed, M, Ms, device="cuda"):
+def sample_rows(seed, M, Ms, device="cuda", group=1):
+    """Row sample; group > 1 draws whole sequences of that many consecutive rows."""
     idx = torch.empty((Ms,), dtype=torch.int32, device=device)      # uint32 bits
-    _check(lib().metis_sample_rows(_stream(), seed, M, Ms, idx.data_ptr()))
+    _check(lib().metis_sample_sequences(_stream(), seed, M, Ms, group, idx.data_ptr()))
     return idx
 
 
@@ -240,6 +243,7 @@ class DecomposeBatch:
             a.workspace, a.workspace_bytes = ptr("workspace"), j["workspace"].numel()
             a.idx, a.n_idx = ptr("idx"), (j["idx"].numel() if j.get("idx") is not None else 0)
             a.omega, a.info = ptr("omega"), ptr("info")
+            a.sample_group = j.get("group", 1)
 
     def run(self):
         _check(lib().metis_decompose_batch(_stream(), len(self.arr), self.arr))

@@ -180,3 +180,25 @@ def test_batch_of_mixed_jobs_matches_single_calls(metis):
     bad["k"] = 0
     with pytest.raises(metis.MetisError):
         metis.DecomposeBatch([jobs[0], bad]).run()
+
+
+def test_sequence_granular_sampling_in_the_decomposition(metis):
+    """Whole sequences of 64 consecutive rows are sampled (job field sample_group); parity with the oracle's grouped sampler."""
+    from paper_2509_00404_amd import workloads
+    M, N, k, p, rho, group, seed = 2048, 768, 32, 8, 1.0 / 8, 64, 4242
+    A = workloads.planted(M, N, workloads.power_law(512, 1.2), 8, rms=1.0, outlier_cols=1)
+    Ad = A.cuda()
+    assert metis.sample_count(M, k, p, rho, group) == 256
+    job = dict(A=Ad, k=k, p=p, rho=rho, seed=seed, group=group,
+               U=torch.empty((M, k), device="cuda"), S=torch.empty((k,), device="cuda"), V=torch.empty((N, k), device="cuda"),
+               workspace=torch.empty((metis.decompose_workspace_bytes(M, N, k, p, rho),), dtype=torch.uint8, device="cuda"),
+               amax=torch.zeros(1, device="cuda"), info=torch.zeros(1, dtype=torch.int32, device="cuda"))
+    metis.DecomposeBatch([job]).run()
+    torch.cuda.synchronize()
+    got = (job["U"].double().cpu().numpy(), job["S"].double().cpu().numpy(), job["V"].double().cpu().numpy(),
+           float(job["amax"].item()))
+    ref = odec.decompose(A.double().numpy(), k, p, rho, seed, group=group)
+    _compare(A, got, ref, k)
+    # and it is a different sample from the row-granular one
+    U1, S1, V1 = metis.decompose(Ad, k, p, rho, seed)
+    assert not torch.equal(S1, job["S"])

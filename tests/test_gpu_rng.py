@@ -40,3 +40,16 @@ def test_omega_matches_oracle(metis, N, r, seed):
     ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -7
     # near the zero crossings of the cosine the fp32 argument reduction adds an absolute error
     assert np.all(np.abs(om - ref) <= ulp + 4e-6)
+
+
+@pytest.mark.parametrize("M,group,k,p,rho", [(4096, 64, 8, 8, 1.0 / 16), (8192, 512, 64, 16, 1.0 / 16),
+                                             (1024, 16, 64, 16, 0.01), (960, 32, 4, 4, 0.5), (256, 256, 8, 8, 0.1),
+                                             (8192, 1, 64, 16, 1.0 / 16)])
+def test_sequence_granular_sample_bit_exact(metis, M, group, k, p, rho):
+    Ms = metis.sample_count(M, k, p, rho, group)
+    assert Ms == orng.sample_count(M, k, p, rho, group)
+    for seed in (3, (1 << 45) + 17):
+        got = metis.sample_rows(seed, M, Ms, group=group).cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+        assert np.array_equal(got, orng.sample_rows(seed, M, Ms, group))
+    with pytest.raises(metis.MetisError):
+        metis.sample_rows(1, M + 1, Ms, group=2 if group == 1 else group)      # M not a multiple of the group
