@@ -464,10 +464,14 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
         x = max((o for o in all_ops), key=lambda o: o.M * o.N)
         sr = timed(torch, lambda: metis.quantize_sr(x.A, 1, x.q.R, None))
         rn = timed(torch, lambda: metis.quantize(x.A, x.q.R, None))
+        rh = timed(torch, lambda: metis.quantize_rht_sr(x.A, 1, x.q.R))
         qb = 2.5625 * x.M * x.N
         out["quantize_plain"] = {"shape": [x.M, x.N],
+                                 "what": "plain quantizer of the largest operand, one orientation: nearest rounding, stochastic "
+                                         "rounding, and the comparison recipe (random 16-point Hadamard rotation + stochastic rounding)",
                                  "nearest": dict(rn, frac_hbm=round(qb / rn["median_ms"] / 1e6 / PEAK_HBM_GBS, 4)),
-                                 "stochastic": dict(sr, frac_hbm=round(qb / sr["median_ms"] / 1e6 / PEAK_HBM_GBS, 4))}
+                                 "stochastic": dict(sr, frac_hbm=round(qb / sr["median_ms"] / 1e6 / PEAK_HBM_GBS, 4)),
+                                 "hadamard_stochastic": dict(rh, frac_hbm=round(qb / rh["median_ms"] / 1e6 / PEAK_HBM_GBS, 4))}
         x.prepare()
     except Exception as e:
         out["quantize_plain"] = {"error": repr(e)[:200]}

@@ -224,6 +224,20 @@ int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, metis_fp4* 
 int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t);
 
 /*
+ * The recipe the paper compares with (Sec. 4.3, "Comparison with Nvidia's Recipe"; Sec. 5, "Hadamard
+ * transformations"): a random Hadamard rotation in front of the stochastically rounded quantizer.  The paper
+ * gives no definition; this build's reading: every block of 16 consecutive columns is rotated,
+ * z = (x * d) H_16 / 4 (H_16 the Sylvester Hadamard matrix in natural order, d_i = -1 iff the top bit of word i of
+ * Philox stream 5 under `seed` is set, the same 16 signs for every block), evaluated in fp32 by the radix-2
+ * butterfly in natural order (h = 1, 2, 4, 8: pairs (i, i + h) -> (a + b, a - b)), then z is quantized as
+ * metis_quantize_sr does (draws: `seed`, stream 3).  H_16 / 4 is orthogonal, so two operands rotated along their
+ * common contraction axis with the same seed keep their product.  A: device bf16 [M,N], N % 16 == 0, 16-byte
+ * aligned rows; out as for metis_quantize (blocks along N).
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (A not bf16).
+ */
+int metis_quantize_rht_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out);
+
+/*
  * Split + quantize: R = A - U diag(S) V^T in fp32 (unquantized factors, Sec. 3.2), then
  * Q(R) into out->R (and Q(R^T) into out->Rt when its codes pointer is non-null), Q(U^T)
  * into out->Ut, Q(V^T) into out->Vt, S copied to out->S.  out->k must equal k.
@@ -345,8 +359,9 @@ int metis_quantize_mx(void* stream, const metis_mat* A, metis_mxfp4* out);
 
 /*
  * C[M,N] = A[M,K] B[N,K]^T on the block-scaled FP4 matrix instruction (the scales are applied by
- * the hardware, fp32 accumulation).  K % 256 == 0; C device, bf16 or fp32, row stride ld >= N.
- * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (K not a multiple of 256).
+ * the hardware, fp32 accumulation).  K % 32 == 0 (whole blocks; a K that is not a multiple of 256 takes a
+ * somewhat slower variant of the kernel); C device, bf16 or fp32, row stride ld >= N.
+ * Errors: METIS_INVALID_ARG, METIS_BAD_SHAPE, METIS_UNSUPPORTED (an operand larger than 4 GiB of codes).
  */
 int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const metis_mxfp4* B, metis_mat* C);
 

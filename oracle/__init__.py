@@ -13,6 +13,9 @@ Modules
              App. C.1).
   decompose  sampled randomized SVD, broadcast, split A = U S V^T + R
              (Sec. 3.1, 3.2).
+  hadamard   16-point random Hadamard rotation in front of the stochastic quantizer (the
+             comparison recipe of Sec. 4.3).
+  mx         MXFP4 quantizer of the microscaling family (Sec. 2.3 names it beside NVFP4).
   linear     fprop / dgrad / wgrad on split-quantized operands (Eq. 2, Eq. 3
              and the W_R gradient listed after it).
 

@@ -67,7 +67,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // ---- Philox4x32-10 (Salmon et al., SC'11), written from the published round function ----
 struct u32x4 { uint32_t x, y, z, w; };
 
-__device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1) {
+__host__ __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         // one 32 x 32 -> 64 bit product per multiplier (a single v_mad_u64_u32) instead of separate high and
@@ -87,7 +87,7 @@ __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1
 }
 
 // word `w` of stream `t` under `seed`: lane w%4 of block w/4, counter (blk lo, blk hi, t, 0)
-__device__ __forceinline__ u32x4 philox_block(uint64_t seed, uint32_t stream, uint64_t blk) {
+__host__ __device__ __forceinline__ u32x4 philox_block(uint64_t seed, uint32_t stream, uint64_t blk) {
     u32x4 c = {(uint32_t)blk, (uint32_t)(blk >> 32), stream, 0u};
     return philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
 }

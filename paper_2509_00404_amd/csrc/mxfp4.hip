@@ -93,7 +93,10 @@ struct MxOperand {
     int64_t rows;
 };
 
-template <typename OUT>
+// TAIL: K is not a multiple of the 256-deep stage.  The last stage then exists only in part: its missing blocks of 32
+// enter as zero codes under a unit scale, and because scale rows are no longer 8-byte aligned every stage's scale
+// bytes are fetched one by one.
+template <typename OUT, bool TAIL>
 __global__ void __launch_bounds__(512)
 k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
     constexpr int TM = 4, TN = 2, BM = 256, BN = 256, KS = MX_KI / 64, NV = 4;   // NV: 16-byte code vectors per thread, operand and stage
@@ -115,7 +118,7 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int niter = (int)(K / MX_KI);
+    const int niter = (int)((K + MX_KI - 1) / MX_KI);
     // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/8 + 64 v, 16-byte segment
     // tid % 8: a row's 128 bytes are read by 8 consecutive lanes) and the 8 scale bytes of rows tid (A) and tid (B);
     // rows past the operand's end re-read its last row.  Byte offsets fit 32 bits (checked by the host).
@@ -143,12 +146,35 @@ k_mxfp4_gemm_nt(MxOperand A, MxOperand B, int64_t K, OUT* __restrict__ C, int64_
     auto load_stage = [&](int st) __attribute__((always_inline)) {
         const uint8_t* ca = A.codes + (size_t)st * (MX_KI / 2);
         const uint8_t* cb = B.codes + (size_t)st * (MX_KI / 2);
+        if (!TAIL) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            ra[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
-            rb[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
+            for (int v = 0; v < NV; ++v) {
+                ra[v] = *reinterpret_cast<const uvec4_t*>(ca + oa[v]);
+                rb[v] = *reinterpret_cast<const uvec4_t*>(cb + ob[v]);
+            }
+            rs = *reinterpret_cast<const uvec2_t*>((tid < 256 ? A.scales + osga : B.scales + osgb) + (size_t)st * (MX_KI / 32));
+        } else {
+            // this lane's 16-byte segment is one block of 32 contraction elements: it exists or it does not
+            const bool seg_ok = (int64_t)st * MX_KI + 32 * (tid & 7) < K;
+            const uvec4_t zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const uvec4_t xa = *reinterpret_cast<const uvec4_t*>(seg_ok ? ca + oa[v] : A.codes);
+                const uvec4_t xb = *reinterpret_cast<const uvec4_t*>(seg_ok ? cb + ob[v] : B.codes);
+                ra[v] = seg_ok ? xa : zero4;
+                rb[v] = seg_ok ? xb : zero4;
+            }
+            const uint8_t* sp = tid < 256 ? A.scales + osga : B.scales + osgb;
+            const int64_t b0 = (int64_t)st * (MX_KI / 32), nb = K / 32;
+            uint32_t w[2] = {0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t byte = b0 + i < nb ? (uint32_t)sp[b0 + i] : 127u;          // 127 = scale 1 for an absent block
+                w[i >> 2] |= byte << (8 * (i & 3));
+            }
+            rs.x = w[0];
+            rs.y = w[1];
         }
-        rs = *reinterpret_cast<const uvec2_t*>((tid < 256 ? A.scales + osga : B.scales + osgb) + (size_t)st * (MX_KI / 32));
     };
     auto store_stage = [&](uint8_t* buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -258,10 +284,17 @@ template <typename OUT>
 int launch_mx_gemm(hipStream_t s, const MxOperand& a, const MxOperand& b, int64_t K, OUT* C, int64_t ldc) {
     const int64_t tm = ceil_div64(a.rows, 256), tn = ceil_div64(b.rows, 256);
     if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
-    auto kern = k_mxfp4_gemm_nt<OUT>;
-    static LdsLimitCache lds_set;
-    if (!ensure_dyn_lds((const void*)kern, MX_LDS, lds_set)) return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(512), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
+    if (K % MX_KI == 0) {
+        auto kern = k_mxfp4_gemm_nt<OUT, false>;
+        static LdsLimitCache lds_set;
+        if (!ensure_dyn_lds((const void*)kern, MX_LDS, lds_set)) return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(512), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
+    } else {
+        auto kern = k_mxfp4_gemm_nt<OUT, true>;
+        static LdsLimitCache lds_set;
+        if (!ensure_dyn_lds((const void*)kern, MX_LDS, lds_set)) return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(512), MX_LDS, s, a, b, K, C, ldc, make_tile_map(tm, tn));
+    }
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
@@ -294,10 +327,9 @@ extern "C" int metis_mxfp4_gemm_nt(void* stream, const metis_mxfp4* A, const met
     if (C->dtype != METIS_BF16 && C->dtype != METIS_F32) return METIS_INVALID_ARG;
     if (A->cols != B->cols || C->rows != A->rows || C->cols != B->rows || C->ld < C->cols) return METIS_BAD_SHAPE;
     const int64_t K = A->cols;
-    if (K % MX_KI) return METIS_UNSUPPORTED;                          // whole stages of 256
     if (A->rows * (K / 2) > 0xFFFFFFFFll || B->rows * (K / 2) > 0xFFFFFFFFll) return METIS_UNSUPPORTED;   // 32-bit byte offsets
     if (reinterpret_cast<uintptr_t>(A->codes) % 16 || reinterpret_cast<uintptr_t>(B->codes) % 16 ||
-        reinterpret_cast<uintptr_t>(A->scales) % 8 || reinterpret_cast<uintptr_t>(B->scales) % 8)
+        (K % MX_KI == 0 && (reinterpret_cast<uintptr_t>(A->scales) % 8 || reinterpret_cast<uintptr_t>(B->scales) % 8)))
         return METIS_BAD_SHAPE;
     const MxOperand a = {A->codes, A->scales, A->rows}, b = {B->codes, B->scales, B->rows};
     hipStream_t s = (hipStream_t)stream;

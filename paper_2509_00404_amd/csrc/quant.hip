@@ -5,10 +5,14 @@
 #define SR_STREAM 3u          // Philox stream of the stochastic-rounding draws, row orientation
 #define SR_STREAM_T 4u        // ... of the transposed copy
 
-template <bool SR>
+// RHT: the block is first rotated, z = (x * d) H_16 / 4 (16-point Sylvester Hadamard matrix, random signs d: bit i of
+// `signs` set = d_i = -1), by the radix-2 butterfly in natural order in fp32 -- the comparison recipe of Sec. 4.3
+// (random Hadamard transform + stochastic rounding).
+template <bool SR, bool RHT>
 __global__ void __launch_bounds__(256)
 k_quantize_rows_bf16(const bf16_t* __restrict__ A, int64_t ld, int64_t M, int64_t nblk /* N/16 */,
-                     QuantParams qp, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint64_t seed) {
+                     QuantParams qp, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint64_t seed,
+                     uint32_t signs) {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= M * nblk) return;
     int64_t row = t / nblk, bc = t - row * nblk;
@@ -20,6 +24,21 @@ k_quantize_rows_bf16(const bf16_t* __restrict__ A, int64_t ld, int64_t M, int64_
     for (int i = 0; i < 8; ++i) {
         v[2 * i] = bf16lo_to_f32(w[i]);
         v[2 * i + 1] = bf16hi_to_f32(w[i]);
+    }
+    if (RHT) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = (signs >> i) & 1u ? -v[i] : v[i];
+#pragma unroll
+        for (int h = 1; h < 16; h <<= 1)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (!(i & h)) {
+                    const float a = v[i], b = v[i + h];
+                    v[i] = a + b;
+                    v[i + h] = a - b;
+                }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] *= 0.25f;
     }
     uint2 c;
     // block t covers the elements 16 t .. 16 t + 15 of the row-major matrix: their draws are those words
@@ -105,9 +124,9 @@ static int quantize_impl(void* stream, const metis_mat* A, metis_fp4* out, metis
     if (vec_ok) {
         int64_t nb = M * (N / 16);
         const int pi = metis_prof_begin(METIS_PROF_QUANTIZE, s);
-        hipLaunchKernelGGL(k_quantize_rows_bf16<SR>, dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
+        hipLaunchKernelGGL((k_quantize_rows_bf16<SR, false>), dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
                            (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale),
-                           out->codes, out->scales, seed);
+                           out->codes, out->scales, seed, 0u);
         metis_prof_end(METIS_PROF_QUANTIZE, pi, s);
         METIS_LAUNCH_CHECK();
         return METIS_OK;
@@ -135,4 +154,28 @@ extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, 
 
 extern "C" int metis_quantize_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out, metis_fp4* out_t) {
     return quantize_impl<true>(stream, A, out, out_t, seed);
+}
+
+// Random Hadamard rotation + stochastic rounding (the recipe Sec. 4.3 compares with).
+extern "C" int metis_quantize_rht_sr(void* stream, const metis_mat* A, uint64_t seed, metis_fp4* out) {
+    if (!A || !A->ptr || !out || !out->codes || !out->scales || !pow2(out->tscale)) return METIS_INVALID_ARG;
+    if (A->dtype != METIS_BF16) return METIS_UNSUPPORTED;
+    const int64_t M = A->rows, N = A->cols;
+    if (M < 1 || N < 1 || A->ld < N || N % 16 || out->rows != M || out->cols != N) return METIS_BAD_SHAPE;
+    if (A->ld % 8 || reinterpret_cast<uintptr_t>(A->ptr) % 16) return METIS_BAD_SHAPE;      // 16-byte loads
+    // the 16 signs: top bits of words 0..15 of Philox stream 5 (host side of the same generator)
+    uint32_t signs = 0;
+    for (int b = 0; b < 4; ++b) {
+        const u32x4 w = philox_block(seed, 5u, (uint64_t)b);
+        signs |= (w.x >> 31) << (4 * b) | (w.y >> 31) << (4 * b + 1) | (w.z >> 31) << (4 * b + 2) | (w.w >> 31) << (4 * b + 3);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t nb = M * (N / 16);
+    const int pi = metis_prof_begin(METIS_PROF_QUANTIZE, s);
+    hipLaunchKernelGGL((k_quantize_rows_bf16<true, true>), dim3((unsigned)ceil_div64(nb, 256)), dim3(256), 0, s,
+                       (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale), out->codes, out->scales,
+                       seed, signs);
+    metis_prof_end(METIS_PROF_QUANTIZE, pi, s);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
 }

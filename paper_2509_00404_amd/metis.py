@@ -67,6 +67,7 @@ _SIGNATURES = {
     "metis_decompose_batch": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(DecomposeJob)]),
     "metis_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(Fp4), C.POINTER(Fp4)]),
     "metis_quantize_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_uint64, C.POINTER(Fp4), C.POINTER(Fp4)]),
+    "metis_quantize_rht_sr": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_uint64, C.POINTER(Fp4)]),
     "metis_split_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "metis_split_quantize": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_int, C.POINTER(Split), C.c_void_p, C.c_void_p, C.c_size_t]),
@@ -290,6 +291,12 @@ def quantize_sr(A, seed, out=None, out_t=None):
     ot = out_t.c() if out_t is not None else None
     _check(lib().metis_quantize_sr(_stream(), C.byref(a), int(seed), C.byref(o) if o else None,
                                    C.byref(ot) if ot else None))
+
+
+def quantize_rht_sr(A, seed, out):
+    """Random 16-point Hadamard rotation of every block, then stochastically rounded NVFP4 quantization."""
+    a, o = _mat(A), out.c()
+    _check(lib().metis_quantize_rht_sr(_stream(), C.byref(a), int(seed), C.byref(o)))
 
 
 def split_workspace_bytes(M, N, k):
