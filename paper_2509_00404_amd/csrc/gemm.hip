@@ -281,7 +281,8 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 template <typename OUT>
 __global__ void __launch_bounds__(256)
 k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-                   const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
+                   const bf16_t* __restrict__ Bext, int Ke_all, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap,
+                   int total_tiles, int tail_first, int tail_parts, float* __restrict__ partial) {
     constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // LDS layout of a stage, chosen so that ONE 16-byte read per lane fetches the raw words of all four row
@@ -294,8 +295,18 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     constexpr int OFF_CB = CODES_OP, OFF_SA = 2 * CODES_OP, OFF_SB = OFF_SA + SC_OP, BUF = OFF_SB + SC_OP;
     static_assert(2 * BUF <= (int)gemm_lds_bytes<256, 256>(), "two stages fit the allocation");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The tiles of the last, partly filled round of workgroups (launch positions tail_first ..) are cut along the
+    // contraction into tail_parts workgroups each, which write fp32 partial tiles that a small kernel adds up:
+    // the round then takes 1 / tail_parts of a tile's time instead of leaving most CUs idle for a whole one.
+    int tile = (int)blockIdx.x, part = 0, parts = 1;
+    if (tile >= tail_first) {
+        const int idx = tile - tail_first;
+        tile = tail_first + idx / tail_parts;
+        part = idx - (tile - tail_first) * tail_parts;
+        parts = tail_parts;
+    }
     int tile_m, tile_n;
-    tile_coords(tmap, tile_m, tile_n);
+    tile_coords_of(tmap, tile, total_tiles, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
     const int li = lane & 31, half = lane >> 5;
@@ -308,7 +319,10 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int niter = (int)(K / G_KI);
+    const int niter_all = (int)(K / G_KI);
+    const int it_begin = (int)((int64_t)part * niter_all / parts), it_end = (int)((int64_t)(part + 1) * niter_all / parts);
+    const int niter = it_end - it_begin;                 // >= 1: the host keeps tail_parts <= K / 128
+    const int Ke = part == 0 ? Ke_all : 0;               // the low-rank columns enter once
     // this thread's share of a stage: code vectors v = 0..3 of each operand (row tid/4 + 64 v, 16-byte
     // segment tid%4) and the scale rows tid (A) and tid (B); rows past the operand's end re-read its last row
     const uint8_t* pa[4];
@@ -319,8 +333,8 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         int64_t ga = m0 + (tid >> 2) + 64 * v, gb = n0 + (tid >> 2) + 64 * v;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
-        pa[v] = A.codes + ga * cstride + 16 * (tid & 3);
-        pb[v] = B.codes + gb * cstride + 16 * (tid & 3);
+        pa[v] = A.codes + ga * cstride + 16 * (tid & 3) + (int64_t)it_begin * (G_KI / 2);
+        pb[v] = B.codes + gb * cstride + 16 * (tid & 3) + (int64_t)it_begin * (G_KI / 2);
     }
     const uint8_t* psa;
     const uint8_t* psb;
@@ -328,12 +342,12 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         int64_t ga = m0 + tid, gb = n0 + tid;
         if (ga >= A.rows) ga = A.rows - 1;
         if (gb >= B.rows) gb = B.rows - 1;
-        psa = A.scales + ga * sstride;
-        psb = B.scales + gb * sstride;
+        psa = A.scales + ga * sstride + (int64_t)it_begin * (G_KI / 16);
+        psb = B.scales + gb * sstride + (int64_t)it_begin * (G_KI / 16);
     }
     uint4 ra[4], rb[4];
     uint2 rsa, rsb;
-    // st = stage index, clamped by the caller
+    // st = stage index within this workgroup's range, clamped by the caller
     auto load_codes = [&](int st, int v) {
         ra[v] = *reinterpret_cast<const uint4*>(pa[v] + st * (G_KI / 2));
         rb[v] = *reinterpret_cast<const uint4*>(pb[v] + st * (G_KI / 2));
@@ -486,6 +500,18 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         }
     }
     // D layout 32x32: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    if (parts > 1) {
+        // partial tile, fp32, [tail tile][part][256][256]; bounds are applied when the parts are added up
+        float* __restrict__ P = partial + ((size_t)(tile - tail_first) * parts + part) * (size_t)(BM * BN);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    P[(wm + 32 * i + 4 * half + 8 * (v >> 2) + (v & 3)) * BN + wn + 32 * j + li] = alpha * acc[i][j][v];
+        return;
+    }
     const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -505,18 +531,68 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         }
 }
 
+// adds the parts of the split tail tiles and writes them to C (see k_fp4_gemm_nt_pipe); one workgroup per 32 rows of a tile
+template <typename OUT>
+__global__ void __launch_bounds__(256)
+k_gemm_tail_sum(const float* __restrict__ partial, int parts, int tail_first, int total_tiles, TileMap tmap, int64_t M,
+                int64_t N, OUT* __restrict__ C, int64_t ldc) {
+    const int tile = tail_first + (int)blockIdx.x / 8, rb = (int)blockIdx.x % 8;
+    int tile_m, tile_n;
+    tile_coords_of(tmap, tile, total_tiles, tile_m, tile_n);
+    const float* __restrict__ P = partial + (size_t)(tile - tail_first) * parts * 65536;
+    for (int e = threadIdx.x; e < 32 * 64; e += 256) {          // 32 rows x 64 float4
+        const int r = 32 * rb + e / 64, c4 = (e % 64) * 4;
+        float4 acc = *reinterpret_cast<const float4*>(P + r * 256 + c4);
+        for (int p = 1; p < parts; ++p) {
+            const float4 x = *reinterpret_cast<const float4*>(P + (size_t)p * 65536 + r * 256 + c4);
+            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+        }
+        const int64_t gr = (int64_t)tile_m * 256 + r, gc = (int64_t)tile_n * 256 + c4;
+        if (gr >= M) continue;
+        const float v[4] = {acc.x, acc.y, acc.z, acc.w};
+        for (int i = 0; i < 4; ++i)
+            if (gc + i < N) store_out<OUT>(C + gr * ldc + gc + i, v[i]);
+    }
+}
+
+// bytes of fp32 partial tiles the pipelined kernel wants for an M x N output (0: no tail split)
+static size_t gemm_tail_bytes(int64_t M, int64_t N, int64_t K, int* parts_out = nullptr, int* tail_first_out = nullptr) {
+    const int64_t tiles = ceil_div64(M, 256) * ceil_div64(N, 256);
+    const int64_t tail = tiles % 256, niter = K / G_KI;
+    int parts = tail > 0 ? (int)(256 / tail) : 1;
+    if (parts > 4) parts = 4;
+    if (parts > niter) parts = (int)niter;
+    if (parts_out) *parts_out = parts;
+    if (tail_first_out) *tail_first_out = (int)(tiles - tail);
+    if (tail == 0 || parts < 2) return 0;
+    return (size_t)tail * parts * 65536 * sizeof(float);
+}
+
 template <typename OUT>
 int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, const bf16_t* Aext,
-                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
+                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc, float* partial, size_t partial_bytes) {
     const int64_t tm = ceil_div64(a.rows, 256), tn = ceil_div64(b.rows, 256);
     if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
     constexpr size_t lds = gemm_lds_bytes<256, 256>();
-    dim3 grid((unsigned)(tm * tn));
+    const int total = (int)(tm * tn);
+    int parts = 1, tail_first = total;
+    const size_t want = gemm_tail_bytes(a.rows, b.rows, K, &parts, &tail_first);
+    const bool split = want > 0 && partial && partial_bytes >= want;
+    if (!split) { parts = 1; tail_first = total; }
+    const int tail = total - tail_first;
+    dim3 grid((unsigned)(tail_first + tail * parts));
     auto kern = k_fp4_gemm_nt_pipe<OUT>;
     static LdsLimitCache lds_set;
     if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn));
+    const TileMap tmap = make_tile_map(tm, tn);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, tmap, total, tail_first, parts,
+                       partial);
     METIS_LAUNCH_CHECK();
+    if (split) {
+        hipLaunchKernelGGL(k_gemm_tail_sum<OUT>, dim3((unsigned)(tail * 8)), dim3(256), 0, s, partial, parts, tail_first, total,
+                           tmap, a.rows, b.rows, C, ldc);
+        METIS_LAUNCH_CHECK();
+    }
     return METIS_OK;
 }
 
@@ -550,19 +626,24 @@ int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
 // ksplit > 1: C (fp32, zero on entry) accumulates the contraction splits with atomics
 template <typename OUT>
 int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf16_t* Aext, const bf16_t* Bext, int Ke,
-                float alpha, OUT* C, int64_t ldc, int ksplit = 1) {
+                float alpha, OUT* C, int64_t ldc, int ksplit = 1, float* partial = nullptr, size_t partial_bytes = 0) {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
     Fp4Operand a = {A.codes, A.scales, M}, b = {B.codes, B.scales, N};
     const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
                      reinterpret_cast<uintptr_t>(B.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(A.scales) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(B.scales) % 8 == 0;
     if (M >= 1024 && N >= 1024) {
+        // 256x256 tile, 4 waves of 128x128, software-pipelined (needs whole 128-deep stages and aligned rows); the
+        // tiles of a partly filled last round are cut along the contraction when the caller brought room for the parts
+        const size_t tail_need = gemm_tail_bytes(M, N, K);
+        const bool can_split = tail_need > 0 && partial && partial_bytes >= tail_need;
+        if (vec && (can_split || ceil_div64(M, 256) * ceil_div64(N, 256) > 128))
+            return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, partial, partial_bytes);
         // an output of at most 128 tiles of 256 x 256 would leave half the CUs without work: 128 x 128 tiles
         // (four times as many workgroups, each less efficient) finish sooner
         if (ceil_div64(M, 256) * ceil_div64(N, 256) <= 128 && ksplit <= 1)
             return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, 1);
-        // 256x256 tile, 4 waves of 128x128, software-pipelined (needs whole 128-deep stages and aligned rows)
-        if (vec) return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc);
+        if (vec) return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, partial, partial_bytes);
         // otherwise 8 waves of 128x64 with bounds-checked staging
         return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     }
@@ -664,11 +745,11 @@ struct NtOperand {            // one side of Abar Bbar^T: Abar = U diag(S) V^T +
 };
 
 struct LinWs {
-    size_t off_t1, off_mk, off_e2, off_aext, off_bext, total;
+    size_t off_t1, off_mk, off_e2, off_aext, off_bext, off_tail, tail_bytes, total;
     int Kep;
 };
 
-LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb) {
+LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb, int64_t Kc) {
     LinWs w;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
@@ -678,6 +759,8 @@ LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb) {
     w.off_e2 = take((size_t)Nb * (ka > 0 ? ka : 1) * 4);
     w.off_aext = take((size_t)Ma * (w.Kep > 0 ? w.Kep : 16) * 2);
     w.off_bext = take((size_t)Nb * (w.Kep > 0 ? w.Kep : 16) * 2);
+    w.tail_bytes = (Ma >= 1024 && Nb >= 1024 && Kc % G_KI == 0) ? gemm_tail_bytes(Ma, Nb, Kc) : 0;
+    w.off_tail = take(w.tail_bytes);
     w.total = o;
     return w;
 }
@@ -702,8 +785,8 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
     const bf16_t *Aext = nullptr, *Bext = nullptr;
     int st;
     if (ka > 0 || kb > 0) {
-        const LinWs w = lin_layout(Ma, Nb, ka, kb);
-        if (!workspace || workspace_bytes < w.total) return METIS_WORKSPACE_TOO_SMALL;
+        const LinWs w = lin_layout(Ma, Nb, ka, kb, Kc);
+        if (!workspace || workspace_bytes < w.off_tail) return METIS_WORKSPACE_TOO_SMALL;   // the tail region is optional
         if (reinterpret_cast<uintptr_t>(workspace) % 16) return METIS_INVALID_ARG;
         char* ws = (char*)workspace;
         float* T1 = (float*)(ws + w.off_t1);
@@ -744,11 +827,21 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         Aext = ae;
         Bext = be;
     }
+    // room for the partial tiles of a split last round, when the workspace has it
+    float* partial = nullptr;
+    size_t partial_bytes = 0;
+    {
+        const LinWs w = lin_layout(Ma, Nb, ka, kb, Kc);
+        if (w.tail_bytes > 0 && workspace && workspace_bytes >= w.total && reinterpret_cast<uintptr_t>(workspace) % 16 == 0) {
+            partial = (float*)((char*)workspace + w.off_tail);
+            partial_bytes = w.tail_bytes;
+        }
+    }
     const int pi = metis_prof_begin(METIS_PROF_GEMM, s);
     if (out->dtype == METIS_BF16)
-        st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld);
+        st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld, 1, partial, partial_bytes);
     else
-        st = launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld);
+        st = launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld, 1, partial, partial_bytes);
     metis_prof_end(METIS_PROF_GEMM, pi, s);
     return st;
 }
@@ -763,7 +856,7 @@ NtOperand nt(const metis_fp4& R, const metis_fp4& Ut, const metis_fp4& Vt, const
 
 extern "C" size_t metis_linear_workspace_bytes(int64_t L, int64_t N, int64_t K, int k) {
     if (L < 1 || N < 1 || K < 1 || k < 0) return 0;
-    size_t a = lin_layout(L, N, k, k).total, b = lin_layout(L, K, k, k).total, c = lin_layout(N, K, k, k).total;
+    size_t a = lin_layout(L, N, k, k, K).total, b = lin_layout(L, K, k, k, N).total, c = lin_layout(N, K, k, k, L).total;
     return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 

@@ -60,8 +60,12 @@ static inline TileMap make_tile_map(int64_t tiles_m, int64_t tiles_n) {
     return t;
 }
 
+__device__ __forceinline__ void tile_coords_of(const TileMap& t, int b, int total, int& tm, int& tn);
 __device__ __forceinline__ void tile_coords(const TileMap& t, int& tm, int& tn) {
-    const int total = gridDim.x, b = blockIdx.x;
+    tile_coords_of(t, (int)blockIdx.x, (int)gridDim.x, tm, tn);
+}
+// b = position in launch order among `total` tiles
+__device__ __forceinline__ void tile_coords_of(const TileMap& t, int b, int total, int& tm, int& tn) {
     if (t.rm > 0) {
         const int xcd = b & 7, local = b >> 3, regions_n = t.tiles_n / t.rn;
         tm = (xcd / regions_n) * t.rm + local / t.rn;
