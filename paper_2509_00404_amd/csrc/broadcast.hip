@@ -211,14 +211,13 @@ k_broadcast(const bf16_t* __restrict__ A, int64_t lda, int64_t M, int64_t N, con
 }
 
 int broadcast_splits(int64_t M, int64_t N) {
-    int64_t row_blocks = ceil_div64(M, BC_ROWS);
-    // about one workgroup (8 waves) per CU, at least two stages each, at most 16 partial results
-    int64_t stages = ceil_div64(N, BC_NC);
-    int64_t nsplit = ceil_div64(256, row_blocks);
-    if (nsplit > stages / 2) nsplit = stages / 2;
-    if (nsplit > 16) nsplit = 16;
-    if (nsplit < 1) nsplit = 1;
-    return (int)nsplit;
+    const int64_t row_blocks = ceil_div64(M, BC_ROWS);
+    // one workgroup (8 waves) per CU at a time; every workgroup at least two stages deep, at most 16 partial
+    // results; the number of contraction splits that fills the last round of workgroups best
+    const int64_t stages = ceil_div64(N, BC_NC);
+    int64_t max_split = stages / 2;
+    if (max_split > 16) max_split = 16;
+    return (int)balanced_split(row_blocks, max_split, 256);
 }
 
 int launch_broadcast(hipStream_t s, const bf16_t* A, int64_t lda, int64_t M, int64_t N, const bf16_t* V0hi,

@@ -62,6 +62,21 @@ static inline bool ensure_dyn_lds(const void* fn, size_t bytes, LdsLimitCache& c
 }
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// How many ways to cut the second grid dimension (1 .. max_split) when `blocks` workgroups exist along the first and
+// the GPU runs `slots` workgroups at a time: the cut whose last round of workgroups is fullest, among those that
+// reach at least one full round when possible; ties go to the fewest cuts (longer runs per workgroup).
+static inline int64_t balanced_split(int64_t blocks, int64_t max_split, int64_t slots) {
+    if (max_split < 1) max_split = 1;
+    int64_t best = 1;
+    double best_eff = -1.0;
+    for (int64_t s = 1; s <= max_split; ++s) {
+        const int64_t wgs = blocks * s, rounds = ceil_div64(wgs, slots);
+        const double eff = (double)wgs / (double)(rounds * slots);
+        if (eff > best_eff + 1e-9) { best_eff = eff; best = s; }
+    }
+    return best;
+}
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), written from the published round function ----

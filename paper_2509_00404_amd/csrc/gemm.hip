@@ -146,21 +146,19 @@ constexpr size_t gemm_lds_bytes() {
     return 2 * ((size_t)BM * (G_CROW + G_SROW) + (size_t)BN * (G_CROW + G_SROW));
 }
 
-// 1-D grid of ceil(M / BM) * ceil(N / BN) workgroups of WMW x WNW waves, each wave TM x TN tiles of
-// 32x32 (BM = 32 TM WMW, BN = 32 TN WNW); workgroup -> tile by TileMap.
+// One output tile by a workgroup of WMW x WNW waves, each wave TM x TN tiles of 32x32 (BM = 32 TM WMW,
+// BN = 32 TN WNW), over the contraction stages [it0, niter).
 template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
-__global__ void __launch_bounds__(64 * WMW * WNW)
-k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
-              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap,
-              int iters_per_split) {
+__device__ __forceinline__ void
+gemm_nt_tile(const Fp4Operand& A, const Fp4Operand& B, int64_t K, const bf16_t* __restrict__ Aext,
+             const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, int tile_m, int tile_n,
+             int64_t it0, int64_t niter) {
     constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // LDS: [buffer][codes A | codes B | scales A | scales B]
     constexpr int OFF_CB = BM * G_CROW, OFF_SA = (BM + BN) * G_CROW, OFF_SB = OFF_SA + BM * G_SROW,
                   BUF = OFF_SB + BN * G_SROW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int tile_m, tile_n;
-    tile_coords(tmap, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int wm = (wave / WNW) * 32 * TM, wn = (wave % WNW) * 32 * TN;
     const int li = lane & 31, half = lane >> 5;
@@ -173,11 +171,7 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // blockIdx.y = contraction split: stages [it0, it1); more than one split accumulates with fp32 atomics
-    const int64_t niter_all = (K + G_KI - 1) / G_KI;
-    const int64_t it0 = (int64_t)blockIdx.y * iters_per_split;
-    const int64_t niter = it0 + iters_per_split < niter_all ? it0 + iters_per_split : niter_all;
-    const bool split = gridDim.y > 1;
+    // this workgroup's stages of the contraction: [it0, niter)
     StageRegs<BM * 4 / NT> ra;
     StageRegs<BN * 4 / NT> rb;
     ScaleRegs<(BM + BN + NT - 1) / NT> rs;
@@ -227,7 +221,7 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
         __syncthreads();
     }
     // low-rank terms: extra contraction columns in bf16, read straight from global memory
-    if (Ke > 0 && blockIdx.y == 0) {
+    if (Ke > 0) {
         for (int ks = 0; ks < Ke; ks += 16) {
             BFrag fa[TM], fb[TN];
 #pragma unroll
@@ -258,12 +252,54 @@ k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 int64_t r = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (r < A.rows && c < B.rows) {
-                    if (split) atomic_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
-                    else store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
-                }
+                if (r < A.rows && c < B.rows) store_out<OUT>(C + r * ldc + c, alpha * acc[i][j][v]);
             }
         }
+}
+
+// 1-D grid of ceil(M / BM) * ceil(N / BN) workgroups; workgroup -> tile by TileMap
+template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
+__global__ void __launch_bounds__(64 * WMW * WNW)
+k_fp4_gemm_nt(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
+              const bf16_t* __restrict__ Bext, int Ke, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap) {
+    int tile_m, tile_n;
+    tile_coords(tmap, tile_m, tile_n);
+    gemm_nt_tile<TM, TN, WMW, WNW, VEC, OUT>(A, B, K, Aext, Bext, Ke, alpha, C, ldc, tile_m, tile_n, 0, (K + G_KI - 1) / G_KI);
+}
+
+// Up to three skinny products in one launch, each cut along the contraction into `splits` parts that are written
+// side by side (part z of problem q at P + z rows_a rows_b, plain stores): the consumer adds the parts in a fixed
+// order, so the result does not depend on the order in which workgroups finish.  128 x 64 tiles, 4 waves.
+struct SkinnyProblem {
+    Fp4Operand A, B;         // C = alpha A B^T, [A.rows, B.rows]
+    float alpha;
+    float* P;
+    int tiles_n, tiles;      // tiles along B.rows, tiles in all
+    int ips;                 // stages per part
+    int first;               // first workgroup of this problem
+};
+struct SkinnyBatch {
+    SkinnyProblem p[3];
+    int count;
+};
+
+template <bool VEC>
+__global__ void __launch_bounds__(256)
+k_fp4_skinny_batch(SkinnyBatch batch, int64_t K) {
+    int q = 0;
+#pragma unroll
+    for (int i = 1; i < 3; ++i)
+        if (i < batch.count && (int)blockIdx.x >= batch.p[i].first) q = i;
+    SkinnyProblem pr = batch.p[0];
+    if (q == 1) pr = batch.p[1];
+    if (q == 2) pr = batch.p[2];
+    const int local = (int)blockIdx.x - pr.first, z = local / pr.tiles, t = local - z * pr.tiles;
+    const int64_t niter_all = (K + G_KI - 1) / G_KI;
+    const int64_t it0 = (int64_t)z * pr.ips;
+    const int64_t niter = it0 + pr.ips < niter_all ? it0 + pr.ips : niter_all;
+    gemm_nt_tile<2, 1, 2, 2, VEC, float>(pr.A, pr.B, K, nullptr, nullptr, 0, pr.alpha,
+                                         pr.P + (size_t)z * pr.A.rows * pr.B.rows, pr.B.rows, t / pr.tiles_n, t % pr.tiles_n,
+                                         it0, niter);
 }
 
 // Software-pipelined variant: 256 x 256 tile, 4 waves of 128 x 128 (16 accumulator tiles per wave,
@@ -598,35 +634,31 @@ int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
 
 template <int TM, int TN, int WMW, int WNW, typename OUT>
 int launch_gemm_tile(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, int64_t K, bool vec, const bf16_t* Aext,
-                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc, int ksplit = 1) {
+                     const bf16_t* Bext, int Ke, float alpha, OUT* C, int64_t ldc) {
     constexpr int BM = 32 * TM * WMW, BN = 32 * TN * WNW, NT = 64 * WMW * WNW;
     static_assert(BM * 4 >= NT && BN * 4 >= NT, "every thread stages at least one code vector");
     const int64_t tm = ceil_div64(a.rows, BM), tn = ceil_div64(b.rows, BN);
     if (tm * tn > 0x7FFFFFFF) return METIS_UNSUPPORTED;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-    const int64_t niter = ceil_div64(K, G_KI);
-    if (ksplit < 1 || sizeof(OUT) != 4) ksplit = 1;
-    const int ips = (int)ceil_div64(niter, ksplit);
-    dim3 grid((unsigned)(tm * tn), (unsigned)ceil_div64(niter, ips));
+    dim3 grid((unsigned)(tm * tn));
     if (vec) {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, true, OUT>;
         static LdsLimitCache lds_set;
         if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn));
     } else {
         auto kern = k_fp4_gemm_nt<TM, TN, WMW, WNW, false, OUT>;
         static LdsLimitCache lds_set;
         if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn), ips);
+        hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, make_tile_map(tm, tn));
     }
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }
 
-// ksplit > 1: C (fp32, zero on entry) accumulates the contraction splits with atomics
 template <typename OUT>
 int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf16_t* Aext, const bf16_t* Bext, int Ke,
-                float alpha, OUT* C, int64_t ldc, int ksplit = 1, float* partial = nullptr, size_t partial_bytes = 0) {
+                float alpha, OUT* C, int64_t ldc, float* partial = nullptr, size_t partial_bytes = 0) {
     const int64_t M = A.rows, N = B.rows, K = A.cols;
     Fp4Operand a = {A.codes, A.scales, M}, b = {B.codes, B.scales, N};
     const bool vec = (K % G_KI) == 0 && reinterpret_cast<uintptr_t>(A.codes) % 16 == 0 &&
@@ -641,15 +673,15 @@ int launch_gemm(hipStream_t s, const metis_fp4& A, const metis_fp4& B, const bf1
             return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, partial, partial_bytes);
         // an output of at most 128 tiles of 256 x 256 would leave half the CUs without work: 128 x 128 tiles
         // (four times as many workgroups, each less efficient) finish sooner
-        if (ceil_div64(M, 256) * ceil_div64(N, 256) <= 128 && ksplit <= 1)
-            return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, 1);
+        if (ceil_div64(M, 256) * ceil_div64(N, 256) <= 128)
+            return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
         if (vec) return launch_gemm_pipe<OUT>(s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, partial, partial_bytes);
         // otherwise 8 waves of 128x64 with bounds-checked staging
         return launch_gemm_tile<4, 2, 2, 4, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
     }
-    if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
-    if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
-    return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc, ksplit);
+    if (N > 64 && M > 64) return launch_gemm_tile<2, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    if (N <= 64) return launch_gemm_tile<2, 1, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
+    return launch_gemm_tile<1, 2, 2, 2, OUT>(s, a, b, K, vec, Aext, Bext, Ke, alpha, C, ldc);
 }
 
 // value of one FP4 element without the tensor scale: grid[code] * e4m3(scale)
@@ -667,75 +699,201 @@ __device__ __forceinline__ float fp4_elem_nog(const uint8_t* codes, const uint8_
 //   Aext[m, kb:kb+ka] = Ua[m,:] without its tensor scale (exact in bf16)
 //   Bext[n, 0:kb]     = Ub[n,:] without its tensor scale (exact in bf16)
 //   Bext[n, kb:kb+ka] = E2[n,:] * Sa * gUa / (gRa gRb)
-// Blocks [0, ceil(Ma/16)) build 16 rows of Aext each: the dequantized factor rows U_a S_a and the small
-// matrix Mk sit in LDS, so the k_a-term sum of the first kb columns reads global memory once.  The
-// remaining blocks build 16 rows of Bext each the same way.  (16 rows: several workgroups per CU; with 64
-// the 8192 + 4096 rows of a layer gave fewer workgroups than CUs and the kernel took three times as long.)
-#define AX_ROWS 16
+// T1, E2 and Mk arrive as n1, n2, n3 contraction parts that are added here in ascending order.
+// Blocks [0, ceil(Ma/32)) build 32 rows of Aext each: the dequantized factor rows U_a and the small matrix
+// Sa Mk sit in LDS; thread (row t/8, column group t%8) owns the columns 64 h + 8 (t%8) + 0..7 of its row.  The
+// remaining blocks build 32 rows of Bext each the same way.  The kernel moves little data and is bound by
+// load latency, so every global load of a thread is issued before the first use: parts are read four at a time.
+#define AX_ROWS 32
+
+// acc[i] += sum over parts p < n of base[p * pstride + off + i], i < cnt <= 8 (vec: cnt = 8 and 16-byte aligned).
+// Four parts per round, loaded before any is used; a round's missing parts re-read the last one with weight 0.
+__device__ __forceinline__ void sum_parts8(const float* __restrict__ base, size_t pstride, int n, size_t off, int cnt,
+                                           bool vec, float (&acc)[8]) {
+    for (int p0 = 0; p0 < n; p0 += 4) {
+        float x[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int p = p0 + u < n ? p0 + u : n - 1;
+            const float* q = base + (size_t)p * pstride + off;
+            if (vec) {
+                const float4 lo = *reinterpret_cast<const float4*>(q), hi = *reinterpret_cast<const float4*>(q + 4);
+                x[u][0] = lo.x; x[u][1] = lo.y; x[u][2] = lo.z; x[u][3] = lo.w;
+                x[u][4] = hi.x; x[u][5] = hi.y; x[u][6] = hi.z; x[u][7] = hi.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[u][i] = i < cnt ? q[i] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = p0 + u < n ? 1.0f : 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, x[u][i], acc[i]);
+        }
+    }
+}
+
+// Rows r0 .. r0 + 31 of a factor stored transposed in FP4 (codes [k, rows], rows % 16 == 0), without the tensor
+// scale, into dst[32][k + 1]: a thread decodes 8 consecutive rows of one stored row j (4 code bytes, one scale).
+__device__ __forceinline__ void decode_factor_rows(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                   int64_t rows, int k, int64_t r0, float* dst, int tid) {
+    const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    const int q = tid & 3;
+    const int64_t r = r0 + 8 * q;
+    for (int j = tid >> 2; j < k; j += 64) {
+        uint32_t by[4] = {0, 0, 0, 0};
+        float sc = 0.0f;
+        if (r < rows) {
+            const uint8_t* c = codes + (int64_t)j * (rows / 2) + r / 2;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) by[i] = c[i];
+            sc = e4m3_decode(scales[(int64_t)j * (rows / 16) + r / 16]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t nib = (i & 1) ? (by[i >> 1] >> 4) : (by[i >> 1] & 15u);
+            const float v = grid[nib & 7u] * sc;
+            dst[(8 * q + i) * (k + 1) + j] = (nib & 8u) ? -v : v;
+        }
+    }
+}
+
+__device__ __forceinline__ uint4 pack8_bf16(const float (&v)[8]) {
+    uint4 o;
+    o.x = (uint32_t)f32_to_bf16_rne(v[0]) | (uint32_t)f32_to_bf16_rne(v[1]) << 16;
+    o.y = (uint32_t)f32_to_bf16_rne(v[2]) | (uint32_t)f32_to_bf16_rne(v[3]) << 16;
+    o.z = (uint32_t)f32_to_bf16_rne(v[4]) | (uint32_t)f32_to_bf16_rne(v[5]) << 16;
+    o.w = (uint32_t)f32_to_bf16_rne(v[6]) | (uint32_t)f32_to_bf16_rne(v[7]) << 16;
+    return o;
+}
+
+// NCH = ceil(kb / 64): column groups of a row that hold T1-type columns
+template <int NCH>
 __global__ void __launch_bounds__(256)
-k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1,
-               const float* __restrict__ Mk, const float* __restrict__ E2,
+k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __restrict__ T1, int n1,
+               const float* __restrict__ Mk, int n3, const float* __restrict__ E2, int n2,
                const uint8_t* __restrict__ ua_codes, const uint8_t* __restrict__ ua_scales, float g_ua,
                const float* __restrict__ Sa, const uint8_t* __restrict__ ub_codes,
                const uint8_t* __restrict__ ub_scales, float g_ub, const float* __restrict__ Sb,
                float inv_grr, bf16_t* __restrict__ Aext, bf16_t* __restrict__ Bext) {
-    extern __shared__ float ax_sm[];
+    extern __shared__ __attribute__((aligned(16))) float ax_sm[];
     const int nblk_a = (int)((Ma + AX_ROWS - 1) / AX_ROWS);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, rr = tid >> 3, cg = tid & 7;
     if ((int)blockIdx.x < nblk_a) {
-        float* ua = ax_sm;                          // [AX_ROWS][ka + 1]: factor entries without tensor scale
-        float* mk = ax_sm + AX_ROWS * (ka + 1);     // [ka][kb]
-        const int64_t r0 = (int64_t)blockIdx.x * AX_ROWS;
-        for (int e = tid; e < AX_ROWS * ka; e += 256) {
-            const int j = e / AX_ROWS, rr = e - j * AX_ROWS;      // consecutive threads walk along a stored factor row
-            const int64_t row = r0 + rr;
-            ua[rr * (ka + 1) + j] = row < Ma ? fp4_elem_nog(ua_codes, ua_scales, Ma, j, row) : 0.0f;
-        }
-        for (int e = tid; e < ka * kb; e += 256) mk[e] = Mk[e] * g_ua * Sa[e / kb];
-        __syncthreads();
-        for (int e = tid; e < AX_ROWS * Kep; e += 256) {
-            const int rr = e / Kep, c = e - rr * Kep;
-            const int64_t row = r0 + rr;
-            if (row >= Ma) continue;
-            float v = 0.0f;
-            if (c < kb) {
-                float acc = T1[row * kb + c];
-                for (int j = 0; j < ka; ++j) acc += ua[rr * (ka + 1) + j] * mk[j * kb + c];
-                v = acc * Sb[c] * g_ub * inv_grr;
-            } else if (c < kb + ka) {
-                v = ua[rr * (ka + 1) + (c - kb)];
+        float* ua = ax_sm;                                          // [AX_ROWS][ka + 1]
+        float* mk = ax_sm + (AX_ROWS * (ka + 1) + 3) / 4 * 4;       // [ka][kb] (+ 8 floats of slack)
+        const int64_t r0 = (int64_t)blockIdx.x * AX_ROWS, row = r0 + rr;
+        const bool in = row < Ma;
+        const int64_t lrow = in ? row : Ma - 1;
+        // this thread's sums of the T1 parts
+        float t1[NCH][8];
+#pragma unroll
+        for (int h = 0; h < NCH; ++h) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t1[h][i] = 0.0f;
+            const int c0 = 64 * h + 8 * cg;
+            if (c0 < kb && n1 > 0) {
+                const int cnt = kb - c0 < 8 ? kb - c0 : 8;
+                sum_parts8(T1, (size_t)Ma * kb, n1, (size_t)lrow * kb + c0, cnt, cnt == 8 && kb % 4 == 0, t1[h]);
             }
-            Aext[row * Kep + c] = f32_to_bf16_rne(v);
+        }
+        // Sa Mk (with U_a's tensor scale) into LDS, the parts added on the way
+        const int nmk = ka * kb;
+        for (int e0 = 8 * tid; e0 < nmk; e0 += 8 * 256) {
+            float m[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+            const int cnt = nmk - e0 < 8 ? nmk - e0 : 8;
+            sum_parts8(Mk, (size_t)nmk, n3, (size_t)e0, cnt, cnt == 8 && nmk % 4 == 0, m);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < cnt) mk[e0 + i] = m[i] * g_ua * Sa[(e0 + i) / kb];
+        }
+        decode_factor_rows(ua_codes, ua_scales, Ma, ka, r0, ua, tid);
+        __syncthreads();
+        if (!in) return;
+        const bool vecmk = kb % 4 == 0;
+        const float gs = g_ub * inv_grr;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const int c0 = 64 * h + 8 * cg;
+            if (c0 >= Kep) continue;
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = c0 + i;
+                v[i] = (c >= kb && c < kb + ka) ? ua[rr * (ka + 1) + c - kb] : 0.0f;
+            }
+            if (h < NCH && c0 < kb) {
+                float acc[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = t1[h < NCH ? h : 0][i];
+                for (int j = 0; j < ka; ++j) {
+                    const float u = ua[rr * (ka + 1) + j];
+                    const float* mrow = mk + j * kb + c0;
+                    if (vecmk) {
+                        const float4 lo = *reinterpret_cast<const float4*>(mrow), hi = *reinterpret_cast<const float4*>(mrow + 4);
+                        acc[0] = fmaf(u, lo.x, acc[0]); acc[1] = fmaf(u, lo.y, acc[1]);
+                        acc[2] = fmaf(u, lo.z, acc[2]); acc[3] = fmaf(u, lo.w, acc[3]);
+                        acc[4] = fmaf(u, hi.x, acc[4]); acc[5] = fmaf(u, hi.y, acc[5]);
+                        acc[6] = fmaf(u, hi.z, acc[6]); acc[7] = fmaf(u, hi.w, acc[7]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[i] = fmaf(u, mrow[i], acc[i]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (c0 + i < kb) v[i] = acc[i] * Sb[c0 + i] * gs;
+            }
+            *reinterpret_cast<uint4*>(Aext + row * Kep + c0) = pack8_bf16(v);
         }
         return;
     }
-    // Bext: 16 rows per block; the stored factor rows of U_b are decoded along their contiguous axis into LDS
+    // Bext rows
     float* ub = ax_sm;                              // [AX_ROWS][kb + 1]
-    const int64_t r0 = ((int64_t)blockIdx.x - nblk_a) * AX_ROWS;
-    for (int e = tid; e < AX_ROWS * kb; e += 256) {
-        const int j = e / AX_ROWS, rr = e - j * AX_ROWS;
-        const int64_t row = r0 + rr;
-        ub[rr * (kb + 1) + j] = row < Nb ? fp4_elem_nog(ub_codes, ub_scales, Nb, j, row) : 0.0f;
-    }
-    __syncthreads();
-    for (int e = tid; e < AX_ROWS * Kep; e += 256) {
-        const int rr = e / Kep, c = e - rr * Kep;
-        const int64_t row = r0 + rr;
-        if (row >= Nb) continue;
-        float v = 0.0f;
-        if (c < kb) {
-            v = ub[rr * (kb + 1) + c];
-        } else if (c < kb + ka) {
-            const int j = c - kb;
-            v = E2[row * ka + j] * Sa[j] * g_ua * inv_grr;
+    const int64_t r0 = ((int64_t)blockIdx.x - nblk_a) * AX_ROWS, row = r0 + rr;
+    const bool in = row < Nb;
+    const int64_t lrow = in ? row : Nb - 1;
+    float e2[4][8];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e2[h][i] = 0.0f;
+        // the E2-type columns of this group: c in [max(c0, kb), min(c0 + 8, kb + ka)) <-> E2 columns c - kb
+        const int c0 = 64 * h + 8 * cg;
+        const int lo = c0 > kb ? c0 : kb, hi = c0 + 8 < kb + ka ? c0 + 8 : kb + ka;
+        if (lo < hi && n2 > 0) {
+            const int cnt = hi - lo;
+            sum_parts8(E2, (size_t)Nb * ka, n2, (size_t)lrow * ka + (lo - kb), cnt,
+                       cnt == 8 && ka % 4 == 0 && (lo - kb) % 4 == 0, e2[h]);
         }
-        Bext[row * Kep + c] = f32_to_bf16_rne(v);
     }
-}
-
-__global__ void k_zero_f32(float* __restrict__ p, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, st = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += st) p[i] = 0.0f;
+    decode_factor_rows(ub_codes, ub_scales, Nb, kb, r0, ub, tid);
+    __syncthreads();
+    if (!in) return;
+    const float gs = g_ua * inv_grr;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const int c0 = 64 * h + 8 * cg;
+        if (c0 >= Kep) continue;
+        const int lo = c0 > kb ? c0 : kb;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = c0 + i;
+            float x = 0.0f;
+            if (c < kb) x = ub[rr * (kb + 1) + c];
+            else if (c < kb + ka) {
+                // e2[h] holds the group's E2-type columns from index 0 on
+                float t = 0.0f;
+#pragma unroll
+                for (int z = 0; z < 8; ++z) t = (c - lo == z) ? e2[h][z] : t;
+                x = t * Sa[c - kb] * gs;
+            }
+            v[i] = x;
+        }
+        *reinterpret_cast<uint4*>(Bext + row * Kep + c0) = pack8_bf16(v);
+    }
 }
 
 struct NtOperand {            // one side of Abar Bbar^T: Abar = U diag(S) V^T + R, R [rows, Kc]
@@ -747,16 +905,33 @@ struct NtOperand {            // one side of Abar Bbar^T: Abar = U diag(S) V^T +
 struct LinWs {
     size_t off_t1, off_mk, off_e2, off_aext, off_bext, off_tail, tail_bytes, total;
     int Kep;
+    int s1, s2, s3;          // contraction parts of T1, E2, Mk
 };
+
+// Parts of a skinny product with rows x cols outputs: few output tiles, long contraction -> cut it so that about
+// 256 workgroups share the work, each with at least two stages.
+int skinny_parts(int64_t rows, int64_t cols, int64_t Kc, int64_t cap) {
+    const int64_t tiles = ceil_div64(rows, 128) * ceil_div64(cols, 64), iters = ceil_div64(Kc, G_KI);
+    int64_t want = ceil_div64(256, tiles);
+    const int64_t maxs = iters / 2 > 0 ? iters / 2 : 1;
+    if (want > maxs) want = maxs;
+    if (want > cap) want = cap;
+    const int64_t ips = ceil_div64(iters, want);
+    return (int)ceil_div64(iters, ips);           // no empty part
+}
 
 LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb, int64_t Kc) {
     LinWs w;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     w.Kep = (ka + kb + 15) / 16 * 16;
-    w.off_t1 = take((size_t)Ma * (kb > 0 ? kb : 1) * 4);
-    w.off_mk = take((size_t)(ka > 0 ? ka : 1) * (kb > 0 ? kb : 1) * 4);
-    w.off_e2 = take((size_t)Nb * (ka > 0 ? ka : 1) * 4);
+    // (the assembly kernel adds the parts up, two rounds of four loads at most)
+    w.s1 = kb > 0 ? skinny_parts(Ma, kb, Kc, 8) : 1;
+    w.s2 = ka > 0 ? skinny_parts(Nb, ka, Kc, 8) : 1;
+    w.s3 = ka > 0 && kb > 0 ? skinny_parts(ka, kb, Kc, 8) : 1;
+    w.off_t1 = take((size_t)w.s1 * Ma * (kb > 0 ? kb : 1) * 4);
+    w.off_mk = take((size_t)w.s3 * (ka > 0 ? ka : 1) * (kb > 0 ? kb : 1) * 4);
+    w.off_e2 = take((size_t)w.s2 * Nb * (ka > 0 ? ka : 1) * 4);
     w.off_aext = take((size_t)Ma * (w.Kep > 0 ? w.Kep : 16) * 2);
     w.off_bext = take((size_t)Nb * (w.Kep > 0 ? w.Kep : 16) * 2);
     w.tail_bytes = (Ma >= 1024 && Nb >= 1024 && Kc % G_KI == 0) ? gemm_tail_bytes(Ma, Nb, Kc) : 0;
@@ -794,33 +969,52 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         float* E2 = (float*)(ws + w.off_e2);
         bf16_t* ae = (bf16_t*)(ws + w.off_aext);
         bf16_t* be = (bf16_t*)(ws + w.off_bext);
-        // skinny products: few output tiles, long contraction -> split it over workgroups
-        auto splits = [&](int64_t rows, int64_t cols) {
-            int64_t tiles = ceil_div64(rows, 128) * ceil_div64(cols, 64), iters = ceil_div64(Kc, G_KI);
-            int64_t want = ceil_div64(256, tiles), maxs = iters / 2 > 0 ? iters / 2 : 1;
-            return (int)(want < maxs ? want : maxs);
+        // the skinny products T1 = R_a V_b^T, E2 = R_b V_a^T and Mk = V_a V_b^T in one launch, cut along the contraction
+        // (Mk is a single output tile: alone, one workgroup would walk the whole contraction, ~100 us at 14336 columns)
+        SkinnyBatch sb;
+        sb.count = 0;
+        int wgs = 0;
+        const int64_t iters = ceil_div64(Kc, G_KI);
+        bool vec = Kc % G_KI == 0;
+        auto add = [&](const metis_fp4& X, const metis_fp4& Y, float* P, int parts) {
+            SkinnyProblem& q = sb.p[sb.count++];
+            q.A = {X.codes, X.scales, X.rows};
+            q.B = {Y.codes, Y.scales, Y.rows};
+            q.alpha = X.tscale * Y.tscale;
+            q.P = P;
+            q.tiles_n = (int)ceil_div64(Y.rows, 64);
+            q.tiles = (int)ceil_div64(X.rows, 128) * q.tiles_n;
+            q.ips = (int)ceil_div64(iters, parts);
+            q.first = wgs;
+            wgs += q.tiles * parts;
+            vec = vec && reinterpret_cast<uintptr_t>(X.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(Y.codes) % 16 == 0 &&
+                  reinterpret_cast<uintptr_t>(X.scales) % 8 == 0 && reinterpret_cast<uintptr_t>(Y.scales) % 8 == 0;
         };
-        // (the k_a x k_b product Mk is a single output tile: without a split one workgroup would walk the whole
-        // contraction alone, ~100 us at 14336 columns)
-        const int s1 = kb > 0 ? splits(Ma, kb) : 1, s2 = ka > 0 ? splits(Nb, ka) : 1;
-        const int s3 = ka > 0 && kb > 0 ? splits(ka, kb) : 1;
-        if (s1 > 1 || s2 > 1 || s3 > 1) {     // T1, Mk, E2 are contiguous at the start of the workspace
-            hipLaunchKernelGGL(k_zero_f32, dim3(256), dim3(256), 0, s, (float*)ws, w.off_aext / 4);
+        if (ceil_div64(Ma, 128) * 64 * w.s1 + ceil_div64(Nb, 128) * 64 * w.s2 > 0x3FFFFFFF) return METIS_UNSUPPORTED;
+        if (kb > 0) add(a.R, b.Vt, T1, w.s1);
+        if (ka > 0) add(b.R, a.Vt, E2, w.s2);
+        if (ka > 0 && kb > 0) add(a.Vt, b.Vt, Mk, w.s3);
+        for (int i = sb.count; i < 3; ++i) sb.p[i] = sb.p[0];
+        {
+            constexpr size_t lds = gemm_lds_bytes<128, 64>();
+            if (vec) {
+                static LdsLimitCache lds_set;
+                if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<true>, lds, lds_set)) return METIS_HIP_ERROR;
+                hipLaunchKernelGGL(k_fp4_skinny_batch<true>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
+            } else {
+                static LdsLimitCache lds_set;
+                if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<false>, lds, lds_set)) return METIS_HIP_ERROR;
+                hipLaunchKernelGGL(k_fp4_skinny_batch<false>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
+            }
             METIS_LAUNCH_CHECK();
         }
-        if (kb > 0 && (st = launch_gemm<float>(s, a.R, b.Vt, nullptr, nullptr, 0, a.R.tscale * b.Vt.tscale, T1, kb, s1)))
-            return st;
-        if (ka > 0 && (st = launch_gemm<float>(s, b.R, a.Vt, nullptr, nullptr, 0, b.R.tscale * a.Vt.tscale, E2, ka, s2)))
-            return st;
-        if (ka > 0 && kb > 0 &&
-            (st = launch_gemm<float>(s, a.Vt, b.Vt, nullptr, nullptr, 0, a.Vt.tscale * b.Vt.tscale, Mk, kb, s3)))
-            return st;
         const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
-        const size_t ax_lds = ((size_t)AX_ROWS * ((ka > kb ? ka : kb) + 1) + (size_t)ka * kb) * sizeof(float);
-        static LdsLimitCache ax_set;
-        if (ax_lds > 48 * 1024 && !ensure_dyn_lds((const void*)k_assemble_ext, ax_lds, ax_set)) return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(k_assemble_ext, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
-                           T1, Mk, E2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
+        const size_t ax_lds = ((size_t)(AX_ROWS * ((ka > kb ? ka : kb) + 1) + 3) / 4 * 4 + (size_t)ka * kb + 8) * sizeof(float);
+        auto assemble = kb > 64 ? k_assemble_ext<2> : k_assemble_ext<1>;
+        static LdsLimitCache ax_set[2];
+        if (ax_lds > 48 * 1024 && !ensure_dyn_lds((const void*)assemble, ax_lds, ax_set[kb > 64])) return METIS_HIP_ERROR;
+        hipLaunchKernelGGL(assemble, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
+                           T1, w.s1, Mk, w.s3, E2, w.s2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
                            b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);
         METIS_LAUNCH_CHECK();
         Ke = w.Kep;
@@ -839,9 +1033,9 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
     }
     const int pi = metis_prof_begin(METIS_PROF_GEMM, s);
     if (out->dtype == METIS_BF16)
-        st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld, 1, partial, partial_bytes);
+        st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld, partial, partial_bytes);
     else
-        st = launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld, 1, partial, partial_bytes);
+        st = launch_gemm<float>(s, a.R, b.R, Aext, Bext, Ke, grr, (float*)out->ptr, out->ld, partial, partial_bytes);
     metis_prof_end(METIS_PROF_GEMM, pi, s);
     return st;
 }

@@ -31,10 +31,6 @@ template <> __device__ __forceinline__ void store_tile16<bf16_t>(bf16_t* p, int6
     }
 }
 
-template <typename T> __device__ __forceinline__ void atomic_out(T* p, float v);
-template <> __device__ __forceinline__ void atomic_out<float>(float* p, float v) { unsafeAtomicAdd(p, v); }
-template <> __device__ __forceinline__ void atomic_out<bf16_t>(bf16_t*, float) {}   // splits are only used with fp32 output
-
 // Workgroup ids are dealt round-robin to the 8 XCDs by the hardware, and each XCD has its own L2.
 // XCD x therefore gets one RM x RN region of the tile grid (when the grid splits that way) and walks it
 // row-major, so the ~32 tiles it runs at a time form a block of few distinct A and B panels; without a

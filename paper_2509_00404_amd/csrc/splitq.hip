@@ -439,9 +439,10 @@ int check_split_out(int64_t M, int64_t N, int k, const metis_split* out) {
 int launch_residual_quant(hipStream_t s, const bf16_t* Ap, int64_t lda, int64_t M, int64_t N, int64_t Mt, int64_t row_off,
                           const bf16_t* us_hi, const bf16_t* us_lo, const bf16_t* v_hi, const bf16_t* v_lo, int kp, float g,
                           uint8_t* codes, uint8_t* scales, uint8_t* ct, uint8_t* st_, float* R_debug, bool sr, uint64_t seed) {
-    // about two workgroups per CU; every workgroup walks at least four 64-column steps
+    // two workgroups per CU at a time; every workgroup walks at least four 64-column steps; the number of column
+    // chunks that fills the last round of workgroups best
     const int64_t row_blocks = ceil_div64(M, RQ_ROWS);
-    int64_t want = ceil_div64(512, row_blocks);
+    const int64_t want = balanced_split(row_blocks, ceil_div64(N, 4 * RQ_COLS), 512);
     int64_t cchunk = ceil_div64(ceil_div64(N, want), RQ_COLS) * RQ_COLS;
     if (cchunk < 4 * RQ_COLS) cchunk = 4 * RQ_COLS;
     dim3 grid((unsigned)row_blocks, (unsigned)ceil_div64(N, cchunk));

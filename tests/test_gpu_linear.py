@@ -72,7 +72,8 @@ def test_config1_forward(metis):
 
 @pytest.mark.parametrize("L,N,K,kx,kw,kg", [(128, 256, 512, 8, 8, 8), (208, 144, 272, 5, 12, 7),
                                             (512, 384, 1024, 64, 64, 64), (256, 128, 128, 0, 16, 16),
-                                            (144, 160, 256, 16, 0, 0), (96, 80, 112, 0, 0, 0)])
+                                            (144, 160, 256, 16, 0, 0), (96, 80, 112, 0, 0, 0),
+                                            (384, 400, 640, 88, 72, 80)])
 @pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
 def test_all_three_products(metis, L, N, K, kx, kw, kg, out_dtype):
     from paper_2509_00404_amd import workloads
