@@ -61,6 +61,19 @@ static inline bool ensure_dyn_lds(const void* fn, size_t bytes, LdsLimitCache& c
     return true;
 }
 
+// compute units of the current device (cached per device), 0 on error
+static inline int device_cu_count() {
+    static int cached[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    const bool slot = dev >= 0 && dev < 16;
+    if (slot && cached[dev] > 0) return cached[dev];
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (slot) cached[dev] = n;
+    return n;
+}
+
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // How many ways to cut the second grid dimension (1 .. max_split) when `blocks` workgroups exist along the first and

@@ -146,6 +146,14 @@ constexpr size_t gemm_lds_bytes() {
     return 2 * ((size_t)BM * (G_CROW + G_SROW) + (size_t)BN * (G_CROW + G_SROW));
 }
 
+// The extra contraction columns (bf16, Ke % 16 == 0) are stored in the order the matrix instruction wants them:
+// element (row r, column c) at (((r/32 * Ke/16 + c/16) * 2 + (c%16)/8) * 32 + r%32) * 8 + c%8, rows padded to a
+// multiple of 32 -- the 64 lanes' 16-byte operands of one 32-row block and 16-column step are 1 KiB of
+// consecutive memory (read row-major, one such load touched 32 cache lines and used a quarter of each).
+__host__ __device__ __forceinline__ int64_t ext_chunk(int64_t row_block, int step, int half, int li, int nsteps) {
+    return (((row_block * nsteps + step) * 2 + half) * 32 + li) * 8;
+}
+
 // One output tile by a workgroup of WMW x WNW waves, each wave TM x TN tiles of 32x32 (BM = 32 TM WMW,
 // BN = 32 TN WNW), over the contraction stages [it0, niter).
 template <int TM, int TN, int WMW, int WNW, bool VEC, typename OUT>
@@ -222,19 +230,21 @@ gemm_nt_tile(const Fp4Operand& A, const Fp4Operand& B, int64_t K, const bf16_t* 
     }
     // low-rank terms: extra contraction columns in bf16, read straight from global memory
     if (Ke > 0) {
-        for (int ks = 0; ks < Ke; ks += 16) {
+        const int nks = Ke >> 4;
+        const int64_t rba_max = (A.rows + 31) / 32 - 1, rbb_max = (B.rows + 31) / 32 - 1;
+        for (int ks = 0; ks < nks; ++ks) {
             BFrag fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                int64_t r = m0 + wm + 32 * i + li;
-                if (r >= A.rows) r = A.rows - 1;
-                fa[i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + ks + 8 * half);
+                int64_t rb = (m0 + wm) / 32 + i;
+                if (rb > rba_max) rb = rba_max;
+                fa[i].u = *reinterpret_cast<const uint4*>(Aext + ext_chunk(rb, ks, half, li, nks));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                int64_t r = n0 + wn + 32 * j + li;
-                if (r >= B.rows) r = B.rows - 1;
-                fb[j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + ks + 8 * half);
+                int64_t rb = (n0 + wn) / 32 + j;
+                if (rb > rbb_max) rb = rbb_max;
+                fb[j].u = *reinterpret_cast<const uint4*>(Bext + ext_chunk(rb, ks, half, li, nks));
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -318,7 +328,7 @@ template <typename OUT>
 __global__ void __launch_bounds__(256)
 k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restrict__ Aext,
                    const bf16_t* __restrict__ Bext, int Ke_all, float alpha, OUT* __restrict__ C, int64_t ldc, TileMap tmap,
-                   int total_tiles, int tail_first, int tail_parts, float* __restrict__ partial) {
+                   int total_tiles, int tail_first, int tail_parts, float* __restrict__ partial, int total_items) {
     constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // LDS layout of a stage, chosen so that ONE 16-byte read per lane fetches the raw words of all four row
@@ -330,11 +340,20 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     constexpr int PL = 528, CODES_OP = 2 * KS * 2 * PL, SC_OP = 2 * (KS / 2) * PL;
     constexpr int OFF_CB = CODES_OP, OFF_SA = 2 * CODES_OP, OFF_SB = OFF_SA + SC_OP, BUF = OFF_SB + SC_OP;
     static_assert(2 * BUF <= (int)gemm_lds_bytes<256, 256>(), "two stages fit the allocation");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // The tiles of the last, partly filled round of workgroups (launch positions tail_first ..) are cut along the
     // contraction into tail_parts workgroups each, which write fp32 partial tiles that a small kernel adds up:
     // the round then takes 1 / tail_parts of a tile's time instead of leaving most CUs idle for a whole one.
-    int tile = (int)blockIdx.x, part = 0, parts = 1;
+    // A workgroup walks the launch positions blockIdx.x, blockIdx.x + gridDim.x, ... itself (one workgroup per CU):
+    // the stores of a finished tile drain while the next tile's contraction runs, and no CU waits for a dispatch.
+    // (No barrier between tiles is needed: after the barrier in the last stage every LDS read fetches words
+    // that are never used, and the next tile's first reads come after the barrier of its own first stage.)
+    for (int pos = (int)blockIdx.x; pos < total_items; pos += (int)gridDim.x) {
+    // (the thread index passes through an empty asm in every round, so that nothing derived from it counts as
+    // loop-invariant: hoisted out of this loop, the per-lane offsets of all phases would be live at once and spill)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    int tile = pos, part = 0, parts = 1;
     if (tile >= tail_first) {
         const int idx = tile - tail_first;
         tile = tail_first + idx / tail_parts;
@@ -504,34 +523,46 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         }
     }
 
-    // low-rank terms: extra contraction columns in bf16, read straight from global memory, four steps
-    // (64 columns) of fragments in flight at a time
-    for (int ks = 0; ks < Ke; ks += 64) {
-        BFrag fa[4][TM], fb[4][TN];
+    // low-rank terms: extra contraction columns in bf16, read straight from global memory; four steps of
+    // fragments in flight, a step's registers are refilled with the step four ahead as soon as it is used
+    const int nks = Ke >> 4;
+    if (nks > 0) {
+        const bf16_t* ea[TM];
+        const bf16_t* eb[TN];
+        const int64_t rba_max = (A.rows + 31) / 32 - 1, rbb_max = (B.rows + 31) / 32 - 1;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int kc = ks + 16 * u < Ke ? ks + 16 * u : ks;      // a short last batch re-reads its first step (unused)
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int64_t r = m0 + wm + 32 * i + li;
-                if (r >= A.rows) r = A.rows - 1;
-                fa[u][i].u = *reinterpret_cast<const uint4*>(Aext + r * Ke + kc + 8 * half);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int64_t r = n0 + wn + 32 * j + li;
-                if (r >= B.rows) r = B.rows - 1;
-                fb[u][j].u = *reinterpret_cast<const uint4*>(Bext + r * Ke + kc + 8 * half);
-            }
+        for (int i = 0; i < TM; ++i) {
+            int64_t rb = (m0 + wm) / 32 + i;
+            if (rb > rba_max) rb = rba_max;
+            ea[i] = Aext + ext_chunk(rb, 0, half, li, nks);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (ks + 16 * u < Ke) {                                   // uniform (kernel argument)
+        for (int j = 0; j < TN; ++j) {
+            int64_t rb = (n0 + wn) / 32 + j;
+            if (rb > rbb_max) rb = rbb_max;
+            eb[j] = Bext + ext_chunk(rb, 0, half, li, nks);
+        }
+        BFrag f[4][TM + TN];
+        auto load_ext = [&](int step, int slot) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i) f[slot][i].u = *reinterpret_cast<const uint4*>(ea[i] + step * 512);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][i].v, fb[u][j].v, acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) f[slot][TM + j].u = *reinterpret_cast<const uint4*>(eb[j] + step * 512);
+        };
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (u < nks) load_ext(u, u);
+        for (int ks = 0; ks < nks; ks += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (ks + u < nks) {                                   // uniform (kernel argument)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[u][i].v, f[u][TM + j].v, acc[i][j], 0, 0, 0);
+                    if (ks + u + 4 < nks) load_ext(ks + u + 4, u);
+                }
             }
         }
     }
@@ -546,7 +577,7 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                     P[(wm + 32 * i + 4 * half + 8 * (v >> 2) + (v & 3)) * BN + wn + 32 * j + li] = alpha * acc[i][j][v];
-        return;
+        continue;
     }
     const bool interior = m0 + BM <= A.rows && n0 + BN <= B.rows;
 #pragma unroll
@@ -565,6 +596,7 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
                 }
             }
         }
+    }
 }
 
 // adds the parts of the split tail tiles and writes them to C (see k_fp4_gemm_nt_pipe); one workgroup per 32 rows of a tile
@@ -616,13 +648,16 @@ int launch_gemm_pipe(hipStream_t s, const Fp4Operand& a, const Fp4Operand& b, in
     const bool split = want > 0 && partial && partial_bytes >= want;
     if (!split) { parts = 1; tail_first = total; }
     const int tail = total - tail_first;
-    dim3 grid((unsigned)(tail_first + tail * parts));
+    const int items = tail_first + tail * parts;
+    const int cus = device_cu_count();
+    if (cus < 1) return METIS_HIP_ERROR;
+    dim3 grid((unsigned)(items < cus ? items : cus));
     auto kern = k_fp4_gemm_nt_pipe<OUT>;
     static LdsLimitCache lds_set;
     if (!ensure_dyn_lds((const void*)kern, lds, lds_set)) return METIS_HIP_ERROR;
     const TileMap tmap = make_tile_map(tm, tn);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, b, K, Aext, Bext, Ke, alpha, C, ldc, tmap, total, tail_first, parts,
-                       partial);
+                       partial, items);
     METIS_LAUNCH_CHECK();
     if (split) {
         hipLaunchKernelGGL(k_gemm_tail_sum<OUT>, dim3((unsigned)(tail * 8)), dim3(256), 0, s, partial, parts, tail_first, total,
@@ -845,7 +880,7 @@ k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __r
                 for (int i = 0; i < 8; ++i)
                     if (c0 + i < kb) v[i] = acc[i] * Sb[c0 + i] * gs;
             }
-            *reinterpret_cast<uint4*>(Aext + row * Kep + c0) = pack8_bf16(v);
+            *reinterpret_cast<uint4*>(Aext + ext_chunk(row >> 5, c0 >> 4, (c0 >> 3) & 1, rr, Kep >> 4)) = pack8_bf16(v);
         }
         return;
     }
@@ -892,7 +927,7 @@ k_assemble_ext(int64_t Ma, int64_t Nb, int ka, int kb, int Kep, const float* __r
             }
             v[i] = x;
         }
-        *reinterpret_cast<uint4*>(Bext + row * Kep + c0) = pack8_bf16(v);
+        *reinterpret_cast<uint4*>(Bext + ext_chunk(row >> 5, c0 >> 4, (c0 >> 3) & 1, rr, Kep >> 4)) = pack8_bf16(v);
     }
 }
 
@@ -932,8 +967,8 @@ LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb, int64_t Kc) {
     w.off_t1 = take((size_t)w.s1 * Ma * (kb > 0 ? kb : 1) * 4);
     w.off_mk = take((size_t)w.s3 * (ka > 0 ? ka : 1) * (kb > 0 ? kb : 1) * 4);
     w.off_e2 = take((size_t)w.s2 * Nb * (ka > 0 ? ka : 1) * 4);
-    w.off_aext = take((size_t)Ma * (w.Kep > 0 ? w.Kep : 16) * 2);
-    w.off_bext = take((size_t)Nb * (w.Kep > 0 ? w.Kep : 16) * 2);
+    w.off_aext = take((size_t)((Ma + 31) / 32 * 32) * (w.Kep > 0 ? w.Kep : 16) * 2);       // rows padded to whole 32-row blocks
+    w.off_bext = take((size_t)((Nb + 31) / 32 * 32) * (w.Kep > 0 ? w.Kep : 16) * 2);
     w.tail_bytes = (Ma >= 1024 && Nb >= 1024 && Kc % G_KI == 0) ? gemm_tail_bytes(Ma, Nb, Kc) : 0;
     w.off_tail = take(w.tail_bytes);
     w.total = o;
