@@ -11,14 +11,24 @@
 #include "smallmat.h"
 #include "splitq.h"
 #include "rng_dev.h"
+#include <algorithm>
 #include <vector>
 
 namespace {
 
+// contraction chunks so that ~2048 workgroups exist: the generic kernel does not prefetch, so a workgroup
+// should own one or two 32-deep stages and the grid, not the loop, should cover the contraction
+int split_for(int64_t K, int64_t tiles) {
+    int64_t s = 2048 / (tiles > 2048 ? 2048 : tiles);
+    int64_t maxs = K / 32;
+    if (s > maxs) s = maxs;
+    return (int)(s < 1 ? 1 : s);
+}
+
 struct Layout {
     int64_t M, N, Ms;
     int k, r;
-    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_flag, off_c, off_b, zero_bytes;
+    size_t off_zacc, off_g1, off_g1b, off_g2, off_g3, off_flag, off_c, off_b, off_parts, zero_bytes;
     size_t off_idx, off_omega, off_linv, off_h1, off_h, off_lam, off_t, off_v0f, off_v0hi, off_v0lo,
         off_lam3, off_w3, off_t3, off_jscr, total;
 };
@@ -29,14 +39,29 @@ Layout make_layout(int64_t M, int64_t N, int k, int p, int64_t Ms) {
     const size_t r = (size_t)L.r, kk = (size_t)k;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.off_flag = take(4);
+    L.zero_bytes = o;                      // cleared at the start of a decomposition: only the flag word
     L.off_zacc = take((size_t)Ms * r * 8);
     L.off_g1 = take(r * r * 8);
     L.off_g1b = take(r * r * 8);
     L.off_g2 = take(r * r * 8);
     L.off_g3 = take(kk * kk * 8);
-    L.off_flag = take(4);
     L.off_b = take(r * (size_t)N * 8);
-    L.zero_bytes = o;
+    {
+        // one region for the partial products of whichever split contraction is running (they run one after the
+        // other): the sketch, the projection and the four Gram matrices; sized for the fast and the generic kernels
+        const int64_t tiles_rr = ceil_div64(L.r, 32) * ceil_div64(L.r, 32), tiles_kk = ceil_div64(k, 32) * ceil_div64(k, 32);
+        const size_t zp = std::max(sketch_parts(Ms, N), dgemm_parts<EPI_PART_F64>(Ms, L.r, N, split_for(N, ceil_div64(Ms, 32) * ceil_div64(L.r, 32))));
+        const size_t bp = std::max(project_parts(Ms, N), dgemm_parts<EPI_PART_F64>(L.r, N, Ms, split_for(Ms, ceil_div64(L.r, 32) * ceil_div64(N, 32))));
+        const size_t g1p = dgemm_parts<EPI_PART_F64>(L.r, L.r, Ms, split_for(Ms, tiles_rr));
+        const size_t g2p = dgemm_parts<EPI_PART_F64>(L.r, L.r, N, split_for(N, tiles_rr));
+        const size_t g3p = std::max((int)ceil_div64(M, GR_ROWS), dgemm_parts<EPI_PART_F64>(k, k, M, split_for(M, tiles_kk)));
+        size_t need = zp * (size_t)Ms * r;
+        need = std::max(need, bp * r * (size_t)N);
+        need = std::max(need, std::max(g1p, g2p) * r * r);
+        need = std::max(need, g3p * kk * kk);
+        L.off_parts = take(need * 8);
+    }
     L.off_c = take((size_t)broadcast_splits(M, N) * (size_t)M * kk * 4);
     L.off_idx = take((size_t)Ms * 4);
     L.off_omega = take((size_t)N * r * 2);
@@ -84,7 +109,7 @@ FusedLayout make_fused_layout(size_t base, int64_t M, int64_t N, int k) {
 }
 
 // Everything the chain needs before its first product, in one launch: blocks [0, zero_blocks) clear the
-// accumulators (a fill kernel, not a memset node, so the call can be graph-captured) and the two optional
+// flag word (a fill kernel, not a memset node, so the call can be graph-captured) and the two optional
 // output words, the next idx_blocks blocks draw the row sample, the rest draw Omega (a null idx / omega means
 // the caller supplied it).
 __global__ void __launch_bounds__(256)
@@ -124,22 +149,20 @@ DOperand op_parts(const void* p, int64_t s_outer, int64_t s_k, int nparts, int64
 
 DEpilogue epi(void* c, int64_t ldc, bf16_t* hi_t = nullptr, bf16_t* lo_t = nullptr, int64_t ld_t = 0) {
     DEpilogue e;
-    e.c = c; e.ldc = ldc; e.hi_t = hi_t; e.lo_t = lo_t; e.ld_t = ld_t; e.skip = nullptr;
+    e.c = c; e.ldc = ldc; e.hi_t = hi_t; e.lo_t = lo_t; e.ld_t = ld_t; e.skip = nullptr; e.part_stride = 0;
+    return e;
+}
+// partial products of a split contraction, M x N each
+DEpilogue epi_part(double* parts, int64_t M, int64_t N, const int32_t* skip = nullptr) {
+    DEpilogue e = epi(parts, N);
+    e.part_stride = M * N;
+    e.skip = skip;
     return e;
 }
 DEpilogue epi_skip(void* c, int64_t ldc, const int32_t* skip) {
     DEpilogue e = epi(c, ldc);
     e.skip = skip;
     return e;
-}
-
-// contraction chunks so that ~2048 workgroups exist: the generic kernel does not prefetch, so a workgroup
-// should own one or two 32-deep stages and the grid, not the loop, should cover the contraction
-int split_for(int64_t K, int64_t tiles) {
-    int64_t s = 2048 / (tiles > 2048 ? 2048 : tiles);
-    int64_t maxs = K / 32;
-    if (s > maxs) s = maxs;
-    return (int)(s < 1 ? 1 : s);
 }
 
 }  // namespace
@@ -169,7 +192,7 @@ struct Job {
     int cparts;
     char* ws;
     Layout L;
-    double *Zacc, *G1, *G1b, *G2, *G3, *Linv, *H1, *H, *B, *lam, *T, *lam3, *W3, *T3, *jscr;
+    double *Zacc, *G1, *G1b, *G2, *G3, *Linv, *H1, *H, *B, *lam, *T, *lam3, *W3, *T3, *jscr, *parts;
     float *C, *V0f;
     uint32_t* idx;
     bf16_t *omega, *V0hi, *V0lo;
@@ -233,6 +256,7 @@ int make_job(const metis_decompose_job& a, Job& j) {
     j.W3 = (double*)(ws + L.off_w3);
     j.T3 = (double*)(ws + L.off_t3);
     j.jscr = (double*)(ws + L.off_jscr);
+    j.parts = (double*)(ws + L.off_parts);
     j.idx_in = a.idx;
     j.omega_in = (const bf16_t*)a.omega;
     j.idx_use = a.idx ? a.idx : j.idx;
@@ -286,9 +310,11 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
     hipStream_t s = (hipStream_t)stream;
     const std::vector<int> zeros(jobs.size(), 0);
 
-    // ---- accumulators to zero, the draws the caller did not supply, sketch Z = A_s Omega, Gram of Z ----
+    // ---- flag and status words to zero, the draws the caller did not supply, sketch Z = A_s Omega, Gram of Z ----
+    // (every split contraction writes its partial products to the job's `parts` region and a batched kernel adds
+    // them in a fixed order: no floating-point atomics anywhere, so a decomposition is reproducible bit for bit)
     for (const Job& j : jobs) {
-        const int zero_blocks = 512, idx_blocks = j.idx_in ? 0 : (int)ceil_div64(j.Ms, 256);
+        const int zero_blocks = 1, idx_blocks = j.idx_in ? 0 : (int)ceil_div64(j.Ms, 256);
         const int64_t omega_count = j.N * (int64_t)j.r;
         const int64_t omega_blocks = j.omega_in ? 0 : ceil_div64(ceil_div64(omega_count, 2), 256);
         hipLaunchKernelGGL(k_decomp_setup, dim3((unsigned)(zero_blocks + idx_blocks + omega_blocks)), dim3(256), 0, s,
@@ -297,23 +323,45 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
         METIS_LAUNCH_CHECK();
     }
     // products of the same kind and step of all jobs go out together (DgemmList): the small ones are latency-bound
-    DgemmList<double, double, EPI_ATOMIC_F64> gram;
+    DgemmList<double, double, EPI_PART_F64> gram;
     DgemmList<double, double, EPI_STORE_F64> mul;
     DgemmList<double, double, EPI_STORE_SPLIT_T> v0mul;
     DgemmList<float, double, EPI_STORE_F32> outmul;
+    SumList sums;
+    auto tiles_rr = [](const Job& j) { return ceil_div64(j.r, 32) * ceil_div64(j.r, 32); };
+    // Gram matrix of X (K x r, row-major, ld r) for every job: partial products, then their sum
+    auto gram_of = [&](double* Job::*X, double* Job::*G, auto K_of, bool skippable) {
+        for (const Job& j : jobs) {
+            const int r = j.r;
+            const int64_t K = K_of(j);
+            const bool by_rows = X != &Job::B;           // Z, H1: contraction over rows; B (r x N): over columns
+            const DOperand o = by_rows ? op(j.*X, 1, r) : op(j.*X, K, 1);
+            const int32_t* skip = skippable ? j.wellcond : nullptr;
+            gram.add(o, o, r, r, K, split_for(K, tiles_rr(j)), epi_part(j.parts, r, r, skip));
+            sums.add(j.parts, dgemm_parts<EPI_PART_F64>(r, r, K, split_for(K, tiles_rr(j))), (int64_t)r * r, (int64_t)r * r,
+                     j.*G, skip);
+        }
+        gram.launch(s);
+        sums.launch(s);
+    };
     for (const Job& j : jobs) {
         const int r = j.r;
-        const int64_t tiles_zr = ceil_div64(j.Ms, 32) * ceil_div64(r, 32), tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
+        const int64_t tiles_zr = ceil_div64(j.Ms, 32) * ceil_div64(r, 32);
+        int zp;
         if (j.fast) {
-            if ((st = launch_sketch(s, j.A, j.lda, j.idx_use, j.Ms, j.N, j.om_use, r, j.Zacc)) != METIS_OK) return st;
+            if ((st = launch_sketch(s, j.A, j.lda, j.idx_use, j.Ms, j.N, j.om_use, r, j.parts)) != METIS_OK) return st;
+            zp = sketch_parts(j.Ms, j.N);
         } else {
-            launch_dgemm<bf16_t, bf16_t, EPI_ATOMIC_F64>(s, op(j.A, j.lda, 1, j.idx_use), op(j.om_use, 1, r), j.Ms, r, j.N,
-                                                          split_for(j.N, tiles_zr), epi(j.Zacc, r));
+            launch_dgemm<bf16_t, bf16_t, EPI_PART_F64>(s, op(j.A, j.lda, 1, j.idx_use), op(j.om_use, 1, r), j.Ms, r, j.N,
+                                                        split_for(j.N, tiles_zr), epi_part(j.parts, j.Ms, r));
+            zp = dgemm_parts<EPI_PART_F64>(j.Ms, r, j.N, split_for(j.N, tiles_zr));
         }
-        gram.add(op(j.Zacc, 1, r), op(j.Zacc, 1, r), r, r, j.Ms, split_for(j.Ms, tiles_rr), epi(j.G1, r));
         METIS_LAUNCH_CHECK();
+        sums.add(j.parts, zp, j.Ms * (int64_t)r, j.Ms * (int64_t)r, j.Zacc);
     }
-    gram.launch(s);
+    sums.launch(s);
+    METIS_LAUNCH_CHECK();
+    gram_of(&Job::Zacc, &Job::G1, [](const Job& j) { return j.Ms; }, false);
     METIS_LAUNCH_CHECK();
     // ---- CholeskyQR2: Z = H R ----
     {
@@ -322,14 +370,9 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
         if ((st = launch_grouped<CholProblem>(jobs, [](const Job& j) { return j.r; }, chol_launch, s, pr, zeros)) != METIS_OK)
             return st;
     }
-    for (const Job& j : jobs) {
-        const int r = j.r;
-        const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
-        mul.add(op(j.Zacc, r, 1), op(j.Linv, r, 1), j.Ms, r, r, 1, epi(j.H1, r));
-        gram.add(op(j.H1, 1, r), op(j.H1, 1, r), r, r, j.Ms, split_for(j.Ms, tiles_rr), epi_skip(j.G1b, r, j.wellcond));
-    }
+    for (const Job& j : jobs) mul.add(op(j.Zacc, j.r, 1), op(j.Linv, j.r, 1), j.Ms, j.r, j.r, 1, epi(j.H1, j.r));
     mul.launch(s);
-    gram.launch(s);
+    gram_of(&Job::H1, &Job::G1b, [](const Job& j) { return j.Ms; }, true);
     METIS_LAUNCH_CHECK();
     {
         std::vector<CholProblem> pr;
@@ -343,17 +386,22 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
     METIS_LAUNCH_CHECK();
     for (const Job& j : jobs) {
         const int r = j.r;
-        const int64_t tiles_rr = ceil_div64(r, 32) * ceil_div64(r, 32);
+        int bp;
         if (j.fast) {
-            if ((st = launch_project(s, j.H, j.H1, j.wellcond, r, j.A, j.lda, j.idx_use, j.Ms, j.N, j.B)) != METIS_OK) return st;
+            if ((st = launch_project(s, j.H, j.H1, j.wellcond, r, j.A, j.lda, j.idx_use, j.Ms, j.N, j.parts)) != METIS_OK) return st;
+            bp = project_parts(j.Ms, j.N);
         } else {
-            launch_dgemm<double, bf16_t, EPI_ATOMIC_F64>(s, op(j.H, 1, r), op(j.A, 1, j.lda, nullptr, j.idx_use), r, j.N, j.Ms,
-                                                          split_for(j.Ms, ceil_div64(r, 32) * ceil_div64(j.N, 32)), epi(j.B, j.N));
+            const int want = split_for(j.Ms, ceil_div64(r, 32) * ceil_div64(j.N, 32));
+            launch_dgemm<double, bf16_t, EPI_PART_F64>(s, op(j.H, 1, r), op(j.A, 1, j.lda, nullptr, j.idx_use), r, j.N, j.Ms,
+                                                        want, epi_part(j.parts, r, j.N));
+            bp = dgemm_parts<EPI_PART_F64>(r, j.N, j.Ms, want);
         }
-        gram.add(op(j.B, j.N, 1), op(j.B, j.N, 1), r, r, j.N, split_for(j.N, tiles_rr), epi(j.G2, r));
         METIS_LAUNCH_CHECK();
+        sums.add(j.parts, bp, (int64_t)r * j.N, (int64_t)r * j.N, j.B);
     }
-    gram.launch(s);
+    sums.launch(s);
+    METIS_LAUNCH_CHECK();
+    gram_of(&Job::B, &Job::G2, [](const Job& j) { return j.N; }, false);
     METIS_LAUNCH_CHECK();
     // ---- top-k right singular vectors of B from the eigen-decomposition of B B^T ----
     {
@@ -414,13 +462,18 @@ extern "C" int metis_decompose_batch(void* stream, int n_jobs, const metis_decom
         const int64_t cstride = j.M * (int64_t)k;
         if (j.gram_fast) {
             // sums the broadcast's partial products into C (part 0) on the way
-            if ((st = launch_gram_parts(s, j.C, k, j.M, j.cparts, cstride, j.C, j.G3)) != METIS_OK) return st;
+            if ((st = launch_gram_parts(s, j.C, k, j.M, j.cparts, cstride, j.C, j.parts)) != METIS_OK) return st;
+            sums.add(j.parts, (int)ceil_div64(j.M, GR_ROWS), (int64_t)k * k, (int64_t)k * k, j.G3);
         } else {
-            launch_dgemm<float, float, EPI_ATOMIC_F64>(s, op_parts(j.C, 1, k, j.cparts, cstride), op_parts(j.C, 1, k, j.cparts, cstride),
-                                                        k, k, j.M, split_for(j.M, tiles_kk), epi(j.G3, k));
+            const int want = split_for(j.M, tiles_kk);
+            launch_dgemm<float, float, EPI_PART_F64>(s, op_parts(j.C, 1, k, j.cparts, cstride), op_parts(j.C, 1, k, j.cparts, cstride),
+                                                      k, k, j.M, want, epi_part(j.parts, k, k));
+            sums.add(j.parts, dgemm_parts<EPI_PART_F64>(k, k, j.M, want), (int64_t)k * k, (int64_t)k * k, j.G3);
         }
         METIS_LAUNCH_CHECK();
     }
+    sums.launch(s);
+    METIS_LAUNCH_CHECK();
     // ---- singular-value form: C = U S W^T, V = V0 W ----
     {
         std::vector<JacobiProblem> pr;

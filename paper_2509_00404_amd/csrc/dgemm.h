@@ -18,7 +18,9 @@ struct DOperand {
     int64_t part_stride;         // ... part_stride elements apart (nparts <= 1: a single array)
 };
 
-enum { EPI_STORE_F64 = 0, EPI_ATOMIC_F64 = 1, EPI_STORE_F32 = 2, EPI_STORE_SPLIT_T = 3 };
+// PART_F64: contraction chunk z stores its partial product at c + z * part_stride (no atomics: the parts are added
+// afterwards in a fixed order, k_sum_parts_batch, so a result does not depend on the order workgroups finish in)
+enum { EPI_STORE_F64 = 0, EPI_PART_F64 = 1, EPI_STORE_F32 = 2, EPI_STORE_SPLIT_T = 3 };
 
 struct DEpilogue {
     void* c;                     // F64 / F32 output, element (m,n) at c[m*ldc + n]
@@ -27,6 +29,7 @@ struct DEpilogue {
     bf16_t* lo_t;
     int64_t ld_t;
     const int32_t* skip;         // optional device flag: nonzero -> the kernel returns at once
+    int64_t part_stride;         // PART_F64: elements between the partial products of consecutive chunks
 };
 
 template <typename T> __device__ __forceinline__ double dload(const void* p, int64_t off);
@@ -127,8 +130,8 @@ __device__ __forceinline__ void dgemm_tile(const DOperand& A, const DOperand& B,
         double x = acc[v];
         if (EPI == EPI_STORE_F64) {
             ((double*)ep.c)[m * ep.ldc + n] = x;
-        } else if (EPI == EPI_ATOMIC_F64) {
-            unsafeAtomicAdd(&((double*)ep.c)[m * ep.ldc + n], x);
+        } else if (EPI == EPI_PART_F64) {
+            ((double*)ep.c)[(int64_t)bz * ep.part_stride + m * ep.ldc + n] = x;
         } else if (EPI == EPI_STORE_F32) {
             ((float*)ep.c)[m * ep.ldc + n] = (float)x;
         } else {
@@ -178,11 +181,11 @@ k_dgemm_batch(const DgemmBatch b) {
 
 // Epilogue shared by both kernels.
 template <int EPI>
-__device__ __forceinline__ void dgemm_store(const DEpilogue& ep, int64_t m, int64_t n, double x) {
+__device__ __forceinline__ void dgemm_store(const DEpilogue& ep, int64_t m, int64_t n, double x, uint32_t z) {
     if (EPI == EPI_STORE_F64) {
         ((double*)ep.c)[m * ep.ldc + n] = x;
-    } else if (EPI == EPI_ATOMIC_F64) {
-        unsafeAtomicAdd(&((double*)ep.c)[m * ep.ldc + n], x);
+    } else if (EPI == EPI_PART_F64) {
+        ((double*)ep.c)[(int64_t)z * ep.part_stride + m * ep.ldc + n] = x;
     } else if (EPI == EPI_STORE_F32) {
         ((float*)ep.c)[m * ep.ldc + n] = (float)x;
     } else {
@@ -284,32 +287,43 @@ k_dgemm_big(DOperand A, DOperand B, int64_t M, int64_t N, int64_t K, int64_t kch
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 int64_t m = m0 + wm + 16 * i + 4 * v + (lane >> 4), n = n0 + wn + 16 * j + (lane & 15);
-                if (m < M && n < N) dgemm_store<EPI>(ep, m, n, acc[i][j][v]);
+                if (m < M && n < N) dgemm_store<EPI>(ep, m, n, acc[i][j][v], blockIdx.z);
             }
+}
+
+static inline bool dgemm_is_big(int64_t M, int64_t N, int64_t K) { return M * N * K >= ((int64_t)1 << 26) && M >= 48 && N >= 48; }
+
+// contraction chunk and number of chunks a product is launched with (ksplit = the caller's wish; only the
+// PART_F64 epilogue may split)
+template <int EPI>
+static inline int dgemm_parts(int64_t M, int64_t N, int64_t K, int ksplit, int64_t* kchunk_out = nullptr) {
+    if (ksplit < 1 || EPI != EPI_PART_F64) ksplit = 1;
+    int64_t kchunk;
+    if (dgemm_is_big(M, N, K)) {
+        // split the contraction only as far as needed for ~512 workgroups
+        const int64_t tiles = ceil_div64(M, DGB_T) * ceil_div64(N, DGB_T);
+        if (EPI == EPI_PART_F64) {
+            const int64_t want = ceil_div64(512, tiles), maxs = K / 128 > 0 ? K / 128 : 1;
+            ksplit = (int)(want < maxs ? want : maxs);
+        }
+        kchunk = ceil_div64(ceil_div64(K, ksplit), DGB_K) * DGB_K;
+    } else {
+        kchunk = ceil_div64(ceil_div64(K, ksplit), DG_BK) * DG_BK;
+    }
+    if (kchunk_out) *kchunk_out = kchunk;
+    return (int)ceil_div64(K, kchunk);
 }
 
 template <typename TA, typename TB, int EPI>
 static inline void launch_dgemm(hipStream_t s, DOperand A, DOperand B, int64_t M, int64_t N, int64_t K,
                                 int ksplit, DEpilogue ep) {
-    if (ksplit < 1) ksplit = 1;
-    const bool big = M * N * K >= ((int64_t)1 << 26) && M >= 48 && N >= 48;
-    if (big) {
-        // split the contraction only as far as needed for ~512 workgroups (atomic epilogue only)
-        int64_t tiles = ceil_div64(M, DGB_T) * ceil_div64(N, DGB_T);
-        if (EPI == EPI_ATOMIC_F64) {
-            int64_t want = ceil_div64(512, tiles), maxs = K / 128 > 0 ? K / 128 : 1;
-            ksplit = (int)(want < maxs ? want : maxs);
-        } else {
-            ksplit = 1;
-        }
-        int64_t kchunk = ceil_div64(ceil_div64(K, ksplit), DGB_K) * DGB_K;
-        ksplit = (int)ceil_div64(K, kchunk);
+    int64_t kchunk;
+    ksplit = dgemm_parts<EPI>(M, N, K, ksplit, &kchunk);
+    if (dgemm_is_big(M, N, K)) {
         dim3 grid((unsigned)ceil_div64(N, DGB_T), (unsigned)ceil_div64(M, DGB_T), (unsigned)ksplit);
         hipLaunchKernelGGL((k_dgemm_big<TA, TB, EPI>), grid, dim3(256), 0, s, A, B, M, N, K, kchunk, ep);
         return;
     }
-    int64_t kchunk = ceil_div64(ceil_div64(K, ksplit), DG_BK) * DG_BK;
-    ksplit = (int)ceil_div64(K, kchunk);
     dim3 grid((unsigned)ceil_div64(N, DG_BN), (unsigned)ceil_div64(M, DG_BM), (unsigned)ksplit);
     hipLaunchKernelGGL((k_dgemm<TA, TB, EPI>), grid, dim3(256), 0, s, A, B, M, N, K, kchunk, ep);
 }
@@ -335,14 +349,12 @@ struct DgemmList {
             b.n = 0;
         };
         for (const Item& it : items) {
-            const bool big = it.M * it.N * it.K >= ((int64_t)1 << 26) && it.M >= 48 && it.N >= 48;
-            if (big) {
+            if (dgemm_is_big(it.M, it.N, it.K)) {
                 launch_dgemm<TA, TB, EPI>(s, it.A, it.B, it.M, it.N, it.K, it.ksplit, it.ep);
                 continue;
             }
-            int ksplit = it.ksplit < 1 ? 1 : it.ksplit;
-            const int64_t kchunk = ceil_div64(ceil_div64(it.K, ksplit), DG_BK) * DG_BK;
-            ksplit = (int)ceil_div64(it.K, kchunk);
+            int64_t kchunk;
+            const int ksplit = dgemm_parts<EPI>(it.M, it.N, it.K, it.ksplit, &kchunk);
             DgemmCall& c = b.c[b.n];
             c.A = it.A; c.B = it.B; c.M = it.M; c.N = it.N; c.K = it.K; c.kchunk = kchunk; c.ep = it.ep;
             c.gx = (uint32_t)ceil_div64(it.N, DG_BN);
@@ -350,6 +362,110 @@ struct DgemmList {
             c.gz = (uint32_t)ksplit;
             b.off[b.n + 1] = b.off[b.n] + c.gx * c.gy * c.gz;
             if (++b.n == DG_MAX_BATCH) flush();
+        }
+        flush();
+        items.clear();
+    }
+};
+
+// Sum of partial arrays in a fixed order: out[i] = sum_p parts[p * stride + i], i < n, for several independent
+// calls in one launch.  Two shapes of work.  Many parts of a small array (the Gram matrices: up to a few hundred
+// parts of r x r): a workgroup owns 32 consecutive elements, its 8 thread groups each add a contiguous range of the
+// parts in ascending order and the 8 subtotals are added in ascending order.  Few parts of a large array (sketch,
+// projection): a thread owns two consecutive elements and adds the parts in ascending order, eight loads in
+// flight.  Either way the result is a function of the parts alone.
+#define SUM_EB 32
+#define SUM_PG 8
+#define SUM_WIDE 512             // elements per workgroup in the few-parts shape
+#define SUM_MAX_BATCH 24
+struct SumCall {
+    const double* parts;
+    double* out;
+    int64_t n, stride;
+    int nparts;
+    int wide;                    // 1: few parts of a large array
+    const int32_t* skip;         // optional device flag: nonzero -> nothing is written
+};
+struct SumBatch {
+    int n;
+    uint32_t off[SUM_MAX_BATCH + 1];
+    SumCall c[SUM_MAX_BATCH];
+};
+
+static __global__ void __launch_bounds__(256)
+k_sum_parts_batch(const SumBatch b) {
+    __shared__ double red[SUM_PG][SUM_EB];
+    const uint32_t blk = blockIdx.x;
+    int c = 0;
+    while (c + 1 < b.n && blk >= b.off[c + 1]) ++c;
+    const SumCall& call = b.c[c];
+    if (call.skip && *call.skip) return;
+    if (call.wide) {
+        const int64_t i = ((int64_t)(blk - b.off[c]) * 256 + threadIdx.x) * 2;
+        if (i >= call.n) return;
+        const double* __restrict__ src = call.parts + i;
+        double a0 = 0.0, a1 = 0.0;
+        if (i + 1 < call.n && (call.stride & 1) == 0) {          // 16-byte loads (parts and out are 16-byte aligned)
+#pragma unroll 8
+            for (int p = 0; p < call.nparts; ++p) {
+                const double2 v = *reinterpret_cast<const double2*>(src + (int64_t)p * call.stride);
+                a0 += v.x;
+                a1 += v.y;
+            }
+            *reinterpret_cast<double2*>(call.out + i) = make_double2(a0, a1);
+        } else {
+            const bool two = i + 1 < call.n;
+#pragma unroll 4
+            for (int p = 0; p < call.nparts; ++p) {
+                a0 += src[(int64_t)p * call.stride];
+                if (two) a1 += src[(int64_t)p * call.stride + 1];
+            }
+            call.out[i] = a0;
+            if (two) call.out[i + 1] = a1;
+        }
+        return;
+    }
+    const int e = threadIdx.x % SUM_EB, g = threadIdx.x / SUM_EB;
+    const int64_t i = (int64_t)(blk - b.off[c]) * SUM_EB + e;
+    const int per = (call.nparts + SUM_PG - 1) / SUM_PG;
+    const int p0 = g * per, p1 = p0 + per < call.nparts ? p0 + per : call.nparts;
+    double acc = 0.0;
+    if (i < call.n) {
+        const double* __restrict__ src = call.parts + i;
+#pragma unroll 4
+        for (int p = p0; p < p1; ++p) acc += src[(int64_t)p * call.stride];
+    }
+    red[g][e] = acc;
+    __syncthreads();
+    if (g == 0 && i < call.n) {
+        double t = red[0][e];
+#pragma unroll
+        for (int q = 1; q < SUM_PG; ++q) t += red[q][e];
+        call.out[i] = t;
+    }
+}
+
+struct SumList {
+    std::vector<SumCall> items;
+    void add(const double* parts, int nparts, int64_t stride, int64_t n, double* out, const int32_t* skip = nullptr) {
+        // few parts of a large array: one thread adds them all; many parts: thread groups share them
+        const int wide = nparts <= 24 || n >= ((int64_t)1 << 18);
+        items.push_back({parts, out, n, stride, nparts, wide, skip});
+    }
+    void launch(hipStream_t s) {
+        SumBatch b;
+        b.n = 0;
+        b.off[0] = 0;
+        auto flush = [&]() {
+            if (b.n == 0) return;
+            for (int i = b.n; i < SUM_MAX_BATCH; ++i) { b.c[i] = b.c[0]; b.off[i + 1] = b.off[b.n]; }
+            hipLaunchKernelGGL(k_sum_parts_batch, dim3(b.off[b.n]), dim3(256), 0, s, b);
+            b.n = 0;
+        };
+        for (const SumCall& it : items) {
+            b.c[b.n] = it;
+            b.off[b.n + 1] = b.off[b.n] + (uint32_t)ceil_div64(it.n, it.wide ? SUM_WIDE : SUM_EB);
+            if (++b.n == SUM_MAX_BATCH) flush();
         }
         flush();
         items.clear();

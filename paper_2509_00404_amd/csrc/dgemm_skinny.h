@@ -3,8 +3,9 @@
 // product is skinny (r = k + p <= 128 columns), so a workgroup owns a full-width strip of the
 // output, the bf16 input travels HBM -> registers -> LDS in 16-byte row pieces, and the fp64
 // matrix cores (v_mfma_f64_16x16x4_f64) do the arithmetic: bf16 values are exact in fp64 and the
-// accumulation is fp64 throughout.  The contraction is split over blockIdx.z and the partial
-// strips are added atomically into a zeroed output.
+// accumulation is fp64 throughout.  The contraction is split over blockIdx.z; chunk z stores its partial
+// strip at part z of the output (parts Ms r resp. r N elements apart), and k_sum_parts_batch adds the parts in
+// a fixed order afterwards: no atomics, so the result does not depend on the order workgroups finish in.
 #pragma once
 #include "dgemm.h"
 
@@ -16,7 +17,7 @@ __device__ __forceinline__ double bf16_bits_to_f64(uint16_t h) {
 // Sketch: Z[m][j] += sum_k A[rowmap[m]][k] * Om[k][j],  m < Ms, j < r, k in the split's chunk.
 //   A   bf16, row stride lda (multiple of 8, base 16-byte aligned), K % 8 == 0
 //   Om  bf16 [K][r] row-major, r % 8 == 0, base 16-byte aligned
-//   Z   fp64 [Ms][r], zeroed by the caller
+//   Z   fp64 [ksplit][Ms][r] partial products
 // grid (1, ceil(Ms/64), ksplit), block 256: wave w owns rows 16w..16w+15 and all NT column tiles.
 // ---------------------------------------------------------------------------------------
 #define SK_ROWS 64
@@ -128,7 +129,7 @@ k_sketch(const bf16_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__
         for (int v = 0; v < 4; ++v) {
             const int64_t m = m0 + wave * 16 + 4 * v + (lane >> 4);
             const int col = 16 * j + (lane & 15);
-            if (m < Ms && col < r) unsafeAtomicAdd(&Z[m * r + col], acc[j][v]);
+            if (m < Ms && col < r) Z[(int64_t)blockIdx.z * Ms * r + m * r + col] = acc[j][v];
         }
 }
 
@@ -136,7 +137,7 @@ k_sketch(const bf16_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__
 // Projection: B[j][n] += sum_k H[k][j] * A[rowmap[k]][n],  j < r, n < N, k < Ms in the split's chunk.
 //   H   fp64 [Ms][r] row-major, r even
 //   A   bf16 as above, N % 8 == 0
-//   B   fp64 [r][N], zeroed by the caller
+//   B   fp64 [ksplit][r][N] partial products
 // grid (ceil(N/64), 1, ksplit), block 256: wave w owns columns 16w..16w+15 and all NT row tiles.
 // Dynamic LDS: 2 H stages (fp64) + 2 A stages (bf16).
 // ---------------------------------------------------------------------------------------
@@ -242,7 +243,7 @@ k_project(const double* __restrict__ H_main, const double* __restrict__ H_alt, c
         for (int v = 0; v < 4; ++v) {
             const int j = 16 * i + 4 * v + (lane >> 4);
             const int64_t n = n0 + wave * 16 + (lane & 15);
-            if (j < r && n < N) unsafeAtomicAdd(&B[(int64_t)j * N + n], acc[i][v]);
+            if (j < r && n < N) B[((int64_t)blockIdx.z * r + j) * N + n] = acc[i][v];
         }
 }
 
@@ -259,6 +260,15 @@ static inline bool skinny_ok(const bf16_t* A, int64_t lda, int64_t N, int r) {
     return r % 8 == 0 && r >= 8 && r <= 128 && N % 8 == 0 && lda % 8 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
 }
 
+// number of partial products the two kernels write
+static inline int sketch_parts(int64_t Ms, int64_t K) {
+    return (int)ceil_div64(K, skinny_kchunk(K, ceil_div64(Ms, SK_ROWS), SK_KS));
+}
+static inline int project_parts(int64_t Ms, int64_t N) {
+    return (int)ceil_div64(Ms, skinny_kchunk(Ms, ceil_div64(N, PJ_COLS), PJ_KS));
+}
+
+// Z = sketch_parts(Ms, K) partial products [Ms][r]
 static inline int launch_sketch(hipStream_t s, const bf16_t* A, int64_t lda, const uint32_t* rowmap, int64_t Ms, int64_t K,
                                 const bf16_t* Om, int r, double* Z) {
     const int64_t kchunk = skinny_kchunk(K, ceil_div64(Ms, SK_ROWS), SK_KS);
@@ -280,6 +290,7 @@ static inline int launch_sketch(hipStream_t s, const bf16_t* A, int64_t lda, con
     return METIS_OK;
 }
 
+// B = project_parts(Ms, N) partial products [r][N]
 static inline int launch_project(hipStream_t s, const double* H, const double* H_alt, const int32_t* use_alt, int r,
                                  const bf16_t* A, int64_t lda, const uint32_t* rowmap, int64_t Ms, int64_t N, double* B) {
     const int64_t kchunk = skinny_kchunk(Ms, ceil_div64(N, PJ_COLS), PJ_KS);
@@ -308,12 +319,13 @@ static inline int launch_project(hipStream_t s, const double* H, const double* H
 
 // ---------------------------------------------------------------------------------------
 // Gram matrix of a tall skinny matrix given as a sum of partial arrays (the broadcast's per-split
-// partial products):  S = sum_p C_p  (M x r, fp32),  G += S^T S  (r x r, fp64, zeroed by the caller).
+// partial products):  S = sum_p C_p  (M x r, fp32),  G_b = S_b^T S_b  (r x r, fp64) for the rows S_b of workgroup b:
+// G holds ceil(M / GR_ROWS) partial Gram matrices, added in a fixed order afterwards (k_sum_parts_batch).
 // The summed matrix is written back as fp32 (sum_out, may alias part 0) for the later U = S T.
 //   r % 4 == 0, C 16-byte aligned.
 // grid (ceil(M / GR_ROWS)), block 256; wave w owns row tiles w, w+4 of G and all NT column tiles.
 // ---------------------------------------------------------------------------------------
-#define GR_ROWS 32                    // rows of C per workgroup
+#define GR_ROWS 64                    // rows of C per workgroup
 #define GR_KS 32                      // rows per stage
 template <int NT>
 __global__ void __launch_bounds__(256)
@@ -401,7 +413,7 @@ k_gram_parts(const float* C, int r, int64_t M, int nparts, int64_t part_stride, 
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int a = 16 * it + 4 * v + (lane >> 4), b = 16 * j + (lane & 15);
-                if (a < r && b < r) unsafeAtomicAdd(&G[(int64_t)a * r + b], acc[i][j][v]);
+                if (a < r && b < r) G[((int64_t)blockIdx.x * r + a) * r + b] = acc[i][j][v];
             }
     }
 }

@@ -6,6 +6,7 @@
 // dense dW with the dequantized factors on the fp64 matrix cores, contraction split over workgroups.
 #include "common.h"
 #include "dgemm.h"
+#include <algorithm>
 #include "dgemm_skinny.h"
 #include "../../include/metis.h"
 
@@ -52,11 +53,6 @@ __global__ void k_f64_to_f32_t(const double* __restrict__ in, int k, int64_t col
     out[t] = (float)in[(int64_t)j * cols + c];
 }
 
-__global__ void k_zero_f64(double* __restrict__ p, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t st = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += st) p[i] = 0.0;
-}
 
 // out[r][j] = (float)(in[r][j] * colscale[j])  (colscale optional)
 __global__ void k_f64_to_f32_cols(const double* __restrict__ in, int64_t rows, int k, const float* __restrict__ colscale,
@@ -67,8 +63,14 @@ __global__ void k_f64_to_f32_cols(const double* __restrict__ in, int64_t rows, i
     out[t] = (float)(colscale ? in[t] * (double)colscale[j] : in[t]);
 }
 
+int splits_for(int64_t Kc, int64_t tiles) {
+    int64_t s = 1024 / (tiles > 1024 ? 1024 : tiles), maxs = Kc / 64;
+    if (s > maxs) s = maxs;
+    return (int)(s < 1 ? 1 : s);
+}
+
 struct FgLayout {
-    size_t off_t, off_dv, off_ds, zero_bytes, off_vd, off_ud, off_uds, off_vbf, off_h64, total;
+    size_t off_t, off_dv, off_ds, off_vd, off_ud, off_uds, off_vbf, off_h64, off_parts, total;
 };
 
 FgLayout fg_layout(int64_t N, int64_t K, int k) {
@@ -78,12 +80,21 @@ FgLayout fg_layout(int64_t N, int64_t K, int k) {
     L.off_t = take((size_t)N * k * 8);
     L.off_dv = take((size_t)K * k * 8);
     L.off_ds = take((size_t)k * k * 8);
-    L.zero_bytes = o;
     L.off_vd = take((size_t)k * K * 4);
     L.off_ud = take((size_t)k * N * 4);
     L.off_uds = take((size_t)k * N * 4);
     L.off_vbf = take((size_t)K * k * 2);
     L.off_h64 = take((size_t)N * k * 8);
+    {
+        // partial products of whichever split contraction is running (fast and generic kernels), added in a fixed order
+        const int64_t tk = ceil_div64(k, 32);
+        const size_t tp = std::max(sketch_parts(N, K), dgemm_parts<EPI_PART_F64>(N, k, K, splits_for(K, ceil_div64(N, 32) * tk)));
+        const size_t vp = std::max(project_parts(N, K), dgemm_parts<EPI_PART_F64>(K, k, N, splits_for(N, ceil_div64(K, 32) * tk)));
+        const size_t sp = dgemm_parts<EPI_PART_F64>(k, k, N, splits_for(N, tk * tk));
+        size_t need = std::max(tp * (size_t)N * k, vp * (size_t)K * k);
+        need = std::max(need, sp * (size_t)k * k);
+        L.off_parts = take(need * 8);
+    }
     L.total = o;
     return L;
 }
@@ -96,14 +107,14 @@ DOperand opnd(const void* p, int64_t s_outer, int64_t s_k) {
 
 DEpilogue epi64(double* c, int64_t ldc) {
     DEpilogue e;
-    e.c = c; e.ldc = ldc; e.hi_t = nullptr; e.lo_t = nullptr; e.ld_t = 0; e.skip = nullptr;
+    e.c = c; e.ldc = ldc; e.hi_t = nullptr; e.lo_t = nullptr; e.ld_t = 0; e.skip = nullptr; e.part_stride = 0;
     return e;
 }
 
-int splits_for(int64_t Kc, int64_t tiles) {
-    int64_t s = 1024 / (tiles > 1024 ? 1024 : tiles), maxs = Kc / 64;
-    if (s > maxs) s = maxs;
-    return (int)(s < 1 ? 1 : s);
+DEpilogue epi_part(double* parts, int64_t M, int64_t N) {
+    DEpilogue e = epi64(parts, N);
+    e.part_stride = M * N;
+    return e;
 }
 
 bool fp4_ok(const metis_fp4& f, int64_t rows, int64_t cols) {
@@ -119,7 +130,8 @@ int run(hipStream_t s, const TW* dW, int64_t ld, int64_t N, int64_t K, int k, co
     float* Vd = (float*)(ws + L.off_vd);
     float* Ud = (float*)(ws + L.off_ud);
     float* UdS = (float*)(ws + L.off_uds);
-    hipLaunchKernelGGL(k_zero_f64, dim3(256), dim3(256), 0, s, (double*)ws, L.zero_bytes / 8);
+    double* parts = (double*)(ws + L.off_parts);
+    SumList sums;
     hipLaunchKernelGGL(k_dequant_factor, dim3((unsigned)ceil_div64((int64_t)k * K, 256)), dim3(256), 0, s, W->Vt.codes,
                        W->Vt.scales, k, K, W->Vt.tscale, (const float*)nullptr, Vd);
     hipLaunchKernelGGL(k_dequant_factor, dim3((unsigned)ceil_div64((int64_t)k * N, 256)), dim3(256), 0, s, W->Ut.codes,
@@ -141,22 +153,34 @@ int run(hipStream_t s, const TW* dW, int64_t ld, int64_t N, int64_t K, int k, co
         METIS_LAUNCH_CHECK();
         int st;
         // T = dW Vbar                  [N,k], contraction over K
-        if ((st = launch_sketch(s, (const bf16_t*)dW, ld, nullptr, N, K, Vbf, k, T)) != METIS_OK) return st;
+        if ((st = launch_sketch(s, (const bf16_t*)dW, ld, nullptr, N, K, Vbf, k, parts)) != METIS_OK) return st;
+        sums.add(parts, sketch_parts(N, K), N * (int64_t)k, N * (int64_t)k, T);
+        sums.launch(s);
         // dV^T = (Ubar S)^T dW         [k,K], contraction over N
-        if ((st = launch_project(s, H64, nullptr, nullptr, k, (const bf16_t*)dW, ld, nullptr, N, K, dV64)) != METIS_OK)
+        if ((st = launch_project(s, H64, nullptr, nullptr, k, (const bf16_t*)dW, ld, nullptr, N, K, parts)) != METIS_OK)
             return st;
+        sums.add(parts, project_parts(N, K), K * (int64_t)k, K * (int64_t)k, dV64);
+        sums.launch(s);
     } else {
         // T = dW Vbar                  [N,k], contraction over K
-        launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, ld, 1), opnd(Vd, K, 1), N, k, K,
-                                                splits_for(K, ceil_div64(N, 32) * tk), epi64(T, k));
+        int want = splits_for(K, ceil_div64(N, 32) * tk);
+        launch_dgemm<TW, float, EPI_PART_F64>(s, opnd(dW, ld, 1), opnd(Vd, K, 1), N, k, K, want, epi_part(parts, N, k));
+        sums.add(parts, dgemm_parts<EPI_PART_F64>(N, k, K, want), N * (int64_t)k, N * (int64_t)k, T);
+        sums.launch(s);
         // dV = dW^T (Ubar S)           [K,k], contraction over N
-        launch_dgemm<TW, float, EPI_ATOMIC_F64>(s, opnd(dW, 1, ld), opnd(UdS, N, 1), K, k, N,
-                                                splits_for(N, ceil_div64(K, 32) * tk), epi64(dV64, k));
+        want = splits_for(N, ceil_div64(K, 32) * tk);
+        launch_dgemm<TW, float, EPI_PART_F64>(s, opnd(dW, 1, ld), opnd(UdS, N, 1), K, k, N, want, epi_part(parts, K, k));
+        sums.add(parts, dgemm_parts<EPI_PART_F64>(K, k, N, want), K * (int64_t)k, K * (int64_t)k, dV64);
+        sums.launch(s);
     }
     METIS_LAUNCH_CHECK();
     // dS = Ubar^T T                    [k,k], contraction over N
-    launch_dgemm<float, double, EPI_ATOMIC_F64>(s, opnd(Ud, N, 1), opnd(T, 1, k), k, k, N, splits_for(N, tk * tk),
-                                                epi64(dS64, k));
+    {
+        const int want = splits_for(N, tk * tk);
+        launch_dgemm<float, double, EPI_PART_F64>(s, opnd(Ud, N, 1), opnd(T, 1, k), k, k, N, want, epi_part(parts, k, k));
+        sums.add(parts, dgemm_parts<EPI_PART_F64>(k, k, N, want), (int64_t)k * k, (int64_t)k * k, dS64);
+        sums.launch(s);
+    }
     METIS_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_f64_to_f32_cols, dim3((unsigned)ceil_div64(N * k, 256)), dim3(256), 0, s, T, N, k, W->S, dU);
     if (fast)

@@ -202,3 +202,28 @@ def test_sequence_granular_sampling_in_the_decomposition(metis):
     # and it is a different sample from the row-granular one
     U1, S1, V1 = metis.decompose(Ad, k, p, rho, seed)
     assert not torch.equal(S1, job["S"])
+
+
+@pytest.mark.parametrize("M,N,rho", [(4096, 4096, 1.0), (8192, 2048, 1.0 / 16)])
+def test_runs_are_bit_identical(metis, M, N, rho):
+    """The split contractions write partial products side by side and add them in a fixed order (no floating-point
+    atomics), so two runs on the same input give the same factors bit for bit, with eager work in between; the
+    codes of the split that follows are then identical as well."""
+    from paper_2509_00404_amd import workloads
+    A = workloads.planted(M, N, workloads.power_law(min(M, N, 512), 1.1), 77, rms=0.5, noise_top=0.01).cuda()
+    k, p = 64, 16
+    first = None
+    for rep in range(3):
+        U, S, V = metis.decompose(A, k, p, rho, 4242)
+        g = metis.tensor_scale(float(A.abs().max()))
+        sp = metis.SplitTensor(M, N, k, 2.0 ** -11, 2.0 ** -11, g, True)
+        metis.split_quantize(A, U, S, V, sp)
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (U, S, V, sp.R.codes, sp.R.scales, sp.Rt.codes, sp.Rt.scales, sp.Ut.codes, sp.Vt.codes)]
+        if first is None:
+            first = got
+        else:
+            for i, (a, b) in enumerate(zip(got, first)):
+                assert torch.equal(a, b), (rep, i)
+        noise = torch.randn((1024, 1024), device="cuda") @ torch.randn((1024, 1024), device="cuda")   # perturbs timing
+        assert torch.isfinite(noise).all()

@@ -83,10 +83,7 @@ def test_step_replays_from_a_graph(metis):
         graph.replay()
         torch.cuda.synchronize()
         for i, (a, b) in enumerate(zip(st.outputs(), eager)):
-            # the split contractions add their partial sums with fp64 atomics in arrival order, so a last
-            # fp64 bit, and once in a long while an fp32 rounding or an FP4 code behind it, may differ
-            if a.dtype == torch.uint8:
-                assert (a != b).float().mean().item() < 1e-4, (rep, i)
-            else:
-                assert (a.double() - b.double()).abs().max().item() <= 1e-4 * b.double().abs().max().item(), (rep, i)
+            # no floating-point atomics anywhere on the path (partial products are written side by side and
+            # added in a fixed order), so a replay reproduces the eager run bit for bit
+            assert torch.equal(a, b), (rep, i, (a != b).float().mean().item())
         assert torch.isfinite(other).all()
