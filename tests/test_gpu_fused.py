@@ -50,7 +50,7 @@ def test_fused_split_matches_oracle_and_two_call_path(metis, M, N, k, p, rho, wa
     Ur, Sr, Vr = odec.decompose(An, k, p, rho, seed)
     assert np.max(np.abs(Sn - Sr) / Sr) < 1e-3
     assert odec.principal_angle(Vn, Vr) < 1e-2 and odec.principal_angle(Un, Ur) < 1e-2
-    # same factors as the two-call path (same kernels up to the order of atomic sums)
+    # same factors as the two-call path (same kernels; a band's broadcast may cut its contraction differently)
     assert np.max(np.abs(Sn - S2.double().cpu().numpy()) / Sn) < 1e-5
     # the quantizer's input is the residual of the returned factors
     R = Rd.double().cpu().numpy()
