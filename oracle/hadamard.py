@@ -2,8 +2,9 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-The paper compares Metis with a recipe that "incorporates a random Hadamard transform alongside SR" (Sec. 4.3,
-Comparison with Nvidia's Recipe; Sec. 5, Hadamard transformations) and gives no further definition.  Readings of
+The paper compares Metis with a recipe that rotates tensors by a random Hadamard transform before rounding them
+stochastically (Sec. 4.3, the comparison with another FP4 recipe; Sec. 5, Hadamard transformations) and gives no
+further definition.  Readings of
 this build: the rotation acts on the blocks of 16 consecutive elements that the quantizer scales together,
     z = (x * d) H_16 / 4,
 H_16 the 16 x 16 Sylvester Hadamard matrix (natural order), d in {+1, -1}^16 one random sign per position in the
