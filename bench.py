@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--fused", action="store_true",
                     help="decompose + split through the fused metis_decompose_split_quantize path (A read once from HBM, "
                          "band by band) instead of two calls per operand; measured slower on this GPU, hence not the default")
+    ap.add_argument("--prep-streams", type=int, default=3,
+                    help="streams the operands' decompositions and splits are spread over (they are independent of one "
+                         "another; the GEMMs always run on the main stream after a join)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
@@ -190,8 +193,9 @@ def main():
     n_split = sum(1 for o in all_ops if o.k)
     useful_flops = sum(l.flops() for l in linears)
 
-    # One step on one stream: every decomposition of the step in one batched call (the single-workgroup
-    # factorizations of all operands then run side by side), the splits, then the GEMMs.
+    # One step: every decomposition in batched calls (the single-workgroup factorizations of the operands then run
+    # side by side), the splits, then the GEMMs.  The operands are independent of one another until the GEMMs, so
+    # their preparation is dealt over --prep-streams streams that the main stream joins before the first GEMM.
     split_ops = [o for o in all_ops if o.k]
     multi = n_split >= 2
 
@@ -202,20 +206,57 @@ def main():
                                           workspace=o.ws_dec, split=o.q if fused else None) for o in ops]) if ops else None
 
     batch_all = batch_of(split_ops)
-    batch_xg = batch_of([o for l in linears for o in (l.X, l.G) if o is not None and o.k])
+    xg_ops = [o for l in linears for o in (l.X, l.G) if o is not None and o.k]
+    batch_xg = batch_of(xg_ops)
+
+    # Optional: the operands' preparation spread over several streams (default priority), largest operands dealt
+    # round-robin; each stream runs its own batched decomposition and its splits, the main stream waits for all.
+    n_prep = max(1, min(args.prep_streams, len(split_ops))) if multi else 1
+    side = [torch.cuda.Stream() for _ in range(n_prep)] if n_prep > 1 else []
+    fork = torch.cuda.Event() if side else None
+    joins = [torch.cuda.Event() for _ in side]
+
+    def deal(ops):
+        groups = [[] for _ in range(n_prep)]
+        for i, o in enumerate(sorted(ops, key=lambda o: -o.M * o.N)):
+            groups[i % n_prep].append(o)
+        return groups
+
+    groups_all = [(g, batch_of(g)) for g in deal(split_ops)] if side else []
+    groups_xg = [(g, batch_of(g)) for g in deal(xg_ops)] if side else []
+
+    def prepare_ops(ops, lin_w, weights_from_parts):
+        for o in ops:
+            if not o.k:
+                o.prepare()
+            elif weights_from_parts and o in lin_w:
+                o.prepare_from_parts()
+            elif not fused:
+                o.split()
 
     def step(weights_from_parts=False):
-        b = batch_xg if weights_from_parts else batch_all
-        if b is not None:
-            b.run()
-        for l in linears:
-            for o in l.ops():
-                if not o.k:
-                    o.prepare()
-                elif weights_from_parts and o is l.W:
-                    o.prepare_from_parts()
-                elif not fused:
-                    o.split()
+        lin_w = [l.W for l in linears]
+        if side:
+            main_stream = torch.cuda.current_stream()
+            fork.record(main_stream)
+            groups = groups_xg if weights_from_parts else groups_all
+            for st, ev, (ops, b) in zip(side, joins, groups):
+                st.wait_event(fork)
+                with torch.cuda.stream(st):
+                    if b is not None:
+                        b.run()
+                    prepare_ops(ops, lin_w, False)
+                    ev.record(st)
+            # what is not decomposed in this step (plain operands, weights taken from their stored parts)
+            rest = [o for o in all_ops if not o.k or (weights_from_parts and o in lin_w)]
+            prepare_ops(rest, lin_w, weights_from_parts)
+            for ev in joins:
+                main_stream.wait_event(ev)
+        else:
+            b = batch_xg if weights_from_parts else batch_all
+            if b is not None:
+                b.run()
+            prepare_ops(all_ops, lin_w, weights_from_parts)
         for l in linears:
             l.gemms()
 
@@ -259,7 +300,10 @@ def main():
                 "frac_of_fp8_peak": round(gemm_tflops / 5000.0, 4), "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
                 "timing": "HIP events on the launch stream around every launch of the timed steps"}
 
-    passes = {"note": "inside the timed step; per-shape figures, warm and cold, under passes_standalone"}
+    passes = {"note": "inside the timed step; per-shape figures, warm and cold, under passes_standalone"
+                      + ("; the operands are prepared on %d streams at once here, so each launch shares the chip with the "
+                         "kernels of other operands and its elapsed time is not a rate of the kernel alone" % n_prep
+                         if n_prep > 1 else "")}
     if n_split:
         bd = timers["broadcast"].durations_ms(args.steps * n_split)
         rd = timers["residual_quant"].durations_ms(args.steps * n_split)
@@ -283,6 +327,7 @@ def main():
                    "linears": [{"name": l.name, "L": l.L, "K": l.K, "N": l.N} for l in linears],
                    "k": all_ops[0].k or linears[0].W.k, "p": linears[0].W.p, "gemms_per_step": n_gemm,
                    "decompositions_per_step": n_split, "useful_tflop_per_step": round(useful_flops / 1e12, 3),
+                   "prep_streams": n_prep,
                    "split_path": "fused decompose + split (one HBM pass over each operand, metis_decompose_batch)" if fused
                                  else "two calls per operand (metis_decompose_batch, then metis_split_quantize)",
                    "setup_s": round(setup_s, 1)},
