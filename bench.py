@@ -59,6 +59,9 @@ def parse():
     ap.add_argument("--prep-streams", type=int, default=3,
                     help="streams the operands' decompositions and splits are spread over (they are independent of one "
                          "another; the GEMMs always run on the main stream after a join)")
+    ap.add_argument("--no-phased-gemms", action="store_true",
+                    help="with several streams: keep each GEMM's pre-pass directly in front of its main kernel instead of "
+                         "running all pre-passes side by side first")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for HBM byte counters)")
     return ap.parse_args()
@@ -126,8 +129,10 @@ class Linear:
         self.name, self.W, self.X, self.G = name, W, X, G
         self.L, self.K, self.N = X.M, X.N, W.M
         kmax = max(W.k, X.k, G.k if G else 0)
-        self.ws = torch.empty((max(metis.linear_workspace_bytes(self.L, self.N, self.K, kmax), 256),),
-                              dtype=torch.uint8, device="cuda")
+        nbytes = max(metis.linear_workspace_bytes(self.L, self.N, self.K, kmax), 256)
+        # one workspace per product, so that the pre-passes of all products can run before the first main kernel
+        self.wss = [torch.empty((nbytes,), dtype=torch.uint8, device="cuda") for _ in range(3 if G else 1)]
+        self.ws = self.wss[0]
         self.Y = torch.empty((self.L, self.N), dtype=torch.bfloat16, device="cuda")
         self.dX = torch.empty((self.L, self.K), dtype=torch.bfloat16, device="cuda") if G else None
         self.dW = torch.empty((self.N, self.K), dtype=torch.bfloat16, device="cuda") if G else None
@@ -141,6 +146,15 @@ class Linear:
 
     def flops(self):
         return 2.0 * self.L * self.K * self.N * self.n_gemms()
+
+    def calls(self):
+        """(product, a, b, out, workspace) of this linear's GEMMs."""
+        m = self.metis
+        c = [(m.LINEAR_FWD, self.X.q, self.W.q, self.Y, self.wss[0])]
+        if self.G:
+            c.append((m.LINEAR_DGRAD, self.G.q, self.W.q, self.dX, self.wss[1]))
+            c.append((m.LINEAR_WGRAD, self.G.q, self.X.q, self.dW, self.wss[2]))
+        return c
 
     def gemms(self):
         m = self.metis
@@ -257,8 +271,25 @@ def main():
             if b is not None:
                 b.run()
             prepare_ops(all_ops, lin_w, weights_from_parts)
-        for l in linears:
-            l.gemms()
+        if side and not args.no_phased_gemms:
+            # the pre-passes of all products (small kernels) side by side on the streams, then the main kernels back
+            # to back on the main stream
+            main_stream = torch.cuda.current_stream()
+            calls = [c for l in linears for c in l.calls()]
+            fork.record(main_stream)
+            for i, (st, ev) in enumerate(zip(side, joins)):
+                st.wait_event(fork)
+                with torch.cuda.stream(st):
+                    for prod, a, b, out, ws in calls[i::n_prep]:
+                        metis.fp4_linear_phase(prod, metis.LINEAR_PREPARE, a, b, None, ws)
+                    ev.record(st)
+            for ev in joins:
+                main_stream.wait_event(ev)
+            for prod, a, b, out, ws in calls:
+                metis.fp4_linear_phase(prod, metis.LINEAR_APPLY, a, b, out, ws)
+        else:
+            for l in linears:
+                l.gemms()
 
     for _ in range(args.warmup):
         step()

@@ -309,6 +309,23 @@ int metis_fp4_linear_dgrad(void* stream, const metis_split* G, const metis_split
 int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const metis_split* X, metis_mat* dW,
                            void* workspace, size_t workspace_bytes);
 
+/*
+ * The same three products in two phases, for callers that want to run the pre-pass of several products side by
+ * side (it is a handful of small kernels: the skinny products with the factors and the assembly of the low-rank
+ * columns, Sec. 3.3's extra terms) and their main kernels back to back afterwards:
+ *   product  METIS_LINEAR_FWD (a = X, b = W), METIS_LINEAR_DGRAD (a = G, b = W), METIS_LINEAR_WGRAD (a = G, b = X)
+ *   phase    METIS_LINEAR_PREPARE writes only the workspace; METIS_LINEAR_APPLY reads what PREPARE of the same
+ *            product, operands and workspace left there and writes `out`; METIS_LINEAR_ALL = both, which is what
+ *            the three calls above do.  `out` may be null for PREPARE.
+ * Between PREPARE and APPLY the workspace must not be used by anything else (one workspace per product in flight).
+ * Same argument rules, workspace size and errors as the three calls above; METIS_INVALID_ARG for an unknown
+ * product or phase.  Asynchronous on `stream`.
+ */
+enum { METIS_LINEAR_FWD = 0, METIS_LINEAR_DGRAD = 1, METIS_LINEAR_WGRAD = 2 };
+enum { METIS_LINEAR_ALL = 0, METIS_LINEAR_PREPARE = 1, METIS_LINEAR_APPLY = 2 };
+int metis_fp4_linear_phase(void* stream, int product, int phase, const metis_split* a, const metis_split* b,
+                           metis_mat* out, void* workspace, size_t workspace_bytes);
+
 /* ---- gradients of the weight's low-rank factors (Sec. 3.2, backward formulas after Eq. 3) --- */
 
 /* Bytes of device workspace metis_fp4_factor_grads needs for W[N,K] split at rank k. */

@@ -977,13 +977,17 @@ LinWs lin_layout(int64_t Ma, int64_t Nb, int ka, int kb, int64_t Kc) {
 
 bool fp4_valid(const metis_fp4& f) { return f.codes && f.scales && f.rows > 0 && f.cols > 0 && f.cols % 16 == 0; }
 
+// phase: METIS_LINEAR_ALL, or only the pre-pass (PREPARE: fills the workspace) / only the main kernel (APPLY)
 int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* out, void* workspace,
-              size_t workspace_bytes) {
-    if (!out || !out->ptr) return METIS_INVALID_ARG;
+              size_t workspace_bytes, int phase = METIS_LINEAR_ALL) {
+    const bool do_pre = phase != METIS_LINEAR_APPLY, do_main = phase != METIS_LINEAR_PREPARE;
+    if (do_main && (!out || !out->ptr)) return METIS_INVALID_ARG;
     if (!fp4_valid(a.R) || !fp4_valid(b.R) || a.R.cols != b.R.cols) return METIS_BAD_SHAPE;
     const int64_t Ma = a.R.rows, Nb = b.R.rows, Kc = a.R.cols;
-    if (out->rows != Ma || out->cols != Nb || out->ld < Nb) return METIS_BAD_SHAPE;
-    if (out->dtype != METIS_BF16 && out->dtype != METIS_F32) return METIS_INVALID_ARG;
+    if (do_main) {
+        if (out->rows != Ma || out->cols != Nb || out->ld < Nb) return METIS_BAD_SHAPE;
+        if (out->dtype != METIS_BF16 && out->dtype != METIS_F32) return METIS_INVALID_ARG;
+    }
     const int ka = a.k, kb = b.k;
     if (ka < 0 || kb < 0 || ka > 128 || kb > 128) return METIS_UNSUPPORTED;
     if (ka > 0 && (!a.S || !fp4_valid(a.Ut) || !fp4_valid(a.Vt) || a.Ut.rows != ka || a.Ut.cols != Ma ||
@@ -1004,54 +1008,56 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
         float* E2 = (float*)(ws + w.off_e2);
         bf16_t* ae = (bf16_t*)(ws + w.off_aext);
         bf16_t* be = (bf16_t*)(ws + w.off_bext);
-        // the skinny products T1 = R_a V_b^T, E2 = R_b V_a^T and Mk = V_a V_b^T in one launch, cut along the contraction
-        // (Mk is a single output tile: alone, one workgroup would walk the whole contraction, ~100 us at 14336 columns)
-        SkinnyBatch sb;
-        sb.count = 0;
-        int wgs = 0;
-        const int64_t iters = ceil_div64(Kc, G_KI);
-        bool vec = Kc % G_KI == 0;
-        auto add = [&](const metis_fp4& X, const metis_fp4& Y, float* P, int parts) {
-            SkinnyProblem& q = sb.p[sb.count++];
-            q.A = {X.codes, X.scales, X.rows};
-            q.B = {Y.codes, Y.scales, Y.rows};
-            q.alpha = X.tscale * Y.tscale;
-            q.P = P;
-            q.tiles_n = (int)ceil_div64(Y.rows, 64);
-            q.tiles = (int)ceil_div64(X.rows, 128) * q.tiles_n;
-            q.ips = (int)ceil_div64(iters, parts);
-            q.first = wgs;
-            wgs += q.tiles * parts;
-            vec = vec && reinterpret_cast<uintptr_t>(X.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(Y.codes) % 16 == 0 &&
-                  reinterpret_cast<uintptr_t>(X.scales) % 8 == 0 && reinterpret_cast<uintptr_t>(Y.scales) % 8 == 0;
-        };
-        if (ceil_div64(Ma, 128) * 64 * w.s1 + ceil_div64(Nb, 128) * 64 * w.s2 > 0x3FFFFFFF) return METIS_UNSUPPORTED;
-        if (kb > 0) add(a.R, b.Vt, T1, w.s1);
-        if (ka > 0) add(b.R, a.Vt, E2, w.s2);
-        if (ka > 0 && kb > 0) add(a.Vt, b.Vt, Mk, w.s3);
-        for (int i = sb.count; i < 3; ++i) sb.p[i] = sb.p[0];
-        {
-            constexpr size_t lds = gemm_lds_bytes<128, 64>();
-            if (vec) {
-                static LdsLimitCache lds_set;
-                if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<true>, lds, lds_set)) return METIS_HIP_ERROR;
-                hipLaunchKernelGGL(k_fp4_skinny_batch<true>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
-            } else {
-                static LdsLimitCache lds_set;
-                if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<false>, lds, lds_set)) return METIS_HIP_ERROR;
-                hipLaunchKernelGGL(k_fp4_skinny_batch<false>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
+        if (do_pre) {
+            // the skinny products T1 = R_a V_b^T, E2 = R_b V_a^T and Mk = V_a V_b^T in one launch, cut along the contraction
+            // (Mk is a single output tile: alone, one workgroup would walk the whole contraction, ~100 us at 14336 columns)
+            SkinnyBatch sb;
+            sb.count = 0;
+            int wgs = 0;
+            const int64_t iters = ceil_div64(Kc, G_KI);
+            bool vec = Kc % G_KI == 0;
+            auto add = [&](const metis_fp4& X, const metis_fp4& Y, float* P, int parts) {
+                SkinnyProblem& q = sb.p[sb.count++];
+                q.A = {X.codes, X.scales, X.rows};
+                q.B = {Y.codes, Y.scales, Y.rows};
+                q.alpha = X.tscale * Y.tscale;
+                q.P = P;
+                q.tiles_n = (int)ceil_div64(Y.rows, 64);
+                q.tiles = (int)ceil_div64(X.rows, 128) * q.tiles_n;
+                q.ips = (int)ceil_div64(iters, parts);
+                q.first = wgs;
+                wgs += q.tiles * parts;
+                vec = vec && reinterpret_cast<uintptr_t>(X.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(Y.codes) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(X.scales) % 8 == 0 && reinterpret_cast<uintptr_t>(Y.scales) % 8 == 0;
+            };
+            if (ceil_div64(Ma, 128) * 64 * w.s1 + ceil_div64(Nb, 128) * 64 * w.s2 > 0x3FFFFFFF) return METIS_UNSUPPORTED;
+            if (kb > 0) add(a.R, b.Vt, T1, w.s1);
+            if (ka > 0) add(b.R, a.Vt, E2, w.s2);
+            if (ka > 0 && kb > 0) add(a.Vt, b.Vt, Mk, w.s3);
+            for (int i = sb.count; i < 3; ++i) sb.p[i] = sb.p[0];
+            {
+                constexpr size_t lds = gemm_lds_bytes<128, 64>();
+                if (vec) {
+                    static LdsLimitCache lds_set;
+                    if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<true>, lds, lds_set)) return METIS_HIP_ERROR;
+                    hipLaunchKernelGGL(k_fp4_skinny_batch<true>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
+                } else {
+                    static LdsLimitCache lds_set;
+                    if (!ensure_dyn_lds((const void*)k_fp4_skinny_batch<false>, lds, lds_set)) return METIS_HIP_ERROR;
+                    hipLaunchKernelGGL(k_fp4_skinny_batch<false>, dim3((unsigned)wgs), dim3(256), lds, s, sb, Kc);
+                }
+                METIS_LAUNCH_CHECK();
             }
+            const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
+            const size_t ax_lds = ((size_t)(AX_ROWS * ((ka > kb ? ka : kb) + 1) + 3) / 4 * 4 + (size_t)ka * kb + 8) * sizeof(float);
+            auto assemble = kb > 64 ? k_assemble_ext<2> : k_assemble_ext<1>;
+            static LdsLimitCache ax_set[2];
+            if (ax_lds > 48 * 1024 && !ensure_dyn_lds((const void*)assemble, ax_lds, ax_set[kb > 64])) return METIS_HIP_ERROR;
+            hipLaunchKernelGGL(assemble, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
+                               T1, w.s1, Mk, w.s3, E2, w.s2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
+                               b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);
             METIS_LAUNCH_CHECK();
         }
-        const int64_t nblk = ceil_div64(Ma, AX_ROWS) + ceil_div64(Nb, AX_ROWS);
-        const size_t ax_lds = ((size_t)(AX_ROWS * ((ka > kb ? ka : kb) + 1) + 3) / 4 * 4 + (size_t)ka * kb + 8) * sizeof(float);
-        auto assemble = kb > 64 ? k_assemble_ext<2> : k_assemble_ext<1>;
-        static LdsLimitCache ax_set[2];
-        if (ax_lds > 48 * 1024 && !ensure_dyn_lds((const void*)assemble, ax_lds, ax_set[kb > 64])) return METIS_HIP_ERROR;
-        hipLaunchKernelGGL(assemble, dim3((unsigned)nblk), dim3(256), ax_lds, s, Ma, Nb, ka, kb, w.Kep,
-                           T1, w.s1, Mk, w.s3, E2, w.s2, a.Ut.codes, a.Ut.scales, ka > 0 ? a.Ut.tscale : 1.0f, a.S, b.Ut.codes,
-                           b.Ut.scales, kb > 0 ? b.Ut.tscale : 1.0f, b.S, 1.0f / grr, ae, be);
-        METIS_LAUNCH_CHECK();
         Ke = w.Kep;
         Aext = ae;
         Bext = be;
@@ -1066,6 +1072,7 @@ int linear_nt(hipStream_t s, const NtOperand& a, const NtOperand& b, metis_mat* 
             partial_bytes = w.tail_bytes;
         }
     }
+    if (!do_main) return METIS_OK;
     const int pi = metis_prof_begin(METIS_PROF_GEMM, s);
     if (out->dtype == METIS_BF16)
         st = launch_gemm<bf16_t>(s, a.R, b.R, Aext, Bext, Ke, grr, (bf16_t*)out->ptr, out->ld, partial, partial_bytes);
@@ -1111,4 +1118,22 @@ extern "C" int metis_fp4_linear_wgrad(void* stream, const metis_split* G, const 
     if (!G || !X) return METIS_INVALID_ARG;
     return linear_nt((hipStream_t)stream, nt(G->Rt, G->Vt, G->Ut, G->S, G->k), nt(X->Rt, X->Vt, X->Ut, X->S, X->k), dW,
                      workspace, workspace_bytes);
+}
+
+extern "C" int metis_fp4_linear_phase(void* stream, int product, int phase, const metis_split* a, const metis_split* b,
+                                      metis_mat* out, void* workspace, size_t workspace_bytes) {
+    if (!a || !b || phase < METIS_LINEAR_ALL || phase > METIS_LINEAR_APPLY) return METIS_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    switch (product) {
+        case METIS_LINEAR_FWD:        // a = X, b = W
+            return linear_nt(s, nt(a->R, a->Ut, a->Vt, a->S, a->k), nt(b->R, b->Ut, b->Vt, b->S, b->k), out, workspace,
+                             workspace_bytes, phase);
+        case METIS_LINEAR_DGRAD:      // a = G, b = W
+            return linear_nt(s, nt(a->R, a->Ut, a->Vt, a->S, a->k), nt(b->Rt, b->Vt, b->Ut, b->S, b->k), out, workspace,
+                             workspace_bytes, phase);
+        case METIS_LINEAR_WGRAD:      // a = G, b = X
+            return linear_nt(s, nt(a->Rt, a->Vt, a->Ut, a->S, a->k), nt(b->Rt, b->Vt, b->Ut, b->S, b->k), out, workspace,
+                             workspace_bytes, phase);
+        default: return METIS_INVALID_ARG;
+    }
 }

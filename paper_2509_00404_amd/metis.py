@@ -90,6 +90,8 @@ _SIGNATURES = {
                                          C.c_void_p, C.c_size_t]),
     "metis_fp4_linear_wgrad": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                          C.c_void_p, C.c_size_t]),
+    "metis_fp4_linear_phase": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
+                                        C.c_void_p, C.c_size_t]),
     "metis_quantize_mx": (C.c_int, [C.c_void_p, C.POINTER(Mat), C.POINTER(MxFp4)]),
     "metis_mxfp4_gemm_nt": (C.c_int, [C.c_void_p, C.POINTER(MxFp4), C.POINTER(MxFp4), C.POINTER(Mat)]),
     "metis_factor_grads_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
@@ -374,6 +376,20 @@ def _linear(fn, a, b, out, workspace):
     _check(fn(_stream(), C.byref(sa), C.byref(sb), C.byref(o),
               workspace.data_ptr() if workspace is not None else None,
               workspace.numel() if workspace is not None else 0))
+    return out
+
+
+LINEAR_FWD, LINEAR_DGRAD, LINEAR_WGRAD = 0, 1, 2
+LINEAR_ALL, LINEAR_PREPARE, LINEAR_APPLY = 0, 1, 2
+
+
+def fp4_linear_phase(product, phase, a, b, out, workspace):
+    """One of the three products, whole or one of its two phases (see metis_fp4_linear_phase)."""
+    sa, sb = a.c(), b.c()
+    o = _mat(out) if out is not None else None
+    _check(lib().metis_fp4_linear_phase(_stream(), product, phase, C.byref(sa), C.byref(sb), C.byref(o) if o is not None else None,
+                                        workspace.data_ptr() if workspace is not None else None,
+                                        workspace.numel() if workspace is not None else 0))
     return out
 
 

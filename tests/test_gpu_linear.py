@@ -115,3 +115,43 @@ def test_workspace_and_shape_errors(metis):
                              torch.empty((1 << 20,), dtype=torch.uint8, device="cuda"))
     with pytest.raises(metis.MetisError):
         metis.fp4_linear_dgrad(xs, ws, Y, torch.empty((1 << 20,), dtype=torch.uint8, device="cuda"))
+
+
+def test_two_phase_form_matches_the_single_calls(metis):
+    """metis_fp4_linear_phase: PREPARE of all three products first (own workspaces), then APPLY, gives bit for bit
+    what the three single calls give; ALL is the single call; bad product / phase are refused."""
+    from paper_2509_00404_amd import workloads
+    L, N, K, k = 1152, 1280, 1024, 16
+    X = workloads.planted(L, K, workloads.power_law(min(L, K, 256), 1.2), 4, rms=1.0, outlier_cols=1)
+    W = workloads.planted(N, K, workloads.power_law(min(N, K, 256), 1.0), 5, noise_top=0.01, rms=0.02)
+    G = workloads.planted(L, N, workloads.power_law(min(L, N, 256), 2.0, head=4, head_gain=100.0), 6, rms=1e-3)
+    xs = make_split(metis, X, k, 8, 0.25, 11)[0]
+    ws = make_split(metis, W, k, 8, 1.0, 12)[0]
+    gs = make_split(metis, G, k, 8, 0.25, 13)[0]
+    nbytes = metis.linear_workspace_bytes(L, N, K, k)
+    spaces = [torch.empty((nbytes,), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    shapes = ((L, N), (L, K), (N, K))
+    products = ((metis.LINEAR_FWD, xs, ws), (metis.LINEAR_DGRAD, gs, ws), (metis.LINEAR_WGRAD, gs, xs))
+    single = [torch.empty(s, dtype=torch.bfloat16, device="cuda") for s in shapes]
+    metis.fp4_linear_fwd(xs, ws, single[0], spaces[0])
+    metis.fp4_linear_dgrad(gs, ws, single[1], spaces[0])
+    metis.fp4_linear_wgrad(gs, xs, single[2], spaces[0])
+    for sp in spaces:
+        sp.fill_(0xA5)                                   # APPLY must find everything it needs written by PREPARE
+    phased = [torch.full(s, float("nan"), dtype=torch.bfloat16, device="cuda") for s in shapes]
+    for (prod, a, b), sp in zip(products, spaces):
+        metis.fp4_linear_phase(prod, metis.LINEAR_PREPARE, a, b, None, sp)
+    for (prod, a, b), sp, out in zip(products, spaces, phased):
+        metis.fp4_linear_phase(prod, metis.LINEAR_APPLY, a, b, out, sp)
+    whole = [torch.empty(s, dtype=torch.bfloat16, device="cuda") for s in shapes]
+    for (prod, a, b), out in zip(products, whole):
+        metis.fp4_linear_phase(prod, metis.LINEAR_ALL, a, b, out, spaces[0])
+    torch.cuda.synchronize()
+    for a, b, c in zip(single, phased, whole):
+        assert torch.equal(a, b) and torch.equal(a, c)
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_phase(7, metis.LINEAR_ALL, xs, ws, whole[0], spaces[0])
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_phase(metis.LINEAR_FWD, 5, xs, ws, whole[0], spaces[0])
+    with pytest.raises(metis.MetisError):
+        metis.fp4_linear_phase(metis.LINEAR_FWD, metis.LINEAR_APPLY, xs, ws, None, spaces[0])
