@@ -29,7 +29,7 @@ typedef enum {
     METIS_BAD_SHAPE = -2,        /* quantized axis not a multiple of 16, k+p too large, mismatched operands */
     METIS_WORKSPACE_TOO_SMALL = -3,
     METIS_HIP_ERROR = -4,        /* a launch failed; hipGetLastError() has the reason */
-    METIS_UNSUPPORTED = -5,      /* size outside what the kernels are built for (e.g. k+p > 128) */
+    METIS_UNSUPPORTED = -5,      /* size outside what the kernels are built for (e.g. k+p > 96) */
     METIS_SCRATCH_TOO_SMALL = -6 /* the input needs more than the library's built-in scratch array holds */
 } metis_status;
 
@@ -139,7 +139,9 @@ size_t metis_decompose_workspace_bytes(int64_t M, int64_t N, int k, int p, doubl
  * omega is [N, k+p] bf16); pass NULL/0 to draw from `seed`.
  * `info` (device int32[1], optional): set non-zero if a Cholesky pivot was not positive
  * (rank-deficient sketch); the outputs are then unspecified.
- * Errors: INVALID_ARG, BAD_SHAPE (k+p > min(l_k, N)), UNSUPPORTED (k+p > 128, dtype not
+ * The result is a function of the arguments alone: split contractions write partial products that are added in a
+ * fixed order (no floating-point atomics), so two calls give the same bits.
+ * Errors: INVALID_ARG, BAD_SHAPE (k+p > min(l_k, N)), UNSUPPORTED (k+p > 96, dtype not
  * bf16), WORKSPACE_TOO_SMALL.
  */
 int metis_decompose(void* stream, const metis_mat* A, int k, int oversample, double sample_rate,
