@@ -434,6 +434,16 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
         "what": "512 MiB streaming copy and read (beyond the 256 MB last-level cache), register-resident 32x32x16 fp16 "
                 "matrix-instruction loop on all CUs (2 waves per SIMD, ~%.0f ms)" % tm["median_ms"]}
 
+    # the GEMM's instruction mix without its memory system: matrix instructions with N packed multiplies each
+    mix = {}
+    for wps in (1, 2):
+        for nv in (0, 4, 5, 6, 8):
+            flm = metis.ceiling_mfma_mix(1000, nv, wps, sink)
+            tmix = timed(torch, lambda: metis.ceiling_mfma_mix(1000, nv, wps, sink))
+            mix["%d wave%s per SIMD, %d multiplies per matrix instruction" % (wps, "s" if wps > 1 else "", nv)] = round(
+                flm / (tmix["median_ms"] * 1e-3) / 1e12, 1)
+    out["ceilings"]["mfma_fp16_with_vector_work_TFLOP/s"] = mix
+
     def sweep():                                   # evicts the last-level cache: 1 GiB of other traffic
         metis.ceiling_copy(buf_a, buf_b)
 

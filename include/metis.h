@@ -405,8 +405,15 @@ int metis_profile_events(int kernel_id, void** start, void** stop, int n);
  *   metis_ceiling_mfma   512 workgroups x 4 waves issue iters x 8 independent 32x32x16 fp16 matrix instructions
  *                        from registers; *flops_out (host, optional) = floating-point operations of the launch;
  *                        sink: device float[512 * 256], normally left untouched.
+ *   metis_ceiling_mfma_mix  the FP4 GEMM's instruction mix without its memory system: one workgroup of four
+ *                        waves per CU and per `waves_per_simd` (1 or 2), every wave issuing iters x 4 matrix
+ *                        instructions (accumulators in the accumulation registers), each followed by
+ *                        `valu_per_mfma` (0, 2, 4, 5, 6 or 8) independent packed fp16 multiplies on registers; shows
+ *                        what the chip sustains when a wave has to issue that much vector work per matrix
+ *                        instruction.  *flops_out as above; sink as above.
  * Errors: METIS_INVALID_ARG.
  */
+int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma, int waves_per_simd, float* sink, double* flops_out);
 int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes);
 int metis_ceiling_read(void* stream, const void* src, size_t bytes, uint32_t* sink);
 int metis_ceiling_mfma(void* stream, int iters, float* sink, double* flops_out);

@@ -56,7 +56,90 @@ __global__ void __launch_bounds__(256) k_ceiling_mfma(int iters, float* __restri
     if (s == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The FP4 GEMM's instruction mix without its memory system: every wave issues `iters` rounds of four independent
+// 32x32x16 fp16 matrix instructions (accumulators in the accumulation registers), each followed by NV independent
+// packed fp16 multiplies on registers -- the expansion work of the GEMM is NV ~ 4.5 per matrix instruction.
+template <int NV>
+__global__ void __launch_bounds__(256) k_ceiling_mfma_mix(int iters, float* __restrict__ sink) {
+    half8_t a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = (_Float16)(0.001f * (float)(threadIdx.x & 7) + (float)i); b[i] = (_Float16)(0.5f * (float)i); }
+    float16_t c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = 0.0f; c1[i] = 1.0f; c2[i] = 2.0f; c3[i] = 3.0f; }
+    uint32_t r0 = threadIdx.x, r1 = r0 * 3u, r2 = r0 * 5u, r3 = r0 * 7u, r4 = r0 * 11u, r5 = r0 * 13u, r6 = r0 * 17u, r7 = r0 * 19u;
+    uint32_t d0 = 0, d1 = 0, d2 = 0, d3 = 0, d4 = 0, d5 = 0, d6 = 0, d7 = 0;
+#define MIX_MFMA(C) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(C) : "v"(a), "v"(b));
+#define MIX_MUL(D, S) asm volatile("v_pk_mul_f16 %0, %1, %1" : "=v"(D) : "v"(S));
+    for (int it = 0; it < iters; ++it) {
+        MIX_MFMA(c0)
+        if (NV >= 1) MIX_MUL(d0, r0)
+        if (NV >= 2) MIX_MUL(d1, r1)
+        if (NV >= 3) MIX_MUL(d2, r2)
+        if (NV >= 4) MIX_MUL(d3, r3)
+        if (NV >= 5) MIX_MUL(d4, r4)
+        if (NV >= 6) MIX_MUL(d5, r5)
+        if (NV >= 7) MIX_MUL(d6, r6)
+        if (NV >= 8) MIX_MUL(d7, r7)
+        MIX_MFMA(c1)
+        if (NV >= 1) MIX_MUL(d0, r1)
+        if (NV >= 2) MIX_MUL(d1, r2)
+        if (NV >= 3) MIX_MUL(d2, r3)
+        if (NV >= 4) MIX_MUL(d3, r4)
+        if (NV >= 5) MIX_MUL(d4, r5)
+        if (NV >= 6) MIX_MUL(d5, r6)
+        if (NV >= 7) MIX_MUL(d6, r7)
+        if (NV >= 8) MIX_MUL(d7, r0)
+        MIX_MFMA(c2)
+        if (NV >= 1) MIX_MUL(d0, r2)
+        if (NV >= 2) MIX_MUL(d1, r3)
+        if (NV >= 3) MIX_MUL(d2, r4)
+        if (NV >= 4) MIX_MUL(d3, r5)
+        if (NV >= 5) MIX_MUL(d4, r6)
+        if (NV >= 6) MIX_MUL(d5, r7)
+        if (NV >= 7) MIX_MUL(d6, r0)
+        if (NV >= 8) MIX_MUL(d7, r1)
+        MIX_MFMA(c3)
+        if (NV >= 1) MIX_MUL(d0, r3)
+        if (NV >= 2) MIX_MUL(d1, r4)
+        if (NV >= 3) MIX_MUL(d2, r5)
+        if (NV >= 4) MIX_MUL(d3, r6)
+        if (NV >= 5) MIX_MUL(d4, r7)
+        if (NV >= 6) MIX_MUL(d5, r0)
+        if (NV >= 7) MIX_MUL(d6, r1)
+        if (NV >= 8) MIX_MUL(d7, r2)
+    }
+#undef MIX_MFMA
+#undef MIX_MUL
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s == 12345.678f || (d0 ^ d1 ^ d2 ^ d3 ^ d4 ^ d5 ^ d6 ^ d7) == 0x9E3779B9u) sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
+
+extern "C" int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma, int waves_per_simd, float* sink,
+                                      double* flops_out) {
+    if (iters < 1 || !sink || waves_per_simd < 1 || waves_per_simd > 2) return METIS_INVALID_ARG;
+    const int cus = device_cu_count();
+    if (cus < 1) return METIS_HIP_ERROR;
+    if (cus * waves_per_simd > 512) return METIS_UNSUPPORTED;          // the sink holds 512 workgroups
+    const dim3 grid((unsigned)(cus * waves_per_simd));                 // workgroups of four waves, one wave per SIMD each
+    hipStream_t s = (hipStream_t)stream;
+    switch (valu_per_mfma) {
+        case 0: hipLaunchKernelGGL(k_ceiling_mfma_mix<0>, grid, dim3(256), 0, s, iters, sink); break;
+        case 2: hipLaunchKernelGGL(k_ceiling_mfma_mix<2>, grid, dim3(256), 0, s, iters, sink); break;
+        case 4: hipLaunchKernelGGL(k_ceiling_mfma_mix<4>, grid, dim3(256), 0, s, iters, sink); break;
+        case 5: hipLaunchKernelGGL(k_ceiling_mfma_mix<5>, grid, dim3(256), 0, s, iters, sink); break;
+        case 6: hipLaunchKernelGGL(k_ceiling_mfma_mix<6>, grid, dim3(256), 0, s, iters, sink); break;
+        case 8: hipLaunchKernelGGL(k_ceiling_mfma_mix<8>, grid, dim3(256), 0, s, iters, sink); break;
+        default: return METIS_INVALID_ARG;
+    }
+    METIS_LAUNCH_CHECK();
+    if (flops_out) *flops_out = (double)grid.x * 4.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return METIS_OK;
+}
 
 extern "C" int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes) {
     if (!src || !dst || bytes < 16 || bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 ||

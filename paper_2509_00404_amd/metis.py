@@ -83,6 +83,7 @@ _SIGNATURES = {
     "metis_ceiling_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
     "metis_ceiling_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "metis_ceiling_mfma": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_double)]),
+    "metis_ceiling_mfma_mix": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double)]),
     "metis_linear_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int]),
     "metis_fp4_linear_fwd": (C.c_int, [C.c_void_p, C.POINTER(Split), C.POINTER(Split), C.POINTER(Mat),
                                        C.c_void_p, C.c_size_t]),
@@ -433,6 +434,13 @@ def ceiling_mfma(iters, sink):
     """Launches the register-resident fp16 matrix-instruction loop; returns the launch's flop count."""
     fl = C.c_double()
     _check(lib().metis_ceiling_mfma(_stream(), iters, sink.data_ptr(), C.byref(fl)))
+    return fl.value
+
+
+def ceiling_mfma_mix(iters, valu_per_mfma, waves_per_simd, sink):
+    """Matrix instructions interleaved with vector instructions (see metis_ceiling_mfma_mix); returns the flop count."""
+    fl = C.c_double()
+    _check(lib().metis_ceiling_mfma_mix(_stream(), iters, valu_per_mfma, waves_per_simd, sink.data_ptr(), C.byref(fl)))
     return fl.value
 
 
