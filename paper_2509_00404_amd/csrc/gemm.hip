@@ -332,7 +332,7 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     constexpr int TM = 4, TN = 4, BM = 256, BN = 256, NT = 256, KS = G_KI / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // LDS layout of a stage, chosen so that ONE 16-byte read per lane fetches the raw words of all four row
-    // tiles of a wave (the wave issues an instruction only every ~9 clocks, so instructions, not bytes, count):
+    // tiles of a wave (a lone wave per SIMD is bound by the number of instructions it issues, so instructions, not bytes, count):
     // codes of an operand: planes (g = row / 128, step s, half) of 32 lanes x 4 tiles dwords,
     //   dword (g, s, half, l, i) = the 8 codes of row 128 g + 32 i + l at contraction 16 s + 8 half;
     // scales: planes (g, pair q of steps) of 32 x 4 dwords, dword (g, q, l, i) = the fp16 scales of blocks 2q, 2q+1.
