@@ -248,9 +248,10 @@ def main():
             elif not fused:
                 o.split()
 
-    def step(weights_from_parts=False):
+    def step(weights_from_parts=False, streams=True):
         lin_w = [l.W for l in linears]
-        if side:
+        use_side = side if streams else []
+        if use_side:
             main_stream = torch.cuda.current_stream()
             fork.record(main_stream)
             groups = groups_xg if weights_from_parts else groups_all
@@ -271,7 +272,7 @@ def main():
             if b is not None:
                 b.run()
             prepare_ops(all_ops, lin_w, weights_from_parts)
-        if side and not args.no_phased_gemms:
+        if use_side and not args.no_phased_gemms:
             # the pre-passes of all products (small kernels) side by side on the streams, then the main kernels back
             # to back on the main stream
             main_stream = torch.cuda.current_stream()
@@ -331,21 +332,40 @@ def main():
                 "frac_of_fp8_peak": round(gemm_tflops / 5000.0, 4), "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
                 "timing": "HIP events on the launch stream around every launch of the timed steps"}
 
-    passes = {"note": "inside the timed step; per-shape figures, warm and cold, under passes_standalone"
-                      + ("; the operands are prepared on %d streams at once here, so each launch shares the chip with the "
-                         "kernels of other operands and its elapsed time is not a rate of the kernel alone" % n_prep
-                         if n_prep > 1 else "")}
+    pass_steps = args.steps
+    if n_prep > 1 and n_split:
+        # with several preparation streams a launch shares the chip with the kernels of other operands, so its elapsed
+        # time is not a rate of the kernel alone: the passes are timed on the same step replayed on one stream
+        for name in ("broadcast", "residual_quant", "quantize"):
+            timers[name].close()
+        pass_steps = 3
+        timers["broadcast"] = metis.KernelTimer(metis.PROF_BROADCAST, pass_steps * n_split)
+        timers["residual_quant"] = metis.KernelTimer(metis.PROF_RESIDUAL_QUANT, pass_steps * n_split)
+        timers["quantize"] = metis.KernelTimer(metis.PROF_QUANTIZE, max(1, pass_steps * 4))
+        step(streams=False)
+        torch.cuda.synchronize()
+        for name in ("broadcast", "residual_quant", "quantize"):
+            timers[name].__enter__()
+        for _ in range(pass_steps):
+            step(streams=False)
+        torch.cuda.synchronize()
+        for name in ("broadcast", "residual_quant", "quantize"):
+            timers[name].__exit__()
+    passes = {"note": ("the step replayed on one stream after the timed region (in the timed step the operands are prepared "
+                       "on %d streams at once and a launch shares the chip with kernels of other operands)" % n_prep
+                       if n_prep > 1 else "inside the timed step")
+                      + "; per-shape figures, warm and cold, under passes_standalone"}
     if n_split:
-        bd = timers["broadcast"].durations_ms(args.steps * n_split)
-        rd = timers["residual_quant"].durations_ms(args.steps * n_split)
-        bc_bytes = sum(2.0 * o.M * o.N for o in all_ops if o.k) * args.steps
-        rq_bytes = sum(o.min_bytes() for o in all_ops if o.k) * args.steps
+        bd = timers["broadcast"].durations_ms(pass_steps * n_split)
+        rd = timers["residual_quant"].durations_ms(pass_steps * n_split)
+        bc_bytes = sum(2.0 * o.M * o.N for o in all_ops if o.k) * pass_steps
+        rq_bytes = sum(o.min_bytes() for o in all_ops if o.k) * pass_steps
         passes["broadcast"] = rate(bc_bytes, sum(bd))
         passes["residual_quant"] = rate(rq_bytes, sum(rd))
     plain = [o for o in all_ops if not o.k]
     if plain:
-        qd = timers["quantize"].durations_ms(args.steps * len(plain))
-        passes["quantize"] = rate(sum(2.5625 * o.M * o.N for o in plain) * args.steps, sum(qd))
+        qd = timers["quantize"].durations_ms(pass_steps * len(plain))
+        passes["quantize"] = rate(sum(2.5625 * o.M * o.N for o in plain) * pass_steps, sum(qd))
     for t in timers.values():
         t.close()
 
