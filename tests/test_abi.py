@@ -61,3 +61,15 @@ def test_tensor_scale_helper_is_the_smallest_covering_power_of_two():
         m, e = np.frexp(g)
         assert m == 0.5                                            # a power of two
         assert 2688.0 * g >= float(a) and 2688.0 * (g / 2) < float(a)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is the whole target: `bench.py --gpus N` with N > 1 exits with a message before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
