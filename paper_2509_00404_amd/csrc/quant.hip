@@ -1,5 +1,6 @@
 // Plain NVFP4 quantization of a dense matrix (Sec. 2.3), row orientation and/or transposed.
 #include "quant_dev.h"
+#include "splitq.h"
 
 // ---- row orientation, bf16 input: one lane per block of 16, 32 contiguous bytes per lane ----
 #define SR_STREAM 3u          // Philox stream of the stochastic-rounding draws, row orientation
@@ -53,12 +54,12 @@ template <> __device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p
 template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
 
 template <typename T, bool SR>
-__global__ void __launch_bounds__(256)
-k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, QuantParams qp, QuantParams qpt,
-                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t, uint64_t seed) {
+__device__ __forceinline__ void
+quantize_tile_body(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, QuantParams qp, QuantParams qpt,
+                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                   uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t, uint64_t seed, int64_t bx, int64_t by) {
     __shared__ float tile[64][65];
-    const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+    const int64_t m0 = by * 64, n0 = bx * 64;
     const int tid = threadIdx.x;
     for (int i = tid; i < 64 * 64; i += 256) {
         int r = i >> 6, c = i & 63;
@@ -95,6 +96,31 @@ k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, Quant
             scales_t[n * (M / 16) + m / 16] = (uint8_t)sc;
         }
     }
+}
+
+template <typename T, bool SR>
+__global__ void __launch_bounds__(256)
+k_quantize_tile(const T* __restrict__ A, int64_t ld, int64_t M, int64_t N, QuantParams qp, QuantParams qpt,
+                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                uint8_t* __restrict__ codes_t, uint8_t* __restrict__ scales_t, uint64_t seed) {
+    quantize_tile_body<T, SR>(A, ld, M, N, qp, qpt, codes, scales, codes_t, scales_t, seed, blockIdx.x, blockIdx.y);
+}
+
+// The transposed quantization of the two fp32 factors of a split, U [M, k] -> Q(U^T) [k, M] and V [N, k] -> Q(V^T)
+// [k, N], and the copy of S, in one launch (three tiny launches otherwise): blocks [0, tiles of U) take U, the rest V.
+template <bool SR>
+__global__ void __launch_bounds__(256)
+k_quantize_factors_t(const float* __restrict__ U, int64_t M, const float* __restrict__ V, int64_t N, int k, QuantParams qu,
+                     QuantParams qv, uint8_t* __restrict__ ut_codes, uint8_t* __restrict__ ut_scales,
+                     uint8_t* __restrict__ vt_codes, uint8_t* __restrict__ vt_scales, uint64_t seed_u, uint64_t seed_v,
+                     const float* __restrict__ S_src, float* __restrict__ S_dst) {
+    const int64_t gx = (k + 63) / 64, tiles_u = gx * ((M + 63) / 64);
+    const int64_t b = blockIdx.x;
+    if (b == 0 && S_src && (int)threadIdx.x < k) S_dst[threadIdx.x] = S_src[threadIdx.x];
+    const bool u = b < tiles_u;
+    const int64_t t = u ? b : b - tiles_u;
+    quantize_tile_body<float, SR>(u ? U : V, k, u ? M : N, k, u ? qu : qv, u ? qu : qv, nullptr, nullptr, u ? ut_codes : vt_codes,
+                                  u ? ut_scales : vt_scales, u ? seed_u : seed_v, t % gx, t / gx);
 }
 
 static bool pow2(float g) {
@@ -176,6 +202,23 @@ extern "C" int metis_quantize_rht_sr(void* stream, const metis_mat* A, uint64_t 
                        (const bf16_t*)A->ptr, A->ld, M, N / 16, make_quant_params(out->tscale), out->codes, out->scales,
                        seed, signs);
     metis_prof_end(METIS_PROF_QUANTIZE, pi, s);
+    METIS_LAUNCH_CHECK();
+    return METIS_OK;
+}
+
+// Q(U^T), Q(V^T) and S of a split in one launch (see k_quantize_factors_t); M % 16 == 0, N % 16 == 0, S_src null for no copy
+int launch_quantize_factors_t(hipStream_t s, const float* U, int64_t M, const float* V, int64_t N, int k, const metis_fp4& Ut,
+                              const metis_fp4& Vt, bool sr, uint64_t seed_u, uint64_t seed_v, const float* S_src, float* S_dst) {
+    if (!pow2(Ut.tscale) || !pow2(Vt.tscale) || k < 1 || k > 256) return METIS_INVALID_ARG;
+    const int64_t gx = (k + 63) / 64, blocks = gx * (ceil_div64(M, 64) + ceil_div64(N, 64));
+    if (blocks > 0x7FFFFFFF) return METIS_UNSUPPORTED;
+    const QuantParams qu = make_quant_params(Ut.tscale), qv = make_quant_params(Vt.tscale);
+    if (sr)
+        hipLaunchKernelGGL(k_quantize_factors_t<true>, dim3((unsigned)blocks), dim3(256), 0, s, U, M, V, N, k, qu, qv, Ut.codes,
+                           Ut.scales, Vt.codes, Vt.scales, seed_u, seed_v, S_src, S_dst);
+    else
+        hipLaunchKernelGGL(k_quantize_factors_t<false>, dim3((unsigned)blocks), dim3(256), 0, s, U, M, V, N, k, qu, qv, Ut.codes,
+                           Ut.scales, Vt.codes, Vt.scales, seed_u, seed_v, S_src, S_dst);
     METIS_LAUNCH_CHECK();
     return METIS_OK;
 }

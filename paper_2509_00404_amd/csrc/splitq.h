@@ -24,3 +24,8 @@ int launch_residual_quant(hipStream_t s, const bf16_t* A, int64_t lda, int64_t M
 // Q(U^T) and Q(V^T) into out->Ut / out->Vt, S copied to out->S
 int quantize_factors(hipStream_t s, const float* U, const float* S, const float* V, int64_t M, int64_t N, int k,
                      metis_split* out, bool sr, uint64_t seed);
+
+// quant.hip: the two transposed factor quantizations (and the copy of S when S_src is not null) in one launch.
+// U [M, k] and V [N, k] fp32 contiguous; Ut [k, M] and Vt [k, N] with M % 16 == 0 and N % 16 == 0
+int launch_quantize_factors_t(hipStream_t s, const float* U, int64_t M, const float* V, int64_t N, int k, const metis_fp4& Ut,
+                              const metis_fp4& Vt, bool sr, uint64_t seed_u, uint64_t seed_v, const float* S_src, float* S_dst);

@@ -378,11 +378,6 @@ bool fp4_ok(const metis_fp4& f, int64_t rows, int64_t cols) {
 }  // namespace
 
 namespace {
-__global__ void k_copy_f32(const float* __restrict__ src, float* __restrict__ dst, int n) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = src[i];
-}
-
 // C = sum of the partial products (fp64 sum in part order, rounded once: the same sum the Gram kernel takes of
 // separate parts), -C as bf16 hi / lo with the rank padded to kp
 __global__ void __launch_bounds__(256)
@@ -480,22 +475,10 @@ extern "C" int metis_quantize(void* stream, const metis_mat* A, metis_fp4* out, 
 
 int quantize_factors(hipStream_t s, const float* U, const float* S, const float* V, int64_t M, int64_t N, int k,
                      metis_split* out, bool sr, uint64_t seed) {
-    // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis
-    metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
-    int st;
-    if (sr) {
-        // the factors draw under their own keys so that no two tensors share draws
-        if ((st = metis_quantize_sr((void*)s, &um, seed + 1, nullptr, &out->Ut)) != METIS_OK) return st;
-        if ((st = metis_quantize_sr((void*)s, &vm, seed + 2, nullptr, &out->Vt)) != METIS_OK) return st;
-    } else {
-        if ((st = metis_quantize((void*)s, &um, nullptr, &out->Ut)) != METIS_OK) return st;
-        if ((st = metis_quantize((void*)s, &vm, nullptr, &out->Vt)) != METIS_OK) return st;
-    }
-    if (S && out->S != S) {
-        hipLaunchKernelGGL(k_copy_f32, dim3(1), dim3(128), 0, s, S, out->S, k);
-        METIS_LAUNCH_CHECK();
-    }
-    return METIS_OK;
+    // factors: Q(U^T) [k,M], Q(V^T) [k,N], blocks along the long axis; with stochastic rounding the two draw under
+    // their own keys so that no two tensors share draws
+    return launch_quantize_factors_t(s, U, M, V, N, k, out->Ut, out->Vt, sr, seed + 1, seed + 2,
+                                     S && out->S != S ? S : nullptr, out->S);
 }
 
 template <bool SR>
@@ -585,19 +568,10 @@ static int split_from_parts_impl(void* stream, const metis_mat* W_R, const float
     if (!fp4_ok(out->R, M, N)) return METIS_BAD_SHAPE;
     if (want_t && (!fp4_ok(out->Rt, N, M) || out->Rt.tscale != out->R.tscale)) return METIS_BAD_SHAPE;
     if (!fp4_ok(out->Ut, k, M) || !fp4_ok(out->Vt, k, N)) return METIS_BAD_SHAPE;
-    metis_mat um = {(void*)U, M, k, k, METIS_F32}, vm = {(void*)V, N, k, k, METIS_F32};
     metis_fp4* rt = want_t ? &out->Rt : nullptr;
     int st = SR ? metis_quantize_sr(stream, W_R, seed, &out->R, rt) : metis_quantize(stream, W_R, &out->R, rt);
     if (st != METIS_OK) return st;
-    st = SR ? metis_quantize_sr(stream, &um, seed + 1, nullptr, &out->Ut) : metis_quantize(stream, &um, nullptr, &out->Ut);
-    if (st != METIS_OK) return st;
-    st = SR ? metis_quantize_sr(stream, &vm, seed + 2, nullptr, &out->Vt) : metis_quantize(stream, &vm, nullptr, &out->Vt);
-    if (st != METIS_OK) return st;
-    if (out->S != S) {
-        hipLaunchKernelGGL(k_copy_f32, dim3(1), dim3(128), 0, (hipStream_t)stream, S, out->S, k);
-        METIS_LAUNCH_CHECK();
-    }
-    return METIS_OK;
+    return quantize_factors((hipStream_t)stream, U, S, V, M, N, k, out, SR, seed);
 }
 
 extern "C" int metis_split_from_parts(void* stream, const metis_mat* W_R, const float* U, const float* S,
