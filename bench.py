@@ -445,8 +445,9 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
     sink = torch.zeros((512 * 256,), dtype=torch.float32, device="cuda")
     tc = timed(torch, lambda: metis.ceiling_copy(buf_a, buf_b))
     tr = timed(torch, lambda: metis.ceiling_read(buf_a, sink.view(torch.int32)))
-    fl = metis.ceiling_mfma(2000, sink)
-    tm = timed(torch, lambda: metis.ceiling_mfma(2000, sink))
+    # (launches of several milliseconds: a sub-millisecond launch after an idle gap runs at a lower clock)
+    fl = metis.ceiling_mfma(20000, sink)
+    tm = timed(torch, lambda: metis.ceiling_mfma(20000, sink))
     out["ceilings"] = {
         "copy_GB/s": round(2 * buf_a.numel() / tc["median_ms"] / 1e6, 1),
         "read_GB/s": round(buf_a.numel() / tr["median_ms"] / 1e6, 1),
@@ -458,11 +459,15 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
     mix = {}
     for wps in (1, 2):
         for nv in (0, 4, 5, 6, 8):
-            flm = metis.ceiling_mfma_mix(1000, nv, wps, sink)
-            tmix = timed(torch, lambda: metis.ceiling_mfma_mix(1000, nv, wps, sink))
+            flm = metis.ceiling_mfma_mix(50000, nv, wps, sink)
+            tmix = timed(torch, lambda: metis.ceiling_mfma_mix(50000, nv, wps, sink))
             mix["%d wave%s per SIMD, %d multiplies per matrix instruction" % (wps, "s" if wps > 1 else "", nv)] = round(
                 flm / (tmix["median_ms"] * 1e-3) / 1e12, 1)
     out["ceilings"]["mfma_fp16_with_vector_work_TFLOP/s"] = mix
+    # the GEMM's own expansion and matrix instructions on registers: the stage loop without LDS, loads, waits, barrier
+    fle = metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION, 1, sink)
+    te = timed(torch, lambda: metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION, 1, sink))
+    out["ceilings"]["gemm_stage_loop_on_registers_TFLOP/s"] = round(fle / (te["median_ms"] * 1e-3) / 1e12, 1)
 
     def sweep():                                   # evicts the last-level cache: 1 GiB of other traffic
         metis.ceiling_copy(buf_a, buf_b)

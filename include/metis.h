@@ -410,9 +410,15 @@ int metis_profile_events(int kernel_id, void** start, void** stop, int n);
  *                        instructions (accumulators in the accumulation registers), each followed by
  *                        `valu_per_mfma` (0, 2, 4, 5, 6 or 8) independent packed fp16 multiplies on registers; shows
  *                        what the chip sustains when a wave has to issue that much vector work per matrix
- *                        instruction.  *flops_out as above; sink as above.
+ *                        instruction.  With valu_per_mfma = METIS_MIX_GEMM_EXPANSION (waves_per_simd 1) a wave
+ *                        runs `iters` (rounded up to even) steps of the GEMM's own stage loop on registers instead:
+ *                        eight fragments expanded from raw words (4 FP4 -> fp16 conversions + 4 packed multiplies
+ *                        each), then the 16 matrix instructions of a 128 x 128 wave tile, in the compiler's order --
+ *                        the GEMM without LDS traffic, global loads, waits and barrier.
+ *                        *flops_out as above; sink as above.
  * Errors: METIS_INVALID_ARG.
  */
+#define METIS_MIX_GEMM_EXPANSION (-1)
 int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma, int waves_per_simd, float* sink, double* flops_out);
 int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes);
 int metis_ceiling_read(void* stream, const void* src, size_t bytes, uint32_t* sink);

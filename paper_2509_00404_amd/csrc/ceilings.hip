@@ -117,6 +117,58 @@ __global__ void __launch_bounds__(256) k_ceiling_mfma_mix(int iters, float* __re
     if (s == 12345.678f || (d0 ^ d1 ^ d2 ^ d3 ^ d4 ^ d5 ^ d6 ^ d7) == 0x9E3779B9u) sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The FP4 GEMM's stage loop with its memory system taken away: per step a wave expands eight fragments from raw
+// words that sit in registers (four FP4 -> fp16 conversions and four packed multiplies by the block scale each, the
+// GEMM's own expansion) and issues the 16 matrix instructions of a 128 x 128 wave tile on them; the compiler orders
+// the step.  What is missing against the GEMM: LDS reads and writes, global loads, waits and the barrier.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ half8_t expand8(uint32_t cw, uint32_t spair, bool hi) {
+    const half2_t sp = __builtin_bit_cast(half2_t, spair);
+    const half2_t s2 = hi ? (half2_t){sp[1], sp[1]} : (half2_t){sp[0], sp[0]};
+    const half2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 0) * s2;
+    const half2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 1) * s2;
+    const half2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 2) * s2;
+    const half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 3) * s2;
+    return (half8_t){p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+}
+__global__ void __launch_bounds__(256) k_ceiling_mfma_expand(int iters, float* __restrict__ sink) {
+    float16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    uint32_t raw[8], sc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        raw[t] = 0x9E3779B9u * (threadIdx.x + 1u) * (uint32_t)(t + 3);
+        sc[t] = 0x3C003800u;                                  // fp16 scales 0.5 and 1.0
+    }
+    for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                          // the two blocks of a scale pair
+            half8_t f[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(raw[t]), "+v"(sc[t]));  // new raw words every step, as if read from LDS
+#pragma unroll
+            for (int t = 0; t < 8; ++t) f[t] = expand8(raw[t], sc[t], h);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+    if (s == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma, int waves_per_simd, float* sink,
@@ -127,6 +179,14 @@ extern "C" int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma
     if (cus * waves_per_simd > 512) return METIS_UNSUPPORTED;          // the sink holds 512 workgroups
     const dim3 grid((unsigned)(cus * waves_per_simd));                 // workgroups of four waves, one wave per SIMD each
     hipStream_t s = (hipStream_t)stream;
+    if (valu_per_mfma == METIS_MIX_GEMM_EXPANSION) {
+        if (waves_per_simd != 1) return METIS_INVALID_ARG;            // 16 accumulator tiles: one wave per SIMD
+        const int steps = (iters + 1) / 2 * 2;
+        hipLaunchKernelGGL(k_ceiling_mfma_expand, grid, dim3(256), 0, s, steps, sink);
+        METIS_LAUNCH_CHECK();
+        if (flops_out) *flops_out = (double)grid.x * 4.0 * (double)steps * 16.0 * 2.0 * 32.0 * 32.0 * 16.0;
+        return METIS_OK;
+    }
     switch (valu_per_mfma) {
         case 0: hipLaunchKernelGGL(k_ceiling_mfma_mix<0>, grid, dim3(256), 0, s, iters, sink); break;
         case 2: hipLaunchKernelGGL(k_ceiling_mfma_mix<2>, grid, dim3(256), 0, s, iters, sink); break;

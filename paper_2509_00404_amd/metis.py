@@ -437,6 +437,9 @@ def ceiling_mfma(iters, sink):
     return fl.value
 
 
+MIX_GEMM_EXPANSION = -1      # valu_per_mfma: run the GEMM's own expansion + matrix instructions on registers
+
+
 def ceiling_mfma_mix(iters, valu_per_mfma, waves_per_simd, sink):
     """Matrix instructions interleaved with vector instructions (see metis_ceiling_mfma_mix); returns the flop count."""
     fl = C.c_double()
