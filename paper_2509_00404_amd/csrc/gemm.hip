@@ -449,7 +449,19 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
     for (int v = 0; v < 4; ++v) store_codes(lds, v);
     store_scales(lds);
     __syncthreads();
-    load_stage(niter > 1 ? 1 : 0);
+    // (in the order the stage loop issues and consumes them -- scheduling fences keep it: the wait in front of the
+    // loop's first LDS write is computed over both ways into the loop, and with this order reversed here it has to
+    // wait for every load in flight instead of the oldest pair)
+    {
+        const int st1 = niter > 1 ? 1 : 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            load_codes(st1, v);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_scales(st1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     // per-lane byte offsets of this wave's planes inside a buffer (step 0 / pair 0)
     typedef uint32_t rawvec_t __attribute__((ext_vector_type(4)));
@@ -507,15 +519,19 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
                 store_scales(bufn);
                 load_scales(stn);
             }
-            // one MFMA, then its share of the other work: 4 of the 64 expansion ops, 1 of the 16 LDS reads,
-            // and where the step has them an LDS write or a global load
+            // one MFMA, then its share of the other work: 4 of the 64 expansion ops (5 early in a staging step: the
+            // address arithmetic of the LDS writes and the loads needs slots too, or it drifts to the end of the
+            // stage and takes the loads with it), 1 of the 16 LDS reads, and where the step has them an LDS write
+            // or a global load.  Four load slots per staging step, right behind its LDS writes: with two, half of
+            // the loads were issued a third of a stage later, and a load has to be back one stage after its issue.
 #pragma unroll
             for (int m = 0; m < TM * TN; ++m) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                if (s <= 4 && m < 12) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 if (s <= 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                if (s <= 4 && m >= 8 && m < 10) {                      // the step's two global loads, after its LDS writes
+                if (s <= 4 && m >= 6 && m < 10) {                      // the step's global loads, after its LDS writes
                     __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 }
