@@ -539,8 +539,8 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
         }
     }
 
-    // low-rank terms: extra contraction columns in bf16, read straight from global memory; four steps of
-    // fragments in flight, a step's registers are refilled with the step four ahead as soon as it is used
+    // low-rank terms: extra contraction columns in bf16, read straight from global memory; three steps of
+    // fragments in flight, a step's registers are refilled with the step three ahead as soon as it is used
     const int nks = Ke >> 4;
     if (nks > 0) {
         const bf16_t* ea[TM];
@@ -558,7 +558,8 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
             if (rb > rbb_max) rb = rbb_max;
             eb[j] = Bext + ext_chunk(rb, 0, half, li, nks);
         }
-        BFrag f[4][TM + TN];
+        constexpr int EXT_DEPTH = 3;      // four fit the registers only with spills, and run no faster
+        BFrag f[EXT_DEPTH][TM + TN];
         auto load_ext = [&](int step, int slot) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) f[slot][i].u = *reinterpret_cast<const uint4*>(ea[i] + step * 512);
@@ -566,18 +567,18 @@ k_fp4_gemm_nt_pipe(Fp4Operand A, Fp4Operand B, int64_t K, const bf16_t* __restri
             for (int j = 0; j < TN; ++j) f[slot][TM + j].u = *reinterpret_cast<const uint4*>(eb[j] + step * 512);
         };
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < EXT_DEPTH; ++u)
             if (u < nks) load_ext(u, u);
-        for (int ks = 0; ks < nks; ks += 4) {
+        for (int ks = 0; ks < nks; ks += EXT_DEPTH) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < EXT_DEPTH; ++u) {
                 if (ks + u < nks) {                                   // uniform (kernel argument)
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[u][i].v, f[u][TM + j].v, acc[i][j], 0, 0, 0);
-                    if (ks + u + 4 < nks) load_ext(ks + u + 4, u);
+                    if (ks + u + EXT_DEPTH < nks) load_ext(ks + u + EXT_DEPTH, u);
                 }
             }
         }
