@@ -468,6 +468,9 @@ def extras(out, args, torch, metis, linears, all_ops, step, multi, useful_flops)
     fle = metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION, 1, sink)
     te = timed(torch, lambda: metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION, 1, sink))
     out["ceilings"]["gemm_stage_loop_on_registers_TFLOP/s"] = round(fle / (te["median_ms"] * 1e-3) / 1e12, 1)
+    fl6 = metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION_FP6, 1, sink)
+    t6 = timed(torch, lambda: metis.ceiling_mfma_mix(20000, metis.MIX_GEMM_EXPANSION_FP6, 1, sink))
+    out["ceilings"]["gemm_stage_loop_on_registers_fp6_containers_TFLOP/s"] = round(fl6 / (t6["median_ms"] * 1e-3) / 1e12, 1)
 
     def sweep():                                   # evicts the last-level cache: 1 GiB of other traffic
         metis.ceiling_copy(buf_a, buf_b)

@@ -414,11 +414,14 @@ int metis_profile_events(int kernel_id, void** start, void** stop, int n);
  *                        runs `iters` (rounded up to even) steps of the GEMM's own stage loop on registers instead:
  *                        eight fragments expanded from raw words (4 FP4 -> fp16 conversions + 4 packed multiplies
  *                        each), then the 16 matrix instructions of a 128 x 128 wave tile, in the compiler's order --
- *                        the GEMM without LDS traffic, global loads, waits and barrier.
+ *                        the GEMM without LDS traffic, global loads, waits and barrier.  METIS_MIX_GEMM_EXPANSION_FP6
+ *                        is that loop with the codes in 6-bit containers, expanded by the 32-wide FP6 converter (two
+ *                        instructions per step instead of 32): what a wider container format would buy.
  *                        *flops_out as above; sink as above.
  * Errors: METIS_INVALID_ARG.
  */
 #define METIS_MIX_GEMM_EXPANSION (-1)
+#define METIS_MIX_GEMM_EXPANSION_FP6 (-2)
 int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma, int waves_per_simd, float* sink, double* flops_out);
 int metis_ceiling_copy(void* stream, const void* src, void* dst, size_t bytes);
 int metis_ceiling_read(void* stream, const void* src, size_t bytes, uint32_t* sink);

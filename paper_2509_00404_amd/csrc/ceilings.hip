@@ -131,6 +131,12 @@ __device__ __forceinline__ half8_t expand8(uint32_t cw, uint32_t spair, bool hi)
     const half2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(cw, 1.0f, 3) * s2;
     return (half8_t){p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
+// FP6 = the same step with the codes held in 6-bit containers and expanded by the 32-wide converter
+// (v_cvt_scalef32_pk32_f16_fp6: one instruction for the four fragments of an operand) instead of 32 two-wide FP4
+// conversions; the packed multiplies by the block scales stay.
+typedef _Float16 half32_t __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x6_t __attribute__((ext_vector_type(6)));
+template <bool FP6>
 __global__ void __launch_bounds__(256) k_ceiling_mfma_expand(int iters, float* __restrict__ sink) {
     float16_t acc[4][4];
 #pragma unroll
@@ -140,19 +146,40 @@ __global__ void __launch_bounds__(256) k_ceiling_mfma_expand(int iters, float* _
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
     uint32_t raw[8], sc[8];
+    u32x6_t r6[2];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         raw[t] = 0x9E3779B9u * (threadIdx.x + 1u) * (uint32_t)(t + 3);
         sc[t] = 0x3C003800u;                                  // fp16 scales 0.5 and 1.0
     }
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int e = 0; e < 6; ++e) r6[g][e] = (0x9E3779B9u * (threadIdx.x + 7u) * (uint32_t)(e + 6 * g + 1)) & 0x3CF3CF3Cu;   // E2M1 values in E2M3 fields
     for (int it = 0; it < iters; it += 2) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {                          // the two blocks of a scale pair
             half8_t f[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(raw[t]), "+v"(sc[t]));  // new raw words every step, as if read from LDS
+            if (FP6) {
+                asm volatile("" : "+v"(r6[0]), "+v"(r6[1]));
 #pragma unroll
-            for (int t = 0; t < 8; ++t) f[t] = expand8(raw[t], sc[t], h);
+                for (int g = 0; g < 2; ++g) {
+                    const half32_t c = __builtin_amdgcn_cvt_scalef32_pk32_f16_fp6(r6[g], 1.0f);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const half2_t sp = __builtin_bit_cast(half2_t, sc[4 * g + t]);
+                        const half2_t s2 = h ? (half2_t){sp[1], sp[1]} : (half2_t){sp[0], sp[0]};
+                        const half2_t p0 = (half2_t){c[8 * t], c[8 * t + 1]} * s2, p1 = (half2_t){c[8 * t + 2], c[8 * t + 3]} * s2;
+                        const half2_t p2 = (half2_t){c[8 * t + 4], c[8 * t + 5]} * s2, p3 = (half2_t){c[8 * t + 6], c[8 * t + 7]} * s2;
+                        f[4 * g + t] = (half8_t){p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) f[t] = expand8(raw[t], sc[t], h);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -179,10 +206,13 @@ extern "C" int metis_ceiling_mfma_mix(void* stream, int iters, int valu_per_mfma
     if (cus * waves_per_simd > 512) return METIS_UNSUPPORTED;          // the sink holds 512 workgroups
     const dim3 grid((unsigned)(cus * waves_per_simd));                 // workgroups of four waves, one wave per SIMD each
     hipStream_t s = (hipStream_t)stream;
-    if (valu_per_mfma == METIS_MIX_GEMM_EXPANSION) {
+    if (valu_per_mfma == METIS_MIX_GEMM_EXPANSION || valu_per_mfma == METIS_MIX_GEMM_EXPANSION_FP6) {
         if (waves_per_simd != 1) return METIS_INVALID_ARG;            // 16 accumulator tiles: one wave per SIMD
         const int steps = (iters + 1) / 2 * 2;
-        hipLaunchKernelGGL(k_ceiling_mfma_expand, grid, dim3(256), 0, s, steps, sink);
+        if (valu_per_mfma == METIS_MIX_GEMM_EXPANSION)
+            hipLaunchKernelGGL(k_ceiling_mfma_expand<false>, grid, dim3(256), 0, s, steps, sink);
+        else
+            hipLaunchKernelGGL(k_ceiling_mfma_expand<true>, grid, dim3(256), 0, s, steps, sink);
         METIS_LAUNCH_CHECK();
         if (flops_out) *flops_out = (double)grid.x * 4.0 * (double)steps * 16.0 * 2.0 * 32.0 * 32.0 * 16.0;
         return METIS_OK;

@@ -438,6 +438,7 @@ def ceiling_mfma(iters, sink):
 
 
 MIX_GEMM_EXPANSION = -1      # valu_per_mfma: run the GEMM's own expansion + matrix instructions on registers
+MIX_GEMM_EXPANSION_FP6 = -2  # ... with the codes in 6-bit containers and the 32-wide FP6 converter
 
 
 def ceiling_mfma_mix(iters, valu_per_mfma, waves_per_simd, sink):

@@ -34,12 +34,14 @@ def test_matrix_loops_report_their_flops(metis):
             assert metis.ceiling_mfma_mix(5, nv, wps, sink) == cus * wps * 4 * 5 * 4 * per_mfma
     # the GEMM's stage loop on registers: steps come in pairs, 16 matrix instructions each
     assert metis.ceiling_mfma_mix(5, metis.MIX_GEMM_EXPANSION, 1, sink) == cus * 4 * 6 * 16 * per_mfma
+    assert metis.ceiling_mfma_mix(5, metis.MIX_GEMM_EXPANSION_FP6, 1, sink) == cus * 4 * 6 * 16 * per_mfma
     torch.cuda.synchronize()
     assert float(sink.abs().max()) == 0.0          # the sink is only there to keep the work alive
 
 
 def test_bad_arguments(metis):
     sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
-    for args in ((0, 4, 1), (5, 3, 1), (5, 4, 3), (5, metis.MIX_GEMM_EXPANSION, 2)):
+    for args in ((0, 4, 1), (5, 3, 1), (5, 4, 3), (5, metis.MIX_GEMM_EXPANSION, 2),
+                 (5, metis.MIX_GEMM_EXPANSION_FP6, 2), (5, -3, 1)):
         with pytest.raises(metis.MetisError):
             metis.ceiling_mfma_mix(*args, sink)
